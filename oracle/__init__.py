@@ -1,0 +1,133 @@
+"""ctypes front end of the CPU oracle (``laq_oracle.c``) -- TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It never imports the HIP package, and
+the HIP package never imports it.
+
+The functions mirror the steps of the re-eviction procedure (paper Sec. 4.3,
+Eq. 4): ``raw_scores`` (window attention summed over the Q-cache and the GQA
+group), ``maxpool``, ``select`` (ArgSort[:B] per KV head with the window
+retained) and ``compact`` (row gather).  ``evict`` chains them for one
+instance.  Tensors are CPU torch tensors (fp32 or bf16); results are fp64 /
+int32 torch tensors.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "laq_oracle.c")
+_LIB = os.path.join(_HERE, "_build", "liblaq_oracle.so")
+_lib: Optional[ctypes.CDLL] = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no threading, no fast-math)."""
+    os.makedirs(os.path.dirname(_LIB), exist_ok=True)
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-shared", "-fPIC", "-Wall", "-Wextra",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        c_int, c_dbl, c_vp = ctypes.c_int, ctypes.c_double, ctypes.c_void_p
+        lib.laq_oracle_raw_scores.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int,
+                                              c_dbl, c_vp]
+        lib.laq_oracle_raw_scores.restype = c_int
+        lib.laq_oracle_maxpool.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp]
+        lib.laq_oracle_maxpool.restype = c_int
+        lib.laq_oracle_select.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp]
+        lib.laq_oracle_select.restype = c_int
+        lib.laq_oracle_compact.argtypes = [c_vp, c_int, c_int, ctypes.c_size_t, c_vp, c_int, c_vp]
+        lib.laq_oracle_compact.restype = c_int
+        _lib = lib
+    return _lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return 0
+    if t.dtype == torch.bfloat16:
+        return 1
+    raise TypeError("oracle takes fp32 or bf16 tensors, got %s" % t.dtype)
+
+
+def _cpu(t: torch.Tensor) -> torch.Tensor:
+    if t.device.type != "cpu":
+        raise ValueError("the oracle works on host tensors")
+    return t.contiguous()
+
+
+def raw_scores(q_win: torch.Tensor, k: torch.Tensor, scale: float = 0.0) -> torch.Tensor:
+    """Steps 1-4 for one instance: q_win [Hq, W, d], k [Hkv, L, d] -> raw [Hkv, L] fp64."""
+    q_win, k = _cpu(q_win), _cpu(k)
+    Hq, W, d = q_win.shape
+    Hkv, L, d2 = k.shape
+    if d != d2 or q_win.dtype != k.dtype:
+        raise ValueError("q_win / k mismatch")
+    raw = torch.empty(Hkv, L, dtype=torch.float64)
+    rc = _load().laq_oracle_raw_scores(q_win.data_ptr(), k.data_ptr(), _dtype_code(k),
+                                       Hq, Hkv, d, L, W, float(scale), raw.data_ptr())
+    if rc != 0:
+        raise ValueError("laq_oracle_raw_scores rejected its arguments")
+    return raw
+
+
+def maxpool(raw: torch.Tensor, W: int, pool: int) -> torch.Tensor:
+    """Step 5: raw [Hkv, L] fp64 -> pooled [Hkv, L] fp64 (prefix pooled, window columns copied)."""
+    raw = _cpu(raw.double())
+    Hkv, L = raw.shape
+    out = torch.empty_like(raw)
+    rc = _load().laq_oracle_maxpool(raw.data_ptr(), Hkv, L, W, pool, out.data_ptr())
+    if rc != 0:
+        raise ValueError("laq_oracle_maxpool rejected its arguments")
+    return out
+
+
+def select(scores_f32: torch.Tensor, W: int, budget: int) -> torch.Tensor:
+    """Step 6: scores [Hkv, L] fp32 -> idx [Hkv, min(budget, L)] int32, ascending."""
+    if scores_f32.dtype != torch.float32:
+        raise TypeError("selection is decided on fp32 scores")
+    s = _cpu(scores_f32)
+    Hkv, L = s.shape
+    Bk = min(int(budget), L)
+    idx = torch.empty(Hkv, Bk, dtype=torch.int32)
+    rc = _load().laq_oracle_select(s.data_ptr(), Hkv, L, W, int(budget), idx.data_ptr())
+    if rc != 0:
+        raise ValueError("laq_oracle_select rejected its arguments")
+    return idx
+
+
+def compact(src: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
+    """Step 7: src [Hkv, L, d], idx [Hkv, Bk] int32 -> [Hkv, Bk, d], bit copies."""
+    src, idx = _cpu(src), _cpu(idx)
+    Hkv, L, d = src.shape
+    Bk = idx.shape[1]
+    out = torch.empty(Hkv, Bk, d, dtype=src.dtype)
+    rc = _load().laq_oracle_compact(src.data_ptr(), Hkv, L, d * src.element_size(),
+                                    idx.data_ptr(), Bk, out.data_ptr())
+    if rc != 0:
+        raise ValueError("laq_oracle_compact rejected its arguments")
+    return out
+
+
+def evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], budget: int,
+          pool: int, scale: float = 0.0
+          ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, Optional[torch.Tensor]]:
+    """Whole path for one instance: returns (pooled fp64 [Hkv, L], idx, k', v')."""
+    W = q_win.shape[1]
+    pooled = maxpool(raw_scores(q_win, k, scale), W, pool)
+    idx = select(pooled.float(), W, budget)
+    return pooled, idx, compact(k, idx), (compact(v, idx) if v is not None else None)

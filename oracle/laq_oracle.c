@@ -1,0 +1,203 @@
+/*
+ * CPU oracle for the LAQ re-eviction hot path -- TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the plain, slow, single-threaded fp64 definition that the HIP
+ * library is checked against.  Only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may call it; the product path never does, and it shares no
+ * code, header, table or helper with the HIP sources.
+ *
+ * What it computes (paper, Sec. 4.3 "KV-Cache Re-eviction", Eq. 4; the
+ * observation-window procedure it defers to is the one summarised in Sec. 2.1
+ * and Sec. 5.1 "Selected baselines"):
+ *
+ *   For one (sequence, layer) instance with Hq query heads sharing Hkv KV heads
+ *   (G = Hq/Hkv consecutive query heads per KV head), the Q-cache holds W
+ *   lookahead queries per query head and the key cache holds L rows per KV
+ *   head, the last W of which are the window tokens themselves.  P = L - W.
+ *
+ *   1. window query w stands at position P + w and sees keys j <= P + w;
+ *   2. logit  s_j = scale * <q[h,w,:], k[h/G, j, :]>;
+ *   3. attention of that query over its visible keys: p_j = exp(s_j - M) / Z;
+ *   4. raw[g, j] = sum over the G heads of the group and the W queries of p_j
+ *      (the sum over the Q-cache of Eq. 4, taken on attention scores);
+ *   5. pooled[g, j] = max of raw[g, i] over |i - j| <= (p-1)/2 clipped to the
+ *      prefix [0, P); window columns keep their raw value;
+ *   6. per KV head keep the (budget - W) largest pooled prefix entries, ties to
+ *      the lower index, plus the W window tokens; indices ascending
+ *      ("ArgSort(...)[:B]" of Eq. 4);
+ *   7. the compacted cache is K and V restricted to those rows.
+ *
+ * Readings where the paper is silent (softmax before the sum, 1/sqrt(d) scale,
+ * max- rather than average-pooling, GQA sum, budget including the window,
+ * tie-break) are listed in the design notes of the repository.
+ *
+ * Pins (tests marked "not gpu"): brute-force attention matrices on tiny inputs,
+ * row-sum and non-negativity invariants, the closed form for identical keys,
+ * the W=1/G=1/pool=1 reduction to ArgSort(q K^T), GQA additivity, key-shift
+ * invariance, hand-computed pooling cases, exhaustive top-k, planted keys.
+ * No function here is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+
+static double load_elem(const void *base, int dtype, size_t i)
+{
+    if (dtype == ORACLE_F32)
+        return (double)((const float *)base)[i];
+    /* bfloat16: the high 16 bits of an IEEE binary32 */
+    uint32_t bits = (uint32_t)((const uint16_t *)base)[i] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+/*
+ * Steps 1-4.  q: [Hq, W, d], k: [Hkv, L, d] in `dtype`; raw: [Hkv, L] doubles.
+ * scale <= 0 selects 1/sqrt(d).  Returns 0, or -1 on bad arguments.
+ */
+int laq_oracle_raw_scores(const void *q, const void *k, int dtype,
+                          int Hq, int Hkv, int d, int L, int W,
+                          double scale, double *raw)
+{
+    if (!q || !k || !raw || Hq <= 0 || Hkv <= 0 || d <= 0 || L <= 0 || W <= 0 ||
+        W > L || Hq % Hkv != 0 || (dtype != ORACLE_F32 && dtype != ORACLE_BF16))
+        return -1;
+    const int G = Hq / Hkv;
+    const int P = L - W;
+    if (scale <= 0.0)
+        scale = 1.0 / sqrt((double)d);
+
+    double *qrow = (double *)malloc(sizeof(double) * (size_t)d);
+    double *s = (double *)malloc(sizeof(double) * (size_t)L);
+    if (!qrow || !s) { free(qrow); free(s); return -1; }
+
+    for (size_t i = 0; i < (size_t)Hkv * (size_t)L; ++i)
+        raw[i] = 0.0;
+
+    for (int h = 0; h < Hq; ++h) {
+        const int g = h / G;
+        for (int w = 0; w < W; ++w) {
+            const int vis = P + w + 1;            /* keys 0 .. P+w are visible */
+            for (int c = 0; c < d; ++c)
+                qrow[c] = load_elem(q, dtype, ((size_t)h * W + w) * d + c);
+            double M = -INFINITY;
+            for (int j = 0; j < vis; ++j) {
+                double acc = 0.0;
+                const size_t off = ((size_t)g * L + j) * d;
+                for (int c = 0; c < d; ++c)
+                    acc += qrow[c] * load_elem(k, dtype, off + c);
+                s[j] = scale * acc;
+                if (s[j] > M) M = s[j];
+            }
+            double Z = 0.0;
+            for (int j = 0; j < vis; ++j) {
+                s[j] = exp(s[j] - M);
+                Z += s[j];
+            }
+            for (int j = 0; j < vis; ++j)
+                raw[(size_t)g * L + j] += s[j] / Z;
+        }
+    }
+    free(qrow);
+    free(s);
+    return 0;
+}
+
+/*
+ * Step 5.  raw, pooled: [Hkv, L] doubles (may not alias).  pool is odd >= 1.
+ * The max runs over the part of the window that lies inside the prefix [0, P);
+ * columns j >= P are copied.
+ */
+int laq_oracle_maxpool(const double *raw, int Hkv, int L, int W, int pool, double *pooled)
+{
+    if (!raw || !pooled || Hkv <= 0 || L <= 0 || W <= 0 || W > L || pool < 1 || pool % 2 == 0)
+        return -1;
+    const int P = L - W, half = (pool - 1) / 2;
+    for (int g = 0; g < Hkv; ++g) {
+        const double *r = raw + (size_t)g * L;
+        double *o = pooled + (size_t)g * L;
+        for (int j = 0; j < P; ++j) {
+            int lo = j - half, hi = j + half;
+            if (lo < 0) lo = 0;
+            if (hi > P - 1) hi = P - 1;
+            double m = r[lo];
+            for (int i = lo + 1; i <= hi; ++i)
+                if (r[i] > m) m = r[i];
+            o[j] = m;
+        }
+        for (int j = P; j < L; ++j)
+            o[j] = r[j];
+    }
+    return 0;
+}
+
+typedef struct { float score; int32_t index; } ranked_t;
+
+static int ranked_cmp(const void *a, const void *b)
+{
+    const ranked_t *x = (const ranked_t *)a, *y = (const ranked_t *)b;
+    if (x->score > y->score) return -1;      /* larger score first */
+    if (x->score < y->score) return 1;
+    return (x->index > y->index) - (x->index < y->index);   /* then lower index */
+}
+
+static int int32_cmp(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * Step 6.  scores: [Hkv, L] fp32 (the precision in which the library takes the
+ * decision); idx: [Hkv, Bk] with Bk = min(budget, L).  budget >= W required.
+ * A full sort of the prefix by (score descending, index ascending); the first
+ * budget - W entries are kept, re-sorted ascending, and followed by P .. L-1.
+ */
+int laq_oracle_select(const float *scores, int Hkv, int L, int W, int budget, int32_t *idx)
+{
+    if (!scores || !idx || Hkv <= 0 || L <= 0 || W <= 0 || W > L || budget < W)
+        return -1;
+    const int P = L - W;
+    const int Bk = budget < L ? budget : L;
+    const int ksel = Bk - W;
+    ranked_t *r = (ranked_t *)malloc(sizeof(ranked_t) * (size_t)(P > 0 ? P : 1));
+    if (!r) return -1;
+    for (int g = 0; g < Hkv; ++g) {
+        int32_t *out = idx + (size_t)g * Bk;
+        for (int j = 0; j < P; ++j) {
+            r[j].score = scores[(size_t)g * L + j];
+            r[j].index = j;
+        }
+        qsort(r, (size_t)P, sizeof(ranked_t), ranked_cmp);
+        for (int t = 0; t < ksel; ++t)
+            out[t] = r[t].index;
+        qsort(out, (size_t)ksel, sizeof(int32_t), int32_cmp);
+        for (int w = 0; w < W; ++w)
+            out[ksel + w] = P + w;
+    }
+    free(r);
+    return 0;
+}
+
+/*
+ * Step 7.  src: [Hkv, L, row_bytes], idx: [Hkv, Bk], dst: [Hkv, Bk, row_bytes].
+ * Byte copy of the selected rows (row_bytes = d * element size).
+ */
+int laq_oracle_compact(const void *src, int Hkv, int L, size_t row_bytes,
+                       const int32_t *idx, int Bk, void *dst)
+{
+    if (!src || !idx || !dst || Hkv <= 0 || L <= 0 || Bk < 0)
+        return -1;
+    for (int g = 0; g < Hkv; ++g)
+        for (int t = 0; t < Bk; ++t) {
+            int32_t j = idx[(size_t)g * Bk + t];
+            if (j < 0 || j >= L) return -1;
+            memcpy((char *)dst + ((size_t)g * Bk + t) * row_bytes,
+                   (const char *)src + ((size_t)g * L + j) * row_bytes, row_bytes);
+        }
+    return 0;
+}

@@ -1,0 +1,385 @@
+"""Pins for the CPU oracle (no GPU): each test fixes the oracle against something
+other than itself -- brute force written independently here, closed forms,
+invariants, metamorphic relations, hand-computed fixtures, library routines on
+special cases -- so that a dropped term, a wrong sign or index, a transposed
+operand or an off-by-one in the mask fails at least one of them.
+
+The paper (Sec. 4.3, Eq. 4) prints no worked numeric example for this path.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from laq_inputs import CONFIGS, budgets_for, make_instance, pyramid_budget
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------
+# independent brute force: the explicit [Hq, W, L] attention matrix with a
+# boolean mask, written with numpy array ops (no shared code with the oracle)
+# ----------------------------------------------------------------------------
+def brute_raw(q, k, scale=None):
+    q = q.double().numpy()
+    k = k.double().numpy()
+    Hq, W, d = q.shape
+    Hkv, L, _ = k.shape
+    G = Hq // Hkv
+    P = L - W
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    kk = np.repeat(k, G, axis=0)                               # [Hq, L, d]
+    S = np.einsum("hwc,hjc->hwj", q, kk) * scale               # [Hq, W, L]
+    pos_q = P + np.arange(W)[:, None]                          # query positions
+    visible = np.arange(L)[None, :] <= pos_q                   # [W, L]
+    S = np.where(visible[None], S, -np.inf)
+    S = S - S.max(axis=2, keepdims=True)
+    E = np.exp(S)
+    A = E / E.sum(axis=2, keepdims=True)                       # attention rows
+    return A.reshape(Hkv, G, W, L).sum(axis=(1, 2))            # [Hkv, L]
+
+
+def brute_pool(raw, W, pool):
+    Hkv, L = raw.shape
+    P = L - W
+    out = raw.copy()
+    h = pool // 2
+    for g in range(Hkv):
+        for j in range(P):
+            out[g, j] = max(raw[g, i] for i in range(max(0, j - h), min(P, j + h + 1)))
+    return out
+
+
+def brute_select(scores, W, budget):
+    Hkv, L = scores.shape
+    P = L - W
+    Bk = min(budget, L)
+    out = np.zeros((Hkv, Bk), dtype=np.int32)
+    for g in range(Hkv):
+        order = sorted(range(P), key=lambda j: (-float(scores[g, j]), j))
+        out[g] = sorted(order[:Bk - W]) + list(range(P, L))
+    return out
+
+
+def rand_case(seed, Hq, Hkv, d, L, W, dtype=torch.float32, qscale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    q = (torch.randn(Hq, W, d, generator=g) * qscale).to(dtype)
+    k = torch.randn(Hkv, L, d, generator=g).to(dtype)
+    v = torch.randn(Hkv, L, d, generator=g).to(dtype)
+    return q, k, v
+
+
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("Hq,Hkv,d,L,W", [
+    (1, 1, 4, 9, 1), (2, 1, 8, 17, 3), (4, 2, 8, 32, 5), (6, 2, 16, 23, 8), (3, 3, 5, 12, 12),
+])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_raw_scores_match_explicit_attention_matrix(Hq, Hkv, d, L, W, dtype):
+    q, k, _ = rand_case(7 + L, Hq, Hkv, d, L, W, dtype, qscale=2.0)
+    got = oracle.raw_scores(q, k).numpy()
+    want = brute_raw(q, k)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-15)
+
+
+def test_explicit_scale_is_used():
+    q, k, _ = rand_case(3, 2, 1, 8, 20, 4)
+    got = oracle.raw_scores(q, k, scale=0.37).numpy()
+    np.testing.assert_allclose(got, brute_raw(q, k, scale=0.37), rtol=1e-12)
+    default = oracle.raw_scores(q, k).numpy()
+    np.testing.assert_allclose(default, brute_raw(q, k, scale=1 / math.sqrt(8)), rtol=1e-12)
+    assert not np.allclose(got, default)
+
+
+def test_rows_sum_to_one_and_nonnegative():
+    # every one of the Hq*W attention rows sums to 1, so each KV head's raw row sums to G*W
+    q, k, _ = rand_case(11, 8, 2, 16, 300, 6, qscale=3.0)
+    raw = oracle.raw_scores(q, k).numpy()
+    assert (raw >= 0).all()
+    np.testing.assert_allclose(raw.sum(axis=1), np.full(2, 4 * 6.0), rtol=1e-12)
+
+
+def test_causal_mask_window_columns():
+    # window key P+w' is visible only to queries w >= w'; the last column gets mass from one
+    # query per head only, and a huge logit there must not leak into earlier queries' rows
+    Hq, Hkv, d, L, W = 2, 1, 4, 10, 4
+    q = torch.ones(Hq, W, d)
+    k = torch.zeros(Hkv, L, d)
+    k[0, L - 1] = 50.0                        # dominant for the one query that can see it
+    raw = oracle.raw_scores(q, k, scale=1.0).numpy()[0]
+    P = L - W
+    # queries w < W-1 see P+w+1 identical (zero) keys -> uniform
+    expect = np.zeros(L)
+    for w in range(W - 1):
+        expect[:P + w + 1] += Hq / (P + w + 1)
+    expect[L - 1] += Hq * 1.0                 # last query: all mass on the heavy key (e^-200 elsewhere)
+    np.testing.assert_allclose(raw, expect, rtol=1e-12, atol=1e-60)
+
+
+def test_identical_keys_closed_form_and_all_ties():
+    # all keys equal -> every visible key gets 1/(P+w+1): harmonic closed form, exact fractions
+    Hq, Hkv, d, L, W, budget, pool = 6, 2, 8, 40, 5, 17, 7
+    G, P = Hq // Hkv, L - W
+    g = torch.Generator().manual_seed(5)
+    q = torch.randn(Hq, W, d, generator=g)
+    k = torch.randn(1, 1, d, generator=g).expand(Hkv, L, d).contiguous()
+    raw = oracle.raw_scores(q, k).numpy()
+    for j in range(L):
+        first_w = max(0, j - P)              # first query that sees column j
+        want = G * sum(Fraction(1, P + w + 1) for w in range(first_w, W))
+        np.testing.assert_allclose(raw[:, j], float(want), rtol=1e-13)
+    pooled = oracle.maxpool(torch.from_numpy(raw), W, pool)
+    idx = oracle.select(pooled.float(), W, budget).numpy()
+    want_idx = list(range(budget - W)) + list(range(P, L))     # all ties -> lowest indices
+    assert (idx == np.array(want_idx, dtype=np.int32)[None]).all()
+
+
+def test_zero_queries_give_uniform_attention():
+    Hq, Hkv, d, L, W = 4, 4, 8, 21, 2
+    _, k, _ = rand_case(2, Hq, Hkv, d, L, W)
+    raw = oracle.raw_scores(torch.zeros(Hq, W, d), k).numpy()
+    P = L - W
+    np.testing.assert_allclose(raw[:, :P], 1 / (P + 1) + 1 / (P + 2), rtol=1e-13)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_reduces_to_argsort_of_qk_for_single_query(seed):
+    # Eq. 4 read literally: with one query, one head per KV head and no pooling the softmax is
+    # monotone, so the retained prefix set is ArgSort(q K^T)[:k_sel]
+    Hq = Hkv = 3
+    d, L, W, budget = 16, 200, 1, 31
+    q, k, v = rand_case(seed, Hq, Hkv, d, L, W)
+    pooled, idx, _, _ = oracle.evict(q, k, v, budget, pool=1)
+    dots = torch.einsum("hc,hjc->hj", q[:, 0].double(), k.double())[:, :L - 1]
+    for h in range(Hkv):
+        top = torch.argsort(dots[h], descending=True)[:budget - 1]
+        assert sorted(top.tolist()) == idx[h, :budget - 1].tolist()
+        assert idx[h, -1].item() == L - 1
+
+
+def test_gqa_group_is_sum_of_single_head_runs():
+    Hq, Hkv, d, L, W = 6, 2, 8, 50, 3
+    q, k, _ = rand_case(9, Hq, Hkv, d, L, W, qscale=2.0)
+    G = Hq // Hkv
+    whole = oracle.raw_scores(q, k).numpy()
+    for g in range(Hkv):
+        parts = sum(oracle.raw_scores(q[h:h + 1], k[g:g + 1]).numpy()[0]
+                    for h in range(g * G, (g + 1) * G))
+        np.testing.assert_allclose(whole[g], parts, rtol=1e-12)
+    # and the head -> group map is by consecutive blocks: swapping two heads of different groups matters
+    q2 = q.clone()
+    q2[[0, G]] = q2[[G, 0]]
+    assert not np.allclose(oracle.raw_scores(q2, k).numpy(), whole)
+
+
+def test_window_sum_is_sum_of_single_query_runs_with_their_own_mask():
+    # one head, W queries: equals the sum of W single-query runs on the truncated key prefix
+    d, L, W = 8, 30, 4
+    q, k, _ = rand_case(21, 1, 1, d, L, W, qscale=2.0)
+    whole = oracle.raw_scores(q, k).numpy()[0]
+    P = L - W
+    acc = np.zeros(L)
+    for w in range(W):
+        vis = P + w + 1
+        acc[:vis] += oracle.raw_scores(q[:, w:w + 1], k[:, :vis]).numpy()[0]
+    np.testing.assert_allclose(whole, acc, rtol=1e-12)
+
+
+def test_shift_of_all_keys_leaves_scores_unchanged():
+    # adding one vector to every key shifts each row's logits by a constant
+    q, k, _ = rand_case(4, 4, 2, 8, 64, 4)
+    k = torch.round(k * 64) / 64                 # on a grid, so that k + u is exact in fp32
+    u = torch.round(torch.randn(8, generator=torch.Generator().manual_seed(1)) * 64) / 64
+    a = oracle.raw_scores(q, k).numpy()
+    b = oracle.raw_scores(q, k + u).numpy()
+    np.testing.assert_allclose(a, b, rtol=1e-9)
+
+
+def test_prefix_permutation_permutes_prefix_scores():
+    q, k, _ = rand_case(6, 4, 2, 8, 40, 4)
+    P = 36
+    perm = torch.randperm(P, generator=torch.Generator().manual_seed(2))
+    k2 = k.clone()
+    k2[:, :P] = k[:, perm]
+    a = oracle.raw_scores(q, k).numpy()
+    b = oracle.raw_scores(q, k2).numpy()
+    np.testing.assert_allclose(b[:, :P], a[:, perm.numpy()], rtol=1e-11)
+    np.testing.assert_allclose(b[:, P:], a[:, P:], rtol=1e-11)
+
+
+def test_softmax_matches_library_on_unmasked_case():
+    # W = 1: a single query after the whole prefix; compare with torch's fp64 softmax
+    q, k, _ = rand_case(8, 2, 2, 16, 100, 1, qscale=3.0)
+    raw = oracle.raw_scores(q, k)
+    logits = torch.einsum("hc,hjc->hj", q[:, 0].double(), k.double()) / 4.0
+    np.testing.assert_allclose(raw.numpy(), torch.softmax(logits, dim=1).numpy(), rtol=1e-12)
+
+
+def test_extreme_logits_do_not_overflow():
+    # the max is subtracted before exponentiation: logits of +-1000 still give a valid distribution
+    q = torch.full((1, 2, 4), 50.0)
+    k = torch.zeros(1, 12, 4)
+    k[0, 3] = 20.0
+    k[0, 5] = -20.0
+    raw = oracle.raw_scores(q, k, scale=1.0).numpy()[0]
+    assert np.isfinite(raw).all()
+    np.testing.assert_allclose(raw.sum(), 2.0, rtol=1e-12)
+    assert raw[3] == pytest.approx(2.0, rel=1e-12)
+
+
+# ----------------------------------------------------------------------------
+def _golden_pool_cases():
+    cases = []
+    with open(os.path.join(GOLDEN, "maxpool_cases.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            head, raw, want = [p.strip() for p in line.split("|")]
+            W, pool = [int(x) for x in head.split()]
+            cases.append((W, pool, [float(x) for x in raw.split()], [float(x) for x in want.split()]))
+    return cases
+
+
+@pytest.mark.parametrize("W,pool,raw,want", _golden_pool_cases())
+def test_maxpool_hand_computed(W, pool, raw, want):
+    got = oracle.maxpool(torch.tensor([raw], dtype=torch.float64), W, pool).numpy()[0]
+    assert got.tolist() == want
+
+
+@pytest.mark.parametrize("pool", [1, 3, 5, 7, 9])
+def test_maxpool_vs_brute_and_library(pool):
+    g = torch.Generator().manual_seed(pool)
+    raw = torch.rand(3, 57, generator=g, dtype=torch.float64)
+    W = 6
+    got = oracle.maxpool(raw, W, pool).numpy()
+    assert (got == brute_pool(raw.numpy(), W, pool)).all()
+    P = 57 - W
+    lib = torch.nn.functional.max_pool1d(raw[:, :P].unsqueeze(0), pool, stride=1, padding=pool // 2)[0]
+    assert (got[:, :P] == lib.numpy()).all()
+    assert (got[:, P:] == raw[:, P:].numpy()).all()
+    assert (got[:, :P] >= raw[:, :P].numpy()).all()
+    if pool == 1:
+        assert (got == raw.numpy()).all()
+
+
+def test_maxpool_isolated_spike_gives_plateau():
+    raw = torch.zeros(1, 40, dtype=torch.float64)
+    raw[0, 20] = 1.0
+    got = oracle.maxpool(raw, 4, 7).numpy()[0]
+    assert got[17:24].tolist() == [1.0] * 7 and got[16] == 0 and got[24] == 0
+
+
+def test_maxpool_rejects_even_kernel():
+    with pytest.raises(ValueError):
+        oracle.maxpool(torch.zeros(1, 8, dtype=torch.float64), 1, 4)
+
+
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(4))
+def test_select_vs_exhaustive_sort_with_ties(seed):
+    g = torch.Generator().manual_seed(seed)
+    Hkv, L, W = 3, 61, 5
+    # few distinct values -> many exact ties, including across the k-th boundary
+    scores = torch.randint(0, 6, (Hkv, L), generator=g).float() / 4
+    for budget in (W, W + 1, 20, L - 1, L, L + 10):
+        got = oracle.select(scores, W, budget).numpy()
+        assert (got == brute_select(scores.numpy(), W, budget)).all()
+        Bk = min(budget, L)
+        assert got.shape == (Hkv, Bk)
+        assert (np.diff(got, axis=1) > 0).all() if Bk > 1 else True
+        assert (got[:, Bk - W:] == np.arange(L - W, L)).all()
+
+
+def test_select_properties_random():
+    g = torch.Generator().manual_seed(3)
+    Hkv, L, W, budget = 4, 500, 8, 64
+    scores = torch.rand(Hkv, L, generator=g)
+    idx = oracle.select(scores, W, budget).numpy()
+    P = L - W
+    for h in range(Hkv):
+        sel = idx[h, :budget - W]
+        rest = np.setdiff1d(np.arange(P), sel)
+        assert scores[h, sel].min() >= scores[h, rest].max()
+        lib = torch.topk(scores[h, :P], budget - W).indices.sort().values
+        assert sel.tolist() == lib.tolist()                      # tie-free -> library top-k agrees
+
+
+def test_select_plateau_takes_lowest_indices():
+    s = torch.zeros(1, 30)
+    s[0, 10:17] = 2.0           # a 7-wide plateau, as max-pooling produces
+    s[0, 20:27] = 2.0
+    idx = oracle.select(s, 2, 2 + 10).numpy()[0]
+    assert idx.tolist() == [10, 11, 12, 13, 14, 15, 16, 20, 21, 22, 28, 29]
+
+
+def test_select_budget_below_window_is_rejected():
+    with pytest.raises(ValueError):
+        oracle.select(torch.zeros(1, 10), 4, 3)
+
+
+def test_compact_is_plain_indexing():
+    q, k, v = rand_case(1, 2, 2, 8, 33, 3, torch.bfloat16)
+    idx = torch.tensor([[0, 5, 7, 30, 31, 32], [1, 2, 3, 30, 31, 32]], dtype=torch.int32)
+    for src in (k, v, k.float()):
+        got = oracle.compact(src, idx)
+        want = torch.stack([src[h, idx[h].long()] for h in range(2)])
+        assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+
+
+# ----------------------------------------------------------------------------
+def test_config1_planted_keys_give_closed_form_set():
+    # 8 planted keys x pool 7 = 56 = budget - W: with planted positions >= 8 apart and >= 4 from
+    # the prefix edges and a dominant amplitude, the retained prefix set is the union of the
+    # planted keys' pooling neighbourhoods
+    import dataclasses
+    cfg = dataclasses.replace(CONFIGS[1], planted_amp=40.0)
+    q, k, v, meta = make_instance(cfg)
+    budget = budgets_for(cfg)[0]
+    pooled, idx, kc, vc = oracle.evict(q, k, v, budget, cfg.pool)
+    for g in range(cfg.Hkv):
+        want = sorted(j for p in meta["planted"][g].tolist() for j in range(p - 3, p + 4))
+        assert len(want) == budget - cfg.W
+        assert idx[g, :budget - cfg.W].tolist() == want
+        assert idx[g, budget - cfg.W:].tolist() == list(range(cfg.P, cfg.L))
+    assert torch.equal(kc, torch.stack([k[g, idx[g].long()] for g in range(cfg.Hkv)]))
+    assert torch.equal(vc, torch.stack([v[g, idx[g].long()] for g in range(cfg.Hkv)]))
+
+
+def test_config1_as_specified_selects_strong_planted_keys():
+    cfg = CONFIGS[1]
+    q, k, v, meta = make_instance(cfg)
+    pooled, idx, _, _ = oracle.evict(q, k, v, 64, 7)
+    raw = oracle.raw_scores(q, k)
+    for g in range(cfg.Hkv):
+        sel = set(idx[g].tolist())
+        # every selected prefix index lies in the pooling neighbourhood of a raw-score peak that
+        # ranks among the selected, and the strongest planted key is retained
+        pl = meta["planted"][g]
+        best = pl[raw[g, pl].argmax()].item()
+        assert best in sel
+        assert len(sel) == 64 and all(j in sel for j in range(cfg.P, cfg.L))
+
+
+def test_invariants_on_bf16_config_shape():
+    import dataclasses
+    cfg = dataclasses.replace(CONFIGS[2], L=700, Hq=8, Hkv=2)
+    q, k, v, meta = make_instance(cfg)
+    pooled, idx, kc, vc = oracle.evict(q, k, v, 128, 7)
+    raw = oracle.raw_scores(q, k)
+    np.testing.assert_allclose(raw.sum(dim=1).numpy(), cfg.G * cfg.W, rtol=1e-12)
+    assert idx.shape == (2, 128)
+    assert (idx[:, 1:] > idx[:, :-1]).all()
+    assert (idx[:, -cfg.W:] == torch.arange(cfg.P, cfg.L, dtype=torch.int32)).all()
+    assert (pooled[:, :cfg.P] >= raw[:, :cfg.P]).all()
+
+
+def test_pyramid_budget_schedule_endpoints_and_monotone():
+    b = [pyramid_budget(l, 32, 2048, 128) for l in range(32)]
+    assert b[0] == 2048 and b[-1] == 128
+    assert all(x > y for x, y in zip(b, b[1:]))
+    assert budgets_for(CONFIGS[4]) == b
+    assert budgets_for(CONFIGS[5]) == [256] * 256
