@@ -1,0 +1,126 @@
+/*
+ * laq.h -- C ABI of the LAQ re-eviction hot path for AMD MI355X (gfx950).
+ *
+ * The library implements the second-round eviction of Lookahead Q-Cache
+ * (paper Sec. 4.3 "KV-Cache Re-eviction", Eq. 4): the cached lookahead queries
+ * (the Q-cache of Sec. 4.2) act as the observation window; their attention to
+ * every cached key is summed, the ranking is cut at the budget B, and the
+ * surviving key/value rows form the cache that decoding continues on.
+ *
+ * Terms used below
+ *   instance   one (sequence, layer) pair; all instances of a call share a shape
+ *   Hq, Hkv    query heads / KV heads, G = Hq / Hkv consecutive query heads per KV head
+ *   L          rows of K (and V) per KV head handed in; the last W rows are the
+ *              window tokens themselves, P = L - W is the prefix that is ranked
+ *   W          cached window queries per query head; query w stands at position
+ *              P + w and sees keys j <= P + w
+ *   Bk         min(budget, L): rows kept per KV head, window included
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; tensors are dense,
+ *     row-major, innermost dimension contiguous.  `budget` is a HOST array.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work on it and return; the caller synchronises.
+ *   - The library allocates and frees no device memory and keeps no state between
+ *     calls; scratch memory comes in through `ws` (size from laq_workspace_bytes).
+ *   - Errors are reported by the return value (LAQ_OK = 0, negative otherwise), never
+ *     by exception or abort.  Arguments are validated before anything is enqueued, so
+ *     a call that returns LAQ_ERR_INVALID / _UNSUPPORTED / _WORKSPACE has done nothing.
+ *     LAQ_ERR_DEVICE reports a failed launch (hipGetLastError).
+ *   - Results are a pure function of the inputs (no floating-point atomics; two runs
+ *     give identical bits).
+ */
+#ifndef LAQ_H
+#define LAQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LAQ_F32 = 0, LAQ_BF16 = 1 } laq_dtype;
+
+enum {
+  LAQ_OK = 0,
+  LAQ_ERR_INVALID = -1,     /* null pointer, bad shape, budget < W, even pool kernel ... */
+  LAQ_ERR_UNSUPPORTED = -2, /* valid request outside what the kernels cover (see each call) */
+  LAQ_ERR_WORKSPACE = -3,   /* ws is NULL or smaller than laq_workspace_bytes() */
+  LAQ_ERR_DEVICE = -4       /* a HIP launch failed */
+};
+
+/* Shape shared by all instances of one call. */
+typedef struct laq_shape {
+  int32_t n_inst;  /* >= 1: sequences x layers */
+  int32_t Hq;      /* query heads, multiple of Hkv */
+  int32_t Hkv;     /* KV heads */
+  int32_t d;       /* head size, multiple of 8, <= 256 */
+  int32_t L;       /* key rows per KV head (prefix + window) */
+  int32_t W;       /* window queries per query head, 1 <= W <= L */
+  int32_t dtype;   /* laq_dtype of q_win, k, v, k_out, v_out */
+  float scale;     /* logit scale; <= 0 selects 1/sqrt(d) */
+} laq_shape;
+
+/* Bytes of device scratch that laq_score / laq_evict need for this shape (0 on a bad shape). */
+size_t laq_workspace_bytes(const laq_shape *shape);
+
+/*
+ * Importance scores (Eq. 4's sum over the Q-cache, taken on attention scores).
+ *   q_win  [n_inst, Hq, W, d]   window (lookahead) queries
+ *   k      [n_inst, Hkv, L, d]  key cache; read exactly once from HBM
+ *   scores [n_inst, Hkv, L]     fp32 out.  For each KV head g and key j:
+ *            raw[g,j] = sum over the G heads of the group and the W queries of
+ *                       softmax_j(scale * <q, k_j>) restricted to j <= P + w.
+ *          With pool_kernel == 1 scores = raw.  With an odd pool_kernel p > 1 the prefix
+ *          columns hold max(raw[g,i] : |i-j| <= (p-1)/2, 0 <= i < P) (the sequence pooling
+ *          of the observation-window procedure, Sec. 2.1 / 5.1) and the W window columns
+ *          keep raw.  Max is exact, so pooling here and pooling in laq_select give the
+ *          same bits.
+ *   ws / ws_bytes  device scratch of at least laq_workspace_bytes(shape)
+ * Supported: dtype BF16 or F32; any Hq/Hkv/W/L within the limits of laq_shape;
+ * pool_kernel odd, 1 <= pool_kernel <= 63.
+ */
+int laq_score(const laq_shape *shape, const void *q_win, const void *k, int pool_kernel,
+              float *scores, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Per-KV-head selection ("ArgSort(...)[:B]" of Eq. 4) under a per-instance budget.
+ *   scores [n_inst, Hkv, L] fp32, non-negative (as laq_score writes them)
+ *   budget [n_inst] HOST array, budget[i] >= W.  Bk(i) = min(budget[i], L).
+ *   pool_kernel  odd >= 1; p > 1 applies the max-pool described above to the prefix
+ *                columns before ranking (use 1 if laq_score already pooled)
+ *   idx    int32 out, packed: instance i starts at element sum_{i'<i} Hkv * Bk(i') and
+ *          holds [Hkv, Bk(i)].  Each row: the Bk - W prefix positions with the largest
+ *          pooled score (ties to the lower position), ascending, then P .. L-1.
+ * budget[i] >= L keeps every row.  Uses no workspace.
+ */
+int laq_select(const laq_shape *shape, const float *scores, const int32_t *budget,
+               int pool_kernel, int32_t *idx, void *stream);
+
+/*
+ * Cache compaction: gather the retained rows.
+ *   k, v         [n_inst, Hkv, L, d]; v (and v_out) may be NULL to compact K only
+ *   idx, budget  as written by / passed to laq_select
+ *   k_out, v_out packed like idx: instance i starts at row sum_{i'<i} Hkv * Bk(i') and
+ *                holds [Hkv, Bk(i), d]; bit copies of the selected rows
+ * Indices must lie in [0, L); out-of-range entries are skipped (row left untouched).
+ */
+int laq_compact(const laq_shape *shape, const void *k, const void *v, const int32_t *idx,
+                const int32_t *budget, void *k_out, void *v_out, void *stream);
+
+/*
+ * laq_score (pooling fused) + laq_select + laq_compact on one stream; identical outputs.
+ * `scores` is required (it is the hand-over buffer between the stages).
+ */
+int laq_evict(const laq_shape *shape, const void *q_win, const void *k, const void *v,
+              const int32_t *budget, int pool_kernel, float *scores, int32_t *idx,
+              void *k_out, void *v_out, void *ws, size_t ws_bytes, void *stream);
+
+/* Static description of an error code. */
+const char *laq_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAQ_H */

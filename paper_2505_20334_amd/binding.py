@@ -1,0 +1,218 @@
+"""ctypes binding of ``liblaq.so`` -- argument marshalling only.
+
+Function names and argument meaning follow ``include/laq.h``.  Tensors are torch
+tensors that already live on the GPU (torch supplies device memory and the
+stream, nothing else); every step of the path runs in the library's kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "liblaq.so")
+_lib: Optional[ctypes.CDLL] = None
+
+LAQ_F32, LAQ_BF16 = 0, 1
+
+
+class LaqError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__("%s failed: %s (code %d)" % (what, laq_strerror(code), code))
+        self.code = code
+
+
+class _Shape(ctypes.Structure):
+    _fields_ = [("n_inst", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("L", ctypes.c_int32), ("W", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("liblaq.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(or paper_2505_20334_amd/_build.py) first")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    sp = ctypes.POINTER(_Shape)
+    lib.laq_workspace_bytes.argtypes = [sp]
+    lib.laq_workspace_bytes.restype = sz
+    lib.laq_score.argtypes = [sp, vp, vp, i32, vp, vp, sz, vp]
+    lib.laq_score.restype = i32
+    lib.laq_select.argtypes = [sp, vp, ctypes.POINTER(ctypes.c_int32), i32, vp, vp]
+    lib.laq_select.restype = i32
+    lib.laq_compact.argtypes = [sp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp, vp, vp]
+    lib.laq_compact.restype = i32
+    lib.laq_evict.argtypes = [sp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.laq_evict.restype = i32
+    lib.laq_strerror.argtypes = [i32]
+    lib.laq_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def laq_strerror(code: int) -> str:
+    return load_library().laq_strerror(int(code)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return LAQ_F32
+    if t.dtype == torch.bfloat16:
+        return LAQ_BF16
+    raise TypeError("LAQ takes fp32 or bf16 tensors, got %s" % t.dtype)
+
+
+def _dev(t: torch.Tensor, name: str) -> torch.Tensor:
+    if t.device.type != "cuda":
+        raise ValueError("%s must live on the GPU" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be dense (contiguous)" % name)
+    return t
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _shape(n: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: int, scale: float) -> _Shape:
+    return _Shape(n, Hq, Hkv, d, L, W, dtype, float(scale))
+
+
+def _budget_array(budget: Sequence[int], n: int):
+    if len(budget) != n:
+        raise ValueError("budget needs one entry per instance")
+    return (ctypes.c_int32 * n)(*[int(b) for b in budget])
+
+
+def packed_rows(budget: Sequence[int], Hkv: int, L: int) -> Tuple[int, List[int]]:
+    """Total packed rows of idx / k_out / v_out and the first row of each instance."""
+    starts, row = [], 0
+    for b in budget:
+        starts.append(row)
+        row += Hkv * min(int(b), L)
+    return row, starts
+
+
+def laq_workspace_bytes(n_inst: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: torch.dtype) -> int:
+    code = LAQ_F32 if dtype == torch.float32 else LAQ_BF16
+    sh = _shape(n_inst, Hq, Hkv, d, L, W, code, 0.0)
+    return int(load_library().laq_workspace_bytes(ctypes.byref(sh)))
+
+
+def _workspace(q_win, k, ws):
+    n, Hq, W, d = q_win.shape
+    _, Hkv, L, _ = k.shape
+    need = laq_workspace_bytes(n, Hq, Hkv, d, L, W, k.dtype)
+    if ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=k.device)
+    return ws, ws.numel() * ws.element_size()
+
+
+def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale: float = 0.0,
+              scores: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+              stream=None) -> torch.Tensor:
+    """q_win [n, Hq, W, d], k [n, Hkv, L, d] -> scores [n, Hkv, L] fp32 (pooled if pool_kernel > 1)."""
+    lib = load_library()
+    _dev(q_win, "q_win"), _dev(k, "k")
+    n, Hq, W, d = q_win.shape
+    n2, Hkv, L, d2 = k.shape
+    if n != n2 or d != d2 or q_win.dtype != k.dtype:
+        raise ValueError("q_win / k mismatch")
+    if scores is None:
+        scores = torch.empty(n, Hkv, L, dtype=torch.float32, device=k.device)
+    ws, ws_bytes = _workspace(q_win, k, ws)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale)
+    rc = lib.laq_score(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), int(pool_kernel), scores.data_ptr(),
+                       ws.data_ptr(), ws_bytes, _stream(stream))
+    if rc != 0:
+        raise LaqError(rc, "laq_score")
+    return scores
+
+
+def laq_select(scores: torch.Tensor, budget: Sequence[int], pool_kernel: int, W: int,
+               idx: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """scores [n, Hkv, L] fp32 -> packed idx (int32, see packed_rows)."""
+    lib = load_library()
+    _dev(scores, "scores")
+    if scores.dtype != torch.float32:
+        raise TypeError("scores must be fp32")
+    n, Hkv, L = scores.shape
+    total, _ = packed_rows(budget, Hkv, L)
+    if idx is None:
+        idx = torch.empty(total, dtype=torch.int32, device=scores.device)
+    sh = _shape(n, Hkv, Hkv, 8, L, W, LAQ_F32, 0.0)
+    rc = lib.laq_select(ctypes.byref(sh), scores.data_ptr(), _budget_array(budget, n), int(pool_kernel),
+                        idx.data_ptr(), _stream(stream))
+    if rc != 0:
+        raise LaqError(rc, "laq_select")
+    return idx
+
+
+def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, budget: Sequence[int], W: int,
+                k_out: Optional[torch.Tensor] = None, v_out: Optional[torch.Tensor] = None, stream=None):
+    """k, v [n, Hkv, L, d] + packed idx -> packed k_out, v_out [rows, d]."""
+    lib = load_library()
+    _dev(k, "k"), _dev(idx, "idx")
+    n, Hkv, L, d = k.shape
+    total, _ = packed_rows(budget, Hkv, L)
+    if k_out is None:
+        k_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
+    if v is not None:
+        _dev(v, "v")
+        if v.shape != k.shape or v.dtype != k.dtype:
+            raise ValueError("k / v mismatch")
+        if v_out is None:
+            v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
+    sh = _shape(n, Hkv, Hkv, d, L, W, _dtype_code(k), 0.0)
+    rc = lib.laq_compact(ctypes.byref(sh), k.data_ptr(), v.data_ptr() if v is not None else None,
+                         idx.data_ptr(), _budget_array(budget, n), k_out.data_ptr(),
+                         v_out.data_ptr() if v is not None else None, _stream(stream))
+    if rc != 0:
+        raise LaqError(rc, "laq_compact")
+    return k_out, v_out
+
+
+def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], budget: Sequence[int],
+              pool_kernel: int, scale: float = 0.0, scores=None, idx=None, k_out=None, v_out=None, ws=None,
+              stream=None):
+    """Whole path on one stream: returns (scores, idx, k_out, v_out); layouts as in the three calls."""
+    lib = load_library()
+    _dev(q_win, "q_win"), _dev(k, "k")
+    n, Hq, W, d = q_win.shape
+    n2, Hkv, L, d2 = k.shape
+    if n != n2 or d != d2 or q_win.dtype != k.dtype:
+        raise ValueError("q_win / k mismatch")
+    total, _ = packed_rows(budget, Hkv, L)
+    if scores is None:
+        scores = torch.empty(n, Hkv, L, dtype=torch.float32, device=k.device)
+    if idx is None:
+        idx = torch.empty(total, dtype=torch.int32, device=k.device)
+    if k_out is None:
+        k_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
+    if v is not None:
+        _dev(v, "v")
+        if v_out is None:
+            v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
+    ws, ws_bytes = _workspace(q_win, k, ws)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale)
+    rc = lib.laq_evict(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), v.data_ptr() if v is not None else None,
+                       _budget_array(budget, n), int(pool_kernel), scores.data_ptr(), idx.data_ptr(),
+                       k_out.data_ptr(), v_out.data_ptr() if v is not None else None, ws.data_ptr(), ws_bytes,
+                       _stream(stream))
+    if rc != 0:
+        raise LaqError(rc, "laq_evict")
+    return scores, idx, k_out, v_out

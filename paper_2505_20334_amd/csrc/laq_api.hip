@@ -1,0 +1,171 @@
+// C ABI of the LAQ re-eviction library (declared in include/laq.h): argument checks,
+// geometry, kernel dispatch.  No device memory is allocated here.
+#include <math.h>
+#include <string.h>
+
+#include "laq_internal.h"
+
+namespace laq {
+
+static bool make_geom(const laq_shape* s, int pool, ScoreGeom* g) {
+  if (!s) return false;
+  if (s->n_inst < 1 || s->Hq < 1 || s->Hkv < 1 || s->d < 8 || s->d > 256 || (s->d % 8) != 0) return false;
+  if (s->L < 1 || s->W < 1 || s->W > s->L || (s->Hq % s->Hkv) != 0) return false;
+  if (s->dtype != LAQ_F32 && s->dtype != LAQ_BF16) return false;
+  if (pool < 1 || pool > MAX_POOL || (pool % 2) == 0) return false;
+  if (!(s->scale == s->scale) || isinf(s->scale)) return false;
+  g->n_inst = s->n_inst; g->Hq = s->Hq; g->Hkv = s->Hkv; g->d = s->d; g->L = s->L; g->W = s->W;
+  g->G = s->Hq / s->Hkv;
+  g->R = g->G * s->W;
+  g->P = s->L - s->W;
+  g->Rpad = (g->R + 31) / 32 * 32;
+  g->pool = pool;
+  g->half = (pool - 1) / 2;
+  g->own = CHUNK_ROWS - 2 * g->half;
+  g->nchunk = (s->L + g->own - 1) / g->own;
+  const float sc = s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d);
+  g->scale2 = sc * 1.44269504088896340736f;
+  return true;
+}
+
+size_t workspace_bytes(const ScoreGeom& g) {
+  const size_t heads = (size_t)g.n_inst * g.Hkv;
+  size_t part = heads * g.nchunk * g.Rpad * sizeof(float2);
+  size_t rowc = heads * g.Rpad * sizeof(float);
+  return ((part + 255) & ~(size_t)255) + ((rowc + 255) & ~(size_t)255);
+}
+
+Workspace carve_workspace(const ScoreGeom& g, void* ws) {
+  const size_t heads = (size_t)g.n_inst * g.Hkv;
+  size_t part = heads * g.nchunk * g.Rpad * sizeof(float2);
+  Workspace w;
+  w.part = static_cast<float2*>(ws);
+  w.rowc = reinterpret_cast<float*>(static_cast<char*>(ws) + ((part + 255) & ~(size_t)255));
+  return w;
+}
+
+// Fill the per-instance table for instances [i0, i0+n) and return the largest Bk among them.
+static int fill_table(const laq_shape* s, const int32_t* budget, int i0, int n, int64_t row_base,
+                      InstTable* tab, int64_t* rows_after) {
+  int bk_max = 0;
+  int64_t row = row_base;
+  for (int i = 0; i < n; ++i) {
+    const int bk = budget[i0 + i] < s->L ? budget[i0 + i] : s->L;
+    tab->bk[i] = bk;
+    tab->row0[i] = row;
+    row += (int64_t)s->Hkv * bk;
+    if (bk > bk_max) bk_max = bk;
+  }
+  *rows_after = row;
+  return bk_max;
+}
+
+static bool budgets_ok(const laq_shape* s, const int32_t* budget) {
+  if (!budget) return false;
+  for (int i = 0; i < s->n_inst; ++i)
+    if (budget[i] < s->W) return false;
+  return true;
+}
+
+static int score_impl(const laq_shape* shape, const void* q_win, const void* k, int pool, float* scores,
+                      void* ws, size_t ws_bytes, hipStream_t st) {
+  ScoreGeom g;
+  if (!make_geom(shape, pool, &g) || !q_win || !k || !scores) return LAQ_ERR_INVALID;
+  if (!ws || ws_bytes < workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
+  if (g.Hkv > 65535 || g.n_inst > 65535) return LAQ_ERR_UNSUPPORTED;   // grid y / z limits
+  const Workspace w = carve_workspace(g, ws);
+  hipError_t e = score_mfma_supported(g, shape->dtype)
+                     ? launch_score_mfma(g, q_win, k, scores, w, st)
+                     : launch_score_generic(g, shape->dtype, q_win, k, scores, w, st);
+  return e == hipSuccess ? LAQ_OK : LAQ_ERR_DEVICE;
+}
+
+static int select_impl(const laq_shape* shape, const float* scores, const int32_t* budget, int pool,
+                       int32_t* idx, hipStream_t st) {
+  ScoreGeom g;
+  if (!make_geom(shape, pool, &g) || !scores || !idx || !budgets_ok(shape, budget)) return LAQ_ERR_INVALID;
+  if (g.Hkv > 65535) return LAQ_ERR_UNSUPPORTED;
+  int64_t row = 0;
+  for (int i0 = 0; i0 < shape->n_inst; i0 += MAX_INST_PER_LAUNCH) {
+    const int n = shape->n_inst - i0 < MAX_INST_PER_LAUNCH ? shape->n_inst - i0 : MAX_INST_PER_LAUNCH;
+    InstTable tab;
+    memset(&tab, 0, sizeof tab);
+    fill_table(shape, budget, i0, n, row, &tab, &row);
+    if (launch_select(n, i0, g.Hkv, g.L, g.W, pool, scores, tab, idx, st) != hipSuccess) return LAQ_ERR_DEVICE;
+  }
+  return LAQ_OK;
+}
+
+static int compact_impl(const laq_shape* shape, const void* k, const void* v, const int32_t* idx,
+                        const int32_t* budget, void* k_out, void* v_out, hipStream_t st) {
+  ScoreGeom g;
+  if (!make_geom(shape, 1, &g) || !k || !k_out || !idx || !budgets_ok(shape, budget)) return LAQ_ERR_INVALID;
+  if ((v == nullptr) != (v_out == nullptr)) return LAQ_ERR_INVALID;
+  const int row_bytes = g.d * (shape->dtype == LAQ_F32 ? 4 : 2);
+  int64_t row = 0;
+  for (int i0 = 0; i0 < shape->n_inst; i0 += MAX_INST_PER_LAUNCH) {
+    const int n = shape->n_inst - i0 < MAX_INST_PER_LAUNCH ? shape->n_inst - i0 : MAX_INST_PER_LAUNCH;
+    InstTable tab;
+    memset(&tab, 0, sizeof tab);
+    const int bk_max = fill_table(shape, budget, i0, n, row, &tab, &row);
+    if (launch_compact(n, i0, g.Hkv, g.L, row_bytes, bk_max, k, v, idx, tab, k_out, v_out, st) != hipSuccess)
+      return LAQ_ERR_DEVICE;
+  }
+  return LAQ_OK;
+}
+
+}  // namespace laq
+
+extern "C" {
+
+size_t laq_workspace_bytes(const laq_shape* shape) {
+  laq::ScoreGeom g;
+  // the largest pooling kernel gives the most chunks, so this bound serves every pool_kernel
+  if (!laq::make_geom(shape, laq::MAX_POOL, &g)) return 0;
+  return laq::workspace_bytes(g);
+}
+
+int laq_score(const laq_shape* shape, const void* q_win, const void* k, int pool_kernel, float* scores,
+              void* ws, size_t ws_bytes, void* stream) {
+  return laq::score_impl(shape, q_win, k, pool_kernel, scores, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int laq_select(const laq_shape* shape, const float* scores, const int32_t* budget, int pool_kernel,
+               int32_t* idx, void* stream) {
+  return laq::select_impl(shape, scores, budget, pool_kernel, idx, static_cast<hipStream_t>(stream));
+}
+
+int laq_compact(const laq_shape* shape, const void* k, const void* v, const int32_t* idx,
+                const int32_t* budget, void* k_out, void* v_out, void* stream) {
+  return laq::compact_impl(shape, k, v, idx, budget, k_out, v_out, static_cast<hipStream_t>(stream));
+}
+
+int laq_evict(const laq_shape* shape, const void* q_win, const void* k, const void* v, const int32_t* budget,
+              int pool_kernel, float* scores, int32_t* idx, void* k_out, void* v_out, void* ws,
+              size_t ws_bytes, void* stream) {
+  // validate everything first so that a rejected call has enqueued nothing
+  laq::ScoreGeom g;
+  if (!laq::make_geom(shape, pool_kernel, &g) || !q_win || !k || !scores || !idx || !k_out ||
+      !laq::budgets_ok(shape, budget) || ((v == nullptr) != (v_out == nullptr)))
+    return LAQ_ERR_INVALID;
+  if (!ws || ws_bytes < laq::workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = laq::score_impl(shape, q_win, k, pool_kernel, scores, ws, ws_bytes, st);
+  if (rc != LAQ_OK) return rc;
+  rc = laq::select_impl(shape, scores, budget, 1, idx, st);
+  if (rc != LAQ_OK) return rc;
+  return laq::compact_impl(shape, k, v, idx, budget, k_out, v_out, st);
+}
+
+const char* laq_strerror(int code) {
+  switch (code) {
+    case LAQ_OK: return "ok";
+    case LAQ_ERR_INVALID: return "invalid argument";
+    case LAQ_ERR_UNSUPPORTED: return "unsupported shape";
+    case LAQ_ERR_WORKSPACE: return "workspace missing or too small";
+    case LAQ_ERR_DEVICE: return "HIP launch failed";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,66 @@
+// Internal declarations shared by the HIP translation units of the LAQ library.
+// Not part of the public boundary (that is include/laq.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "laq.h"
+
+namespace laq {
+
+// ---------------------------------------------------------------------------
+// Chunk geometry of the scoring kernels.
+//
+// Each workgroup stages CHUNK_ROWS consecutive key rows in LDS.  With a pooling
+// kernel p the first and last (p-1)/2 staged rows are a halo: the group computes
+// their raw score (so that the pooled value of every owned key is local) but the
+// softmax statistics count only the owned rows, so every key is counted once.
+// ---------------------------------------------------------------------------
+constexpr int CHUNK_ROWS = 256;
+constexpr int MAX_POOL = 63;
+constexpr int MAX_INST_PER_LAUNCH = 256;   // size of the per-instance tables passed as kernel arguments
+
+struct ScoreGeom {
+  int n_inst, Hq, Hkv, d, L, W;
+  int G, R, P;
+  int Rpad;      // R rounded up to a multiple of 32
+  int half;      // (pool - 1) / 2
+  int own;       // keys owned per chunk = CHUNK_ROWS - 2 * half
+  int nchunk;    // ceil(L / own)
+  int pool;
+  float scale2;  // scale * log2(e): logits are kept in base-2 units
+};
+
+// Workspace carving: [partials | row constants]
+//   partials: float2 (m, z) per (instance, KV head, chunk, padded row)
+//   rowc:     float c = m + log2(z) per (instance, KV head, padded row)
+struct Workspace {
+  float2* part;
+  float* rowc;
+};
+
+size_t workspace_bytes(const ScoreGeom& g);
+Workspace carve_workspace(const ScoreGeom& g, void* ws);
+
+// Per-instance output table for select / compact (passed by value as a kernel argument).
+struct InstTable {
+  int32_t bk[MAX_INST_PER_LAUNCH];      // rows kept per KV head
+  int64_t row0[MAX_INST_PER_LAUNCH];    // first packed output row (units of rows of idx, i.e. Hkv*Bk sums)
+};
+
+// launchers (each returns hipGetLastError() after the launch)
+hipError_t launch_score_generic(const ScoreGeom& g, int dtype, const void* q, const void* k,
+                                float* scores, const Workspace& ws, hipStream_t st);
+hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStream_t st);
+bool score_mfma_supported(const ScoreGeom& g, int dtype);
+hipError_t launch_score_mfma(const ScoreGeom& g, const void* q, const void* k, float* scores,
+                             const Workspace& ws, hipStream_t st);
+hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int W, int pool,
+                         const float* scores, const InstTable& tab, int32_t* idx, hipStream_t st);
+hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, int bk_max,
+                          const void* k, const void* v, const int32_t* idx, const InstTable& tab,
+                          void* k_out, void* v_out, hipStream_t st);
+
+}  // namespace laq

@@ -1,0 +1,160 @@
+// Generic scoring path (plain fp32 FMA): any head size, any number of score rows,
+// fp32 or bf16 storage.  Used for fp32 inputs and for shapes the MFMA path does not
+// take (fewer than 16 score rows per KV head, unusual head sizes).
+//
+// Computes, per KV head, the window attention of Eq. 4's observation window in two
+// passes over the staged key chunk: (1) per-row softmax statistics of the chunk,
+// (2) after the statistics of all chunks are combined, the normalised sum over rows
+// and the sequence max-pool.  The combine step (row_constants_kernel) is shared with
+// the MFMA path.
+#include "laq_internal.h"
+
+namespace laq {
+
+namespace {
+
+constexpr float NEG_BIG = -1.0e30f;   // finite "minus infinity" for running maxima
+
+__device__ __forceinline__ float ld_elem(const float* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float ld_elem(const uint16_t* p, size_t i) {
+  return __uint_as_float((uint32_t)p[i] << 16);   // bf16 -> fp32 is exact
+}
+
+template <typename T>
+__device__ __forceinline__ float dot_row(const T* __restrict__ qrow, const T* __restrict__ krow, int d) {
+  float acc = 0.f;
+  for (int c = 0; c < d; ++c) acc = fmaf(ld_elem(qrow, c), ld_elem(krow, c), acc);
+  return acc;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// One workgroup per (chunk, KV head, instance); thread t owns staged row t.
+template <typename T>
+__global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, const T* __restrict__ q,
+                                                                   const T* __restrict__ k,
+                                                                   float2* __restrict__ part) {
+  __shared__ float red[4];
+  const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int j = chunk * g.own - g.half + t;
+  const bool owned = (t >= g.half) && (t < CHUNK_ROWS - g.half) && (j >= 0) && (j < g.L);
+  const T* krow = k + (((size_t)inst * g.Hkv + head) * g.L + (owned ? j : 0)) * g.d;
+  const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d;
+  float2* out = part + (((size_t)inst * g.Hkv + head) * g.nchunk + chunk) * g.Rpad;
+
+  for (int r = 0; r < g.R; ++r) {
+    const int w = r % g.W;
+    const bool vis = owned && (j <= g.P + w);
+    float s = vis ? g.scale2 * dot_row(qg + (size_t)r * g.d, krow, g.d) : NEG_BIG;
+    float m = wave_max(s);
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float e = vis ? exp2f(s - m) : 0.f;
+    e = wave_sum(e);
+    if (lane == 0) red[wave] = e;
+    __syncthreads();
+    if (t == 0) out[r] = make_float2(m, (red[0] + red[1]) + (red[2] + red[3]));
+    __syncthreads();
+  }
+}
+
+// Thread t of the group computes the raw score of staged row t, then the group pools.
+template <typename T>
+__global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, const T* __restrict__ q,
+                                                                  const T* __restrict__ k,
+                                                                  const float* __restrict__ rowc,
+                                                                  float* __restrict__ scores) {
+  __shared__ float raw[CHUNK_ROWS];
+  const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
+  const int t = threadIdx.x;
+  const int j0 = chunk * g.own - g.half;
+  const int j = j0 + t;
+  const bool in_range = (j >= 0) && (j < g.L);
+  const T* krow = k + (((size_t)inst * g.Hkv + head) * g.L + (in_range ? j : 0)) * g.d;
+  const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d;
+  const float* c = rowc + ((size_t)inst * g.Hkv + head) * g.Rpad;
+
+  float acc = 0.f;
+  if (in_range) {
+    for (int r = 0; r < g.R; ++r) {
+      const int w = r % g.W;
+      if (j <= g.P + w) acc += exp2f(g.scale2 * dot_row(qg + (size_t)r * g.d, krow, g.d) - c[r]);
+    }
+  }
+  raw[t] = acc;
+  __syncthreads();
+
+  if (t >= g.half && t < CHUNK_ROWS - g.half && in_range) {
+    float v = acc;
+    if (j < g.P) {
+      int lo = max(j - g.half, 0) - j0, hi = min(j + g.half, g.P - 1) - j0;
+      v = raw[lo];
+      for (int i = lo + 1; i <= hi; ++i) v = fmaxf(v, raw[i]);
+    }
+    scores[((size_t)inst * g.Hkv + head) * g.L + j] = v;
+  }
+}
+
+}  // namespace
+
+// Combine the per-chunk (m, z) of every score row into c = M + log2(Z), so that the
+// attention probability of a logit s (base-2 units) is exp2(s - c).  Rows beyond R
+// (padding up to a multiple of 32) get a huge c, i.e. probability 0.
+__global__ void row_constants_kernel(ScoreGeom g, const float2* __restrict__ part, float* __restrict__ rowc) {
+  const int head = blockIdx.x, inst = blockIdx.y;
+  const float2* p = part + ((size_t)inst * g.Hkv + head) * g.nchunk * g.Rpad;
+  float* c = rowc + ((size_t)inst * g.Hkv + head) * g.Rpad;
+  for (int r = threadIdx.x; r < g.Rpad; r += blockDim.x) {
+    if (r >= g.R) { c[r] = 1.0e30f; continue; }
+    float M = NEG_BIG;
+    for (int ch = 0; ch < g.nchunk; ++ch) M = fmaxf(M, p[(size_t)ch * g.Rpad + r].x);
+    float Z = 0.f;
+    for (int ch = 0; ch < g.nchunk; ++ch) {
+      float2 mz = p[(size_t)ch * g.Rpad + r];
+      Z += mz.y * exp2f(mz.x - M);
+    }
+    c[r] = M + log2f(Z);
+  }
+}
+
+hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStream_t st) {
+  dim3 grid(g.Hkv, g.n_inst);
+  hipLaunchKernelGGL(row_constants_kernel, grid, dim3(128), 0, st, g, ws.part, ws.rowc);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_generic(const ScoreGeom& g, int dtype, const void* q, const void* k, float* scores,
+                                const Workspace& ws, hipStream_t st) {
+  dim3 grid(g.nchunk, g.Hkv, g.n_inst), block(CHUNK_ROWS);
+  if (dtype == LAQ_F32) {
+    hipLaunchKernelGGL(stats_generic_kernel<float>, grid, block, 0, st, g, (const float*)q, (const float*)k,
+                       ws.part);
+  } else {
+    hipLaunchKernelGGL(stats_generic_kernel<uint16_t>, grid, block, 0, st, g, (const uint16_t*)q,
+                       (const uint16_t*)k, ws.part);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  e = launch_row_constants(g, ws, st);
+  if (e != hipSuccess) return e;
+  if (dtype == LAQ_F32) {
+    hipLaunchKernelGGL(norm_generic_kernel<float>, grid, block, 0, st, g, (const float*)q, (const float*)k,
+                       ws.rowc, scores);
+  } else {
+    hipLaunchKernelGGL(norm_generic_kernel<uint16_t>, grid, block, 0, st, g, (const uint16_t*)q,
+                       (const uint16_t*)k, ws.rowc, scores);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace laq

@@ -1,0 +1,91 @@
+"""CPU-only checks of the boundary: the library loads, exports what include/laq.h declares, and
+rejects bad arguments synchronously (these calls return before anything touches a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+import paper_2505_20334_amd as laq
+from paper_2505_20334_amd import binding
+
+
+def declared_functions(repo_root):
+    text = open(os.path.join(repo_root, "include", "laq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(laq_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(repo_root):
+    lib = laq.load_library()
+    names = declared_functions(repo_root)
+    assert names == ["laq_compact", "laq_evict", "laq_score", "laq_select", "laq_strerror",
+                     "laq_workspace_bytes"]
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_library_is_in_tree():
+    assert os.path.dirname(laq.lib_path()) == os.path.dirname(os.path.abspath(laq.__file__))
+
+
+def test_strerror():
+    assert laq.laq_strerror(0) == "ok"
+    assert "invalid" in laq.laq_strerror(-1)
+    assert "workspace" in laq.laq_strerror(-3)
+    assert "unknown" in laq.laq_strerror(-99)
+
+
+def test_workspace_bytes_grows_with_shape():
+    a = laq.laq_workspace_bytes(1, 32, 8, 128, 4096, 8, torch.bfloat16)
+    b = laq.laq_workspace_bytes(2, 32, 8, 128, 4096, 8, torch.bfloat16)
+    c = laq.laq_workspace_bytes(1, 32, 8, 128, 8192, 8, torch.bfloat16)
+    assert 0 < a < b and a < c
+    assert laq.laq_workspace_bytes(1, 32, 7, 128, 4096, 8, torch.bfloat16) == 0      # Hq % Hkv != 0
+    assert laq.laq_workspace_bytes(1, 32, 8, 128, 4, 8, torch.bfloat16) == 0          # W > L
+
+
+def _shape(**kw):
+    base = dict(n_inst=1, Hq=8, Hkv=2, d=128, L=512, W=8, dtype=1, scale=0.0)
+    base.update(kw)
+    return binding._Shape(*[base[f] for f, _ in binding._Shape._fields_])
+
+
+def test_bad_arguments_are_rejected_without_a_gpu():
+    lib = laq.load_library()
+    fake = ctypes.c_void_p(0x1000)        # never dereferenced: validation fails first
+    bud = (ctypes.c_int32 * 1)(64)
+    sh = _shape()
+    INVALID, WORKSPACE = -1, -3
+    assert lib.laq_score(ctypes.byref(sh), None, fake, 7, fake, fake, 1 << 30, None) == INVALID
+    assert lib.laq_score(ctypes.byref(sh), fake, fake, 4, fake, fake, 1 << 30, None) == INVALID     # even pool
+    assert lib.laq_score(ctypes.byref(sh), fake, fake, 65, fake, fake, 1 << 30, None) == INVALID    # pool too wide
+    assert lib.laq_score(ctypes.byref(sh), fake, fake, 7, fake, fake, 16, None) == WORKSPACE
+    assert lib.laq_score(ctypes.byref(sh), fake, fake, 7, fake, None, 1 << 30, None) == WORKSPACE
+    for bad in (_shape(W=0), _shape(W=600), _shape(Hq=7), _shape(d=12), _shape(d=512), _shape(dtype=5),
+                _shape(n_inst=0), _shape(scale=float("nan"))):
+        assert lib.laq_score(ctypes.byref(bad), fake, fake, 7, fake, fake, 1 << 30, None) == INVALID
+    small = (ctypes.c_int32 * 1)(7)       # budget < W
+    assert lib.laq_select(ctypes.byref(sh), fake, small, 7, fake, None) == INVALID
+    assert lib.laq_select(ctypes.byref(sh), fake, None, 7, fake, None) == INVALID
+    assert lib.laq_select(ctypes.byref(sh), fake, bud, 2, fake, None) == INVALID
+    assert lib.laq_compact(ctypes.byref(sh), fake, fake, fake, bud, fake, None, None) == INVALID   # v without v_out
+    assert lib.laq_compact(ctypes.byref(sh), fake, None, fake, small, fake, None, None) == INVALID
+    assert lib.laq_evict(ctypes.byref(sh), fake, fake, fake, small, 7, fake, fake, fake, fake, fake, 1 << 30,
+                         None) == INVALID
+    assert lib.laq_evict(ctypes.byref(sh), fake, fake, fake, bud, 7, fake, fake, fake, fake, fake, 8,
+                         None) == WORKSPACE
+
+
+def test_packed_rows():
+    total, starts = laq.packed_rows([2048, 128, 40000], 8, 32768)
+    assert starts == [0, 8 * 2048, 8 * (2048 + 128)]
+    assert total == 8 * (2048 + 128 + 32768)
+
+
+def test_binding_refuses_host_tensors():
+    q = torch.zeros(1, 8, 8, 128, dtype=torch.bfloat16)
+    k = torch.zeros(1, 2, 512, 128, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        laq.laq_score(q, k, 7)

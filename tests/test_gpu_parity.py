@@ -1,0 +1,247 @@
+"""HIP path vs CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from laq_inputs import CONFIGS, budgets_for, make_batch, make_instance
+from parity_util import RTOL, check_index_row, check_scores, split_packed
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def laq():
+    import paper_2505_20334_amd as m
+    m.load_library()
+    assert torch.cuda.is_available()
+    return m
+
+
+def run_and_check(laq, q, k, v, budgets, pool, what, heads=None, scale=0.0, exact_expected=None):
+    """q [n,Hq,W,d], k/v [n,Hkv,L,d] on the GPU.  Runs laq_evict and the three calls, compares with
+    the oracle instance by instance (optionally only some KV heads)."""
+    n, Hq, W, d = q.shape
+    _, Hkv, L, _ = k.shape
+    G = Hq // Hkv
+    print("case:", what, "n=%d Hq=%d Hkv=%d d=%d L=%d W=%d pool=%d" % (n, Hq, Hkv, d, L, W, pool), flush=True)
+    scores, idx, ko, vo = laq.laq_evict(q, k, v, budgets, pool, scale=scale)
+    torch.cuda.synchronize()
+    # the three-call sequence gives the same bits
+    s3 = laq.laq_score(q, k, pool, scale=scale)
+    i3 = laq.laq_select(s3, budgets, 1, W)
+    k3, v3 = laq.laq_compact(k, v, i3, budgets, W)
+    torch.cuda.synchronize()
+    assert torch.equal(s3, scores) and torch.equal(i3, idx) and torch.equal(k3, ko)
+    if v is not None:
+        assert torch.equal(v3, vo)
+    # pooling in select instead of in score: identical bits
+    s_raw = laq.laq_score(q, k, 1, scale=scale)
+    i_alt = laq.laq_select(s_raw, budgets, pool, W)
+    torch.cuda.synchronize()
+    assert torch.equal(i_alt, idx)
+
+    idx_l = split_packed(idx.cpu(), budgets, Hkv, L)
+    ko_l = split_packed(ko.cpu(), budgets, Hkv, L)
+    vo_l = split_packed(vo.cpu(), budgets, Hkv, L) if v is not None else None
+    qc, kc = q.cpu(), k.cpu()
+    vc = v.cpu() if v is not None else None
+    sc = scores.cpu()
+    heads = list(range(Hkv)) if heads is None else heads
+    n_exact = 0
+    for i in range(n):
+        # compaction: bit-exact given the library's own indices
+        for g in range(Hkv):
+            rows = idx_l[i][g].long()
+            assert torch.equal(ko_l[i][g].view(torch.int16 if k.dtype == torch.bfloat16 else torch.int32),
+                               kc[i, g, rows].view(torch.int16 if k.dtype == torch.bfloat16 else torch.int32))
+            if v is not None:
+                assert torch.equal(vo_l[i][g], vc[i, g, rows])
+        for g in heads:
+            raw = oracle.raw_scores(qc[i, g * G:(g + 1) * G], kc[i, g:g + 1], scale)
+            pooled = oracle.maxpool(raw, W, pool)
+            check_scores(sc[i, g], pooled[0], k.dtype, "%s inst %d head %d" % (what, i, g))
+            check_scores(s_raw[i, g].cpu(), raw[0], k.dtype, "%s raw inst %d head %d" % (what, i, g))
+            ex = check_index_row(idx_l[i][g].numpy(), pooled[0].float().numpy(), W, budgets[i],
+                                 RTOL[k.dtype], "%s inst %d head %d" % (what, i, g))
+            n_exact += int(ex)
+            # selection on identical fp32 scores is bit-exact
+            o_idx = oracle.select(sc[i, g:g + 1], W, budgets[i])
+            assert torch.equal(o_idx[0], idx_l[i][g]), "%s: select differs on identical scores" % what
+    if exact_expected is not None:
+        assert n_exact >= exact_expected
+    return scores, idx, ko, vo
+
+
+def test_config1_tiny_fp32(laq):
+    cfg = CONFIGS[1]
+    q, k, v, budgets, metas = make_batch(cfg, device=DEV)
+    run_and_check(laq, q, k, v, budgets, cfg.pool, "cfg1")
+
+
+def test_config1_planted_exact_set(laq):
+    cfg = dataclasses.replace(CONFIGS[1], planted_amp=40.0)
+    q, k, v, budgets, metas = make_batch(cfg, device=DEV)
+    scores, idx, _, _ = run_and_check(laq, q, k, v, budgets, cfg.pool, "cfg1-planted")
+    got = idx.cpu().reshape(cfg.Hkv, 64)
+    for g in range(cfg.Hkv):
+        want = sorted(j for p in metas[0]["planted"][g].tolist() for j in range(p - 3, p + 4))
+        assert got[g, :56].tolist() == want
+
+
+def test_config2_llama_4k(laq):
+    cfg = CONFIGS[2]
+    q, k, v, budgets, _ = make_batch(cfg, device=DEV)
+    run_and_check(laq, q, k, v, budgets, cfg.pool, "cfg2")
+
+
+def test_config3_two_layers_full_length(laq):
+    cfg = CONFIGS[3]
+    q, k, v, budgets, _ = make_batch(cfg, device=DEV, instances=[0, 31])
+    run_and_check(laq, q, k, v, budgets, cfg.pool, "cfg3", heads=[0, 5])
+
+
+def test_config4_sampled_full_size(laq):
+    # full 32-layer launch shape; the oracle checks sampled (instance, head) pairs
+    cfg = CONFIGS[4]
+    q, k, v, budgets, _ = make_batch(cfg, device=DEV)
+    n, Hkv, L, W, G = cfg.n_inst, cfg.Hkv, cfg.L, cfg.W, cfg.G
+    scores, idx, ko, vo = laq.laq_evict(q, k, v, budgets, cfg.pool)
+    torch.cuda.synchronize()
+    idx_l = split_packed(idx.cpu(), budgets, Hkv, L)
+    ko_l = split_packed(ko.cpu(), budgets, Hkv, L)
+    vo_l = split_packed(vo.cpu(), budgets, Hkv, L)
+    for (i, g) in [(0, 0), (13, 3), (31, 7)]:
+        print("cfg4 sample", i, g, flush=True)
+        qc, kc = q[i, g * G:(g + 1) * G].cpu(), k[i, g:g + 1].cpu()
+        pooled = oracle.maxpool(oracle.raw_scores(qc, kc), W, cfg.pool)
+        check_scores(scores[i, g].cpu(), pooled[0], k.dtype, "cfg4 inst %d head %d" % (i, g))
+        check_index_row(idx_l[i][g].numpy(), pooled[0].float().numpy(), W, budgets[i], 1e-3, "cfg4")
+        assert torch.equal(oracle.select(scores[i, g:g + 1].cpu(), W, budgets[i])[0], idx_l[i][g])
+        rows = idx_l[i][g].long()
+        assert torch.equal(ko_l[i][g], k[i, g].cpu()[rows]) and torch.equal(vo_l[i][g], v[i, g].cpu()[rows])
+    # properties that hold at any size, on every instance and head
+    sums = scores.double().sum(dim=2)      # not R exactly (pooled), but raw sums are:
+    raw = laq.laq_score(q, k, 1)
+    np.testing.assert_allclose(raw.double().sum(dim=2).cpu().numpy(), cfg.R, rtol=2e-4)
+    assert (scores >= raw).all() and (sums > 0).all()
+    for i in range(n):
+        assert (idx_l[i][:, 1:] > idx_l[i][:, :-1]).all()
+        assert (idx_l[i][:, -W:] == torch.arange(L - W, L, dtype=torch.int32)).all()
+
+
+def test_config5_sampled(laq):
+    # 4 of the 256 instances at full length (heavy-tailed query norms), sampled heads
+    cfg = CONFIGS[5]
+    inst = [0, 77, 200, 255]
+    q, k, v, budgets, _ = make_batch(cfg, device=DEV, instances=inst)
+    run_and_check(laq, q, k, v, budgets, cfg.pool, "cfg5", heads=[2])
+
+
+EDGE = [
+    # name, dtype, Hq, Hkv, d, L, W, pool, budget
+    ("ragged-L", torch.bfloat16, 8, 2, 128, 1000, 8, 7, 100),
+    ("one-chunk", torch.bfloat16, 8, 2, 128, 200, 8, 7, 64),
+    ("L-lt-tile", torch.bfloat16, 8, 2, 128, 19, 4, 7, 8),
+    ("budget-ge-L", torch.bfloat16, 8, 2, 128, 300, 8, 7, 400),
+    ("budget-eq-W", torch.bfloat16, 8, 2, 128, 300, 8, 7, 8),
+    ("budget-eq-L-1", torch.bfloat16, 8, 2, 128, 300, 8, 7, 299),
+    ("pool1", torch.bfloat16, 8, 2, 128, 777, 8, 1, 64),
+    ("pool3", torch.bfloat16, 8, 2, 128, 777, 8, 3, 64),
+    ("pool63", torch.bfloat16, 8, 2, 128, 777, 8, 63, 200),
+    ("W1-G1-generic", torch.bfloat16, 2, 2, 128, 600, 1, 7, 50),
+    ("R48-three-tiles", torch.bfloat16, 12, 2, 128, 900, 8, 7, 64),
+    ("R160-two-groups", torch.bfloat16, 10, 1, 128, 700, 16, 7, 64),
+    ("R20-padded", torch.bfloat16, 5, 1, 128, 700, 4, 7, 64),
+    ("d64-mfma", torch.bfloat16, 8, 2, 64, 1500, 8, 7, 128),
+    ("d64-R64", torch.bfloat16, 16, 2, 64, 1500, 8, 7, 128),
+    ("d96-generic-bf16", torch.bfloat16, 4, 2, 96, 400, 4, 7, 32),
+    ("fp32-d128", torch.float32, 8, 2, 128, 700, 4, 7, 64),
+    ("fp32-G1", torch.float32, 3, 3, 32, 300, 5, 5, 40),
+    ("window-is-everything", torch.bfloat16, 8, 2, 128, 32, 32, 7, 32),
+    ("P-eq-1", torch.bfloat16, 8, 2, 128, 9, 8, 7, 9),
+    ("long-window", torch.bfloat16, 8, 2, 128, 900, 300, 7, 400),
+]
+
+
+@pytest.mark.parametrize("name,dtype,Hq,Hkv,d,L,W,pool,budget", EDGE, ids=[e[0] for e in EDGE])
+def test_edge_cases(laq, name, dtype, Hq, Hkv, d, L, W, pool, budget):
+    g = torch.Generator().manual_seed(len(name) * 1000 + L)
+    n = 2
+    q = (torch.randn(n, Hq, W, d, generator=g) * 1.5).to(dtype).to(DEV)
+    k = torch.randn(n, Hkv, L, d, generator=g).to(dtype).to(DEV)
+    v = torch.randn(n, Hkv, L, d, generator=g).to(dtype).to(DEV)
+    run_and_check(laq, q, k, v, [budget, max(W, budget - 3)], pool, name)
+
+
+def test_per_instance_budgets_pack_correctly(laq):
+    cfg = dataclasses.replace(CONFIGS[4], L=2048, n_layer=5)
+    q, k, v, budgets, _ = make_batch(cfg, device=DEV)
+    assert len(set(budgets)) == 5
+    run_and_check(laq, q, k, v, budgets, cfg.pool, "pyramid-small")
+
+
+def test_all_keys_identical_all_ties(laq):
+    Hq, Hkv, d, L, W, budget = 8, 2, 128, 700, 8, 100
+    g = torch.Generator().manual_seed(1)
+    q = torch.randn(1, Hq, W, d, generator=g).bfloat16().to(DEV)
+    k = torch.randn(1, 1, 1, d, generator=g).bfloat16().expand(1, Hkv, L, d).contiguous().to(DEV)
+    scores, idx, _, _ = laq.laq_evict(q, k, None, [budget], 7)
+    got = idx.cpu().reshape(Hkv, budget)
+    # every prefix score is the same number, so the lowest positions win
+    P = L - W
+    s = scores.cpu()
+    assert (s[0, :, :P] == s[0, :, :1]).all()
+    want = torch.tensor(list(range(budget - W)) + list(range(P, L)), dtype=torch.int32)
+    assert (got == want).all()
+    expect = 4 * sum(1.0 / (P + w + 1) for w in range(W))
+    np.testing.assert_allclose(s[0, :, :P].double().numpy(), expect, rtol=1e-5)
+
+
+def test_extreme_logits(laq):
+    # logits of magnitude >> 10 (what the heavy-tailed config stresses): no overflow, rows still sum to 1
+    Hq, Hkv, d, L, W = 8, 2, 128, 1024, 8
+    g = torch.Generator().manual_seed(2)
+    q = (torch.randn(1, Hq, W, d, generator=g) * 40).bfloat16().to(DEV)
+    k = torch.randn(1, Hkv, L, d, generator=g).bfloat16().to(DEV)
+    v = torch.randn(1, Hkv, L, d, generator=g).bfloat16().to(DEV)
+    run_and_check(laq, q, k, v, [64], 7, "extreme")
+    raw = laq.laq_score(q, k, 1)
+    assert torch.isfinite(raw).all()
+    np.testing.assert_allclose(raw.double().sum(dim=2).cpu().numpy(), 32.0, rtol=1e-4)
+
+
+def test_select_alone_with_ties_and_memory_path(laq):
+    # scores with few distinct values (many ties across the boundary); L above the register-resident limit
+    g = torch.Generator().manual_seed(4)
+    for (Hkv, L, W, budget, pool) in [(3, 5000, 8, 600, 1), (2, 40000, 16, 3000, 1), (2, 40000, 16, 3000, 7),
+                                      (2, 2000, 4, 100, 5), (1, 70000, 8, 70000 - 5, 1)]:
+        s = (torch.randint(0, 50, (2, Hkv, L), generator=g).float() / 7).to(DEV)
+        print("select case", Hkv, L, W, budget, pool, flush=True)
+        idx = laq.laq_select(s, [budget, budget + 1], pool, W)
+        torch.cuda.synchronize()
+        parts = split_packed(idx.cpu(), [budget, budget + 1], Hkv, L)
+        for i, b in enumerate([budget, budget + 1]):
+            pooled = oracle.maxpool(s[i].cpu().double(), W, pool).float()
+            assert torch.equal(parts[i], oracle.select(pooled, W, b))
+
+
+def test_deterministic_bits(laq):
+    cfg = dataclasses.replace(CONFIGS[3], L=4096, n_layer=3)
+    q, k, v, budgets, _ = make_batch(cfg, device=DEV)
+    a = laq.laq_evict(q, k, v, budgets, cfg.pool)
+    b = laq.laq_evict(q, k, v, budgets, cfg.pool)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_explicit_scale(laq):
+    g = torch.Generator().manual_seed(9)
+    q = torch.randn(1, 8, 8, 128, generator=g).bfloat16().to(DEV)
+    k = torch.randn(1, 2, 500, 128, generator=g).bfloat16().to(DEV)
+    run_and_check(laq, q, k, None, [64], 7, "scale", scale=0.02)
