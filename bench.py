@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the LAQ re-eviction hot path (score -> select -> compact) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu-baseline]
+
+A step is one pass of the whole path (laq_evict) over every (sequence, layer) instance of the
+workload, inputs resident in HBM.  Prints ONE JSON line: whole-job throughput in prefill
+key-tokens scored+compacted per second per layer, the roofline of the dominant kernel
+(algorithmic bytes / live HIP-event duration against 8 TB/s) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(cfg, budgets):
+    """Bytes the method must move for one step, per stage (design notes: 'algorithmic bytes')."""
+    e = cfg.elem_bytes
+    n = cfg.n_inst
+    k_stream = n * cfg.Hkv * cfg.L * cfg.d * e                    # K read once
+    q_read = n * cfg.Hq * cfg.W * cfg.d * e
+    scores_w = n * cfg.Hkv * cfg.L * 4
+    score = k_stream + q_read + scores_w
+    rows = sum(cfg.Hkv * min(b, cfg.L) for b in budgets)
+    select = scores_w + rows * 4                                   # scores read, idx written
+    compact = rows * 4 + 4 * rows * cfg.d * e                      # idx read; K',V' rows read + written
+    return {"score": score, "select": select, "compact": compact, "total": score + select + compact}
+
+
+def read_traffic(workload):
+    """HBM bytes per score-stage launch from committed rocprofv3 --pmc summaries, if present."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch="):
+            return float(line.split("=", 1)[1])
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload: index into BASELINE.json configs (1-based)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-instances", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU (every KV head is independent; nothing is sharded or "
+              "exchanged) -- run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2505_20334_amd as laq
+    from laq_inputs import CONFIGS, budgets_for, make_instance
+
+    laq.load_library()                     # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = CONFIGS[args.config]
+    budgets = budgets_for(cfg)
+    n = cfg.n_inst
+
+    # ---- inputs, generated on the device, resident before any timing ----
+    dt = cfg.torch_dtype
+    q = torch.empty(n, cfg.Hq, cfg.W, cfg.d, dtype=dt, device=dev)
+    k = torch.empty(n, cfg.Hkv, cfg.L, cfg.d, dtype=dt, device=dev)
+    v = torch.empty(n, cfg.Hkv, cfg.L, cfg.d, dtype=dt, device=dev)
+    for i in range(n):
+        seq, layer = divmod(i, cfg.n_layer)
+        qi, ki, vi, _ = make_instance(cfg, seq, layer, device=dev)
+        q[i].copy_(qi); k[i].copy_(ki); v[i].copy_(vi)
+    total_rows, _ = laq.packed_rows(budgets, cfg.Hkv, cfg.L)
+    scores = torch.empty(n, cfg.Hkv, cfg.L, dtype=torch.float32, device=dev)
+    idx = torch.empty(total_rows, dtype=torch.int32, device=dev)
+    k_out = torch.empty(total_rows, cfg.d, dtype=dt, device=dev)
+    v_out = torch.empty(total_rows, cfg.d, dtype=dt, device=dev)
+    ws = torch.empty(laq.laq_workspace_bytes(n, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, cfg.W, dt), dtype=torch.uint8,
+                     device=dev)
+
+    def step():
+        laq.laq_evict(q, k, v, budgets, cfg.pool, scores=scores, idx=idx, k_out=k_out, v_out=v_out, ws=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = n * cfg.L / (ms_per_step * 1e-3)
+
+    # ---- per-stage durations with events on the launch stream (torch's current stream) ----
+    stages = {"score": 0.0, "select": 0.0, "compact": 0.0}
+    reps = max(3, min(args.steps, 10))
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for _ in range(reps):
+        ev[0].record()
+        laq.laq_score(q, k, cfg.pool, scores=scores, ws=ws)
+        ev[1].record()
+        laq.laq_select(scores, budgets, 1, cfg.W, idx=idx)
+        ev[2].record()
+        laq.laq_compact(k, v, idx, budgets, cfg.W, k_out=k_out, v_out=v_out)
+        ev[3].record()
+        torch.cuda.synchronize()
+        stages["score"] += ev[0].elapsed_time(ev[1]) / reps
+        stages["select"] += ev[1].elapsed_time(ev[2]) / reps
+        stages["compact"] += ev[2].elapsed_time(ev[3]) / reps
+    ab = algorithmic_bytes(cfg, budgets)
+    achieved = ab["score"] / (stages["score"] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(cfg.name),
+                "kernel": "laq_score stage (stats + row constants + normalise/pool kernels)",
+                "algorithmic_bytes_per_launch": ab["score"],
+                "ms_per_launch": round(stages["score"], 4)}
+
+    out = {
+        "metric": "prefill key-tokens scored+compacted/sec per layer (all heads)",
+        "value": round(value, 1), "unit": "key-tokens/s/layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "cfg_id": cfg.cfg_id, "instances": n, "Hq": cfg.Hq, "Hkv": cfg.Hkv,
+                   "d": cfg.d, "L": cfg.L, "W": cfg.W, "pool": cfg.pool, "budget": cfg.budget},
+        "whole_path": {"algorithmic_GBs": round(ab["total"] / (ms_per_step * 1e-3) / 1e9, 1),
+                       "frac_of_hbm_peak": round(ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                       "stage_ms": {s: round(t, 4) for s, t in stages.items()}},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        ids = sorted(set([0, n - 1][:args.cpu_instances])) if args.cpu_instances <= 2 else \
+            list(range(min(args.cpu_instances, n)))
+        t_cpu = 0.0
+        for i in ids:
+            qi, ki, vi = q[i].cpu(), k[i].cpu(), v[i].cpu()
+            c0 = time.perf_counter()
+            oracle.evict(qi, ki, vi, budgets[i], cfg.pool)
+            t_cpu += time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": round(len(ids) * cfg.L / t_cpu, 1), "unit": "key-tokens/s/layer",
+                               "cores": 1, "kind": "oracle",
+                               "sample": "instances %s of %d (all heads, full length), %.1f s" % (ids, n, t_cpu)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -75,8 +75,10 @@ size_t laq_workspace_bytes(const laq_shape *shape);
  *          With pool_kernel == 1 scores = raw.  With an odd pool_kernel p > 1 the prefix
  *          columns hold max(raw[g,i] : |i-j| <= (p-1)/2, 0 <= i < P) (the sequence pooling
  *          of the observation-window procedure, Sec. 2.1 / 5.1) and the W window columns
- *          keep raw.  Max is exact, so pooling here and pooling in laq_select give the
- *          same bits.
+ *          keep raw.  Max is exact, so a pooled plateau consists of bit-identical values
+ *          whether the pooling is done here or in laq_select.  (Raw scores of two calls with
+ *          different pool_kernel may differ in the last bits: the softmax statistics are
+ *          grouped by key chunk and the chunk size depends on the pooling halo.)
  *   ws / ws_bytes  device scratch of at least laq_workspace_bytes(shape)
  * Supported: dtype BF16 or F32; any Hq/Hkv/W/L within the limits of laq_shape;
  * pool_kernel odd, 1 <= pool_kernel <= 63.

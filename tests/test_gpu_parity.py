@@ -39,11 +39,11 @@ def run_and_check(laq, q, k, v, budgets, pool, what, heads=None, scale=0.0, exac
     assert torch.equal(s3, scores) and torch.equal(i3, idx) and torch.equal(k3, ko)
     if v is not None:
         assert torch.equal(v3, vo)
-    # pooling in select instead of in score: identical bits
+    # pooling in select instead of in score: the same selection rule on (nearly) the same numbers
     s_raw = laq.laq_score(q, k, 1, scale=scale)
     i_alt = laq.laq_select(s_raw, budgets, pool, W)
     torch.cuda.synchronize()
-    assert torch.equal(i_alt, idx)
+    alt_l = split_packed(i_alt.cpu(), budgets, Hkv, L)
 
     idx_l = split_packed(idx.cpu(), budgets, Hkv, L)
     ko_l = split_packed(ko.cpu(), budgets, Hkv, L)
@@ -72,6 +72,11 @@ def run_and_check(laq, q, k, v, budgets, pool, what, heads=None, scale=0.0, exac
             # selection on identical fp32 scores is bit-exact
             o_idx = oracle.select(sc[i, g:g + 1], W, budgets[i])
             assert torch.equal(o_idx[0], idx_l[i][g]), "%s: select differs on identical scores" % what
+            # ... also when the pooling is done inside laq_select
+            p_alt = oracle.maxpool(s_raw[i, g:g + 1].cpu().double(), W, pool).float()
+            assert torch.equal(oracle.select(p_alt, W, budgets[i])[0], alt_l[i][g]), "%s: select+pool" % what
+            check_index_row(alt_l[i][g].numpy(), pooled[0].float().numpy(), W, budgets[i],
+                            RTOL[k.dtype], "%s alt inst %d head %d" % (what, i, g))
     if exact_expected is not None:
         assert n_exact >= exact_expected
     return scores, idx, ko, vo
@@ -128,7 +133,7 @@ def test_config4_sampled_full_size(laq):
     sums = scores.double().sum(dim=2)      # not R exactly (pooled), but raw sums are:
     raw = laq.laq_score(q, k, 1)
     np.testing.assert_allclose(raw.double().sum(dim=2).cpu().numpy(), cfg.R, rtol=2e-4)
-    assert (scores >= raw).all() and (sums > 0).all()
+    assert (scores >= raw * (1 - 1e-5)).all() and (sums > 0).all()
     for i in range(n):
         assert (idx_l[i][:, 1:] > idx_l[i][:, :-1]).all()
         assert (idx_l[i][:, -W:] == torch.arange(L - W, L, dtype=torch.int32)).all()
