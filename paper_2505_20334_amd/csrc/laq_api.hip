@@ -32,7 +32,8 @@ size_t workspace_bytes(const ScoreGeom& g) {
   const size_t heads = (size_t)g.n_inst * g.Hkv;
   size_t part = heads * g.nchunk * g.Rpad * sizeof(float2);
   size_t rowc = heads * g.Rpad * sizeof(float);
-  return ((part + 255) & ~(size_t)255) + ((rowc + 255) & ~(size_t)255);
+  size_t sync = (2 * heads + 1) * sizeof(int);
+  return ((part + 255) & ~(size_t)255) + ((rowc + 255) & ~(size_t)255) + ((sync + 255) & ~(size_t)255);
 }
 
 Workspace carve_workspace(const ScoreGeom& g, void* ws) {
@@ -40,7 +41,10 @@ Workspace carve_workspace(const ScoreGeom& g, void* ws) {
   size_t part = heads * g.nchunk * g.Rpad * sizeof(float2);
   Workspace w;
   w.part = static_cast<float2*>(ws);
-  w.rowc = reinterpret_cast<float*>(static_cast<char*>(ws) + ((part + 255) & ~(size_t)255));
+  size_t rowc = heads * g.Rpad * sizeof(float);
+  char* base = static_cast<char*>(ws);
+  w.rowc = reinterpret_cast<float*>(base + ((part + 255) & ~(size_t)255));
+  w.sync = reinterpret_cast<int*>(base + ((part + 255) & ~(size_t)255) + ((rowc + 255) & ~(size_t)255));
   return w;
 }
 

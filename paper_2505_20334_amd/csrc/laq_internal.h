@@ -33,12 +33,14 @@ struct ScoreGeom {
   float scale2;  // scale * log2(e): logits are kept in base-2 units
 };
 
-// Workspace carving: [partials | row constants]
+// Workspace carving: [partials | row constants | sync words]
 //   partials: float2 (m, z) per (instance, KV head, chunk, padded row)
 //   rowc:     float c = m + log2(z) per (instance, KV head, padded row)
+//   sync:     int arrival counter per head, int ready flag per head, one int error word
 struct Workspace {
   float2* part;
   float* rowc;
+  int* sync;
 };
 
 size_t workspace_bytes(const ScoreGeom& g);

@@ -108,7 +108,124 @@ __device__ __forceinline__ f32x16 tile_product(const char* ldsK, int kt, int lan
 // groups of four consecutive rows alternate between the two lane halves).
 __device__ __forceinline__ int acc_row(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
 
-// ---- pass 1 ---------------------------------------------------------------------------
+#define LAQ_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+__device__ __forceinline__ bf16x8 lds_operand(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+// Initial accumulator values that take the halo rows of a chunk out of the statistics:
+// -inf for staged rows t < half (first tile) resp. t >= CHUNK_ROWS - half (last tile), else 0.
+// A wave whose tile range does not touch that end of the chunk gets all zeros.
+__device__ __forceinline__ void halo_bias(int half, int kt0, int kt1, int lane, f32x16& first, f32x16& last) {
+  const int hf = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int r = acc_row(i, hf);
+    first[i] = (kt0 == 0 && r < half) ? -INFINITY : 0.f;
+    last[i] = (kt1 == KTILES && r >= 32 - half) ? -INFINITY : 0.f;
+  }
+}
+
+// ---- software-pipelined passes for chunks without causally masked keys -----------------
+// The MFMA chain of key tile i+1 is issued one instruction at a time, each followed by a
+// slice of the VALU work of tile i, so that the matrix pipe and the vector ALU run
+// concurrently inside one wave; LDS operands are fetched two MFMAs ahead.  The
+// scheduling fences pin that interleaving.
+template <int D, int NT>
+__device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS], int kt0,
+                                           const f32x16& first_bias, const f32x16& last_bias, float scale2,
+                                           int lane, float& m_run, float& z_run) {
+  using T = Tile<D>;
+  constexpr int KS = T::KSTEPS, N = NT * KS;
+  const char* base = ldsK + (kt0 * 32 + (lane & 31)) * T::ROWB + (lane >> 5) * 16;
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  bf16x8 r0 = lds_operand(base), r1 = lds_operand(base + 32);
+  f32x16 cur = zero, nxt = zero;
+#pragma unroll
+  for (int i = 0; i <= NT; ++i) {
+    float m_new = m_run, s = 0.f;
+#pragma unroll
+    for (int t = 0; t < KS; ++t) {
+      const int n = i * KS + t;
+      if (i < NT) {
+        bf16x8 r2 = r0;
+        if (n + 2 < N) r2 = lds_operand(base + ((n + 2) / KS) * 32 * T::ROWB + ((n + 2) % KS) * 32);
+        const f32x16 c = (t > 0) ? nxt : (i == 0 ? first_bias : (i == NT - 1 ? last_bias : zero));
+        nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r0, qreg[t], c, 0, 0, 0);
+        r0 = r1;
+        r1 = r2;
+      }
+      if (i > 0) {
+        if (t == 0) {
+          float mx = fmaxf(fmaxf(cur[0], cur[1]), cur[2]);
+#pragma unroll
+          for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(mx, cur[e]), cur[e + 1]);
+          mx = fmaxf(mx, cur[15]);
+          m_new = fmaxf(m_run, mx * scale2);
+        } else {
+          constexpr int SL = KS - 1;
+          const int lo = (t - 1) * 16 / SL, hi = t * 16 / SL;
+          float x[16];
+#pragma unroll
+          for (int e = lo; e < hi; ++e) x[e] = fmaf(cur[e], scale2, -m_new);
+#pragma unroll
+          for (int e = lo; e < hi; ++e) x[e] = __builtin_amdgcn_exp2f(x[e]);
+#pragma unroll
+          for (int e = lo; e < hi; ++e) s += x[e];
+        }
+      }
+      LAQ_SCHED_FENCE();
+    }
+    if (i > 0) {
+      z_run = fmaf(z_run, __builtin_amdgcn_exp2f(m_run - m_new), s);
+      m_run = m_new;
+    }
+    cur = nxt;
+  }
+}
+
+template <int D, int NT>
+__device__ __forceinline__ void pass2_pipe(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS], int kt0,
+                                           const float (&c)[16], float scale2, int lane, float* slotbuf) {
+  using T = Tile<D>;
+  constexpr int KS = T::KSTEPS, N = NT * KS, PER = 16 / KS;
+  const int hf = lane >> 5, n32 = lane & 31;
+  const char* base = ldsK + (kt0 * 32 + n32) * T::ROWB + hf * 16;
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  bf16x8 r0 = lds_operand(base), r1 = lds_operand(base + 32);
+  f32x16 cur = zero, nxt = zero;
+#pragma unroll
+  for (int i = 0; i <= NT; ++i) {
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < KS; ++t) {
+      const int n = i * KS + t;
+      if (i < NT) {
+        bf16x8 r2 = r0;
+        if (n + 2 < N) r2 = lds_operand(base + ((n + 2) / KS) * 32 * T::ROWB + ((n + 2) % KS) * 32);
+        nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[t], r0, (t > 0) ? nxt : zero, 0, 0, 0);
+        r0 = r1;
+        r1 = r2;
+      }
+      if (i > 0) {
+        float x[16];
+#pragma unroll
+        for (int e = t * PER; e < (t + 1) * PER; ++e) x[e] = fmaf(cur[e], scale2, -c[e]);
+#pragma unroll
+        for (int e = t * PER; e < (t + 1) * PER; ++e) x[e] = __builtin_amdgcn_exp2f(x[e]);
+#pragma unroll
+        for (int e = t * PER; e < (t + 1) * PER; ++e) s += x[e];
+      }
+      LAQ_SCHED_FENCE();
+    }
+    if (i > 0) {
+      s += __shfl_xor(s, 32);
+      if (hf == 0) slotbuf[(kt0 + i - 1) * 32 + n32] += s;
+    }
+    cur = nxt;
+  }
+}
+
+// ---- per-tile passes for chunks that touch the causal region (the last chunks of a head) ----
 template <int D>
 __device__ __forceinline__ void pass1_wave(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS],
                                            const ScoreGeom& g, int rt, int kt0, int kt1, int j0, int lane,
@@ -146,69 +263,12 @@ __device__ __forceinline__ void pass1_wave(const char* ldsK, const bf16x8 (&qreg
   }
 }
 
-template <int D, int NRT>
-__global__ __launch_bounds__(THREADS) void stats_mfma_kernel(ScoreGeom g, const uint16_t* __restrict__ q,
-                                                             const uint16_t* __restrict__ k,
-                                                             float2* __restrict__ part) {
-  extern __shared__ __align__(16) char smem[];
-  using S = Smem<D, NRT>;
-  constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
-  const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int j0 = chunk * g.own - g.half;
-  const uint16_t* khead = k + ((size_t)inst * g.Hkv + head) * g.L * D;
-  const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
-  float2* out = part + (((size_t)inst * g.Hkv + head) * g.nchunk + chunk) * g.Rpad;
-  float2* stat = reinterpret_cast<float2*>(smem + S::OFF_STAT);
-
-  stage_chunk<D>(smem, khead, j0, g.L, tid);
-  __syncthreads();
-
-  const int slot = wave % NRT, ks = wave / NRT;
-  const int ntile = g.Rpad / 32;
-  for (int rg = 0; rg * NRT < ntile; ++rg) {
-    const int rt = rg * NRT + slot;
-    float m_run = NEG_BIG, z_run = 0.f;
-    if (rt < ntile) {
-      bf16x8 qreg[Tile<D>::KSTEPS];
-      load_q_tile<D>(qreg, qg, rt, g.R, lane);
-      pass1_wave<D>(smem, qreg, g, rt, ks * TPW, ks * TPW + TPW, j0, lane, m_run, z_run);
-    }
-    stat[tid] = make_float2(m_run, z_run);
-    __syncthreads();
-    if (tid < NRT * 32) {
-      const int s = tid >> 5, n = tid & 31;
-      if (rg * NRT + s < ntile) {
-        float M = NEG_BIG;
-#pragma unroll
-        for (int c = 0; c < KSPLIT; ++c) {
-          const int wv = s + NRT * c;
-          M = fmaxf(M, fmaxf(stat[wv * 64 + n].x, stat[wv * 64 + 32 + n].x));
-        }
-        float Z = 0.f;
-#pragma unroll
-        for (int c = 0; c < KSPLIT; ++c) {
-          const int wv = s + NRT * c;
-          const float2 a = stat[wv * 64 + n], b = stat[wv * 64 + 32 + n];
-          Z += a.y * __builtin_amdgcn_exp2f(a.x - M);
-          Z += b.y * __builtin_amdgcn_exp2f(b.x - M);
-        }
-        out[(rg * NRT + s) * 32 + n] = make_float2(M, Z);
-      }
-    }
-    __syncthreads();
-  }
-}
-
-// ---- pass 2 ---------------------------------------------------------------------------
+// c32: the row constants of this wave's 32-row tile
 template <int D>
 __device__ __forceinline__ void pass2_wave(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS],
-                                           const ScoreGeom& g, const float* __restrict__ rowc, int rt, int kt0,
-                                           int kt1, int j0, int lane, float* slotbuf) {
+                                           const ScoreGeom& g, const float (&c)[16], int rt, int kt0, int kt1,
+                                           int j0, int lane, float* slotbuf) {
   const int hf = lane >> 5, n = lane & 31;
-  float c[16];
-#pragma unroll
-  for (int i = 0; i < 16; ++i) c[i] = rowc[rt * 32 + acc_row(i, hf)];
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int kt = kt0; kt < kt1; ++kt) {
     const int t0 = kt * 32;
@@ -233,36 +293,130 @@ __device__ __forceinline__ void pass2_wave(const char* ldsK, const bf16x8 (&qreg
   }
 }
 
-template <int D, int NRT>
-__global__ __launch_bounds__(THREADS) void norm_mfma_kernel(ScoreGeom g, const uint16_t* __restrict__ q,
-                                                            const uint16_t* __restrict__ k,
-                                                            const float* __restrict__ rowc,
-                                                            float* __restrict__ scores) {
-  extern __shared__ __align__(16) char smem[];
+// ---- words that workgroups hand to each other -------------------------------------------
+// The fused kernel never relies on cache maintenance for them: agent-scope release/acquire
+// fences write back and invalidate the whole L2 on this part and cost tens of microseconds
+// each.  Instead every such word is written with a *returning* agent-scope atomic exchange
+// (its return means it has been performed at the device-coherent level), the workgroup barrier
+// then orders those exchanges before the arrival counter / flag update, and readers use
+// agent-scope atomic loads.
+__device__ __forceinline__ void coherent_put(float2* p, float2 v) {
+  const unsigned long long bits = ((unsigned long long)__float_as_uint(v.y) << 32) | __float_as_uint(v.x);
+  const unsigned long long old = __hip_atomic_exchange(reinterpret_cast<unsigned long long*>(p), bits,
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  asm volatile("" ::"v"(old));   // keep the exchange in its returning form
+}
+__device__ __forceinline__ void coherent_put(float* p, float v) {
+  const unsigned old = __hip_atomic_exchange(reinterpret_cast<unsigned*>(p), __float_as_uint(v), __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+  asm volatile("" ::"v"(old));
+}
+__device__ __forceinline__ float2 coherent_get(const float2* p) {
+  const unsigned long long b = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((unsigned)b), __uint_as_float((unsigned)(b >> 32)));
+}
+__device__ __forceinline__ float coherent_get(const float* p) {
+  return __uint_as_float(__hip_atomic_load(reinterpret_cast<const unsigned*>(p), __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT));
+}
+
+__device__ __forceinline__ void merge_stat(float& M, float& Z, float2 p) {
+  const float Mn = fmaxf(M, p.x);
+  Z = Z * __builtin_amdgcn_exp2f(M - Mn) + p.y * __builtin_amdgcn_exp2f(p.x - Mn);
+  M = Mn;
+}
+
+// ---- one (head, chunk) unit ---------------------------------------------------------------
+// Pass 1 over the staged chunk: (m, z) of every score row goes to out[0 .. Rpad).
+// q0 holds this wave's Q tile of the first row group (loaded by the caller, reused by pass 2).
+template <int D, int NRT, bool COHERENT>
+__device__ __forceinline__ void unit_pass1(char* smem, const ScoreGeom& g, const uint16_t* __restrict__ qg,
+                                           const bf16x8 (&q0)[Tile<D>::KSTEPS], int j0, int tid, int lane, int wave,
+                                           float2* out) {
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
-  const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int j0 = chunk * g.own - g.half;
-  const uint16_t* khead = k + ((size_t)inst * g.Hkv + head) * g.L * D;
-  const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
-  const float* c = rowc + ((size_t)inst * g.Hkv + head) * g.Rpad;
+  float2* stat = reinterpret_cast<float2*>(smem + S::OFF_STAT);
+  const int slot = wave % NRT, ks = wave / NRT;
+  const int ntile = g.Rpad / 32;
+  const bool plain_chunk = (j0 + CHUNK_ROWS - 1 <= g.P);    // no key beyond the prefix: no causal mask
+  f32x16 first_bias, last_bias;
+  halo_bias(g.half, ks * TPW, ks * TPW + TPW, lane, first_bias, last_bias);
+  for (int rg = 0; rg * NRT < ntile; ++rg) {
+    const int rt = rg * NRT + slot;
+    float m_run = NEG_BIG, z_run = 0.f;
+    if (rt < ntile) {
+      bf16x8 qreg[Tile<D>::KSTEPS];
+      if (rg == 0) {
+#pragma unroll
+        for (int t = 0; t < Tile<D>::KSTEPS; ++t) qreg[t] = q0[t];
+      } else {
+        load_q_tile<D>(qreg, qg, rt, g.R, lane);
+      }
+      if (plain_chunk)
+        pass1_pipe<D, TPW>(smem, qreg, ks * TPW, first_bias, last_bias, g.scale2, lane, m_run, z_run);
+      else
+        pass1_wave<D>(smem, qreg, g, rt, ks * TPW, ks * TPW + TPW, j0, lane, m_run, z_run);
+    }
+    stat[tid] = make_float2(m_run, z_run);
+    __syncthreads();
+    if (tid < NRT * 32) {
+      const int s = tid >> 5, n = tid & 31;
+      if (rg * NRT + s < ntile) {
+        float M = NEG_BIG, Z = 0.f;
+#pragma unroll
+        for (int c = 0; c < KSPLIT; ++c) {
+          const int wv = s + NRT * c;
+          merge_stat(M, Z, stat[wv * 64 + n]);
+          merge_stat(M, Z, stat[wv * 64 + 32 + n]);
+        }
+        if (COHERENT)
+          coherent_put(out + (rg * NRT + s) * 32 + n, make_float2(M, Z));
+        else
+          out[(rg * NRT + s) * 32 + n] = make_float2(M, Z);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// Pass 2 over the staged chunk with the head's row constants c[0 .. Rpad): raw scores of all
+// staged rows, max-pool, owned rows written to scores_head.
+// If crow0_staged, the caller has already put the first row group's constants into the LDS slice.
+template <int D, int NRT, bool COHERENT>
+__device__ __forceinline__ void unit_pass2(char* smem, const ScoreGeom& g, const uint16_t* __restrict__ qg,
+                                           const bf16x8 (&q0)[Tile<D>::KSTEPS], const float* c, bool crow0_staged,
+                                           int j0, int tid, int lane, int wave, float* __restrict__ scores_head) {
+  using S = Smem<D, NRT>;
+  constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
+  float* crow = reinterpret_cast<float*>(smem + S::OFF_STAT);      // row constants of the current row group
   float* slots = reinterpret_cast<float*>(smem + S::OFF_SLOT);
   float* raw = reinterpret_cast<float*>(smem + S::OFF_RAW);
-
-  stage_chunk<D>(smem, khead, j0, g.L, tid);
 #pragma unroll
   for (int s = 0; s < NRT; ++s) slots[s * CHUNK_ROWS + tid] = 0.f;
-  __syncthreads();
-
   const int slot = wave % NRT, ks = wave / NRT;
   const int ntile = g.Rpad / 32;
   for (int rg = 0; rg * NRT < ntile; ++rg) {
+    if (rg > 0) __syncthreads();
+    if (!(rg == 0 && crow0_staged) && tid < NRT * 32 && rg * NRT * 32 + tid < g.Rpad)
+      crow[tid] = COHERENT ? coherent_get(c + rg * NRT * 32 + tid) : c[rg * NRT * 32 + tid];
+    __syncthreads();
     const int rt = rg * NRT + slot;
     if (rt < ntile) {
       bf16x8 qreg[Tile<D>::KSTEPS];
-      load_q_tile<D>(qreg, qg, rt, g.R, lane);
-      pass2_wave<D>(smem, qreg, g, c, rt, ks * TPW, ks * TPW + TPW, j0, lane, slots + slot * CHUNK_ROWS);
+      if (rg == 0) {
+#pragma unroll
+        for (int t = 0; t < Tile<D>::KSTEPS; ++t) qreg[t] = q0[t];
+      } else {
+        load_q_tile<D>(qreg, qg, rt, g.R, lane);
+      }
+      float cr[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) cr[i] = crow[slot * 32 + acc_row(i, lane >> 5)];
+      if (j0 + CHUNK_ROWS - 1 <= g.P)
+        pass2_pipe<D, TPW>(smem, qreg, ks * TPW, cr, g.scale2, lane, slots + slot * CHUNK_ROWS);
+      else
+        pass2_wave<D>(smem, qreg, g, cr, rt, ks * TPW, ks * TPW + TPW, j0, lane, slots + slot * CHUNK_ROWS);
     }
   }
   __syncthreads();
@@ -271,7 +425,6 @@ __global__ __launch_bounds__(THREADS) void norm_mfma_kernel(ScoreGeom g, const u
   for (int s = 1; s < NRT; ++s) v += slots[s * CHUNK_ROWS + tid];
   raw[tid] = v;
   __syncthreads();
-
   const int j = j0 + tid;
   if (tid >= g.half && tid < CHUNK_ROWS - g.half && j < g.L) {
     if (j < g.P) {
@@ -279,31 +432,240 @@ __global__ __launch_bounds__(THREADS) void norm_mfma_kernel(ScoreGeom g, const u
       v = raw[lo];
       for (int i = lo + 1; i <= hi; ++i) v = fmaxf(v, raw[i]);
     }
-    scores[((size_t)inst * g.Hkv + head) * g.L + j] = v;
+    scores_head[j] = v;
+  }
+}
+
+// ---- two-kernel route (K read twice; for heads with more chunks than resident workgroups) ----
+template <int D, int NRT>
+__global__ __launch_bounds__(THREADS) void stats_mfma_kernel(ScoreGeom g, const uint16_t* __restrict__ q,
+                                                             const uint16_t* __restrict__ k,
+                                                             float2* __restrict__ part) {
+  extern __shared__ __align__(16) char smem[];
+  const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j0 = chunk * g.own - g.half;
+  const size_t hg = (size_t)inst * g.Hkv + head;
+  const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
+  bf16x8 q0[Tile<D>::KSTEPS];
+  load_q_tile<D>(q0, qg, wave % NRT, g.R, lane);
+  stage_chunk<D>(smem, k + hg * g.L * D, j0, g.L, tid);
+  __syncthreads();
+  unit_pass1<D, NRT, false>(smem, g, qg, q0, j0, tid, lane, wave, part + (hg * g.nchunk + chunk) * g.Rpad);
+}
+
+template <int D, int NRT>
+__global__ __launch_bounds__(THREADS) void norm_mfma_kernel(ScoreGeom g, const uint16_t* __restrict__ q,
+                                                            const uint16_t* __restrict__ k,
+                                                            const float* __restrict__ rowc,
+                                                            float* __restrict__ scores) {
+  extern __shared__ __align__(16) char smem[];
+  const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j0 = chunk * g.own - g.half;
+  const size_t hg = (size_t)inst * g.Hkv + head;
+  const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
+  bf16x8 q0[Tile<D>::KSTEPS];
+  load_q_tile<D>(q0, qg, wave % NRT, g.R, lane);
+  stage_chunk<D>(smem, k + hg * g.L * D, j0, g.L, tid);
+  __syncthreads();
+  unit_pass2<D, NRT, false>(smem, g, qg, q0, rowc + hg * g.Rpad, false, j0, tid, lane, wave, scores + hg * g.L);
+}
+
+// ---- fused single-read kernel -----------------------------------------------------------
+// Persistent workgroups walk the list of (KV head, chunk) units in order, unit u going to
+// workgroup u mod gridDim.x.  A unit's key rows are read from HBM once: they stay in LDS from
+// pass 1 to pass 2.  Between the passes the chunks of a head meet at a per-head counter; the
+// workgroup that arrives last combines the per-chunk statistics into the row constants and
+// raises the head's flag, the others wait for the flag.  All workgroups of the grid are
+// resident at once (the grid is sized from the occupancy query), and a unit only ever waits
+// for units that come before it in the list, so every wait ends; the spin is bounded all the
+// same and records a timeout in the error word.  While a unit is being computed the key rows
+// of the workgroup's next unit are already on their way from HBM into registers.
+
+constexpr int SPIN_LIMIT = 1 << 20;   // x ~1 us per probe: about a second, far beyond any legitimate wait
+
+template <int D>
+__device__ __forceinline__ void prefetch_chunk(uint4 (&buf)[Tile<D>::PIECES_PER_THREAD],
+                                               const uint16_t* __restrict__ khead, int j0, int L, int tid) {
+  using T = Tile<D>;
+#pragma unroll
+  for (int it = 0; it < T::PIECES_PER_THREAD; ++it) {
+    const int p = tid + THREADS * it;
+    const int row = p / T::PIECES_PER_ROW, col = p % T::PIECES_PER_ROW;
+    const int j = min(max(j0 + row, 0), L - 1);     // rows outside [0, L) are never counted: any valid row will do
+    buf[it] = *reinterpret_cast<const uint4*>(khead + (size_t)j * D + col * 8);
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void commit_chunk(char* ldsK, const uint4 (&buf)[Tile<D>::PIECES_PER_THREAD], int tid) {
+  using T = Tile<D>;
+#pragma unroll
+  for (int it = 0; it < T::PIECES_PER_THREAD; ++it) {
+    const int p = tid + THREADS * it;
+    const int row = p / T::PIECES_PER_ROW, col = p % T::PIECES_PER_ROW;
+    *reinterpret_cast<uint4*>(ldsK + row * T::ROWB + col * 16) = buf[it];
+  }
+}
+
+// Combine the (m, z) of all chunks of one head into c = M + log2 Z per score row (fixed order,
+// so the result does not depend on which workgroup does it).
+__device__ __forceinline__ void combine_head(const ScoreGeom& g, const float2* part_head, float* rowc_head,
+                                             float2* stat, int tid) {
+  for (int r0 = 0; r0 < g.Rpad; r0 += THREADS) {
+    const int rows = min(THREADS, g.Rpad - r0);
+    const int tpr = (THREADS % rows == 0) ? THREADS / rows : 1;      // threads sharing a row
+    const int r = tid % rows, sel = tid / rows;
+    float M = NEG_BIG, Z = 0.f;
+    if (sel < tpr) {
+      // loads go out in batches (they are independent); only the merges are sequential
+      constexpr int B = 24;
+      const float2* p = part_head + r0 + r;
+      for (int c0 = sel; c0 < g.nchunk; c0 += B * tpr) {
+        float2 buf[B];
+#pragma unroll
+        for (int b = 0; b < B; ++b) buf[b] = coherent_get(p + (size_t)min(c0 + b * tpr, g.nchunk - 1) * g.Rpad);
+#pragma unroll
+        for (int b = 0; b < B; ++b)
+          if (c0 + b * tpr < g.nchunk) merge_stat(M, Z, buf[b]);
+      }
+    }
+    stat[tid] = make_float2(M, Z);
+    __syncthreads();
+    if (tid < rows) {
+      for (int s2 = 1; s2 < tpr; ++s2) merge_stat(M, Z, stat[s2 * rows + tid]);
+      coherent_put(rowc_head + r0 + tid, (r0 + tid < g.R) ? M + __builtin_amdgcn_logf(Z) : 1.0e30f);
+    }
+    __syncthreads();
   }
 }
 
 template <int D, int NRT>
-hipError_t launch_pair(const ScoreGeom& g, const uint16_t* q, const uint16_t* k, float* scores,
-                       const Workspace& ws, hipStream_t st) {
-  constexpr int bytes = Smem<D, NRT>::BYTES;
-  static bool attr_done = false;   // raising the dynamic-LDS limit is idempotent
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stats_mfma_kernel<D, NRT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&norm_mfma_kernel<D, NRT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
+__global__ __launch_bounds__(THREADS, 2) void score_fused_kernel(ScoreGeom g, const uint16_t* __restrict__ q,
+                                                                 const uint16_t* __restrict__ k, float2* part,
+                                                                 float* rowc, int* sync,
+                                                                 float* __restrict__ scores, int n_units) {
+  extern __shared__ __align__(16) char smem[];
+  using S = Smem<D, NRT>;
+  __shared__ int sh_last;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n_heads = g.n_inst * g.Hkv;
+  int* cnt = sync;
+  int* flag = sync + n_heads;
+  int* err = sync + 2 * n_heads;
+  float2* stat = reinterpret_cast<float2*>(smem + S::OFF_STAT);
+
+  uint4 pre[Tile<D>::PIECES_PER_THREAD];
+  int u = blockIdx.x;
+  if (u < n_units) {
+    const int hg = u / g.nchunk, c = u - hg * g.nchunk;
+    prefetch_chunk<D>(pre, k + (size_t)hg * g.L * D, c * g.own - g.half, g.L, tid);
+    commit_chunk<D>(smem, pre, tid);
   }
-  dim3 grid(g.nchunk, g.Hkv, g.n_inst), block(THREADS);
-  hipLaunchKernelGGL((stats_mfma_kernel<D, NRT>), grid, block, bytes, st, g, q, k, ws.part);
+  __syncthreads();
+
+  for (; u < n_units; u += gridDim.x) {
+    const int hg = u / g.nchunk, c = u - hg * g.nchunk;
+    const int inst = hg / g.Hkv, head = hg - inst * g.Hkv;
+    const int j0 = c * g.own - g.half;
+    const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
+    const int un = u + gridDim.x;
+    bf16x8 q0[Tile<D>::KSTEPS];
+    load_q_tile<D>(q0, qg, wave % NRT, g.R, lane);
+
+    // the statistics are published with returning exchanges; the barrier that ends unit_pass1
+    // waits for them, so they are performed before the arrival is counted
+    unit_pass1<D, NRT, true>(smem, g, qg, q0, j0, tid, lane, wave, part + ((size_t)hg * g.nchunk + c) * g.Rpad);
+    if (tid == 0) {
+      const int old = __hip_atomic_fetch_add(&cnt[hg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      sh_last = (old == g.nchunk - 1);
+    }
+    __syncthreads();
+    if (sh_last) {
+      combine_head(g, part + (size_t)hg * g.nchunk * g.Rpad, rowc + (size_t)hg * g.Rpad, stat, tid);
+      if (tid == 0) __hip_atomic_store(&flag[hg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      if (tid == 0) {
+        // once any wait has timed out, later waits give up at once: the kernel always drains
+        int probes = 0;
+        while (__hip_atomic_load(&flag[hg], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+          if (++probes > SPIN_LIMIT || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+            __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+          }
+          __builtin_amdgcn_s_sleep(8);
+        }
+      }
+      __syncthreads();
+    }
+
+    // Memory operations retire in order, so anything waited for after the prefetch is issued
+    // would wait for the prefetch too: fetch the row constants first, then start the next unit's
+    // key rows; pass 2 itself issues no loads (Q stays in registers from pass 1).
+    float c0v = 0.f;
+    if (tid < NRT * 32 && tid < g.Rpad) c0v = coherent_get(rowc + (size_t)hg * g.Rpad + tid);
+    if (un < n_units) {
+      const int hn = un / g.nchunk, cn = un - hn * g.nchunk;
+      prefetch_chunk<D>(pre, k + (size_t)hn * g.L * D, cn * g.own - g.half, g.L, tid);
+    }
+    if (tid < NRT * 32) reinterpret_cast<float*>(smem + S::OFF_STAT)[tid] = c0v;
+    unit_pass2<D, NRT, true>(smem, g, qg, q0, rowc + (size_t)hg * g.Rpad, true, j0, tid, lane, wave,
+                             scores + (size_t)hg * g.L);
+    __syncthreads();                      // every wave is done with this chunk's rows
+    if (un < n_units) commit_chunk<D>(smem, pre, tid);
+    __syncthreads();
+  }
+}
+
+__global__ void reset_sync_kernel(int* sync, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) sync[i] = 0;
+}
+
+template <int D, int NRT>
+hipError_t launch_fused(const ScoreGeom& g, const uint16_t* q, const uint16_t* k, float* scores,
+                        const Workspace& ws, hipStream_t st) {
+  constexpr int bytes = Smem<D, NRT>::BYTES;
+  static int resident = 0;                 // workgroups the device holds at once (queried once)
+  const void* fn = reinterpret_cast<const void*>(&score_fused_kernel<D, NRT>);
+  if (resident == 0) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    int dev = 0, cus = 0, per_cu = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, THREADS, bytes)) != hipSuccess) return e;
+    if (cus < 1 || per_cu < 1) return hipErrorInvalidValue;
+    resident = cus * per_cu;
+  }
+  const int n_heads = g.n_inst * g.Hkv;
+  const long long n_units_ll = (long long)n_heads * g.nchunk;
+  if (n_units_ll > 0x7fffffffLL) return hipErrorInvalidValue;
+  const int n_units = (int)n_units_ll;
+  if (g.nchunk > resident) {
+    // A head with more chunks than resident workgroups would make a workgroup wait for its own
+    // later unit: such (very long) sequences take the two-kernel route, which reads K twice.
+    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&stats_mfma_kernel<D, NRT>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e2 != hipSuccess) return e2;
+    e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&norm_mfma_kernel<D, NRT>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e2 != hipSuccess) return e2;
+    dim3 grid2(g.nchunk, g.Hkv, g.n_inst), block2(THREADS);
+    hipLaunchKernelGGL((stats_mfma_kernel<D, NRT>), grid2, block2, bytes, st, g, q, k, ws.part);
+    if ((e2 = hipGetLastError()) != hipSuccess) return e2;
+    if ((e2 = launch_row_constants(g, ws, st)) != hipSuccess) return e2;
+    hipLaunchKernelGGL((norm_mfma_kernel<D, NRT>), grid2, block2, bytes, st, g, q, k, ws.rowc, scores);
+    return hipGetLastError();
+  }
+  const int n_sync = 2 * n_heads + 1;
+  hipLaunchKernelGGL(reset_sync_kernel, dim3((n_sync + 255) / 256), dim3(256), 0, st, ws.sync, n_sync);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = launch_row_constants(g, ws, st);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((norm_mfma_kernel<D, NRT>), grid, block, bytes, st, g, q, k, ws.rowc, scores);
+  const int grid = n_units < resident ? n_units : resident;
+  hipLaunchKernelGGL((score_fused_kernel<D, NRT>), dim3(grid), dim3(THREADS), bytes, st, g, q, k, ws.part, ws.rowc,
+                     ws.sync, scores, n_units);
   return hipGetLastError();
 }
 
@@ -311,9 +673,9 @@ template <int D>
 hipError_t launch_for_rows(const ScoreGeom& g, const uint16_t* q, const uint16_t* k, float* scores,
                            const Workspace& ws, hipStream_t st) {
   const int ntile = g.Rpad / 32;
-  if (ntile == 1) return launch_pair<D, 1>(g, q, k, scores, ws, st);
-  if (ntile == 2) return launch_pair<D, 2>(g, q, k, scores, ws, st);
-  return launch_pair<D, 4>(g, q, k, scores, ws, st);
+  if (ntile == 1) return launch_fused<D, 1>(g, q, k, scores, ws, st);
+  if (ntile == 2) return launch_fused<D, 2>(g, q, k, scores, ws, st);
+  return launch_fused<D, 4>(g, q, k, scores, ws, st);
 }
 
 }  // namespace

@@ -183,6 +183,16 @@ def test_edge_cases(laq, name, dtype, Hq, Hkv, d, L, W, pool, budget):
     run_and_check(laq, q, k, v, [budget, max(W, budget - 3)], pool, name)
 
 
+def test_very_long_sequence_takes_two_kernel_route(laq):
+    # more chunks per head than resident workgroups (L > 128000): the single-read kernel does not apply
+    g = torch.Generator().manual_seed(77)
+    Hq, Hkv, d, L, W = 4, 1, 128, 131072 + 40, 8
+    q = torch.randn(1, Hq, W, d, generator=g).bfloat16().to(DEV)
+    k = torch.randn(1, Hkv, L, d, generator=g).bfloat16().to(DEV)
+    v = torch.randn(1, Hkv, L, d, generator=g).bfloat16().to(DEV)
+    run_and_check(laq, q, k, v, [1024], 7, "L131k")
+
+
 def test_per_instance_budgets_pack_correctly(laq):
     cfg = dataclasses.replace(CONFIGS[4], L=2048, n_layer=5)
     q, k, v, budgets, _ = make_batch(cfg, device=DEV)
