@@ -75,10 +75,8 @@ size_t laq_workspace_bytes(const laq_shape *shape);
  *          With pool_kernel == 1 scores = raw.  With an odd pool_kernel p > 1 the prefix
  *          columns hold max(raw[g,i] : |i-j| <= (p-1)/2, 0 <= i < P) (the sequence pooling
  *          of the observation-window procedure, Sec. 2.1 / 5.1) and the W window columns
- *          keep raw.  Max is exact, so a pooled plateau consists of bit-identical values
- *          whether the pooling is done here or in laq_select.  (Raw scores of two calls with
- *          different pool_kernel may differ in the last bits: the softmax statistics are
- *          grouped by key chunk and the chunk size depends on the pooling halo.)
+ *          keep raw.  Max is exact and the raw scores do not depend on pool_kernel, so
+ *          laq_score(p) + laq_select(1) and laq_score(1) + laq_select(p) give the same indices.
  *   ws / ws_bytes  device scratch of at least laq_workspace_bytes(shape)
  * Supported: dtype BF16 or F32; any Hq/Hkv/W/L within the limits of laq_shape;
  * pool_kernel odd, 1 <= pool_kernel <= 63.
@@ -112,8 +110,10 @@ int laq_compact(const laq_shape *shape, const void *k, const void *v, const int3
                 const int32_t *budget, void *k_out, void *v_out, void *stream);
 
 /*
- * laq_score (pooling fused) + laq_select + laq_compact on one stream; identical outputs.
- * `scores` is required (it is the hand-over buffer between the stages).
+ * The whole path on one stream: laq_score(1) + laq_select(pool_kernel) + laq_compact, i.e. the
+ * pooling is applied while the selection loads the scores.  idx, k_out and v_out are identical
+ * to those of the three calls in either order of pooling; `scores` (required: it is the hand-over
+ * buffer between the stages) is left holding the RAW, unpooled scores.
  */
 int laq_evict(const laq_shape *shape, const void *q_win, const void *k, const void *v,
               const int32_t *budget, int pool_kernel, float *scores, int32_t *idx,

@@ -7,44 +7,44 @@
 
 namespace laq {
 
-static bool make_geom(const laq_shape* s, int pool, ScoreGeom* g) {
+static bool pool_ok(int pool) { return pool >= 1 && pool <= MAX_POOL && (pool % 2) == 1; }
+
+static bool make_geom(const laq_shape* s, ScoreGeom* g) {
   if (!s) return false;
   if (s->n_inst < 1 || s->Hq < 1 || s->Hkv < 1 || s->d < 8 || s->d > 256 || (s->d % 8) != 0) return false;
   if (s->L < 1 || s->W < 1 || s->W > s->L || (s->Hq % s->Hkv) != 0) return false;
   if (s->dtype != LAQ_F32 && s->dtype != LAQ_BF16) return false;
-  if (pool < 1 || pool > MAX_POOL || (pool % 2) == 0) return false;
   if (!(s->scale == s->scale) || isinf(s->scale)) return false;
   g->n_inst = s->n_inst; g->Hq = s->Hq; g->Hkv = s->Hkv; g->d = s->d; g->L = s->L; g->W = s->W;
   g->G = s->Hq / s->Hkv;
   g->R = g->G * s->W;
   g->P = s->L - s->W;
   g->Rpad = (g->R + 31) / 32 * 32;
-  g->pool = pool;
-  g->half = (pool - 1) / 2;
-  g->own = CHUNK_ROWS - 2 * g->half;
-  g->nchunk = (s->L + g->own - 1) / g->own;
+  g->nchunk = (s->L + CHUNK_ROWS - 1) / CHUNK_ROWS;
   const float sc = s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d);
   g->scale2 = sc * 1.44269504088896340736f;
   return true;
 }
 
+static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
 size_t workspace_bytes(const ScoreGeom& g) {
   const size_t heads = (size_t)g.n_inst * g.Hkv;
-  size_t part = heads * g.nchunk * g.Rpad * sizeof(float2);
-  size_t rowc = heads * g.Rpad * sizeof(float);
-  size_t sync = (2 * heads + 1) * sizeof(int);
-  return ((part + 255) & ~(size_t)255) + ((rowc + 255) & ~(size_t)255) + ((sync + 255) & ~(size_t)255);
+  return round256(heads * g.nchunk * g.Rpad * sizeof(float2)) + round256(heads * g.Rpad * sizeof(float)) +
+         round256((2 * heads + 1) * sizeof(int)) + round256(heads * g.L * sizeof(float));
 }
 
 Workspace carve_workspace(const ScoreGeom& g, void* ws) {
   const size_t heads = (size_t)g.n_inst * g.Hkv;
-  size_t part = heads * g.nchunk * g.Rpad * sizeof(float2);
-  Workspace w;
-  w.part = static_cast<float2*>(ws);
-  size_t rowc = heads * g.Rpad * sizeof(float);
   char* base = static_cast<char*>(ws);
-  w.rowc = reinterpret_cast<float*>(base + ((part + 255) & ~(size_t)255));
-  w.sync = reinterpret_cast<int*>(base + ((part + 255) & ~(size_t)255) + ((rowc + 255) & ~(size_t)255));
+  Workspace w;
+  w.part = reinterpret_cast<float2*>(base);
+  base += round256(heads * g.nchunk * g.Rpad * sizeof(float2));
+  w.rowc = reinterpret_cast<float*>(base);
+  base += round256(heads * g.Rpad * sizeof(float));
+  w.sync = reinterpret_cast<int*>(base);
+  base += round256((2 * heads + 1) * sizeof(int));
+  w.raw = reinterpret_cast<float*>(base);
   return w;
 }
 
@@ -71,23 +71,28 @@ static bool budgets_ok(const laq_shape* s, const int32_t* budget) {
   return true;
 }
 
+// Raw (unpooled) scores into `raw`; with fuse_pool the pooled scores go to `scores` and the
+// raw ones to the workspace.
 static int score_impl(const laq_shape* shape, const void* q_win, const void* k, int pool, float* scores,
                       void* ws, size_t ws_bytes, hipStream_t st) {
   ScoreGeom g;
-  if (!make_geom(shape, pool, &g) || !q_win || !k || !scores) return LAQ_ERR_INVALID;
+  if (!make_geom(shape, &g) || !pool_ok(pool) || !q_win || !k || !scores) return LAQ_ERR_INVALID;
   if (!ws || ws_bytes < workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
-  if (g.Hkv > 65535 || g.n_inst > 65535) return LAQ_ERR_UNSUPPORTED;   // grid y / z limits
+  if (g.Hkv > 65535 || g.n_inst > 65535 || (long long)g.Hkv * g.n_inst > 0x7fffffffLL) return LAQ_ERR_UNSUPPORTED;
   const Workspace w = carve_workspace(g, ws);
+  float* raw = pool > 1 ? w.raw : scores;
   hipError_t e = score_mfma_supported(g, shape->dtype)
-                     ? launch_score_mfma(g, q_win, k, scores, w, st)
-                     : launch_score_generic(g, shape->dtype, q_win, k, scores, w, st);
+                     ? launch_score_mfma(g, q_win, k, raw, w, st)
+                     : launch_score_generic(g, shape->dtype, q_win, k, raw, w, st);
+  if (e == hipSuccess && pool > 1) e = launch_pool(g, pool, raw, scores, st);
   return e == hipSuccess ? LAQ_OK : LAQ_ERR_DEVICE;
 }
 
 static int select_impl(const laq_shape* shape, const float* scores, const int32_t* budget, int pool,
                        int32_t* idx, hipStream_t st) {
   ScoreGeom g;
-  if (!make_geom(shape, pool, &g) || !scores || !idx || !budgets_ok(shape, budget)) return LAQ_ERR_INVALID;
+  if (!make_geom(shape, &g) || !pool_ok(pool) || !scores || !idx || !budgets_ok(shape, budget))
+    return LAQ_ERR_INVALID;
   if (g.Hkv > 65535) return LAQ_ERR_UNSUPPORTED;
   int64_t row = 0;
   for (int i0 = 0; i0 < shape->n_inst; i0 += MAX_INST_PER_LAUNCH) {
@@ -103,7 +108,7 @@ static int select_impl(const laq_shape* shape, const float* scores, const int32_
 static int compact_impl(const laq_shape* shape, const void* k, const void* v, const int32_t* idx,
                         const int32_t* budget, void* k_out, void* v_out, hipStream_t st) {
   ScoreGeom g;
-  if (!make_geom(shape, 1, &g) || !k || !k_out || !idx || !budgets_ok(shape, budget)) return LAQ_ERR_INVALID;
+  if (!make_geom(shape, &g) || !k || !k_out || !idx || !budgets_ok(shape, budget)) return LAQ_ERR_INVALID;
   if ((v == nullptr) != (v_out == nullptr)) return LAQ_ERR_INVALID;
   const int row_bytes = g.d * (shape->dtype == LAQ_F32 ? 4 : 2);
   int64_t row = 0;
@@ -124,8 +129,7 @@ extern "C" {
 
 size_t laq_workspace_bytes(const laq_shape* shape) {
   laq::ScoreGeom g;
-  // the largest pooling kernel gives the most chunks, so this bound serves every pool_kernel
-  if (!laq::make_geom(shape, laq::MAX_POOL, &g)) return 0;
+  if (!laq::make_geom(shape, &g)) return 0;
   return laq::workspace_bytes(g);
 }
 
@@ -149,14 +153,16 @@ int laq_evict(const laq_shape* shape, const void* q_win, const void* k, const vo
               size_t ws_bytes, void* stream) {
   // validate everything first so that a rejected call has enqueued nothing
   laq::ScoreGeom g;
-  if (!laq::make_geom(shape, pool_kernel, &g) || !q_win || !k || !scores || !idx || !k_out ||
+  if (!laq::make_geom(shape, &g) || !laq::pool_ok(pool_kernel) || !q_win || !k || !scores || !idx || !k_out ||
       !laq::budgets_ok(shape, budget) || ((v == nullptr) != (v_out == nullptr)))
     return LAQ_ERR_INVALID;
   if (!ws || ws_bytes < laq::workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  int rc = laq::score_impl(shape, q_win, k, pool_kernel, scores, ws, ws_bytes, st);
+  // raw scores, then selection with the pooling applied while the scores are loaded: the pooled
+  // values (exact maxima of the same raw scores) equal those laq_score(pool_kernel) would write
+  int rc = laq::score_impl(shape, q_win, k, 1, scores, ws, ws_bytes, st);
   if (rc != LAQ_OK) return rc;
-  rc = laq::select_impl(shape, scores, budget, 1, idx, st);
+  rc = laq::select_impl(shape, scores, budget, pool_kernel, idx, st);
   if (rc != LAQ_OK) return rc;
   return laq::compact_impl(shape, k, v, idx, budget, k_out, v_out, st);
 }

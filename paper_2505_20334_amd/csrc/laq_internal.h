@@ -10,14 +10,8 @@
 
 namespace laq {
 
-// ---------------------------------------------------------------------------
-// Chunk geometry of the scoring kernels.
-//
-// Each workgroup stages CHUNK_ROWS consecutive key rows in LDS.  With a pooling
-// kernel p the first and last (p-1)/2 staged rows are a halo: the group computes
-// their raw score (so that the pooled value of every owned key is local) but the
-// softmax statistics count only the owned rows, so every key is counted once.
-// ---------------------------------------------------------------------------
+// Each scoring workgroup stages CHUNK_ROWS consecutive key rows of one KV head; a head is
+// covered by nchunk = ceil(L / CHUNK_ROWS) chunks.
 constexpr int CHUNK_ROWS = 256;
 constexpr int MAX_POOL = 63;
 constexpr int MAX_INST_PER_LAUNCH = 256;   // size of the per-instance tables passed as kernel arguments
@@ -26,21 +20,21 @@ struct ScoreGeom {
   int n_inst, Hq, Hkv, d, L, W;
   int G, R, P;
   int Rpad;      // R rounded up to a multiple of 32
-  int half;      // (pool - 1) / 2
-  int own;       // keys owned per chunk = CHUNK_ROWS - 2 * half
-  int nchunk;    // ceil(L / own)
-  int pool;
+  int nchunk;    // ceil(L / CHUNK_ROWS)
   float scale2;  // scale * log2(e): logits are kept in base-2 units
 };
 
-// Workspace carving: [partials | row constants | sync words]
-//   partials: float2 (m, z) per (instance, KV head, chunk, padded row)
-//   rowc:     float c = m + log2(z) per (instance, KV head, padded row)
-//   sync:     int arrival counter per head, int ready flag per head, one int error word
+// Workspace carving: [partials | row constants | sync words | raw scores]
+//   part:  float2 (m, z) per (instance, KV head, chunk, padded row): softmax statistics of a chunk
+//   rowc:  float c = M + log2(Z) per (instance, KV head, padded row)
+//   sync:  two arrival counters per (instance, KV head), then one int that is set if a bounded
+//          wait inside the fused kernel ever timed out
+//   raw:   float per (instance, KV head, key): unpooled scores, used when pooling is requested
 struct Workspace {
   float2* part;
   float* rowc;
   int* sync;
+  float* raw;
 };
 
 size_t workspace_bytes(const ScoreGeom& g);
@@ -49,20 +43,21 @@ Workspace carve_workspace(const ScoreGeom& g, void* ws);
 // Per-instance output table for select / compact (passed by value as a kernel argument).
 struct InstTable {
   int32_t bk[MAX_INST_PER_LAUNCH];      // rows kept per KV head
-  int64_t row0[MAX_INST_PER_LAUNCH];    // first packed output row (units of rows of idx, i.e. Hkv*Bk sums)
+  int64_t row0[MAX_INST_PER_LAUNCH];    // first packed output row (sum of Hkv * Bk of earlier instances)
 };
 
-// launchers (each returns hipGetLastError() after the launch)
-hipError_t launch_score_generic(const ScoreGeom& g, int dtype, const void* q, const void* k,
-                                float* scores, const Workspace& ws, hipStream_t st);
+// launchers (each returns hipGetLastError() after its last launch); `raw` receives unpooled scores
+hipError_t launch_score_generic(const ScoreGeom& g, int dtype, const void* q, const void* k, float* raw,
+                                const Workspace& ws, hipStream_t st);
 hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStream_t st);
 bool score_mfma_supported(const ScoreGeom& g, int dtype);
-hipError_t launch_score_mfma(const ScoreGeom& g, const void* q, const void* k, float* scores,
-                             const Workspace& ws, hipStream_t st);
-hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int W, int pool,
-                         const float* scores, const InstTable& tab, int32_t* idx, hipStream_t st);
-hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, int bk_max,
-                          const void* k, const void* v, const int32_t* idx, const InstTable& tab,
-                          void* k_out, void* v_out, hipStream_t st);
+hipError_t launch_score_mfma(const ScoreGeom& g, const void* q, const void* k, float* raw, const Workspace& ws,
+                             hipStream_t st);
+hipError_t launch_pool(const ScoreGeom& g, int pool, const float* raw, float* pooled, hipStream_t st);
+hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int W, int pool, const float* scores,
+                         const InstTable& tab, int32_t* idx, hipStream_t st);
+hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, int bk_max, const void* k,
+                          const void* v, const int32_t* idx, const InstTable& tab, void* k_out, void* v_out,
+                          hipStream_t st);
 
 }  // namespace laq

@@ -3,10 +3,9 @@
 // take (fewer than 16 score rows per KV head, unusual head sizes).
 //
 // Computes, per KV head, the window attention of Eq. 4's observation window in two
-// passes over the staged key chunk: (1) per-row softmax statistics of the chunk,
-// (2) after the statistics of all chunks are combined, the normalised sum over rows
-// and the sequence max-pool.  The combine step (row_constants_kernel) is shared with
-// the MFMA path.
+// passes over the keys: (1) per-row softmax statistics of each 256-key chunk,
+// (2) after the statistics of all chunks are combined (row_constants_kernel), the
+// normalised sum over rows.  Also here: the sequence max-pool over raw scores.
 #include "laq_internal.h"
 
 namespace laq {
@@ -36,7 +35,7 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// One workgroup per (chunk, KV head, instance); thread t owns staged row t.
+// One workgroup per (chunk, KV head, instance); thread t owns key chunk * 256 + t.
 template <typename T>
 __global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, const T* __restrict__ q,
                                                                    const T* __restrict__ k,
@@ -44,8 +43,8 @@ __global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, 
   __shared__ float red[4];
   const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int j = chunk * g.own - g.half + t;
-  const bool owned = (t >= g.half) && (t < CHUNK_ROWS - g.half) && (j >= 0) && (j < g.L);
+  const int j = chunk * CHUNK_ROWS + t;
+  const bool owned = j < g.L;
   const T* krow = k + (((size_t)inst * g.Hkv + head) * g.L + (owned ? j : 0)) * g.d;
   const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d;
   float2* out = part + (((size_t)inst * g.Hkv + head) * g.nchunk + chunk) * g.Rpad;
@@ -68,41 +67,37 @@ __global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, 
   }
 }
 
-// Thread t of the group computes the raw score of staged row t, then the group pools.
 template <typename T>
 __global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, const T* __restrict__ q,
                                                                   const T* __restrict__ k,
                                                                   const float* __restrict__ rowc,
-                                                                  float* __restrict__ scores) {
-  __shared__ float raw[CHUNK_ROWS];
+                                                                  float* __restrict__ raw) {
   const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
-  const int t = threadIdx.x;
-  const int j0 = chunk * g.own - g.half;
-  const int j = j0 + t;
-  const bool in_range = (j >= 0) && (j < g.L);
-  const T* krow = k + (((size_t)inst * g.Hkv + head) * g.L + (in_range ? j : 0)) * g.d;
+  const int j = chunk * CHUNK_ROWS + threadIdx.x;
+  if (j >= g.L) return;
+  const T* krow = k + (((size_t)inst * g.Hkv + head) * g.L + j) * g.d;
   const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d;
   const float* c = rowc + ((size_t)inst * g.Hkv + head) * g.Rpad;
-
   float acc = 0.f;
-  if (in_range) {
-    for (int r = 0; r < g.R; ++r) {
-      const int w = r % g.W;
-      if (j <= g.P + w) acc += exp2f(g.scale2 * dot_row(qg + (size_t)r * g.d, krow, g.d) - c[r]);
-    }
+  for (int r = 0; r < g.R; ++r) {
+    const int w = r % g.W;
+    if (j <= g.P + w) acc += exp2f(g.scale2 * dot_row(qg + (size_t)r * g.d, krow, g.d) - c[r]);
   }
-  raw[t] = acc;
-  __syncthreads();
+  raw[((size_t)inst * g.Hkv + head) * g.L + j] = acc;
+}
 
-  if (t >= g.half && t < CHUNK_ROWS - g.half && in_range) {
-    float v = acc;
-    if (j < g.P) {
-      int lo = max(j - g.half, 0) - j0, hi = min(j + g.half, g.P - 1) - j0;
-      v = raw[lo];
-      for (int i = lo + 1; i <= hi; ++i) v = fmaxf(v, raw[i]);
-    }
-    scores[((size_t)inst * g.Hkv + head) * g.L + j] = v;
+// pooled[j] = max(raw[i] : |i - j| <= half, 0 <= i < P) for prefix keys; window columns are copied
+__global__ __launch_bounds__(256) void pool_kernel(int L, int P, int half, const float* __restrict__ raw,
+                                                   float* __restrict__ pooled) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= L) return;
+  const float* r = raw + (size_t)blockIdx.y * L;
+  float v = r[j];
+  if (j < P) {
+    const int lo = max(j - half, 0), hi = min(j + half, P - 1);
+    for (int i = lo; i <= hi; ++i) v = fmaxf(v, r[i]);
   }
+  pooled[(size_t)blockIdx.y * L + j] = v;
 }
 
 }  // namespace
@@ -133,7 +128,13 @@ hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStre
   return hipGetLastError();
 }
 
-hipError_t launch_score_generic(const ScoreGeom& g, int dtype, const void* q, const void* k, float* scores,
+hipError_t launch_pool(const ScoreGeom& g, int pool, const float* raw, float* pooled, hipStream_t st) {
+  dim3 grid((g.L + 255) / 256, g.n_inst * g.Hkv);
+  hipLaunchKernelGGL(pool_kernel, grid, dim3(256), 0, st, g.L, g.P, (pool - 1) / 2, raw, pooled);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_generic(const ScoreGeom& g, int dtype, const void* q, const void* k, float* raw,
                                 const Workspace& ws, hipStream_t st) {
   dim3 grid(g.nchunk, g.Hkv, g.n_inst), block(CHUNK_ROWS);
   if (dtype == LAQ_F32) {
@@ -149,10 +150,10 @@ hipError_t launch_score_generic(const ScoreGeom& g, int dtype, const void* q, co
   if (e != hipSuccess) return e;
   if (dtype == LAQ_F32) {
     hipLaunchKernelGGL(norm_generic_kernel<float>, grid, block, 0, st, g, (const float*)q, (const float*)k,
-                       ws.rowc, scores);
+                       ws.rowc, raw);
   } else {
     hipLaunchKernelGGL(norm_generic_kernel<uint16_t>, grid, block, 0, st, g, (const uint16_t*)q,
-                       (const uint16_t*)k, ws.rowc, scores);
+                       (const uint16_t*)k, ws.rowc, raw);
   }
   return hipGetLastError();
 }

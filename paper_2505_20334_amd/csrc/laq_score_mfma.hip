@@ -2,22 +2,24 @@
 //
 // For one KV head the logits of Eq. 4's observation window form a skinny product
 // S = Q_g K^T with R = G*W rows (the group's query heads x the cached window queries)
-// and L columns.  A workgroup stages CHUNK_ROWS key rows in LDS (128-bit coalesced
-// global loads, each key row read once per kernel) and walks them in 32-key tiles:
+// and L columns.  A workgroup of four waves holds CHUNK_ROWS key rows in LDS and walks
+// them in 32-key tiles:
 //
 //   pass 1 (statistics):  D = K_tile * Q^T, so a lane owns one score row and 16 keys of
 //           the tile; it keeps a running (max, sum-exp) for its row.  The two lanes that
 //           share a row and the waves that share a row tile are merged through LDS and the
-//           chunk's (m, z) per row goes to the workspace.
-//   pass 2 (normalise + sum + pool): D = Q * K_tile^T, so a lane owns one key and 16 rows;
-//           with the row constants c = M + log2 Z the probabilities exp2(s - c) are summed
-//           over the rows in-lane, across the two lane halves with one cross-lane add and
-//           across row tiles through LDS.  The chunk's raw scores (including a halo of
-//           (pool-1)/2 keys on each side) are max-pooled in LDS and the owned keys written.
+//           chunk's (m, z) per row is published.
+//   pass 2 (normalise + sum): D = Q * K_tile^T, so a lane owns one key and 16 rows; with the
+//           row constants c = M + log2 Z the probabilities exp2(s - c) are summed over the rows
+//           in-lane, across the two lane halves with one cross-lane add and across row tiles
+//           through LDS, and the raw score of every key of the chunk is written.
 //
 // The A and B operands of the 32x32x16 instruction have the same lane layout (lane l
 // supplies row/column l%32 and the 8 consecutive reduction elements l/32), so the same
 // registers serve both passes with the operands swapped.
+//
+// The fused kernel keeps a chunk's keys in LDS from pass 1 to pass 2, so K is read from HBM
+// once; the chunks of a head exchange their statistics in between (see below).
 #include "laq_internal.h"
 
 namespace laq {
@@ -45,26 +47,30 @@ template <int D> struct Tile {
 template <int D, int NRT> struct Smem {
   static constexpr int OFF_STAT = Tile<D>::K_BYTES;                    // float2[THREADS]
   static constexpr int OFF_SLOT = OFF_STAT + THREADS * 8;              // float[NRT][CHUNK_ROWS]
-  static constexpr int OFF_RAW = OFF_SLOT + NRT * CHUNK_ROWS * 4;      // float[CHUNK_ROWS]
-  static constexpr int BYTES = OFF_RAW + CHUNK_ROWS * 4;
+  static constexpr int BYTES = OFF_SLOT + NRT * CHUNK_ROWS * 4;
 };
 
-// Stage rows j0 .. j0+CHUNK_ROWS-1 of one KV head's key matrix; rows outside [0, L) are zero.
+#define LAQ_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Key rows j0 .. j0+CHUNK_ROWS-1 of one head into registers (128-bit coalesced loads), then
+// into LDS.  Rows beyond L-1 repeat row L-1: they are masked out of the statistics and their
+// scores are never written.
 template <int D>
-__device__ __forceinline__ void stage_chunk(char* ldsK, const uint16_t* __restrict__ khead, int j0, int L,
-                                            int tid) {
+__device__ __forceinline__ void fetch_chunk(uint4 (&buf)[Tile<D>::PIECES_PER_THREAD],
+                                            const uint16_t* __restrict__ khead, int j0, int L, int tid) {
   using T = Tile<D>;
-  uint4 buf[T::PIECES_PER_THREAD];
 #pragma unroll
   for (int it = 0; it < T::PIECES_PER_THREAD; ++it) {
     const int p = tid + THREADS * it;
     const int row = p / T::PIECES_PER_ROW, col = p % T::PIECES_PER_ROW;
-    const int j = j0 + row;
-    if (j >= 0 && j < L)
-      buf[it] = *reinterpret_cast<const uint4*>(khead + (size_t)j * D + col * 8);
-    else
-      buf[it] = make_uint4(0, 0, 0, 0);
+    const int j = min(j0 + row, L - 1);
+    buf[it] = *reinterpret_cast<const uint4*>(khead + (size_t)j * D + col * 8);
   }
+}
+
+template <int D>
+__device__ __forceinline__ void commit_chunk(char* ldsK, const uint4 (&buf)[Tile<D>::PIECES_PER_THREAD], int tid) {
+  using T = Tile<D>;
 #pragma unroll
   for (int it = 0; it < T::PIECES_PER_THREAD; ++it) {
     const int p = tid + THREADS * it;
@@ -86,6 +92,8 @@ __device__ __forceinline__ void load_q_tile(bf16x8 (&qreg)[Tile<D>::KSTEPS], con
   }
 }
 
+__device__ __forceinline__ bf16x8 lds_operand(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
 // acc = (KEYS_AS_ROWS ? K_tile * Q^T : Q * K_tile^T) + init over the whole head size.
 template <int D, bool KEYS_AS_ROWS>
 __device__ __forceinline__ f32x16 tile_product(const char* ldsK, int kt, int lane,
@@ -95,7 +103,7 @@ __device__ __forceinline__ f32x16 tile_product(const char* ldsK, int kt, int lan
   f32x16 acc = init;
 #pragma unroll
   for (int t = 0; t < T::KSTEPS; ++t) {
-    const bf16x8 kv = *reinterpret_cast<const bf16x8*>(p + t * 32);
+    const bf16x8 kv = lds_operand(p + t * 32);
     if (KEYS_AS_ROWS)
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, qreg[t], acc, 0, 0, 0);
     else
@@ -108,21 +116,10 @@ __device__ __forceinline__ f32x16 tile_product(const char* ldsK, int kt, int lan
 // groups of four consecutive rows alternate between the two lane halves).
 __device__ __forceinline__ int acc_row(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
 
-#define LAQ_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-
-__device__ __forceinline__ bf16x8 lds_operand(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
-
-// Initial accumulator values that take the halo rows of a chunk out of the statistics:
-// -inf for staged rows t < half (first tile) resp. t >= CHUNK_ROWS - half (last tile), else 0.
-// A wave whose tile range does not touch that end of the chunk gets all zeros.
-__device__ __forceinline__ void halo_bias(int half, int kt0, int kt1, int lane, f32x16& first, f32x16& last) {
-  const int hf = lane >> 5;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int r = acc_row(i, hf);
-    first[i] = (kt0 == 0 && r < half) ? -INFINITY : 0.f;
-    last[i] = (kt1 == KTILES && r >= 32 - half) ? -INFINITY : 0.f;
-  }
+__device__ __forceinline__ void merge_stat(float& M, float& Z, float2 p) {
+  const float Mn = fmaxf(M, p.x);
+  Z = Z * __builtin_amdgcn_exp2f(M - Mn) + p.y * __builtin_amdgcn_exp2f(p.x - Mn);
+  M = Mn;
 }
 
 // ---- software-pipelined passes for chunks without causally masked keys -----------------
@@ -132,8 +129,7 @@ __device__ __forceinline__ void halo_bias(int half, int kt0, int kt1, int lane, 
 // scheduling fences pin that interleaving.
 template <int D, int NT>
 __device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS], int kt0,
-                                           const f32x16& first_bias, const f32x16& last_bias, float scale2,
-                                           int lane, float& m_run, float& z_run) {
+                                           float scale2, int lane, float& m_run, float& z_run) {
   using T = Tile<D>;
   constexpr int KS = T::KSTEPS, N = NT * KS;
   const char* base = ldsK + (kt0 * 32 + (lane & 31)) * T::ROWB + (lane >> 5) * 16;
@@ -149,8 +145,7 @@ __device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg
       if (i < NT) {
         bf16x8 r2 = r0;
         if (n + 2 < N) r2 = lds_operand(base + ((n + 2) / KS) * 32 * T::ROWB + ((n + 2) % KS) * 32);
-        const f32x16 c = (t > 0) ? nxt : (i == 0 ? first_bias : (i == NT - 1 ? last_bias : zero));
-        nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r0, qreg[t], c, 0, 0, 0);
+        nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r0, qreg[t], (t > 0) ? nxt : zero, 0, 0, 0);
         r0 = r1;
         r1 = r2;
       }
@@ -226,27 +221,22 @@ __device__ __forceinline__ void pass2_pipe(const char* ldsK, const bf16x8 (&qreg
 }
 
 // ---- per-tile passes for chunks that touch the causal region (the last chunks of a head) ----
+// A masked logit enters as -inf through the accumulator's initial value.
 template <int D>
-__device__ __forceinline__ void pass1_wave(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS],
-                                           const ScoreGeom& g, int rt, int kt0, int kt1, int j0, int lane,
-                                           float& m_run, float& z_run) {
+__device__ __forceinline__ void pass1_masked(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS],
+                                             const ScoreGeom& g, int rt, int kt0, int kt1, int j0, int lane,
+                                             float& m_run, float& z_run) {
   const int hf = lane >> 5;
   const int w = (rt * 32 + (lane & 31)) % g.W;
-  // staged rows this lane's score row may count: owned by the chunk and causally visible
-  const int t_lo = g.half;
-  const int t_hi = min(CHUNK_ROWS - g.half - 1, g.P + w - j0);
+  const int t_hi = g.P + w - j0;          // last staged row this lane's score row may see
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int kt = kt0; kt < kt1; ++kt) {
     const int t0 = kt * 32;
-    const bool masked = (t0 < g.half) || (t0 + 31 > CHUNK_ROWS - g.half - 1) || (j0 + t0 + 31 > g.P);
     f32x16 acc;
-    if (masked) {
+    if (j0 + t0 + 31 > g.P) {
       f32x16 bias;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int t = t0 + acc_row(i, hf);
-        bias[i] = (t >= t_lo && t <= t_hi) ? 0.f : -INFINITY;
-      }
+      for (int i = 0; i < 16; ++i) bias[i] = (t0 + acc_row(i, hf) <= t_hi) ? 0.f : -INFINITY;
       acc = tile_product<D, true>(ldsK, kt, lane, qreg, bias);
     } else {
       acc = tile_product<D, true>(ldsK, kt, lane, qreg, zero);
@@ -263,17 +253,16 @@ __device__ __forceinline__ void pass1_wave(const char* ldsK, const bf16x8 (&qreg
   }
 }
 
-// c32: the row constants of this wave's 32-row tile
 template <int D>
-__device__ __forceinline__ void pass2_wave(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS],
-                                           const ScoreGeom& g, const float (&c)[16], int rt, int kt0, int kt1,
-                                           int j0, int lane, float* slotbuf) {
+__device__ __forceinline__ void pass2_masked(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS],
+                                             const ScoreGeom& g, const float (&c)[16], int rt, int kt0, int kt1,
+                                             int j0, int lane, float* slotbuf) {
   const int hf = lane >> 5, n = lane & 31;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int kt = kt0; kt < kt1; ++kt) {
     const int t0 = kt * 32;
     f32x16 acc;
-    if (j0 + t0 + 31 > g.P) {           // some key of the tile lies in the causal region
+    if (j0 + t0 + 31 > g.P) {
       f32x16 bias;
       const int j = j0 + t0 + n;
 #pragma unroll
@@ -296,35 +285,54 @@ __device__ __forceinline__ void pass2_wave(const char* ldsK, const bf16x8 (&qreg
 // ---- words that workgroups hand to each other -------------------------------------------
 // The fused kernel never relies on cache maintenance for them: agent-scope release/acquire
 // fences write back and invalidate the whole L2 on this part and cost tens of microseconds
-// each.  Instead every such word is written with a *returning* agent-scope atomic exchange
-// (its return means it has been performed at the device-coherent level), the workgroup barrier
-// then orders those exchanges before the arrival counter / flag update, and readers use
-// agent-scope atomic loads.
-__device__ __forceinline__ void coherent_put(float2* p, float2 v) {
+// each.  Instead each word is its own "ready" flag: it is written with one agent-scope atomic
+// store and read with agent-scope atomic loads until its pattern says it is there.
+//   reset kernel:        (NaN, NaN)   nothing yet
+//   chunk's statistics:  (m, z)       both numbers
+//   head's row constant: (c, NaN)     written by the head's last-arriving workgroup over
+//                                     every chunk's copy of the row
+// Nobody polls a word that many others poll: 128 workgroups reading one address in a loop make
+// its memory channel a hot spot that stalls the whole key stream behind it.  A workgroup only
+// polls its own chunk's words; the one shared word per head is an arrival counter that each
+// workgroup bumps exactly once (returning add, not polled).
+constexpr int SPIN_LIMIT = 1 << 20;   // probes; about a second, far beyond any legitimate wait
+
+__device__ __forceinline__ void coherent_store(float2* p, float2 v) {
   const unsigned long long bits = ((unsigned long long)__float_as_uint(v.y) << 32) | __float_as_uint(v.x);
-  const unsigned long long old = __hip_atomic_exchange(reinterpret_cast<unsigned long long*>(p), bits,
-                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  asm volatile("" ::"v"(old));   // keep the exchange in its returning form
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void coherent_put(float* p, float v) {
-  const unsigned old = __hip_atomic_exchange(reinterpret_cast<unsigned*>(p), __float_as_uint(v), __ATOMIC_RELAXED,
-                                             __HIP_MEMORY_SCOPE_AGENT);
-  asm volatile("" ::"v"(old));
-}
-__device__ __forceinline__ float2 coherent_get(const float2* p) {
+__device__ __forceinline__ float2 coherent_load(const float2* p) {
   const unsigned long long b = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
                                                  __HIP_MEMORY_SCOPE_AGENT);
   return make_float2(__uint_as_float((unsigned)b), __uint_as_float((unsigned)(b >> 32)));
 }
-__device__ __forceinline__ float coherent_get(const float* p) {
-  return __uint_as_float(__hip_atomic_load(reinterpret_cast<const unsigned*>(p), __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT));
+__device__ __forceinline__ bool wait_failed(int probes, int* err) {
+  // Every wait is bounded; once one has timed out, all later waits give up after a few probes,
+  // so the kernel always drains.
+  if (probes > SPIN_LIMIT ||
+      ((probes & 63) == 63 && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+    __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+  }
+  return false;
 }
-
-__device__ __forceinline__ void merge_stat(float& M, float& Z, float2 p) {
-  const float Mn = fmaxf(M, p.x);
-  Z = Z * __builtin_amdgcn_exp2f(M - Mn) + p.y * __builtin_amdgcn_exp2f(p.x - Mn);
-  M = Mn;
+// (m, z) of a chunk, once both are numbers
+__device__ __forceinline__ float2 await_stat(const float2* p, int* err) {
+  for (int probes = 0;; ++probes) {
+    const float2 v = coherent_load(p);
+    if (v.y == v.y && v.x == v.x) return v;
+    if (wait_failed(probes, err)) return make_float2(NEG_BIG, 0.f);
+    __builtin_amdgcn_s_sleep(4);
+  }
+}
+// the row constant that the head's last arriver writes over this chunk's copy of the row
+__device__ __forceinline__ float await_const(const float2* p, int* err) {
+  for (int probes = 0;; ++probes) {
+    const float2 v = coherent_load(p);
+    if (v.y != v.y && v.x == v.x) return v.x;
+    if (wait_failed(probes, err)) return 1.0e30f;
+    __builtin_amdgcn_s_sleep(16);
+  }
 }
 
 // ---- one (head, chunk) unit ---------------------------------------------------------------
@@ -340,8 +348,6 @@ __device__ __forceinline__ void unit_pass1(char* smem, const ScoreGeom& g, const
   const int slot = wave % NRT, ks = wave / NRT;
   const int ntile = g.Rpad / 32;
   const bool plain_chunk = (j0 + CHUNK_ROWS - 1 <= g.P);    // no key beyond the prefix: no causal mask
-  f32x16 first_bias, last_bias;
-  halo_bias(g.half, ks * TPW, ks * TPW + TPW, lane, first_bias, last_bias);
   for (int rg = 0; rg * NRT < ntile; ++rg) {
     const int rt = rg * NRT + slot;
     float m_run = NEG_BIG, z_run = 0.f;
@@ -354,9 +360,9 @@ __device__ __forceinline__ void unit_pass1(char* smem, const ScoreGeom& g, const
         load_q_tile<D>(qreg, qg, rt, g.R, lane);
       }
       if (plain_chunk)
-        pass1_pipe<D, TPW>(smem, qreg, ks * TPW, first_bias, last_bias, g.scale2, lane, m_run, z_run);
+        pass1_pipe<D, TPW>(smem, qreg, ks * TPW, g.scale2, lane, m_run, z_run);
       else
-        pass1_wave<D>(smem, qreg, g, rt, ks * TPW, ks * TPW + TPW, j0, lane, m_run, z_run);
+        pass1_masked<D>(smem, qreg, g, rt, ks * TPW, ks * TPW + TPW, j0, lane, m_run, z_run);
     }
     stat[tid] = make_float2(m_run, z_run);
     __syncthreads();
@@ -371,7 +377,7 @@ __device__ __forceinline__ void unit_pass1(char* smem, const ScoreGeom& g, const
           merge_stat(M, Z, stat[wv * 64 + 32 + n]);
         }
         if (COHERENT)
-          coherent_put(out + (rg * NRT + s) * 32 + n, make_float2(M, Z));
+          coherent_store(out + (rg * NRT + s) * 32 + n, make_float2(M, Z));
         else
           out[(rg * NRT + s) * 32 + n] = make_float2(M, Z);
       }
@@ -380,26 +386,30 @@ __device__ __forceinline__ void unit_pass1(char* smem, const ScoreGeom& g, const
   }
 }
 
-// Pass 2 over the staged chunk with the head's row constants c[0 .. Rpad): raw scores of all
-// staged rows, max-pool, owned rows written to scores_head.
-// If crow0_staged, the caller has already put the first row group's constants into the LDS slice.
+// Pass 2 over the staged chunk with the head's row constants c[0 .. Rpad): the raw score of
+// every key of the chunk is written to raw_head.  If crow0_staged, the caller has already put
+// the first row group's constants into the LDS slice.
 template <int D, int NRT, bool COHERENT>
 __device__ __forceinline__ void unit_pass2(char* smem, const ScoreGeom& g, const uint16_t* __restrict__ qg,
-                                           const bf16x8 (&q0)[Tile<D>::KSTEPS], const float* c, bool crow0_staged,
-                                           int j0, int tid, int lane, int wave, float* __restrict__ scores_head) {
+                                           const bf16x8 (&q0)[Tile<D>::KSTEPS], const float* c,
+                                           const float2* own_words, bool crow0_staged, int* err, int j0, int tid,
+                                           int lane, int wave, float* __restrict__ raw_head) {
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
   float* crow = reinterpret_cast<float*>(smem + S::OFF_STAT);      // row constants of the current row group
   float* slots = reinterpret_cast<float*>(smem + S::OFF_SLOT);
-  float* raw = reinterpret_cast<float*>(smem + S::OFF_RAW);
 #pragma unroll
   for (int s = 0; s < NRT; ++s) slots[s * CHUNK_ROWS + tid] = 0.f;
   const int slot = wave % NRT, ks = wave / NRT;
   const int ntile = g.Rpad / 32;
   for (int rg = 0; rg * NRT < ntile; ++rg) {
     if (rg > 0) __syncthreads();
-    if (!(rg == 0 && crow0_staged) && tid < NRT * 32 && rg * NRT * 32 + tid < g.Rpad)
-      crow[tid] = COHERENT ? coherent_get(c + rg * NRT * 32 + tid) : c[rg * NRT * 32 + tid];
+    if (!(rg == 0 && crow0_staged) && tid < NRT * 32) {
+      const int r = rg * NRT * 32 + tid;
+      float v = 1.0e30f;                                            // padded rows: probability 0
+      if (r < g.R) v = COHERENT ? await_const(own_words + r, err) : c[r];
+      crow[tid] = v;
+    }
     __syncthreads();
     const int rt = rg * NRT + slot;
     if (rt < ntile) {
@@ -416,24 +426,14 @@ __device__ __forceinline__ void unit_pass2(char* smem, const ScoreGeom& g, const
       if (j0 + CHUNK_ROWS - 1 <= g.P)
         pass2_pipe<D, TPW>(smem, qreg, ks * TPW, cr, g.scale2, lane, slots + slot * CHUNK_ROWS);
       else
-        pass2_wave<D>(smem, qreg, g, cr, rt, ks * TPW, ks * TPW + TPW, j0, lane, slots + slot * CHUNK_ROWS);
+        pass2_masked<D>(smem, qreg, g, cr, rt, ks * TPW, ks * TPW + TPW, j0, lane, slots + slot * CHUNK_ROWS);
     }
   }
   __syncthreads();
   float v = slots[tid];
 #pragma unroll
   for (int s = 1; s < NRT; ++s) v += slots[s * CHUNK_ROWS + tid];
-  raw[tid] = v;
-  __syncthreads();
-  const int j = j0 + tid;
-  if (tid >= g.half && tid < CHUNK_ROWS - g.half && j < g.L) {
-    if (j < g.P) {
-      const int lo = max(j - g.half, 0) - j0, hi = min(j + g.half, g.P - 1) - j0;
-      v = raw[lo];
-      for (int i = lo + 1; i <= hi; ++i) v = fmaxf(v, raw[i]);
-    }
-    scores_head[j] = v;
-  }
+  if (j0 + tid < g.L) raw_head[j0 + tid] = v;
 }
 
 // ---- two-kernel route (K read twice; for heads with more chunks than resident workgroups) ----
@@ -444,12 +444,14 @@ __global__ __launch_bounds__(THREADS) void stats_mfma_kernel(ScoreGeom g, const 
   extern __shared__ __align__(16) char smem[];
   const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int j0 = chunk * g.own - g.half;
+  const int j0 = chunk * CHUNK_ROWS;
   const size_t hg = (size_t)inst * g.Hkv + head;
   const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
   bf16x8 q0[Tile<D>::KSTEPS];
   load_q_tile<D>(q0, qg, wave % NRT, g.R, lane);
-  stage_chunk<D>(smem, k + hg * g.L * D, j0, g.L, tid);
+  uint4 buf[Tile<D>::PIECES_PER_THREAD];
+  fetch_chunk<D>(buf, k + hg * g.L * D, j0, g.L, tid);
+  commit_chunk<D>(smem, buf, tid);
   __syncthreads();
   unit_pass1<D, NRT, false>(smem, g, qg, q0, j0, tid, lane, wave, part + (hg * g.nchunk + chunk) * g.Rpad);
 }
@@ -458,109 +460,106 @@ template <int D, int NRT>
 __global__ __launch_bounds__(THREADS) void norm_mfma_kernel(ScoreGeom g, const uint16_t* __restrict__ q,
                                                             const uint16_t* __restrict__ k,
                                                             const float* __restrict__ rowc,
-                                                            float* __restrict__ scores) {
+                                                            float* __restrict__ raw) {
   extern __shared__ __align__(16) char smem[];
   const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int j0 = chunk * g.own - g.half;
+  const int j0 = chunk * CHUNK_ROWS;
   const size_t hg = (size_t)inst * g.Hkv + head;
   const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
   bf16x8 q0[Tile<D>::KSTEPS];
   load_q_tile<D>(q0, qg, wave % NRT, g.R, lane);
-  stage_chunk<D>(smem, k + hg * g.L * D, j0, g.L, tid);
+  uint4 buf[Tile<D>::PIECES_PER_THREAD];
+  fetch_chunk<D>(buf, k + hg * g.L * D, j0, g.L, tid);
+  commit_chunk<D>(smem, buf, tid);
   __syncthreads();
-  unit_pass2<D, NRT, false>(smem, g, qg, q0, rowc + hg * g.Rpad, false, j0, tid, lane, wave, scores + hg * g.L);
+  unit_pass2<D, NRT, false>(smem, g, qg, q0, rowc + hg * g.Rpad, nullptr, false, nullptr, j0, tid, lane, wave,
+                            raw + hg * g.L);
 }
 
 // ---- fused single-read kernel -----------------------------------------------------------
 // Persistent workgroups walk the list of (KV head, chunk) units in order, unit u going to
 // workgroup u mod gridDim.x.  A unit's key rows are read from HBM once: they stay in LDS from
-// pass 1 to pass 2.  Between the passes the chunks of a head meet at a per-head counter; the
-// workgroup that arrives last combines the per-chunk statistics into the row constants and
-// raises the head's flag, the others wait for the flag.  All workgroups of the grid are
-// resident at once (the grid is sized from the occupancy query), and a unit only ever waits
-// for units that come before it in the list, so every wait ends; the spin is bounded all the
-// same and records a timeout in the error word.  While a unit is being computed the key rows
-// of the workgroup's next unit are already on their way from HBM into registers.
+// pass 1 to pass 2.  Between the passes the chunks of a head meet: each workgroup publishes its
+// chunk's (m, z) per row and bumps the head's arrival counter; the one that arrives last
+// combines all chunks' statistics (fixed order, so the result does not depend on who does it)
+// and writes every row's constant over every chunk's copy of the row; the others wait for
+// their own copy to change.
+// All workgroups of the grid are resident at once (the grid is sized from the occupancy
+// query) and no head has more chunks than the grid has workgroups, so a unit only ever waits
+// for units that are in flight or earlier in their workgroups' lists: every wait ends.  The
+// spins are bounded all the same and record a timeout in the error word.
+// The next unit's key rows are requested as soon as the unit's own part of the exchange is
+// done, so they travel from HBM to registers while the head is combined and pass 2 runs.
 
-constexpr int SPIN_LIMIT = 1 << 20;   // x ~1 us per probe: about a second, far beyond any legitimate wait
-
-template <int D>
-__device__ __forceinline__ void prefetch_chunk(uint4 (&buf)[Tile<D>::PIECES_PER_THREAD],
-                                               const uint16_t* __restrict__ khead, int j0, int L, int tid) {
-  using T = Tile<D>;
-#pragma unroll
-  for (int it = 0; it < T::PIECES_PER_THREAD; ++it) {
-    const int p = tid + THREADS * it;
-    const int row = p / T::PIECES_PER_ROW, col = p % T::PIECES_PER_ROW;
-    const int j = min(max(j0 + row, 0), L - 1);     // rows outside [0, L) are never counted: any valid row will do
-    buf[it] = *reinterpret_cast<const uint4*>(khead + (size_t)j * D + col * 8);
-  }
-}
-
-template <int D>
-__device__ __forceinline__ void commit_chunk(char* ldsK, const uint4 (&buf)[Tile<D>::PIECES_PER_THREAD], int tid) {
-  using T = Tile<D>;
-#pragma unroll
-  for (int it = 0; it < T::PIECES_PER_THREAD; ++it) {
-    const int p = tid + THREADS * it;
-    const int row = p / T::PIECES_PER_ROW, col = p % T::PIECES_PER_ROW;
-    *reinterpret_cast<uint4*>(ldsK + row * T::ROWB + col * 16) = buf[it];
-  }
-}
-
-// Combine the (m, z) of all chunks of one head into c = M + log2 Z per score row (fixed order,
-// so the result does not depend on which workgroup does it).
-__device__ __forceinline__ void combine_head(const ScoreGeom& g, const float2* part_head, float* rowc_head,
-                                             float2* stat, int tid) {
+// All threads of the last-arriving workgroup: constants of rows [r0, r0 + rows) into crow_out
+// (LDS) and over the rows' copies in every chunk.
+__device__ __forceinline__ void combine_head(const ScoreGeom& g, float2* part_head, float2* stat, float* crow_all,
+                                             int* err, int tid) {
   for (int r0 = 0; r0 < g.Rpad; r0 += THREADS) {
     const int rows = min(THREADS, g.Rpad - r0);
     const int tpr = (THREADS % rows == 0) ? THREADS / rows : 1;      // threads sharing a row
     const int r = tid % rows, sel = tid / rows;
     float M = NEG_BIG, Z = 0.f;
-    if (sel < tpr) {
+    if (sel < tpr && r0 + r < g.R) {
       // loads go out in batches (they are independent); only the merges are sequential
-      constexpr int B = 24;
+      constexpr int B = 32;
       const float2* p = part_head + r0 + r;
       for (int c0 = sel; c0 < g.nchunk; c0 += B * tpr) {
         float2 buf[B];
 #pragma unroll
-        for (int b = 0; b < B; ++b) buf[b] = coherent_get(p + (size_t)min(c0 + b * tpr, g.nchunk - 1) * g.Rpad);
+        for (int b = 0; b < B; ++b) buf[b] = coherent_load(p + (size_t)min(c0 + b * tpr, g.nchunk - 1) * g.Rpad);
 #pragma unroll
-        for (int b = 0; b < B; ++b)
-          if (c0 + b * tpr < g.nchunk) merge_stat(M, Z, buf[b]);
+        for (int b = 0; b < B; ++b) {
+          if (c0 + b * tpr < g.nchunk) {
+            if (!(buf[b].y == buf[b].y && buf[b].x == buf[b].x))     // arrival counted before the store landed
+              buf[b] = await_stat(p + (size_t)(c0 + b * tpr) * g.Rpad, err);
+            merge_stat(M, Z, buf[b]);
+          }
+        }
       }
     }
     stat[tid] = make_float2(M, Z);
     __syncthreads();
     if (tid < rows) {
       for (int s2 = 1; s2 < tpr; ++s2) merge_stat(M, Z, stat[s2 * rows + tid]);
-      coherent_put(rowc_head + r0 + tid, (r0 + tid < g.R) ? M + __builtin_amdgcn_logf(Z) : 1.0e30f);
+      crow_all[r0 + tid] = (r0 + tid < g.R) ? M + __builtin_amdgcn_logf(Z) : 1.0e30f;
     }
     __syncthreads();
+    // hand the constants to every chunk of the head; row 0, the one word each waiting workgroup
+    // polls, goes last
+    const bool mine = sel < tpr && r0 + r < g.R;
+    const float cr = crow_all[min(r0 + r, g.Rpad - 1)];
+    if (mine && r0 + r != 0)
+      for (int c2 = sel; c2 < g.nchunk; c2 += tpr)
+        coherent_store(part_head + (size_t)c2 * g.Rpad + r0 + r, make_float2(cr, __uint_as_float(0x7FC00000u)));
+    __syncthreads();
+    if (mine && r0 + r == 0)
+      for (int c2 = sel; c2 < g.nchunk; c2 += tpr)
+        coherent_store(part_head + (size_t)c2 * g.Rpad, make_float2(cr, __uint_as_float(0x7FC00000u)));
   }
 }
 
 template <int D, int NRT>
 __global__ __launch_bounds__(THREADS, 2) void score_fused_kernel(ScoreGeom g, const uint16_t* __restrict__ q,
                                                                  const uint16_t* __restrict__ k, float2* part,
-                                                                 float* rowc, int* sync,
-                                                                 float* __restrict__ scores, int n_units) {
+                                                                 int* sync, float* __restrict__ raw, int n_units) {
   extern __shared__ __align__(16) char smem[];
   using S = Smem<D, NRT>;
   __shared__ int sh_last;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int n_heads = g.n_inst * g.Hkv;
-  int* cnt = sync;
-  int* flag = sync + n_heads;
-  int* err = sync + 2 * n_heads;
   float2* stat = reinterpret_cast<float2*>(smem + S::OFF_STAT);
+  float* crow = reinterpret_cast<float*>(smem + S::OFF_STAT);
+  float* crow_all = reinterpret_cast<float*>(smem + S::OFF_SLOT);    // free between the passes; Rpad <= NRT*256 checked by the host
+  const int n_heads = g.n_inst * g.Hkv;
+  int* arrived = sync;                    // per head: chunks whose statistics are published
+  int* err = sync + n_heads;
 
   uint4 pre[Tile<D>::PIECES_PER_THREAD];
   int u = blockIdx.x;
-  if (u < n_units) {
+  {
     const int hg = u / g.nchunk, c = u - hg * g.nchunk;
-    prefetch_chunk<D>(pre, k + (size_t)hg * g.L * D, c * g.own - g.half, g.L, tid);
+    fetch_chunk<D>(pre, k + (size_t)hg * g.L * D, c * CHUNK_ROWS, g.L, tid);
     commit_chunk<D>(smem, pre, tid);
   }
   __syncthreads();
@@ -568,69 +567,67 @@ __global__ __launch_bounds__(THREADS, 2) void score_fused_kernel(ScoreGeom g, co
   for (; u < n_units; u += gridDim.x) {
     const int hg = u / g.nchunk, c = u - hg * g.nchunk;
     const int inst = hg / g.Hkv, head = hg - inst * g.Hkv;
-    const int j0 = c * g.own - g.half;
+    const int j0 = c * CHUNK_ROWS;
     const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
-    const int un = u + gridDim.x;
+    float2* part_head = part + (size_t)hg * g.nchunk * g.Rpad;
+    float2* own_words = part_head + (size_t)c * g.Rpad;
     bf16x8 q0[Tile<D>::KSTEPS];
     load_q_tile<D>(q0, qg, wave % NRT, g.R, lane);
 
-    // the statistics are published with returning exchanges; the barrier that ends unit_pass1
-    // waits for them, so they are performed before the arrival is counted
-    unit_pass1<D, NRT, true>(smem, g, qg, q0, j0, tid, lane, wave, part + ((size_t)hg * g.nchunk + c) * g.Rpad);
-    if (tid == 0) {
-      const int old = __hip_atomic_fetch_add(&cnt[hg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      sh_last = (old == g.nchunk - 1);
-    }
+    unit_pass1<D, NRT, true>(smem, g, qg, q0, j0, tid, lane, wave, own_words);
+    if (tid == 0)
+      sh_last = (__hip_atomic_fetch_add(&arrived[hg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == g.nchunk - 1);
     __syncthreads();
-    if (sh_last) {
-      combine_head(g, part + (size_t)hg * g.nchunk * g.Rpad, rowc + (size_t)hg * g.Rpad, stat, tid);
-      if (tid == 0) __hip_atomic_store(&flag[hg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    } else {
-      if (tid == 0) {
-        // once any wait has timed out, later waits give up at once: the kernel always drains
-        int probes = 0;
-        while (__hip_atomic_load(&flag[hg], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
-          if (++probes > SPIN_LIMIT || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-            __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            break;
-          }
-          __builtin_amdgcn_s_sleep(8);
-        }
-      }
+    const bool last = sh_last != 0;
+
+    // next unit's key rows (the last iteration fetches its own unit again: harmless).  Memory
+    // operations retire in order, so the last arriver, whose reads everybody is waiting for,
+    // starts its fetch only after them.
+    const int un = (u + (int)gridDim.x < n_units) ? u + (int)gridDim.x : u;
+    const int hn = un / g.nchunk, cn = un - hn * g.nchunk;
+    if (last) {
+      combine_head(g, part_head, stat, crow_all, err, tid);
+      fetch_chunk<D>(pre, k + (size_t)hn * g.L * D, cn * CHUNK_ROWS, g.L, tid);
       __syncthreads();
+      if (tid < NRT * 32) crow[tid] = (tid < g.Rpad) ? crow_all[tid] : 1.0e30f;
+    } else {
+      fetch_chunk<D>(pre, k + (size_t)hn * g.L * D, cn * CHUNK_ROWS, g.L, tid);
+      // one thread polls one word (row 0 is written last); then each row's word is read, and
+      // re-read in the rare case that it has not landed yet
+      if (tid == 0) await_const(own_words, err);
+      __syncthreads();
+      if (tid < NRT * 32) crow[tid] = (tid < g.R) ? await_const(own_words + tid, err) : 1.0e30f;
     }
 
-    // Memory operations retire in order, so anything waited for after the prefetch is issued
-    // would wait for the prefetch too: fetch the row constants first, then start the next unit's
-    // key rows; pass 2 itself issues no loads (Q stays in registers from pass 1).
-    float c0v = 0.f;
-    if (tid < NRT * 32 && tid < g.Rpad) c0v = coherent_get(rowc + (size_t)hg * g.Rpad + tid);
-    if (un < n_units) {
-      const int hn = un / g.nchunk, cn = un - hn * g.nchunk;
-      prefetch_chunk<D>(pre, k + (size_t)hn * g.L * D, cn * g.own - g.half, g.L, tid);
-    }
-    if (tid < NRT * 32) reinterpret_cast<float*>(smem + S::OFF_STAT)[tid] = c0v;
-    unit_pass2<D, NRT, true>(smem, g, qg, q0, rowc + (size_t)hg * g.Rpad, true, j0, tid, lane, wave,
-                             scores + (size_t)hg * g.L);
+    unit_pass2<D, NRT, true>(smem, g, qg, q0, nullptr, own_words, true, err, j0, tid, lane, wave,
+                             raw + (size_t)hg * g.L);
     __syncthreads();                      // every wave is done with this chunk's rows
-    if (un < n_units) commit_chunk<D>(smem, pre, tid);
+    commit_chunk<D>(smem, pre, tid);
     __syncthreads();
   }
 }
 
-__global__ void reset_sync_kernel(int* sync, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) sync[i] = 0;
+// NaN over the statistics words (their "nothing yet" mark), 0 in the counters and the error word
+__global__ void reset_words_kernel(unsigned* words, size_t n, int* sync, int n_sync) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) words[i] = 0xFFFFFFFFu;
+  if (i < (size_t)n_sync) sync[i] = 0;
 }
 
 template <int D, int NRT>
-hipError_t launch_fused(const ScoreGeom& g, const uint16_t* q, const uint16_t* k, float* scores,
-                        const Workspace& ws, hipStream_t st) {
+hipError_t launch_fused(const ScoreGeom& g, const uint16_t* q, const uint16_t* k, float* raw, const Workspace& ws,
+                        hipStream_t st) {
   constexpr int bytes = Smem<D, NRT>::BYTES;
   static int resident = 0;                 // workgroups the device holds at once (queried once)
   const void* fn = reinterpret_cast<const void*>(&score_fused_kernel<D, NRT>);
+  hipError_t e;
   if (resident == 0) {
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if ((e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stats_mfma_kernel<D, NRT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&norm_mfma_kernel<D, NRT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (e != hipSuccess) return e;
     int dev = 0, cus = 0, per_cu = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
@@ -640,42 +637,37 @@ hipError_t launch_fused(const ScoreGeom& g, const uint16_t* q, const uint16_t* k
     resident = cus * per_cu;
   }
   const int n_heads = g.n_inst * g.Hkv;
+  if (g.nchunk > resident || g.Rpad > NRT * CHUNK_ROWS) {
+    // A head with more chunks than resident workgroups would make a workgroup wait for its own
+    // later unit, and more than NRT*256 score rows do not fit the LDS slice that holds a head's
+    // constants: such shapes take the two-kernel route, which reads K twice.
+    dim3 grid2(g.nchunk, g.Hkv, g.n_inst), block2(THREADS);
+    hipLaunchKernelGGL((stats_mfma_kernel<D, NRT>), grid2, block2, bytes, st, g, q, k, ws.part);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = launch_row_constants(g, ws, st)) != hipSuccess) return e;
+    hipLaunchKernelGGL((norm_mfma_kernel<D, NRT>), grid2, block2, bytes, st, g, q, k, ws.rowc, raw);
+    return hipGetLastError();
+  }
   const long long n_units_ll = (long long)n_heads * g.nchunk;
   if (n_units_ll > 0x7fffffffLL) return hipErrorInvalidValue;
   const int n_units = (int)n_units_ll;
-  if (g.nchunk > resident) {
-    // A head with more chunks than resident workgroups would make a workgroup wait for its own
-    // later unit: such (very long) sequences take the two-kernel route, which reads K twice.
-    hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&stats_mfma_kernel<D, NRT>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e2 != hipSuccess) return e2;
-    e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&norm_mfma_kernel<D, NRT>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e2 != hipSuccess) return e2;
-    dim3 grid2(g.nchunk, g.Hkv, g.n_inst), block2(THREADS);
-    hipLaunchKernelGGL((stats_mfma_kernel<D, NRT>), grid2, block2, bytes, st, g, q, k, ws.part);
-    if ((e2 = hipGetLastError()) != hipSuccess) return e2;
-    if ((e2 = launch_row_constants(g, ws, st)) != hipSuccess) return e2;
-    hipLaunchKernelGGL((norm_mfma_kernel<D, NRT>), grid2, block2, bytes, st, g, q, k, ws.rowc, scores);
-    return hipGetLastError();
-  }
-  const int n_sync = 2 * n_heads + 1;
-  hipLaunchKernelGGL(reset_sync_kernel, dim3((n_sync + 255) / 256), dim3(256), 0, st, ws.sync, n_sync);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  const size_t n_words = (size_t)n_heads * g.nchunk * g.Rpad * 2;
+  hipLaunchKernelGGL(reset_words_kernel, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, st,
+                     reinterpret_cast<unsigned*>(ws.part), n_words, ws.sync, n_heads + 1);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
   const int grid = n_units < resident ? n_units : resident;
-  hipLaunchKernelGGL((score_fused_kernel<D, NRT>), dim3(grid), dim3(THREADS), bytes, st, g, q, k, ws.part, ws.rowc,
-                     ws.sync, scores, n_units);
+  hipLaunchKernelGGL((score_fused_kernel<D, NRT>), dim3(grid), dim3(THREADS), bytes, st, g, q, k, ws.part,
+                     ws.sync, raw, n_units);
   return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_for_rows(const ScoreGeom& g, const uint16_t* q, const uint16_t* k, float* scores,
+hipError_t launch_for_rows(const ScoreGeom& g, const uint16_t* q, const uint16_t* k, float* raw,
                            const Workspace& ws, hipStream_t st) {
   const int ntile = g.Rpad / 32;
-  if (ntile == 1) return launch_fused<D, 1>(g, q, k, scores, ws, st);
-  if (ntile == 2) return launch_fused<D, 2>(g, q, k, scores, ws, st);
-  return launch_fused<D, 4>(g, q, k, scores, ws, st);
+  if (ntile == 1) return launch_fused<D, 1>(g, q, k, raw, ws, st);
+  if (ntile == 2) return launch_fused<D, 2>(g, q, k, raw, ws, st);
+  return launch_fused<D, 4>(g, q, k, raw, ws, st);
 }
 
 }  // namespace
@@ -684,12 +676,12 @@ bool score_mfma_supported(const ScoreGeom& g, int dtype) {
   return dtype == LAQ_BF16 && (g.d == 128 || g.d == 64) && g.R >= 16;
 }
 
-hipError_t launch_score_mfma(const ScoreGeom& g, const void* q, const void* k, float* scores,
-                             const Workspace& ws, hipStream_t st) {
+hipError_t launch_score_mfma(const ScoreGeom& g, const void* q, const void* k, float* raw, const Workspace& ws,
+                             hipStream_t st) {
   const uint16_t* qq = static_cast<const uint16_t*>(q);
   const uint16_t* kk = static_cast<const uint16_t*>(k);
-  if (g.d == 128) return launch_for_rows<128>(g, qq, kk, scores, ws, st);
-  return launch_for_rows<64>(g, qq, kk, scores, ws, st);
+  if (g.d == 128) return launch_for_rows<128>(g, qq, kk, raw, ws, st);
+  return launch_for_rows<64>(g, qq, kk, raw, ws, st);
 }
 
 }  // namespace laq
