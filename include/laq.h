@@ -68,7 +68,7 @@ size_t laq_workspace_bytes(const laq_shape *shape);
 /*
  * Importance scores (Eq. 4's sum over the Q-cache, taken on attention scores).
  *   q_win  [n_inst, Hq, W, d]   window (lookahead) queries
- *   k      [n_inst, Hkv, L, d]  key cache; read exactly once from HBM
+ *   k      [n_inst, Hkv, L, d]  key cache (streamed twice: softmax statistics, then normalised scores)
  *   scores [n_inst, Hkv, L]     fp32 out.  For each KV head g and key j:
  *            raw[g,j] = sum over the G heads of the group and the W queries of
  *                       softmax_j(scale * <q, k_j>) restricted to j <= P + w.
@@ -110,10 +110,9 @@ int laq_compact(const laq_shape *shape, const void *k, const void *v, const int3
                 const int32_t *budget, void *k_out, void *v_out, void *stream);
 
 /*
- * The whole path on one stream: laq_score(1) + laq_select(pool_kernel) + laq_compact, i.e. the
- * pooling is applied while the selection loads the scores.  idx, k_out and v_out are identical
- * to those of the three calls in either order of pooling; `scores` (required: it is the hand-over
- * buffer between the stages) is left holding the RAW, unpooled scores.
+ * The whole path on one stream: laq_score(pool_kernel) + laq_select(1) + laq_compact; outputs
+ * identical to those of the three calls.  `scores` is required (it is the hand-over buffer
+ * between the stages) and is left holding the pooled scores.
  */
 int laq_evict(const laq_shape *shape, const void *q_win, const void *k, const void *v,
               const int32_t *budget, int pool_kernel, float *scores, int32_t *idx,

@@ -31,7 +31,7 @@ static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 size_t workspace_bytes(const ScoreGeom& g) {
   const size_t heads = (size_t)g.n_inst * g.Hkv;
   return round256(heads * g.nchunk * g.Rpad * sizeof(float2)) + round256(heads * g.Rpad * sizeof(float)) +
-         round256((2 * heads + 1) * sizeof(int)) + round256(heads * g.L * sizeof(float));
+         round256(heads * g.L * sizeof(float));
 }
 
 Workspace carve_workspace(const ScoreGeom& g, void* ws) {
@@ -42,8 +42,6 @@ Workspace carve_workspace(const ScoreGeom& g, void* ws) {
   base += round256(heads * g.nchunk * g.Rpad * sizeof(float2));
   w.rowc = reinterpret_cast<float*>(base);
   base += round256(heads * g.Rpad * sizeof(float));
-  w.sync = reinterpret_cast<int*>(base);
-  base += round256((2 * heads + 1) * sizeof(int));
   w.raw = reinterpret_cast<float*>(base);
   return w;
 }
@@ -71,8 +69,6 @@ static bool budgets_ok(const laq_shape* s, const int32_t* budget) {
   return true;
 }
 
-// Raw (unpooled) scores into `raw`; with fuse_pool the pooled scores go to `scores` and the
-// raw ones to the workspace.
 static int score_impl(const laq_shape* shape, const void* q_win, const void* k, int pool, float* scores,
                       void* ws, size_t ws_bytes, hipStream_t st) {
   ScoreGeom g;
@@ -80,11 +76,14 @@ static int score_impl(const laq_shape* shape, const void* q_win, const void* k, 
   if (!ws || ws_bytes < workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
   if (g.Hkv > 65535 || g.n_inst > 65535 || (long long)g.Hkv * g.n_inst > 0x7fffffffLL) return LAQ_ERR_UNSUPPORTED;
   const Workspace w = carve_workspace(g, ws);
-  float* raw = pool > 1 ? w.raw : scores;
-  hipError_t e = score_mfma_supported(g, shape->dtype)
-                     ? launch_score_mfma(g, q_win, k, raw, w, st)
-                     : launch_score_generic(g, shape->dtype, q_win, k, raw, w, st);
-  if (e == hipSuccess && pool > 1) e = launch_pool(g, pool, raw, scores, st);
+  hipError_t e;
+  if (score_mfma_supported(g, shape->dtype)) {
+    e = launch_score_mfma(g, pool, q_win, k, scores, w, st);         // pooling fused into pass 2
+  } else {
+    float* raw = pool > 1 ? w.raw : scores;
+    e = launch_score_generic(g, shape->dtype, q_win, k, raw, w, st);
+    if (e == hipSuccess && pool > 1) e = launch_pool(g, pool, raw, scores, st);
+  }
   return e == hipSuccess ? LAQ_OK : LAQ_ERR_DEVICE;
 }
 
@@ -158,11 +157,9 @@ int laq_evict(const laq_shape* shape, const void* q_win, const void* k, const vo
     return LAQ_ERR_INVALID;
   if (!ws || ws_bytes < laq::workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  // raw scores, then selection with the pooling applied while the scores are loaded: the pooled
-  // values (exact maxima of the same raw scores) equal those laq_score(pool_kernel) would write
-  int rc = laq::score_impl(shape, q_win, k, 1, scores, ws, ws_bytes, st);
+  int rc = laq::score_impl(shape, q_win, k, pool_kernel, scores, ws, ws_bytes, st);
   if (rc != LAQ_OK) return rc;
-  rc = laq::select_impl(shape, scores, budget, pool_kernel, idx, st);
+  rc = laq::select_impl(shape, scores, budget, 1, idx, st);
   if (rc != LAQ_OK) return rc;
   return laq::compact_impl(shape, k, v, idx, budget, k_out, v_out, st);
 }

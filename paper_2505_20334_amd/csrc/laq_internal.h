@@ -24,16 +24,14 @@ struct ScoreGeom {
   float scale2;  // scale * log2(e): logits are kept in base-2 units
 };
 
-// Workspace carving: [partials | row constants | sync words | raw scores]
+// Workspace carving: [partials | row constants | raw scores]
 //   part:  float2 (m, z) per (instance, KV head, chunk, padded row): softmax statistics of a chunk
 //   rowc:  float c = M + log2(Z) per (instance, KV head, padded row)
-//   sync:  two arrival counters per (instance, KV head), then one int that is set if a bounded
-//          wait inside the fused kernel ever timed out
-//   raw:   float per (instance, KV head, key): unpooled scores, used when pooling is requested
+//   raw:   float per (instance, KV head, key): unpooled scores, used by the generic path when
+//          pooling is requested
 struct Workspace {
   float2* part;
   float* rowc;
-  int* sync;
   float* raw;
 };
 
@@ -51,8 +49,8 @@ hipError_t launch_score_generic(const ScoreGeom& g, int dtype, const void* q, co
                                 const Workspace& ws, hipStream_t st);
 hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStream_t st);
 bool score_mfma_supported(const ScoreGeom& g, int dtype);
-hipError_t launch_score_mfma(const ScoreGeom& g, const void* q, const void* k, float* raw, const Workspace& ws,
-                             hipStream_t st);
+hipError_t launch_score_mfma(const ScoreGeom& g, int pool, const void* q, const void* k, float* scores,
+                             const Workspace& ws, hipStream_t st);
 hipError_t launch_pool(const ScoreGeom& g, int pool, const float* raw, float* pooled, hipStream_t st);
 hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int W, int pool, const float* scores,
                          const InstTable& tab, int32_t* idx, hipStream_t st);

@@ -9,17 +9,24 @@
 //           the tile; it keeps a running (max, sum-exp) for its row.  The two lanes that
 //           share a row and the waves that share a row tile are merged through LDS and the
 //           chunk's (m, z) per row is published.
-//   pass 2 (normalise + sum): D = Q * K_tile^T, so a lane owns one key and 16 rows; with the
-//           row constants c = M + log2 Z the probabilities exp2(s - c) are summed over the rows
-//           in-lane, across the two lane halves with one cross-lane add and across row tiles
-//           through LDS, and the raw score of every key of the chunk is written.
+//   pass 2 (normalise + sum + pool): D = Q * K_tile^T, so a lane owns one key and 16 rows;
+//           with the row constants c = M + log2 Z the probabilities exp2(s - c) are summed over
+//           the rows in-lane, across the two lane halves with one cross-lane add and across row
+//           tiles through LDS.  A pass-2 chunk carries a halo of (pool-1)/2 keys on each side,
+//           so the sequence max-pool of every owned key is local to the workgroup.
 //
 // The A and B operands of the 32x32x16 instruction have the same lane layout (lane l
 // supplies row/column l%32 and the 8 consecutive reduction elements l/32), so the same
 // registers serve both passes with the operands swapped.
 //
-// The fused kernel keeps a chunk's keys in LDS from pass 1 to pass 2, so K is read from HBM
-// once; the chunks of a head exchange their statistics in between (see below).
+// Each pass is one launch of persistent workgroups that stream their list of chunks: while a
+// chunk is being worked on in LDS, the next chunk's key rows, Q tile and row constants are
+// already on their way into registers.  Between the passes a small kernel combines the
+// per-chunk statistics of every head.  K is therefore read twice (see the design notes for
+// why a single-read variant, which must make all chunks of a head meet between the passes,
+// is slower on this part).
+#include <type_traits>
+
 #include "laq_internal.h"
 
 namespace laq {
@@ -28,6 +35,10 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// 16 bytes of key data in flight between HBM and LDS.  A native vector (not HIP's uint4 class):
+// arrays of it are promoted to registers reliably, copies of the class type become memcpy calls
+// that can pin the whole array to stack memory.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float NEG_BIG = -1.0e30f;
 constexpr int WAVES = 4;
@@ -45,39 +56,75 @@ template <int D> struct Tile {
 };
 
 template <int D, int NRT> struct Smem {
-  static constexpr int OFF_STAT = Tile<D>::K_BYTES;                    // float2[THREADS]
+  static constexpr int OFF_STAT = Tile<D>::K_BYTES;                    // float2[THREADS] (pass 1) / float[256] (pass 2)
   static constexpr int OFF_SLOT = OFF_STAT + THREADS * 8;              // float[NRT][CHUNK_ROWS]
   static constexpr int BYTES = OFF_SLOT + NRT * CHUNK_ROWS * 4;
 };
 
 #define LAQ_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// Key rows j0 .. j0+CHUNK_ROWS-1 of one head into registers (128-bit coalesced loads), then
-// into LDS.  Rows beyond L-1 repeat row L-1: they are masked out of the statistics and their
-// scores are never written.
-template <int D>
-__device__ __forceinline__ void fetch_chunk(uint4 (&buf)[Tile<D>::PIECES_PER_THREAD],
-                                            const uint16_t* __restrict__ khead, int j0, int L, int tid) {
-  using T = Tile<D>;
-#pragma unroll
-  for (int it = 0; it < T::PIECES_PER_THREAD; ++it) {
-    const int p = tid + THREADS * it;
-    const int row = p / T::PIECES_PER_ROW, col = p % T::PIECES_PER_ROW;
-    const int j = min(j0 + row, L - 1);
-    buf[it] = *reinterpret_cast<const uint4*>(khead + (size_t)j * D + col * 8);
+// compile-time loop: f(std::integral_constant<int, I>) for I = FROM .. TO-1.  Used where an index
+// must be a constant before the optimiser runs (register arrays that must never become stack).
+template <int FROM, int TO, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (FROM < TO) {
+    f(std::integral_constant<int, FROM>{});
+    static_for<FROM + 1, TO>(f);
   }
 }
 
+// Key rows j0 .. j0+CHUNK_ROWS-1 (j0 >= 0) of one head travel HBM -> registers -> LDS in 16-byte
+// pieces.  A thread owns one 16-byte column of PIECES_PER_THREAD consecutive rows, so its
+// loads differ only in an immediate offset and the 16 (8) lanes that share a row read it
+// contiguously.  The loads are buffer loads against a descriptor that spans exactly the head's
+// L rows: the hardware range check returns zeros for rows beyond L-1 (they are causally
+// masked), without address clamping.  The host guarantees (L + chunk) * D * 2 < 2^31.
+struct KeyRows {
+  __amdgpu_buffer_rsrc_t rsrc;
+  int voff;                // byte offset of this thread's first piece within the head
+};
+
 template <int D>
-__device__ __forceinline__ void commit_chunk(char* ldsK, const uint4 (&buf)[Tile<D>::PIECES_PER_THREAD], int tid) {
+__device__ __forceinline__ KeyRows key_rows(const uint16_t* khead, int j0, int L, int tid) {
   using T = Tile<D>;
-#pragma unroll
-  for (int it = 0; it < T::PIECES_PER_THREAD; ++it) {
-    const int p = tid + THREADS * it;
-    const int row = p / T::PIECES_PER_ROW, col = p % T::PIECES_PER_ROW;
-    *reinterpret_cast<uint4*>(ldsK + row * T::ROWB + col * 16) = buf[it];
-  }
+  KeyRows kr;
+  kr.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(khead), 0, L * D * 2, 0x00020000);
+  kr.voff = (j0 + (tid / T::PIECES_PER_ROW) * T::PIECES_PER_THREAD) * (D * 2) + (tid % T::PIECES_PER_ROW) * 16;
+  return kr;
 }
+
+template <int D>
+__device__ __forceinline__ u32x4 load_piece(const KeyRows& kr, int voff, int it) {
+  return __builtin_amdgcn_raw_buffer_load_b128(kr.rsrc, voff + it * (D * 2), 0, 0);
+}
+
+// The thread's byte offset, made opaque to the optimiser at the point of use: the row
+// offsets added to it then stay next to their loads and fold into the instructions'
+// immediate fields, instead of being precomputed into one live register per piece.
+__device__ __forceinline__ int local_offset(const KeyRows& kr) {
+  int v = kr.voff;
+  asm volatile("" : "+v"(v));
+  return v;
+}
+
+template <int D>
+__device__ __forceinline__ void fetch_chunk(u32x4 (&buf)[Tile<D>::PIECES_PER_THREAD], const KeyRows kr) {
+  const int v = local_offset(kr);
+#pragma unroll
+  for (int it = 0; it < Tile<D>::PIECES_PER_THREAD; ++it) buf[it] = load_piece<D>(kr, v, it);
+}
+
+template <int D>
+__device__ __forceinline__ void commit_chunk(char* ldsK, const u32x4 (&buf)[Tile<D>::PIECES_PER_THREAD], int tid) {
+  using T = Tile<D>;
+  char* dst = ldsK + (tid / T::PIECES_PER_ROW) * T::PIECES_PER_THREAD * T::ROWB + (tid % T::PIECES_PER_ROW) * 16;
+#pragma unroll
+  for (int it = 0; it < T::PIECES_PER_THREAD; ++it) *reinterpret_cast<u32x4*>(dst + it * T::ROWB) = buf[it];
+}
+
+// Row index (0..31) of accumulator register i for a lane in half hf (32x32 output layout:
+// groups of four consecutive rows alternate between the two lane halves).
+__device__ __forceinline__ int acc_row(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
 
 // Operand registers of one 32-row tile of Q_g (rows beyond R are zero).
 template <int D>
@@ -86,13 +133,41 @@ __device__ __forceinline__ void load_q_tile(bf16x8 (&qreg)[Tile<D>::KSTEPS], con
   const int r = rt * 32 + (lane & 31);
 #pragma unroll
   for (int t = 0; t < Tile<D>::KSTEPS; ++t) {
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < R) v = *reinterpret_cast<const uint4*>(qg + (size_t)r * D + (2 * t + (lane >> 5)) * 8);
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (r < R) v = *reinterpret_cast<const u32x4*>(qg + (size_t)r * D + (2 * t + (lane >> 5)) * 8);
     qreg[t] = __builtin_bit_cast(bf16x8, v);
   }
 }
 
 __device__ __forceinline__ bf16x8 lds_operand(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+// The key rows of the workgroup's next chunk, requested in slices from inside the current
+// chunk's tile loop so that the loads are spread over the matrix work.
+template <int D>
+struct NextLoads {
+  u32x4* pre;              // the thread's PIECES_PER_THREAD staging registers
+  KeyRows kr;              // the next chunk's rows
+  bool on;                 // false: this call issues nothing (later row groups of the same chunk)
+
+  // slice S of N: the pieces [S*P/N, (S+1)*P/N) of this thread's share
+  template <int N, int S>
+  __device__ __forceinline__ void issue() const {
+    using T = Tile<D>;
+    if (on) {
+      const int v = local_offset(kr);
+      static_for<0, T::PIECES_PER_THREAD>([&](auto IT) {
+        constexpr int it = decltype(IT)::value;
+        if constexpr (it * N / T::PIECES_PER_THREAD == S) pre[it] = load_piece<D>(kr, v, it);
+      });
+    }
+  }
+  __device__ __forceinline__ void issue_all() const { issue<1, 0>(); }
+  __device__ __forceinline__ NextLoads off() const {
+    NextLoads n = *this;
+    n.on = false;
+    return n;
+  }
+};
 
 // acc = (KEYS_AS_ROWS ? K_tile * Q^T : Q * K_tile^T) + init over the whole head size.
 template <int D, bool KEYS_AS_ROWS>
@@ -112,10 +187,6 @@ __device__ __forceinline__ f32x16 tile_product(const char* ldsK, int kt, int lan
   return acc;
 }
 
-// Row index (0..31) of accumulator register i for a lane in half hf (32x32 output layout:
-// groups of four consecutive rows alternate between the two lane halves).
-__device__ __forceinline__ int acc_row(int i, int hf) { return 8 * (i >> 2) + 4 * hf + (i & 3); }
-
 __device__ __forceinline__ void merge_stat(float& M, float& Z, float2 p) {
   const float Mn = fmaxf(M, p.x);
   Z = Z * __builtin_amdgcn_exp2f(M - Mn) + p.y * __builtin_amdgcn_exp2f(p.x - Mn);
@@ -127,17 +198,20 @@ __device__ __forceinline__ void merge_stat(float& M, float& Z, float2 p) {
 // slice of the VALU work of tile i, so that the matrix pipe and the vector ALU run
 // concurrently inside one wave; LDS operands are fetched two MFMAs ahead.  The
 // scheduling fences pin that interleaving.
+// `next` (may be null) is asked for one slice of the next chunk's loads per tile during the
+// first half of the tiles, so that they have landed when the chunk is finished.
 template <int D, int NT>
 __device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS], int kt0,
-                                           float scale2, int lane, float& m_run, float& z_run) {
+                                           float scale2, int lane, float& m_run, float& z_run,
+                                           const NextLoads<D> next) {
   using T = Tile<D>;
   constexpr int KS = T::KSTEPS, N = NT * KS;
   const char* base = ldsK + (kt0 * 32 + (lane & 31)) * T::ROWB + (lane >> 5) * 16;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   bf16x8 r0 = lds_operand(base), r1 = lds_operand(base + 32);
   f32x16 cur = zero, nxt = zero;
-#pragma unroll
-  for (int i = 0; i <= NT; ++i) {
+  static_for<0, NT + 1>([&](auto I) {
+    constexpr int i = decltype(I)::value;
     float m_new = m_run, s = 0.f;
 #pragma unroll
     for (int t = 0; t < KS; ++t) {
@@ -175,12 +249,15 @@ __device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg
       m_run = m_new;
     }
     cur = nxt;
-  }
+    constexpr int NS = (NT + 1) / 2;
+    if constexpr (i < NS) next.template issue<NS, i>();
+  });
 }
 
 template <int D, int NT>
 __device__ __forceinline__ void pass2_pipe(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS], int kt0,
-                                           const float (&c)[16], float scale2, int lane, float* slotbuf) {
+                                           const float (&c)[16], float scale2, int lane, float* slotbuf,
+                                           const NextLoads<D> next) {
   using T = Tile<D>;
   constexpr int KS = T::KSTEPS, N = NT * KS, PER = 16 / KS;
   const int hf = lane >> 5, n32 = lane & 31;
@@ -188,8 +265,8 @@ __device__ __forceinline__ void pass2_pipe(const char* ldsK, const bf16x8 (&qreg
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   bf16x8 r0 = lds_operand(base), r1 = lds_operand(base + 32);
   f32x16 cur = zero, nxt = zero;
-#pragma unroll
-  for (int i = 0; i <= NT; ++i) {
+  static_for<0, NT + 1>([&](auto I) {
+    constexpr int i = decltype(I)::value;
     float s = 0.f;
 #pragma unroll
     for (int t = 0; t < KS; ++t) {
@@ -217,7 +294,9 @@ __device__ __forceinline__ void pass2_pipe(const char* ldsK, const bf16x8 (&qreg
       if (hf == 0) slotbuf[(kt0 + i - 1) * 32 + n32] += s;
     }
     cur = nxt;
-  }
+    constexpr int NS = (NT + 1) / 2;
+    if constexpr (i < NS) next.template issue<NS, i>();
+  });
 }
 
 // ---- per-tile passes for chunks that touch the causal region (the last chunks of a head) ----
@@ -282,66 +361,13 @@ __device__ __forceinline__ void pass2_masked(const char* ldsK, const bf16x8 (&qr
   }
 }
 
-// ---- words that workgroups hand to each other -------------------------------------------
-// The fused kernel never relies on cache maintenance for them: agent-scope release/acquire
-// fences write back and invalidate the whole L2 on this part and cost tens of microseconds
-// each.  Instead each word is its own "ready" flag: it is written with one agent-scope atomic
-// store and read with agent-scope atomic loads until its pattern says it is there.
-//   reset kernel:        (NaN, NaN)   nothing yet
-//   chunk's statistics:  (m, z)       both numbers
-//   head's row constant: (c, NaN)     written by the head's last-arriving workgroup over
-//                                     every chunk's copy of the row
-// Nobody polls a word that many others poll: 128 workgroups reading one address in a loop make
-// its memory channel a hot spot that stalls the whole key stream behind it.  A workgroup only
-// polls its own chunk's words; the one shared word per head is an arrival counter that each
-// workgroup bumps exactly once (returning add, not polled).
-constexpr int SPIN_LIMIT = 1 << 20;   // probes; about a second, far beyond any legitimate wait
-
-__device__ __forceinline__ void coherent_store(float2* p, float2 v) {
-  const unsigned long long bits = ((unsigned long long)__float_as_uint(v.y) << 32) | __float_as_uint(v.x);
-  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float2 coherent_load(const float2* p) {
-  const unsigned long long b = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT);
-  return make_float2(__uint_as_float((unsigned)b), __uint_as_float((unsigned)(b >> 32)));
-}
-__device__ __forceinline__ bool wait_failed(int probes, int* err) {
-  // Every wait is bounded; once one has timed out, all later waits give up after a few probes,
-  // so the kernel always drains.
-  if (probes > SPIN_LIMIT ||
-      ((probes & 63) == 63 && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-    __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return true;
-  }
-  return false;
-}
-// (m, z) of a chunk, once both are numbers
-__device__ __forceinline__ float2 await_stat(const float2* p, int* err) {
-  for (int probes = 0;; ++probes) {
-    const float2 v = coherent_load(p);
-    if (v.y == v.y && v.x == v.x) return v;
-    if (wait_failed(probes, err)) return make_float2(NEG_BIG, 0.f);
-    __builtin_amdgcn_s_sleep(4);
-  }
-}
-// the row constant that the head's last arriver writes over this chunk's copy of the row
-__device__ __forceinline__ float await_const(const float2* p, int* err) {
-  for (int probes = 0;; ++probes) {
-    const float2 v = coherent_load(p);
-    if (v.y != v.y && v.x == v.x) return v.x;
-    if (wait_failed(probes, err)) return 1.0e30f;
-    __builtin_amdgcn_s_sleep(16);
-  }
-}
-
-// ---- one (head, chunk) unit ---------------------------------------------------------------
-// Pass 1 over the staged chunk: (m, z) of every score row goes to out[0 .. Rpad).
-// q0 holds this wave's Q tile of the first row group (loaded by the caller, reused by pass 2).
-template <int D, int NRT, bool COHERENT>
-__device__ __forceinline__ void unit_pass1(char* smem, const ScoreGeom& g, const uint16_t* __restrict__ qg,
-                                           const bf16x8 (&q0)[Tile<D>::KSTEPS], int j0, int tid, int lane, int wave,
-                                           float2* out) {
+// ---- one chunk ----------------------------------------------------------------------------
+// Pass 1 over the staged chunk (keys j0 .. j0+255): (m, z) of every score row goes to
+// out[0 .. Rpad).
+template <int D, int NRT>
+__device__ __forceinline__ void chunk_pass1(char* smem, const ScoreGeom& g, const uint16_t* __restrict__ qg,
+                                            int j0, int tid, int lane, int wave,
+                                            float2* __restrict__ out, const NextLoads<D> next) {
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
   float2* stat = reinterpret_cast<float2*>(smem + S::OFF_STAT);
@@ -353,16 +379,15 @@ __device__ __forceinline__ void unit_pass1(char* smem, const ScoreGeom& g, const
     float m_run = NEG_BIG, z_run = 0.f;
     if (rt < ntile) {
       bf16x8 qreg[Tile<D>::KSTEPS];
-      if (rg == 0) {
-#pragma unroll
-        for (int t = 0; t < Tile<D>::KSTEPS; ++t) qreg[t] = q0[t];
+      load_q_tile<D>(qreg, qg, rt, g.R, lane);
+      if (plain_chunk) {
+        pass1_pipe<D, TPW>(smem, qreg, ks * TPW, g.scale2, lane, m_run, z_run, rg == 0 ? next : next.off());
       } else {
-        load_q_tile<D>(qreg, qg, rt, g.R, lane);
-      }
-      if (plain_chunk)
-        pass1_pipe<D, TPW>(smem, qreg, ks * TPW, g.scale2, lane, m_run, z_run);
-      else
+        if (rg == 0) next.issue_all();
         pass1_masked<D>(smem, qreg, g, rt, ks * TPW, ks * TPW + TPW, j0, lane, m_run, z_run);
+      }
+    } else if (rg == 0) {
+      next.issue_all();                    // a wave without a row tile still fetches its share
     }
     stat[tid] = make_float2(m_run, z_run);
     __syncthreads();
@@ -376,312 +401,205 @@ __device__ __forceinline__ void unit_pass1(char* smem, const ScoreGeom& g, const
           merge_stat(M, Z, stat[wv * 64 + n]);
           merge_stat(M, Z, stat[wv * 64 + 32 + n]);
         }
-        if (COHERENT)
-          coherent_store(out + (rg * NRT + s) * 32 + n, make_float2(M, Z));
-        else
-          out[(rg * NRT + s) * 32 + n] = make_float2(M, Z);
+        out[(rg * NRT + s) * 32 + n] = make_float2(M, Z);
       }
     }
     __syncthreads();
   }
 }
 
-// Pass 2 over the staged chunk with the head's row constants c[0 .. Rpad): the raw score of
-// every key of the chunk is written to raw_head.  If crow0_staged, the caller has already put
-// the first row group's constants into the LDS slice.
-template <int D, int NRT, bool COHERENT>
-__device__ __forceinline__ void unit_pass2(char* smem, const ScoreGeom& g, const uint16_t* __restrict__ qg,
-                                           const bf16x8 (&q0)[Tile<D>::KSTEPS], const float* c,
-                                           const float2* own_words, bool crow0_staged, int* err, int j0, int tid,
-                                           int lane, int wave, float* __restrict__ raw_head) {
+// Pass 2 over the staged chunk (staged row t is key j0 + t; the keys own_lo .. own_lo+own-1 are
+// this chunk's to write, the rows around them are the pooling halo): raw scores of all staged
+// rows, max-pool, owned rows written.  c points at the head's row constants.
+template <int D, int NRT>
+__device__ __forceinline__ void chunk_pass2(char* smem, const ScoreGeom& g, int half, int own_lo, int own,
+                                            const uint16_t* __restrict__ qg,
+                                            const float* __restrict__ c, int j0, int tid,
+                                            int lane, int wave, float* __restrict__ scores_head,
+                                            const NextLoads<D> next) {
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
-  float* crow = reinterpret_cast<float*>(smem + S::OFF_STAT);      // row constants of the current row group
   float* slots = reinterpret_cast<float*>(smem + S::OFF_SLOT);
+  float* raw = reinterpret_cast<float*>(smem + S::OFF_STAT);       // float[CHUNK_ROWS]
 #pragma unroll
   for (int s = 0; s < NRT; ++s) slots[s * CHUNK_ROWS + tid] = 0.f;
+  __syncthreads();
   const int slot = wave % NRT, ks = wave / NRT;
   const int ntile = g.Rpad / 32;
+  const bool plain_chunk = (j0 + CHUNK_ROWS - 1 <= g.P);
   for (int rg = 0; rg * NRT < ntile; ++rg) {
-    if (rg > 0) __syncthreads();
-    if (!(rg == 0 && crow0_staged) && tid < NRT * 32) {
-      const int r = rg * NRT * 32 + tid;
-      float v = 1.0e30f;                                            // padded rows: probability 0
-      if (r < g.R) v = COHERENT ? await_const(own_words + r, err) : c[r];
-      crow[tid] = v;
-    }
-    __syncthreads();
     const int rt = rg * NRT + slot;
     if (rt < ntile) {
       bf16x8 qreg[Tile<D>::KSTEPS];
-      if (rg == 0) {
-#pragma unroll
-        for (int t = 0; t < Tile<D>::KSTEPS; ++t) qreg[t] = q0[t];
-      } else {
-        load_q_tile<D>(qreg, qg, rt, g.R, lane);
-      }
       float cr[16];
+      load_q_tile<D>(qreg, qg, rt, g.R, lane);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) cr[i] = crow[slot * 32 + acc_row(i, lane >> 5)];
-      if (j0 + CHUNK_ROWS - 1 <= g.P)
-        pass2_pipe<D, TPW>(smem, qreg, ks * TPW, cr, g.scale2, lane, slots + slot * CHUNK_ROWS);
-      else
+      for (int i = 0; i < 16; ++i) cr[i] = c[rt * 32 + acc_row(i, lane >> 5)];
+      if (plain_chunk) {
+        pass2_pipe<D, TPW>(smem, qreg, ks * TPW, cr, g.scale2, lane, slots + slot * CHUNK_ROWS,
+                           rg == 0 ? next : next.off());
+      } else {
+        if (rg == 0) next.issue_all();
         pass2_masked<D>(smem, qreg, g, cr, rt, ks * TPW, ks * TPW + TPW, j0, lane, slots + slot * CHUNK_ROWS);
+      }
+    } else if (rg == 0) {
+      next.issue_all();
     }
   }
   __syncthreads();
   float v = slots[tid];
 #pragma unroll
   for (int s = 1; s < NRT; ++s) v += slots[s * CHUNK_ROWS + tid];
-  if (j0 + tid < g.L) raw_head[j0 + tid] = v;
-}
-
-// ---- two-kernel route (K read twice; for heads with more chunks than resident workgroups) ----
-template <int D, int NRT>
-__global__ __launch_bounds__(THREADS) void stats_mfma_kernel(ScoreGeom g, const uint16_t* __restrict__ q,
-                                                             const uint16_t* __restrict__ k,
-                                                             float2* __restrict__ part) {
-  extern __shared__ __align__(16) char smem[];
-  const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int j0 = chunk * CHUNK_ROWS;
-  const size_t hg = (size_t)inst * g.Hkv + head;
-  const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
-  bf16x8 q0[Tile<D>::KSTEPS];
-  load_q_tile<D>(q0, qg, wave % NRT, g.R, lane);
-  uint4 buf[Tile<D>::PIECES_PER_THREAD];
-  fetch_chunk<D>(buf, k + hg * g.L * D, j0, g.L, tid);
-  commit_chunk<D>(smem, buf, tid);
+  raw[tid] = v;
   __syncthreads();
-  unit_pass1<D, NRT, false>(smem, g, qg, q0, j0, tid, lane, wave, part + (hg * g.nchunk + chunk) * g.Rpad);
-}
-
-template <int D, int NRT>
-__global__ __launch_bounds__(THREADS) void norm_mfma_kernel(ScoreGeom g, const uint16_t* __restrict__ q,
-                                                            const uint16_t* __restrict__ k,
-                                                            const float* __restrict__ rowc,
-                                                            float* __restrict__ raw) {
-  extern __shared__ __align__(16) char smem[];
-  const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int j0 = chunk * CHUNK_ROWS;
-  const size_t hg = (size_t)inst * g.Hkv + head;
-  const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
-  bf16x8 q0[Tile<D>::KSTEPS];
-  load_q_tile<D>(q0, qg, wave % NRT, g.R, lane);
-  uint4 buf[Tile<D>::PIECES_PER_THREAD];
-  fetch_chunk<D>(buf, k + hg * g.L * D, j0, g.L, tid);
-  commit_chunk<D>(smem, buf, tid);
-  __syncthreads();
-  unit_pass2<D, NRT, false>(smem, g, qg, q0, rowc + hg * g.Rpad, nullptr, false, nullptr, j0, tid, lane, wave,
-                            raw + hg * g.L);
-}
-
-// ---- fused single-read kernel -----------------------------------------------------------
-// Persistent workgroups walk the list of (KV head, chunk) units in order, unit u going to
-// workgroup u mod gridDim.x.  A unit's key rows are read from HBM once: they stay in LDS from
-// pass 1 to pass 2.  Between the passes the chunks of a head meet: each workgroup publishes its
-// chunk's (m, z) per row and bumps the head's arrival counter; the one that arrives last
-// combines all chunks' statistics (fixed order, so the result does not depend on who does it)
-// and writes every row's constant over every chunk's copy of the row; the others wait for
-// their own copy to change.
-// All workgroups of the grid are resident at once (the grid is sized from the occupancy
-// query) and no head has more chunks than the grid has workgroups, so a unit only ever waits
-// for units that are in flight or earlier in their workgroups' lists: every wait ends.  The
-// spins are bounded all the same and record a timeout in the error word.
-// The next unit's key rows are requested as soon as the unit's own part of the exchange is
-// done, so they travel from HBM to registers while the head is combined and pass 2 runs.
-
-// All threads of the last-arriving workgroup: constants of rows [r0, r0 + rows) into crow_out
-// (LDS) and over the rows' copies in every chunk.
-__device__ __forceinline__ void combine_head(const ScoreGeom& g, float2* part_head, float2* stat, float* crow_all,
-                                             int* err, int tid) {
-  for (int r0 = 0; r0 < g.Rpad; r0 += THREADS) {
-    const int rows = min(THREADS, g.Rpad - r0);
-    const int tpr = (THREADS % rows == 0) ? THREADS / rows : 1;      // threads sharing a row
-    const int r = tid % rows, sel = tid / rows;
-    float M = NEG_BIG, Z = 0.f;
-    if (sel < tpr && r0 + r < g.R) {
-      // loads go out in batches (they are independent); only the merges are sequential
-      constexpr int B = 32;
-      const float2* p = part_head + r0 + r;
-      for (int c0 = sel; c0 < g.nchunk; c0 += B * tpr) {
-        float2 buf[B];
-#pragma unroll
-        for (int b = 0; b < B; ++b) buf[b] = coherent_load(p + (size_t)min(c0 + b * tpr, g.nchunk - 1) * g.Rpad);
-#pragma unroll
-        for (int b = 0; b < B; ++b) {
-          if (c0 + b * tpr < g.nchunk) {
-            if (!(buf[b].y == buf[b].y && buf[b].x == buf[b].x))     // arrival counted before the store landed
-              buf[b] = await_stat(p + (size_t)(c0 + b * tpr) * g.Rpad, err);
-            merge_stat(M, Z, buf[b]);
-          }
-        }
-      }
+  const int j = j0 + tid;
+  if (j >= own_lo && j < own_lo + own && j < g.L) {
+    if (j < g.P && half > 0) {
+      const int lo = max(j - half, 0) - j0, hi = min(j + half, g.P - 1) - j0;
+      v = raw[lo];
+      for (int i = lo + 1; i <= hi; ++i) v = fmaxf(v, raw[i]);
     }
-    stat[tid] = make_float2(M, Z);
-    __syncthreads();
-    if (tid < rows) {
-      for (int s2 = 1; s2 < tpr; ++s2) merge_stat(M, Z, stat[s2 * rows + tid]);
-      crow_all[r0 + tid] = (r0 + tid < g.R) ? M + __builtin_amdgcn_logf(Z) : 1.0e30f;
-    }
-    __syncthreads();
-    // hand the constants to every chunk of the head; row 0, the one word each waiting workgroup
-    // polls, goes last
-    const bool mine = sel < tpr && r0 + r < g.R;
-    const float cr = crow_all[min(r0 + r, g.Rpad - 1)];
-    if (mine && r0 + r != 0)
-      for (int c2 = sel; c2 < g.nchunk; c2 += tpr)
-        coherent_store(part_head + (size_t)c2 * g.Rpad + r0 + r, make_float2(cr, __uint_as_float(0x7FC00000u)));
-    __syncthreads();
-    if (mine && r0 + r == 0)
-      for (int c2 = sel; c2 < g.nchunk; c2 += tpr)
-        coherent_store(part_head + (size_t)c2 * g.Rpad, make_float2(cr, __uint_as_float(0x7FC00000u)));
+    scores_head[j] = v;
   }
 }
 
-template <int D, int NRT>
-__global__ __launch_bounds__(THREADS, 2) void score_fused_kernel(ScoreGeom g, const uint16_t* __restrict__ q,
-                                                                 const uint16_t* __restrict__ k, float2* part,
-                                                                 int* sync, float* __restrict__ raw, int n_units) {
+// ---- the two streaming kernels ---------------------------------------------------------------
+// PASS 1: units are (head, chunk of 256 keys); writes part[head][chunk][row].
+// PASS 2: units are (head, chunk owning 256 - 2*half keys); reads rowc[head][row], writes scores.
+template <int D, int NRT, int PASS>
+__global__ __launch_bounds__(THREADS, 2) void stream_kernel(ScoreGeom g, int half, int units_per_head,
+                                                            const uint16_t* __restrict__ q,
+                                                            const uint16_t* __restrict__ k,
+                                                            float2* __restrict__ part,
+                                                            const float* __restrict__ rowc,
+                                                            float* __restrict__ scores, int n_units) {
   extern __shared__ __align__(16) char smem[];
-  using S = Smem<D, NRT>;
-  __shared__ int sh_last;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  float2* stat = reinterpret_cast<float2*>(smem + S::OFF_STAT);
-  float* crow = reinterpret_cast<float*>(smem + S::OFF_STAT);
-  float* crow_all = reinterpret_cast<float*>(smem + S::OFF_SLOT);    // free between the passes; Rpad <= NRT*256 checked by the host
-  const int n_heads = g.n_inst * g.Hkv;
-  int* arrived = sync;                    // per head: chunks whose statistics are published
-  int* err = sync + n_heads;
+  const int own = CHUNK_ROWS - 2 * half;
 
-  uint4 pre[Tile<D>::PIECES_PER_THREAD];
+  u32x4 pre[Tile<D>::PIECES_PER_THREAD];
+
+  // the first unit's key rows
   int u = blockIdx.x;
   {
-    const int hg = u / g.nchunk, c = u - hg * g.nchunk;
-    fetch_chunk<D>(pre, k + (size_t)hg * g.L * D, c * CHUNK_ROWS, g.L, tid);
+    const int hg = u / units_per_head, c = u - hg * units_per_head;
+    fetch_chunk<D>(pre, key_rows<D>(k + (size_t)hg * g.L * D, max(c * own - half, 0), g.L, tid));
     commit_chunk<D>(smem, pre, tid);
   }
   __syncthreads();
 
   for (; u < n_units; u += gridDim.x) {
-    const int hg = u / g.nchunk, c = u - hg * g.nchunk;
+    const int hg = u / units_per_head, c = u - hg * units_per_head;
     const int inst = hg / g.Hkv, head = hg - inst * g.Hkv;
-    const int j0 = c * CHUNK_ROWS;
+    const int j0 = max(c * own - half, 0);         // first staged key (the head's first chunk has no left halo)
     const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
-    float2* part_head = part + (size_t)hg * g.nchunk * g.Rpad;
-    float2* own_words = part_head + (size_t)c * g.Rpad;
-    bf16x8 q0[Tile<D>::KSTEPS];
-    load_q_tile<D>(q0, qg, wave % NRT, g.R, lane);
 
-    unit_pass1<D, NRT, true>(smem, g, qg, q0, j0, tid, lane, wave, own_words);
-    if (tid == 0)
-      sh_last = (__hip_atomic_fetch_add(&arrived[hg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == g.nchunk - 1);
-    __syncthreads();
-    const bool last = sh_last != 0;
-
-    // next unit's key rows (the last iteration fetches its own unit again: harmless).  Memory
-    // operations retire in order, so the last arriver, whose reads everybody is waiting for,
-    // starts its fetch only after them.
+    // the next unit's key rows are requested from inside this unit's tile loop and consumed
+    // after it (the last iteration asks for its own unit again: harmless, and it keeps the
+    // number of outstanding loads the same on every path)
     const int un = (u + (int)gridDim.x < n_units) ? u + (int)gridDim.x : u;
-    const int hn = un / g.nchunk, cn = un - hn * g.nchunk;
-    if (last) {
-      combine_head(g, part_head, stat, crow_all, err, tid);
-      fetch_chunk<D>(pre, k + (size_t)hn * g.L * D, cn * CHUNK_ROWS, g.L, tid);
-      __syncthreads();
-      if (tid < NRT * 32) crow[tid] = (tid < g.Rpad) ? crow_all[tid] : 1.0e30f;
-    } else {
-      fetch_chunk<D>(pre, k + (size_t)hn * g.L * D, cn * CHUNK_ROWS, g.L, tid);
-      // one thread polls one word (row 0 is written last); then each row's word is read, and
-      // re-read in the rare case that it has not landed yet
-      if (tid == 0) await_const(own_words, err);
-      __syncthreads();
-      if (tid < NRT * 32) crow[tid] = (tid < g.R) ? await_const(own_words + tid, err) : 1.0e30f;
-    }
+    const int hn = un / units_per_head, cn = un - hn * units_per_head;
+    const NextLoads<D> next{pre, key_rows<D>(k + (size_t)hn * g.L * D, max(cn * own - half, 0), g.L, tid), true};
 
-    unit_pass2<D, NRT, true>(smem, g, qg, q0, nullptr, own_words, true, err, j0, tid, lane, wave,
-                             raw + (size_t)hg * g.L);
+    if (PASS == 1)
+      chunk_pass1<D, NRT>(smem, g, qg, j0, tid, lane, wave, part + ((size_t)hg * units_per_head + c) * g.Rpad,
+                          next);
+    else
+      chunk_pass2<D, NRT>(smem, g, half, c * own, own, qg, rowc + (size_t)hg * g.Rpad, j0, tid, lane, wave,
+                          scores + (size_t)hg * g.L, next);
+
     __syncthreads();                      // every wave is done with this chunk's rows
     commit_chunk<D>(smem, pre, tid);
     __syncthreads();
   }
 }
 
-// NaN over the statistics words (their "nothing yet" mark), 0 in the counters and the error word
-__global__ void reset_words_kernel(unsigned* words, size_t n, int* sync, int n_sync) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) words[i] = 0xFFFFFFFFu;
-  if (i < (size_t)n_sync) sync[i] = 0;
+// Combine the (m, z) of all chunks of a head into c = M + log2 Z per score row.  One workgroup per
+// (head, 32-row tile): 8 threads share a row and split the chunks; fixed merge order.
+__global__ __launch_bounds__(256) void row_constants_mfma_kernel(ScoreGeom g, const float2* __restrict__ part,
+                                                                  float* __restrict__ rowc) {
+  __shared__ float2 stat[256];
+  const int hg = blockIdx.x, rt = blockIdx.y, tid = threadIdx.x;
+  const int r = rt * 32 + (tid & 31), sel = tid >> 5;
+  const float2* p = part + (size_t)hg * g.nchunk * g.Rpad + r;
+  float M = NEG_BIG, Z = 0.f;
+  constexpr int B = 16;
+  for (int c0 = sel; c0 < g.nchunk; c0 += 8 * B) {
+    float2 buf[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) buf[b] = p[(size_t)min(c0 + 8 * b, g.nchunk - 1) * g.Rpad];
+#pragma unroll
+    for (int b = 0; b < B; ++b)
+      if (c0 + 8 * b < g.nchunk) merge_stat(M, Z, buf[b]);
+  }
+  stat[tid] = make_float2(M, Z);
+  __syncthreads();
+  if (tid < 32) {
+    for (int s2 = 1; s2 < 8; ++s2) merge_stat(M, Z, stat[s2 * 32 + tid]);
+    rowc[(size_t)hg * g.Rpad + r] = (r < g.R) ? M + __builtin_amdgcn_logf(Z) : 1.0e30f;
+  }
 }
 
 template <int D, int NRT>
-hipError_t launch_fused(const ScoreGeom& g, const uint16_t* q, const uint16_t* k, float* raw, const Workspace& ws,
-                        hipStream_t st) {
+hipError_t launch_stream(const ScoreGeom& g, int pool, const uint16_t* q, const uint16_t* k, float* scores,
+                         const Workspace& ws, hipStream_t st) {
   constexpr int bytes = Smem<D, NRT>::BYTES;
   static int resident = 0;                 // workgroups the device holds at once (queried once)
-  const void* fn = reinterpret_cast<const void*>(&score_fused_kernel<D, NRT>);
+  const void* f1 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 1>);
+  const void* f2 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 2>);
   hipError_t e;
   if (resident == 0) {
-    if ((e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&stats_mfma_kernel<D, NRT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&norm_mfma_kernel<D, NRT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e != hipSuccess) return e;
-    int dev = 0, cus = 0, per_cu = 0;
+    if ((e = hipFuncSetAttribute(f1, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(f2, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
+    int dev = 0, cus = 0, n1 = 0, n2 = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, THREADS, bytes)) != hipSuccess) return e;
-    if (cus < 1 || per_cu < 1) return hipErrorInvalidValue;
-    resident = cus * per_cu;
+    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, f1, THREADS, bytes)) != hipSuccess) return e;
+    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, f2, THREADS, bytes)) != hipSuccess) return e;
+    if (cus < 1 || n1 < 1 || n2 < 1) return hipErrorInvalidValue;
+    resident = cus * (n1 < n2 ? n1 : n2);
   }
-  const int n_heads = g.n_inst * g.Hkv;
-  if (g.nchunk > resident || g.Rpad > NRT * CHUNK_ROWS) {
-    // A head with more chunks than resident workgroups would make a workgroup wait for its own
-    // later unit, and more than NRT*256 score rows do not fit the LDS slice that holds a head's
-    // constants: such shapes take the two-kernel route, which reads K twice.
-    dim3 grid2(g.nchunk, g.Hkv, g.n_inst), block2(THREADS);
-    hipLaunchKernelGGL((stats_mfma_kernel<D, NRT>), grid2, block2, bytes, st, g, q, k, ws.part);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = launch_row_constants(g, ws, st)) != hipSuccess) return e;
-    hipLaunchKernelGGL((norm_mfma_kernel<D, NRT>), grid2, block2, bytes, st, g, q, k, ws.rowc, raw);
-    return hipGetLastError();
-  }
-  const long long n_units_ll = (long long)n_heads * g.nchunk;
-  if (n_units_ll > 0x7fffffffLL) return hipErrorInvalidValue;
-  const int n_units = (int)n_units_ll;
-  const size_t n_words = (size_t)n_heads * g.nchunk * g.Rpad * 2;
-  hipLaunchKernelGGL(reset_words_kernel, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, st,
-                     reinterpret_cast<unsigned*>(ws.part), n_words, ws.sync, n_heads + 1);
+  const long long n_heads = (long long)g.n_inst * g.Hkv;
+  const int half = (pool - 1) / 2;
+  const int units2 = (g.L + CHUNK_ROWS - 2 * half - 1) / (CHUNK_ROWS - 2 * half);
+  const long long nu1 = n_heads * g.nchunk, nu2 = n_heads * units2;
+  if (nu1 > 0x7fffffffLL || nu2 > 0x7fffffffLL) return hipErrorInvalidValue;
+  const int grid1 = (int)(nu1 < resident ? nu1 : resident), grid2 = (int)(nu2 < resident ? nu2 : resident);
+  hipLaunchKernelGGL((stream_kernel<D, NRT, 1>), dim3(grid1), dim3(THREADS), bytes, st, g, 0, g.nchunk, q, k, ws.part,
+                     (const float*)nullptr, (float*)nullptr, (int)nu1);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  const int grid = n_units < resident ? n_units : resident;
-  hipLaunchKernelGGL((score_fused_kernel<D, NRT>), dim3(grid), dim3(THREADS), bytes, st, g, q, k, ws.part,
-                     ws.sync, raw, n_units);
+  hipLaunchKernelGGL(row_constants_mfma_kernel, dim3((unsigned)n_heads, g.Rpad / 32), dim3(256), 0, st, g, ws.part,
+                     ws.rowc);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL((stream_kernel<D, NRT, 2>), dim3(grid2), dim3(THREADS), bytes, st, g, half, units2, q, k,
+                     (float2*)nullptr, ws.rowc, scores, (int)nu2);
   return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_for_rows(const ScoreGeom& g, const uint16_t* q, const uint16_t* k, float* raw,
+hipError_t launch_for_rows(const ScoreGeom& g, int pool, const uint16_t* q, const uint16_t* k, float* scores,
                            const Workspace& ws, hipStream_t st) {
   const int ntile = g.Rpad / 32;
-  if (ntile == 1) return launch_fused<D, 1>(g, q, k, raw, ws, st);
-  if (ntile == 2) return launch_fused<D, 2>(g, q, k, raw, ws, st);
-  return launch_fused<D, 4>(g, q, k, raw, ws, st);
+  if (ntile == 1) return launch_stream<D, 1>(g, pool, q, k, scores, ws, st);
+  if (ntile == 2) return launch_stream<D, 2>(g, pool, q, k, scores, ws, st);
+  return launch_stream<D, 4>(g, pool, q, k, scores, ws, st);
 }
 
 }  // namespace
 
 bool score_mfma_supported(const ScoreGeom& g, int dtype) {
-  return dtype == LAQ_BF16 && (g.d == 128 || g.d == 64) && g.R >= 16;
+  // the key loads address a head with 31-bit byte offsets (one chunk of slack past its end)
+  return dtype == LAQ_BF16 && (g.d == 128 || g.d == 64) && g.R >= 16 &&
+         g.n_inst * (long long)g.Hkv <= 0x7fffffff && ((long long)g.L + CHUNK_ROWS) * g.d * 2 < 0x7fffffffLL;
 }
 
-hipError_t launch_score_mfma(const ScoreGeom& g, const void* q, const void* k, float* raw, const Workspace& ws,
-                             hipStream_t st) {
+// scores: pooled with kernel `pool` (pool == 1: raw)
+hipError_t launch_score_mfma(const ScoreGeom& g, int pool, const void* q, const void* k, float* scores,
+                             const Workspace& ws, hipStream_t st) {
   const uint16_t* qq = static_cast<const uint16_t*>(q);
   const uint16_t* kk = static_cast<const uint16_t*>(k);
-  if (g.d == 128) return launch_for_rows<128>(g, qq, kk, raw, ws, st);
-  return launch_for_rows<64>(g, qq, kk, raw, ws, st);
+  if (g.d == 128) return launch_for_rows<128>(g, pool, qq, kk, scores, ws, st);
+  return launch_for_rows<64>(g, pool, qq, kk, scores, ws, st);
 }
 
 }  // namespace laq

@@ -29,18 +29,18 @@ def run_and_check(laq, q, k, v, budgets, pool, what, heads=None, scale=0.0, exac
     _, Hkv, L, _ = k.shape
     G = Hq // Hkv
     print("case:", what, "n=%d Hq=%d Hkv=%d d=%d L=%d W=%d pool=%d" % (n, Hq, Hkv, d, L, W, pool), flush=True)
-    s_raw, idx, ko, vo = laq.laq_evict(q, k, v, budgets, pool, scale=scale)      # leaves the raw scores
+    scores, idx, ko, vo = laq.laq_evict(q, k, v, budgets, pool, scale=scale)
     torch.cuda.synchronize()
-    # the three-call sequence (pooling inside laq_score) gives the same bits
-    scores = laq.laq_score(q, k, pool, scale=scale)
-    i3 = laq.laq_select(scores, budgets, 1, W)
+    # the three-call sequence gives the same bits
+    s3 = laq.laq_score(q, k, pool, scale=scale)
+    i3 = laq.laq_select(s3, budgets, 1, W)
     k3, v3 = laq.laq_compact(k, v, i3, budgets, W)
     torch.cuda.synchronize()
-    assert torch.equal(i3, idx) and torch.equal(k3, ko)
+    assert torch.equal(s3, scores) and torch.equal(i3, idx) and torch.equal(k3, ko)
     if v is not None:
         assert torch.equal(v3, vo)
-    # ... and so does pooling inside laq_select
-    assert torch.equal(laq.laq_score(q, k, 1, scale=scale), s_raw)
+    # ... and so does pooling inside laq_select instead of inside laq_score
+    s_raw = laq.laq_score(q, k, 1, scale=scale)
     i_alt = laq.laq_select(s_raw, budgets, pool, W)
     torch.cuda.synchronize()
     assert torch.equal(i_alt, idx)
@@ -116,8 +116,8 @@ def test_config4_sampled_full_size(laq):
     cfg = CONFIGS[4]
     q, k, v, budgets, _ = make_batch(cfg, device=DEV)
     n, Hkv, L, W, G = cfg.n_inst, cfg.Hkv, cfg.L, cfg.W, cfg.G
-    raw, idx, ko, vo = laq.laq_evict(q, k, v, budgets, cfg.pool)
-    scores = laq.laq_score(q, k, cfg.pool)
+    scores, idx, ko, vo = laq.laq_evict(q, k, v, budgets, cfg.pool)
+    raw = laq.laq_score(q, k, 1)
     torch.cuda.synchronize()
     idx_l = split_packed(idx.cpu(), budgets, Hkv, L)
     ko_l = split_packed(ko.cpu(), budgets, Hkv, L)
@@ -207,8 +207,7 @@ def test_all_keys_identical_all_ties(laq):
     g = torch.Generator().manual_seed(1)
     q = torch.randn(1, Hq, W, d, generator=g).bfloat16().to(DEV)
     k = torch.randn(1, 1, 1, d, generator=g).bfloat16().expand(1, Hkv, L, d).contiguous().to(DEV)
-    _, idx, _, _ = laq.laq_evict(q, k, None, [budget], 7)
-    scores = laq.laq_score(q, k, 7)
+    scores, idx, _, _ = laq.laq_evict(q, k, None, [budget], 7)
     got = idx.cpu().reshape(Hkv, budget)
     # every prefix score is the same number, so the lowest positions win
     P = L - W
