@@ -19,9 +19,9 @@
 // supplies row/column l%32 and the 8 consecutive reduction elements l/32), so the same
 // registers serve both passes with the operands swapped.
 //
-// Each pass is one launch of persistent workgroups that stream their list of chunks: while a
-// chunk is being worked on in LDS, the next chunk's key rows, Q tile and row constants are
-// already on their way into registers.  Between the passes a small kernel combines the
+// Each pass is one launch of persistent workgroups that stream a run of consecutive chunks:
+// while a chunk is being worked on in LDS, the next chunk's key rows are already on their way
+// into registers; Q and the row constants are loaded once per head.  Between the passes a small kernel combines the
 // per-chunk statistics of every head.  K is therefore read twice (see the design notes for
 // why a single-read variant, which must make all chunks of a head meet between the passes,
 // is slower on this part).
@@ -44,6 +44,10 @@ constexpr float NEG_BIG = -1.0e30f;
 constexpr int WAVES = 4;
 constexpr int THREADS = WAVES * 64;
 constexpr int KTILES = CHUNK_ROWS / 32;
+#ifndef LAQ_LDS_AHEAD
+#define LAQ_LDS_AHEAD 2
+#endif
+constexpr int LDS_AHEAD = LAQ_LDS_AHEAD;          // must not exceed the MFMAs of one wave's share (>= 8)
 
 // LDS row stride: the key row plus 16 bytes, so that the 16 lanes of a 128-bit LDS read
 // phase (rows r .. r+15, same column) fall on 16 distinct 4-bank groups.
@@ -62,6 +66,10 @@ template <int D, int NRT> struct Smem {
 };
 
 #define LAQ_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+// Forces `v` to be complete at this point of the instruction stream.  The scheduling fence
+// alone does not hold arithmetic in its slot: instruction selection is free to sink pure
+// computations down to their first use, across fences.
+#define LAQ_PIN(v) asm volatile("" : "+v"(v))
 
 // compile-time loop: f(std::integral_constant<int, I>) for I = FROM .. TO-1.  Used where an index
 // must be a constant before the optimiser runs (register arrays that must never become stack).
@@ -141,34 +149,6 @@ __device__ __forceinline__ void load_q_tile(bf16x8 (&qreg)[Tile<D>::KSTEPS], con
 
 __device__ __forceinline__ bf16x8 lds_operand(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
-// The key rows of the workgroup's next chunk, requested in slices from inside the current
-// chunk's tile loop so that the loads are spread over the matrix work.
-template <int D>
-struct NextLoads {
-  u32x4* pre;              // the thread's PIECES_PER_THREAD staging registers
-  KeyRows kr;              // the next chunk's rows
-  bool on;                 // false: this call issues nothing (later row groups of the same chunk)
-
-  // slice S of N: the pieces [S*P/N, (S+1)*P/N) of this thread's share
-  template <int N, int S>
-  __device__ __forceinline__ void issue() const {
-    using T = Tile<D>;
-    if (on) {
-      const int v = local_offset(kr);
-      static_for<0, T::PIECES_PER_THREAD>([&](auto IT) {
-        constexpr int it = decltype(IT)::value;
-        if constexpr (it * N / T::PIECES_PER_THREAD == S) pre[it] = load_piece<D>(kr, v, it);
-      });
-    }
-  }
-  __device__ __forceinline__ void issue_all() const { issue<1, 0>(); }
-  __device__ __forceinline__ NextLoads off() const {
-    NextLoads n = *this;
-    n.on = false;
-    return n;
-  }
-};
-
 // acc = (KEYS_AS_ROWS ? K_tile * Q^T : Q * K_tile^T) + init over the whole head size.
 template <int D, bool KEYS_AS_ROWS>
 __device__ __forceinline__ f32x16 tile_product(const char* ldsK, int kt, int lane,
@@ -196,20 +176,35 @@ __device__ __forceinline__ void merge_stat(float& M, float& Z, float2 p) {
 // ---- software-pipelined passes for chunks without causally masked keys -----------------
 // The MFMA chain of key tile i+1 is issued one instruction at a time, each followed by a
 // slice of the VALU work of tile i, so that the matrix pipe and the vector ALU run
-// concurrently inside one wave; LDS operands are fetched two MFMAs ahead.  The
-// scheduling fences pin that interleaving.
-// `next` (may be null) is asked for one slice of the next chunk's loads per tile during the
-// first half of the tiles, so that they have landed when the chunk is finished.
-template <int D, int NT>
+// concurrently inside one wave; LDS operands are fetched LDS_AHEAD MFMAs ahead (the LDS pipe
+// is as busy as the matrix pipe here -- every MFMA consumes 1 KB of key rows -- so its latency
+// under load is several MFMA durations).  The scheduling fences pin that interleaving.
+// With PREFETCH the wave also requests its share of the workgroup's next chunk, one 16-byte piece
+// per MFMA slot from the first slot on: the requests then trickle out at the rate the texture
+// path accepts them instead of blocking the wave in front of its arithmetic.
+// (plain fmaxf, which the compiler fuses into three-input maxima: hand-written instructions on
+// accumulator registers would bypass the wait states it inserts between an MFMA and the first
+// read of its result)
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+template <int D, int NT, bool PREFETCH>
 __device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS], int kt0,
                                            float scale2, int lane, float& m_run, float& z_run,
-                                           const NextLoads<D> next) {
+                                           u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
   using T = Tile<D>;
   constexpr int KS = T::KSTEPS, N = NT * KS;
+  static_assert(LDS_AHEAD <= N, "operand prefetch deeper than the wave's share of a chunk");
+  static_assert(T::PIECES_PER_THREAD <= N, "more pieces to request than MFMA slots");
   const char* base = ldsK + (kt0 * 32 + (lane & 31)) * T::ROWB + (lane >> 5) * 16;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  bf16x8 r0 = lds_operand(base), r1 = lds_operand(base + 32);
+  const int voff = PREFETCH ? local_offset(nkr) : 0;
+  bf16x8 ring[LDS_AHEAD];
+#pragma unroll
+  for (int n = 0; n < LDS_AHEAD; ++n) ring[n] = lds_operand(base + (n / KS) * 32 * T::ROWB + (n % KS) * 32);
   f32x16 cur = zero, nxt = zero;
+  // running maximum of the raw dot products (the logit scale is positive, so the order is the
+  // same); m_run enters as "nothing seen yet"
+  float raw_max = -3.0e38f;
   static_for<0, NT + 1>([&](auto I) {
     constexpr int i = decltype(I)::value;
     float m_new = m_run, s = 0.f;
@@ -217,19 +212,19 @@ __device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg
     for (int t = 0; t < KS; ++t) {
       const int n = i * KS + t;
       if (i < NT) {
-        bf16x8 r2 = r0;
-        if (n + 2 < N) r2 = lds_operand(base + ((n + 2) / KS) * 32 * T::ROWB + ((n + 2) % KS) * 32);
-        nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(r0, qreg[t], (t > 0) ? nxt : zero, 0, 0, 0);
-        r0 = r1;
-        r1 = r2;
+        nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[n % LDS_AHEAD], qreg[t], (t > 0) ? nxt : zero, 0, 0, 0);
+        const int f = n + LDS_AHEAD;
+        if (f < N) ring[n % LDS_AHEAD] = lds_operand(base + (f / KS) * 32 * T::ROWB + (f % KS) * 32);
+        if (PREFETCH && n < T::PIECES_PER_THREAD) pre[n] = load_piece<D>(nkr, voff, n);
       }
       if (i > 0) {
         if (t == 0) {
-          float mx = fmaxf(fmaxf(cur[0], cur[1]), cur[2]);
+          float mx = max3(raw_max, cur[0], cur[1]);
 #pragma unroll
-          for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(mx, cur[e]), cur[e + 1]);
-          mx = fmaxf(mx, cur[15]);
-          m_new = fmaxf(m_run, mx * scale2);
+          for (int e = 2; e < 16; e += 2) mx = max3(mx, cur[e], cur[e + 1]);
+          raw_max = mx;
+          m_new = mx * scale2;
+          LAQ_PIN(m_new);
         } else {
           constexpr int SL = KS - 1;
           const int lo = (t - 1) * 16 / SL, hi = t * 16 / SL;
@@ -240,6 +235,7 @@ __device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg
           for (int e = lo; e < hi; ++e) x[e] = __builtin_amdgcn_exp2f(x[e]);
 #pragma unroll
           for (int e = lo; e < hi; ++e) s += x[e];
+          LAQ_PIN(s);
         }
       }
       LAQ_SCHED_FENCE();
@@ -249,21 +245,25 @@ __device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg
       m_run = m_new;
     }
     cur = nxt;
-    constexpr int NS = (NT + 1) / 2;
-    if constexpr (i < NS) next.template issue<NS, i>();
   });
 }
 
-template <int D, int NT>
+// `first`: this call's sums start the chunk's slot buffer (they are stored); otherwise they are added.
+template <int D, int NT, bool PREFETCH>
 __device__ __forceinline__ void pass2_pipe(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS], int kt0,
-                                           const float (&c)[16], float scale2, int lane, float* slotbuf,
-                                           const NextLoads<D> next) {
+                                           const float (&c)[16], float scale2, int lane, float* slotbuf, bool first,
+                                           u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
   using T = Tile<D>;
   constexpr int KS = T::KSTEPS, N = NT * KS, PER = 16 / KS;
+  static_assert(LDS_AHEAD <= N, "operand prefetch deeper than the wave's share of a chunk");
+  static_assert(T::PIECES_PER_THREAD <= N, "more pieces to request than MFMA slots");
   const int hf = lane >> 5, n32 = lane & 31;
   const char* base = ldsK + (kt0 * 32 + n32) * T::ROWB + hf * 16;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  bf16x8 r0 = lds_operand(base), r1 = lds_operand(base + 32);
+  const int voff = PREFETCH ? local_offset(nkr) : 0;
+  bf16x8 ring[LDS_AHEAD];
+#pragma unroll
+  for (int n = 0; n < LDS_AHEAD; ++n) ring[n] = lds_operand(base + (n / KS) * 32 * T::ROWB + (n % KS) * 32);
   f32x16 cur = zero, nxt = zero;
   static_for<0, NT + 1>([&](auto I) {
     constexpr int i = decltype(I)::value;
@@ -272,11 +272,10 @@ __device__ __forceinline__ void pass2_pipe(const char* ldsK, const bf16x8 (&qreg
     for (int t = 0; t < KS; ++t) {
       const int n = i * KS + t;
       if (i < NT) {
-        bf16x8 r2 = r0;
-        if (n + 2 < N) r2 = lds_operand(base + ((n + 2) / KS) * 32 * T::ROWB + ((n + 2) % KS) * 32);
-        nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[t], r0, (t > 0) ? nxt : zero, 0, 0, 0);
-        r0 = r1;
-        r1 = r2;
+        nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[t], ring[n % LDS_AHEAD], (t > 0) ? nxt : zero, 0, 0, 0);
+        const int f = n + LDS_AHEAD;
+        if (f < N) ring[n % LDS_AHEAD] = lds_operand(base + (f / KS) * 32 * T::ROWB + (f % KS) * 32);
+        if (PREFETCH && n < T::PIECES_PER_THREAD) pre[n] = load_piece<D>(nkr, voff, n);
       }
       if (i > 0) {
         float x[16];
@@ -286,16 +285,18 @@ __device__ __forceinline__ void pass2_pipe(const char* ldsK, const bf16x8 (&qreg
         for (int e = t * PER; e < (t + 1) * PER; ++e) x[e] = __builtin_amdgcn_exp2f(x[e]);
 #pragma unroll
         for (int e = t * PER; e < (t + 1) * PER; ++e) s += x[e];
+        LAQ_PIN(s);
       }
       LAQ_SCHED_FENCE();
     }
     if (i > 0) {
       s += __shfl_xor(s, 32);
-      if (hf == 0) slotbuf[(kt0 + i - 1) * 32 + n32] += s;
+      if (hf == 0) {
+        float* dst = slotbuf + (kt0 + i - 1) * 32 + n32;
+        *dst = first ? s : *dst + s;
+      }
     }
     cur = nxt;
-    constexpr int NS = (NT + 1) / 2;
-    if constexpr (i < NS) next.template issue<NS, i>();
   });
 }
 
@@ -335,7 +336,7 @@ __device__ __forceinline__ void pass1_masked(const char* ldsK, const bf16x8 (&qr
 template <int D>
 __device__ __forceinline__ void pass2_masked(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS],
                                              const ScoreGeom& g, const float (&c)[16], int rt, int kt0, int kt1,
-                                             int j0, int lane, float* slotbuf) {
+                                             int j0, int lane, float* slotbuf, bool first) {
   const int hf = lane >> 5, n = lane & 31;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int kt = kt0; kt < kt1; ++kt) {
@@ -357,17 +358,27 @@ __device__ __forceinline__ void pass2_masked(const char* ldsK, const bf16x8 (&qr
 #pragma unroll
     for (int i = 0; i < 16; ++i) s += __builtin_amdgcn_exp2f(fmaf(acc[i], g.scale2, -c[i]));
     s += __shfl_xor(s, 32);
-    if (hf == 0) slotbuf[t0 + n] += s;
+    if (hf == 0) slotbuf[t0 + n] = first ? s : slotbuf[t0 + n] + s;
   }
 }
 
 // ---- one chunk ----------------------------------------------------------------------------
+// Both passes walk the score rows in groups of NRT 32-row tiles, one tile per wave slot.  The
+// wave's Q operands (and, in pass 2, its row constants) live in registers owned by the caller:
+// with a single row group they stay valid for as long as the workgroup stays on one head and
+// are only loaded when `reload` is set; with several row groups every group loads its own.
+
+// Both return with every wave's LDS reads of the key rows complete (their last barrier comes
+// after them), so the caller may overwrite the rows at once.  The row group that runs first
+// also requests the key rows of the workgroup's next chunk (nkr) into `pre`.
+
 // Pass 1 over the staged chunk (keys j0 .. j0+255): (m, z) of every score row goes to
 // out[0 .. Rpad).
 template <int D, int NRT>
 __device__ __forceinline__ void chunk_pass1(char* smem, const ScoreGeom& g, const uint16_t* __restrict__ qg,
-                                            int j0, int tid, int lane, int wave,
-                                            float2* __restrict__ out, const NextLoads<D> next) {
+                                            bf16x8 (&qreg)[Tile<D>::KSTEPS], bool reload, int j0, int tid, int lane,
+                                            int wave, float2* __restrict__ out,
+                                            u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
   float2* stat = reinterpret_cast<float2*>(smem + S::OFF_STAT);
@@ -377,17 +388,20 @@ __device__ __forceinline__ void chunk_pass1(char* smem, const ScoreGeom& g, cons
   for (int rg = 0; rg * NRT < ntile; ++rg) {
     const int rt = rg * NRT + slot;
     float m_run = NEG_BIG, z_run = 0.f;
+    if (rg > 0) __syncthreads();                             // the previous group's statistics have been merged
     if (rt < ntile) {
-      bf16x8 qreg[Tile<D>::KSTEPS];
-      load_q_tile<D>(qreg, qg, rt, g.R, lane);
+      if (reload) load_q_tile<D>(qreg, qg, rt, g.R, lane);
       if (plain_chunk) {
-        pass1_pipe<D, TPW>(smem, qreg, ks * TPW, g.scale2, lane, m_run, z_run, rg == 0 ? next : next.off());
+        if (rg == 0)
+          pass1_pipe<D, TPW, true>(smem, qreg, ks * TPW, g.scale2, lane, m_run, z_run, pre, nkr);
+        else
+          pass1_pipe<D, TPW, false>(smem, qreg, ks * TPW, g.scale2, lane, m_run, z_run, pre, nkr);
       } else {
-        if (rg == 0) next.issue_all();
+        if (rg == 0) fetch_chunk<D>(pre, nkr);
         pass1_masked<D>(smem, qreg, g, rt, ks * TPW, ks * TPW + TPW, j0, lane, m_run, z_run);
       }
     } else if (rg == 0) {
-      next.issue_all();                    // a wave without a row tile still fetches its share
+      fetch_chunk<D>(pre, nkr);                              // a wave without a row tile still fetches its share
     }
     stat[tid] = make_float2(m_run, z_run);
     __syncthreads();
@@ -404,7 +418,6 @@ __device__ __forceinline__ void chunk_pass1(char* smem, const ScoreGeom& g, cons
         out[(rg * NRT + s) * 32 + n] = make_float2(M, Z);
       }
     }
-    __syncthreads();
   }
 }
 
@@ -413,40 +426,44 @@ __device__ __forceinline__ void chunk_pass1(char* smem, const ScoreGeom& g, cons
 // rows, max-pool, owned rows written.  c points at the head's row constants.
 template <int D, int NRT>
 __device__ __forceinline__ void chunk_pass2(char* smem, const ScoreGeom& g, int half, int own_lo, int own,
-                                            const uint16_t* __restrict__ qg,
-                                            const float* __restrict__ c, int j0, int tid,
-                                            int lane, int wave, float* __restrict__ scores_head,
-                                            const NextLoads<D> next) {
+                                            const uint16_t* __restrict__ qg, const float* __restrict__ c,
+                                            bf16x8 (&qreg)[Tile<D>::KSTEPS], float (&cr)[16], bool reload, int j0,
+                                            int tid, int lane, int wave, float* __restrict__ scores_head,
+                                            u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
   float* slots = reinterpret_cast<float*>(smem + S::OFF_SLOT);
   float* raw = reinterpret_cast<float*>(smem + S::OFF_STAT);       // float[CHUNK_ROWS]
-#pragma unroll
-  for (int s = 0; s < NRT; ++s) slots[s * CHUNK_ROWS + tid] = 0.f;
-  __syncthreads();
   const int slot = wave % NRT, ks = wave / NRT;
   const int ntile = g.Rpad / 32;
   const bool plain_chunk = (j0 + CHUNK_ROWS - 1 <= g.P);
+  // every (slot, key tile) cell of the slot buffer belongs to exactly one wave; a slot whose first
+  // row tile does not exist (fewer tiles than slots) is cleared by its wave instead
+  if (slot >= ntile) {
+    for (int t = lane; t < TPW * 32; t += 64) slots[slot * CHUNK_ROWS + ks * TPW * 32 + t] = 0.f;
+    fetch_chunk<D>(pre, nkr);
+  }
   for (int rg = 0; rg * NRT < ntile; ++rg) {
     const int rt = rg * NRT + slot;
     if (rt < ntile) {
-      bf16x8 qreg[Tile<D>::KSTEPS];
-      float cr[16];
-      load_q_tile<D>(qreg, qg, rt, g.R, lane);
+      if (reload) {
+        load_q_tile<D>(qreg, qg, rt, g.R, lane);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) cr[i] = c[rt * 32 + acc_row(i, lane >> 5)];
-      if (plain_chunk) {
-        pass2_pipe<D, TPW>(smem, qreg, ks * TPW, cr, g.scale2, lane, slots + slot * CHUNK_ROWS,
-                           rg == 0 ? next : next.off());
-      } else {
-        if (rg == 0) next.issue_all();
-        pass2_masked<D>(smem, qreg, g, cr, rt, ks * TPW, ks * TPW + TPW, j0, lane, slots + slot * CHUNK_ROWS);
+        for (int i = 0; i < 16; ++i) cr[i] = c[rt * 32 + acc_row(i, lane >> 5)];
       }
-    } else if (rg == 0) {
-      next.issue_all();
+      float* myslot = slots + slot * CHUNK_ROWS;
+      if (plain_chunk) {
+        if (rg == 0)
+          pass2_pipe<D, TPW, true>(smem, qreg, ks * TPW, cr, g.scale2, lane, myslot, true, pre, nkr);
+        else
+          pass2_pipe<D, TPW, false>(smem, qreg, ks * TPW, cr, g.scale2, lane, myslot, false, pre, nkr);
+      } else {
+        if (rg == 0) fetch_chunk<D>(pre, nkr);
+        pass2_masked<D>(smem, qreg, g, cr, rt, ks * TPW, ks * TPW + TPW, j0, lane, myslot, rg == 0);
+      }
     }
   }
-  __syncthreads();
+  __syncthreads();                        // slots complete, key rows no longer read
   float v = slots[tid];
 #pragma unroll
   for (int s = 1; s < NRT; ++s) v += slots[s * CHUNK_ROWS + tid];
@@ -466,8 +483,13 @@ __device__ __forceinline__ void chunk_pass2(char* smem, const ScoreGeom& g, int 
 // ---- the two streaming kernels ---------------------------------------------------------------
 // PASS 1: units are (head, chunk of 256 keys); writes part[head][chunk][row].
 // PASS 2: units are (head, chunk owning 256 - 2*half keys); reads rowc[head][row], writes scores.
+// A workgroup takes `units_per_block` consecutive units, i.e. it walks along one head (sometimes
+// across a head boundary), so Q and the row constants are loaded once per head, and the only
+// per-unit traffic is the key rows.  The next unit's rows are requested before the current
+// unit's arithmetic starts and stay in flight, in registers, for its whole duration.
 template <int D, int NRT, int PASS>
 __global__ __launch_bounds__(THREADS, 2) void stream_kernel(ScoreGeom g, int half, int units_per_head,
+                                                            int units_per_block,
                                                             const uint16_t* __restrict__ q,
                                                             const uint16_t* __restrict__ k,
                                                             float2* __restrict__ part,
@@ -476,11 +498,14 @@ __global__ __launch_bounds__(THREADS, 2) void stream_kernel(ScoreGeom g, int hal
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int own = CHUNK_ROWS - 2 * half;
+  const bool one_group = (g.Rpad / 32 <= NRT);
+  int u = blockIdx.x * units_per_block;
+  const int u_end = min(u + units_per_block, n_units);
+  if (u >= u_end) return;
 
   u32x4 pre[Tile<D>::PIECES_PER_THREAD];
-
-  // the first unit's key rows
-  int u = blockIdx.x;
+  bf16x8 qreg[Tile<D>::KSTEPS];
+  float cr[16];
   {
     const int hg = u / units_per_head, c = u - hg * units_per_head;
     fetch_chunk<D>(pre, key_rows<D>(k + (size_t)hg * g.L * D, max(c * own - half, 0), g.L, tid));
@@ -488,27 +513,35 @@ __global__ __launch_bounds__(THREADS, 2) void stream_kernel(ScoreGeom g, int hal
   }
   __syncthreads();
 
-  for (; u < n_units; u += gridDim.x) {
+  int hg_loaded = -1;
+  for (; u < u_end; ++u) {
     const int hg = u / units_per_head, c = u - hg * units_per_head;
     const int inst = hg / g.Hkv, head = hg - inst * g.Hkv;
     const int j0 = max(c * own - half, 0);         // first staged key (the head's first chunk has no left halo)
     const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
-
-    // the next unit's key rows are requested from inside this unit's tile loop and consumed
-    // after it (the last iteration asks for its own unit again: harmless, and it keeps the
-    // number of outstanding loads the same on every path)
-    const int un = (u + (int)gridDim.x < n_units) ? u + (int)gridDim.x : u;
+    const bool reload = !one_group || hg != hg_loaded;
+    hg_loaded = hg;
+    if (one_group && reload) {
+      // operands of the new head first, so that they are not queued behind the key rows
+      const int rt = wave % NRT;
+      load_q_tile<D>(qreg, qg, rt, g.R, lane);
+      if (PASS == 2) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) cr[i] = rowc[(size_t)hg * g.Rpad + rt * 32 + acc_row(i, lane >> 5)];
+      }
+    }
+    // the next unit's key rows, requested during this unit's arithmetic (the last unit asks for
+    // its own rows again: harmless, and every iteration then has the same loads in flight)
+    const int un = (u + 1 < u_end) ? u + 1 : u;
     const int hn = un / units_per_head, cn = un - hn * units_per_head;
-    const NextLoads<D> next{pre, key_rows<D>(k + (size_t)hn * g.L * D, max(cn * own - half, 0), g.L, tid), true};
-
+    const KeyRows nkr = key_rows<D>(k + (size_t)hn * g.L * D, max(cn * own - half, 0), g.L, tid);
     if (PASS == 1)
-      chunk_pass1<D, NRT>(smem, g, qg, j0, tid, lane, wave, part + ((size_t)hg * units_per_head + c) * g.Rpad,
-                          next);
+      chunk_pass1<D, NRT>(smem, g, qg, qreg, !one_group, j0, tid, lane, wave,
+                          part + ((size_t)hg * units_per_head + c) * g.Rpad, pre, nkr);
     else
-      chunk_pass2<D, NRT>(smem, g, half, c * own, own, qg, rowc + (size_t)hg * g.Rpad, j0, tid, lane, wave,
-                          scores + (size_t)hg * g.L, next);
-
-    __syncthreads();                      // every wave is done with this chunk's rows
+      chunk_pass2<D, NRT>(smem, g, half, c * own, own, qg, rowc + (size_t)hg * g.Rpad, qreg, cr, !one_group, j0, tid,
+                          lane, wave, scores + (size_t)hg * g.L, pre, nkr);
+    // (every wave's reads of this chunk's rows are behind a barrier by now)
     commit_chunk<D>(smem, pre, tid);
     __syncthreads();
   }
@@ -564,15 +597,17 @@ hipError_t launch_stream(const ScoreGeom& g, int pool, const uint16_t* q, const 
   const int units2 = (g.L + CHUNK_ROWS - 2 * half - 1) / (CHUNK_ROWS - 2 * half);
   const long long nu1 = n_heads * g.nchunk, nu2 = n_heads * units2;
   if (nu1 > 0x7fffffffLL || nu2 > 0x7fffffffLL) return hipErrorInvalidValue;
-  const int grid1 = (int)(nu1 < resident ? nu1 : resident), grid2 = (int)(nu2 < resident ? nu2 : resident);
-  hipLaunchKernelGGL((stream_kernel<D, NRT, 1>), dim3(grid1), dim3(THREADS), bytes, st, g, 0, g.nchunk, q, k, ws.part,
-                     (const float*)nullptr, (float*)nullptr, (int)nu1);
+  // consecutive units per workgroup, as few workgroups as keep every resident slot busy
+  const int upb1 = (int)((nu1 + resident - 1) / resident), upb2 = (int)((nu2 + resident - 1) / resident);
+  const int grid1 = (int)((nu1 + upb1 - 1) / upb1), grid2 = (int)((nu2 + upb2 - 1) / upb2);
+  hipLaunchKernelGGL((stream_kernel<D, NRT, 1>), dim3(grid1), dim3(THREADS), bytes, st, g, 0, g.nchunk, upb1, q, k,
+                     ws.part, (const float*)nullptr, (float*)nullptr, (int)nu1);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(row_constants_mfma_kernel, dim3((unsigned)n_heads, g.Rpad / 32), dim3(256), 0, st, g, ws.part,
                      ws.rowc);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL((stream_kernel<D, NRT, 2>), dim3(grid2), dim3(THREADS), bytes, st, g, half, units2, q, k,
-                     (float2*)nullptr, ws.rowc, scores, (int)nu2);
+  hipLaunchKernelGGL((stream_kernel<D, NRT, 2>), dim3(grid2), dim3(THREADS), bytes, st, g, half, units2, upb2, q,
+                     k, (float2*)nullptr, ws.rowc, scores, (int)nu2);
   return hipGetLastError();
 }
 
