@@ -31,7 +31,7 @@ static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 size_t workspace_bytes(const ScoreGeom& g) {
   const size_t heads = (size_t)g.n_inst * g.Hkv;
   return round256(heads * g.nchunk * g.Rpad * sizeof(float2)) + round256(heads * g.Rpad * sizeof(float)) +
-         round256(heads * g.L * sizeof(float));
+         round256(heads * g.L * sizeof(float)) + 256;
 }
 
 Workspace carve_workspace(const ScoreGeom& g, void* ws) {
@@ -43,6 +43,8 @@ Workspace carve_workspace(const ScoreGeom& g, void* ws) {
   w.rowc = reinterpret_cast<float*>(base);
   base += round256(heads * g.Rpad * sizeof(float));
   w.raw = reinterpret_cast<float*>(base);
+  base += round256(heads * g.L * sizeof(float));
+  w.ctr = reinterpret_cast<int*>(base);
   return w;
 }
 

@@ -29,10 +29,12 @@ struct ScoreGeom {
 //   rowc:  float c = M + log2(Z) per (instance, KV head, padded row)
 //   raw:   float per (instance, KV head, key): unpooled scores, used by the generic path when
 //          pooling is requested
+//   ctr:   two work counters (one per streaming pass of the MFMA path), reset by every call
 struct Workspace {
   float2* part;
   float* rowc;
   float* raw;
+  int* ctr;
 };
 
 size_t workspace_bytes(const ScoreGeom& g);

@@ -62,7 +62,8 @@ template <int D> struct Tile {
 template <int D, int NRT> struct Smem {
   static constexpr int OFF_STAT = Tile<D>::K_BYTES;                    // float2[THREADS] (pass 1) / float[256] (pass 2)
   static constexpr int OFF_SLOT = OFF_STAT + THREADS * 8;              // float[NRT][CHUNK_ROWS]
-  static constexpr int BYTES = OFF_SLOT + NRT * CHUNK_ROWS * 4;
+  static constexpr int OFF_CTL = OFF_SLOT + NRT * CHUNK_ROWS * 4;      // int: the workgroup's next run of units
+  static constexpr int BYTES = OFF_CTL + 16;
 };
 
 #define LAQ_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -483,68 +484,115 @@ __device__ __forceinline__ void chunk_pass2(char* smem, const ScoreGeom& g, int 
 // ---- the two streaming kernels ---------------------------------------------------------------
 // PASS 1: units are (head, chunk of 256 keys); writes part[head][chunk][row].
 // PASS 2: units are (head, chunk owning 256 - 2*half keys); reads rowc[head][row], writes scores.
-// A workgroup takes `units_per_block` consecutive units, i.e. it walks along one head (sometimes
-// across a head boundary), so Q and the row constants are loaded once per head, and the only
-// per-unit traffic is the key rows.  The next unit's rows are requested before the current
-// unit's arithmetic starts and stay in flight, in registers, for its whole duration.
+//
+// A workgroup works through runs of consecutive units, i.e. it walks along one head, so Q and
+// the row constants are loaded once per head and the only per-unit traffic is the key rows.  Its
+// first run is a fixed share of `static_units` units; the units beyond static_units * gridDim.x
+// are handed out in runs of RUN_UNITS through a counter, because the two workgroups that share
+// a compute unit do not progress at the same speed (the older one wins instruction arbitration)
+// and a purely static split leaves half the machine idle at the end.  The next run is claimed
+// at the start of the current one, so the counter's round trip is never waited for.
+// The next unit's key rows are requested during the current unit's arithmetic and stay in
+// flight, in registers, for its whole duration.
+constexpr int RUN_UNITS = 4;
+
+struct StreamPlan {
+  int units_per_head;      // units along one head
+  int n_units;             // all units of the launch
+  int static_units;        // units of every workgroup's first run
+  int dynamic;             // 1: the units from static_units * gridDim.x on are claimed through ctr
+};
+
 template <int D, int NRT, int PASS>
-__global__ __launch_bounds__(THREADS, 2) void stream_kernel(ScoreGeom g, int half, int units_per_head,
-                                                            int units_per_block,
+__global__ __launch_bounds__(THREADS, 2) void stream_kernel(ScoreGeom g, int half, StreamPlan plan,
                                                             const uint16_t* __restrict__ q,
                                                             const uint16_t* __restrict__ k,
                                                             float2* __restrict__ part,
                                                             const float* __restrict__ rowc,
-                                                            float* __restrict__ scores, int n_units) {
+                                                            float* __restrict__ scores, int* __restrict__ ctr) {
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int own = CHUNK_ROWS - 2 * half;
   const bool one_group = (g.Rpad / 32 <= NRT);
-  int u = blockIdx.x * units_per_block;
-  const int u_end = min(u + units_per_block, n_units);
-  if (u >= u_end) return;
+  const int units_per_head = plan.units_per_head, n_units = plan.n_units;
+  volatile int* ctl = reinterpret_cast<volatile int*>(smem + Smem<D, NRT>::OFF_CTL);
+  const int dyn0 = min(plan.static_units * (int)gridDim.x, n_units);    // first dynamically assigned unit
+  int run_u = blockIdx.x * plan.static_units;
+  int run_end = min(run_u + plan.static_units, dyn0);
+  if (run_u >= run_end) return;           // (host: never with a dynamic part, every workgroup has a first run)
 
   u32x4 pre[Tile<D>::PIECES_PER_THREAD];
   bf16x8 qreg[Tile<D>::KSTEPS];
   float cr[16];
   {
-    const int hg = u / units_per_head, c = u - hg * units_per_head;
+    const int hg = run_u / units_per_head, c = run_u - hg * units_per_head;
     fetch_chunk<D>(pre, key_rows<D>(k + (size_t)hg * g.L * D, max(c * own - half, 0), g.L, tid));
     commit_chunk<D>(smem, pre, tid);
   }
   __syncthreads();
 
   int hg_loaded = -1;
-  for (; u < u_end; ++u) {
-    const int hg = u / units_per_head, c = u - hg * units_per_head;
-    const int inst = hg / g.Hkv, head = hg - inst * g.Hkv;
-    const int j0 = max(c * own - half, 0);         // first staged key (the head's first chunk has no left halo)
-    const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
-    const bool reload = !one_group || hg != hg_loaded;
-    hg_loaded = hg;
-    if (one_group && reload) {
-      // operands of the new head first, so that they are not queued behind the key rows
-      const int rt = wave % NRT;
-      load_q_tile<D>(qreg, qg, rt, g.R, lane);
-      if (PASS == 2) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) cr[i] = rowc[(size_t)hg * g.Rpad + rt * 32 + acc_row(i, lane >> 5)];
+  for (;;) {
+    int claimed = 0;                      // thread 0: the run claimed while this one is worked on
+    for (int u = run_u; u < run_end; ++u) {
+      const bool first = (u == run_u), single = (run_end - run_u == 1);
+      if (plan.dynamic && first) {
+        if (tid == 0) claimed = atomicAdd(ctr, 1);
+        if (single) {                     // a one-unit run (tail only): its successor is needed at once
+          __syncthreads();
+          if (tid == 0) ctl[0] = claimed;
+          __syncthreads();
+        }
       }
+      const int hg = u / units_per_head, c = u - hg * units_per_head;
+      const int inst = hg / g.Hkv, head = hg - inst * g.Hkv;
+      const int j0 = max(c * own - half, 0);       // first staged key (the head's first chunk has no left halo)
+      const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
+      const bool reload = !one_group || hg != hg_loaded;
+      hg_loaded = hg;
+      if (one_group && reload) {
+        // operands of the new head first, so that they are not queued behind the key rows
+        const int rt = wave % NRT;
+        load_q_tile<D>(qreg, qg, rt, g.R, lane);
+        if (PASS == 2) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) cr[i] = rowc[(size_t)hg * g.Rpad + rt * 32 + acc_row(i, lane >> 5)];
+        }
+      }
+      // the unit after this one: the next of the run, else the first of the claimed run, else (nothing
+      // left) this unit again, which is harmless and keeps the loads in flight the same everywhere
+      int un = u + 1;
+      if (un >= run_end) {
+        un = u;
+        if (plan.dynamic) {
+          const int s = dyn0 + ctl[0] * RUN_UNITS;
+          if (s < n_units) un = s;
+        }
+      }
+      const int hn = un / units_per_head, cn = un - hn * units_per_head;
+      const KeyRows nkr = key_rows<D>(k + (size_t)hn * g.L * D, max(cn * own - half, 0), g.L, tid);
+      if (PASS == 1)
+        chunk_pass1<D, NRT>(smem, g, qg, qreg, !one_group, j0, tid, lane, wave,
+                            part + ((size_t)hg * units_per_head + c) * g.Rpad, pre, nkr);
+      else
+        chunk_pass2<D, NRT>(smem, g, half, c * own, own, qg, rowc + (size_t)hg * g.Rpad, qreg, cr, !one_group, j0,
+                            tid, lane, wave, scores + (size_t)hg * g.L, pre, nkr);
+      // (every wave's reads of this chunk's rows are behind a barrier by now)
+      if (plan.dynamic && first && !single && tid == 0) ctl[0] = claimed;
+      commit_chunk<D>(smem, pre, tid);
+      __syncthreads();
     }
-    // the next unit's key rows, requested during this unit's arithmetic (the last unit asks for
-    // its own rows again: harmless, and every iteration then has the same loads in flight)
-    const int un = (u + 1 < u_end) ? u + 1 : u;
-    const int hn = un / units_per_head, cn = un - hn * units_per_head;
-    const KeyRows nkr = key_rows<D>(k + (size_t)hn * g.L * D, max(cn * own - half, 0), g.L, tid);
-    if (PASS == 1)
-      chunk_pass1<D, NRT>(smem, g, qg, qreg, !one_group, j0, tid, lane, wave,
-                          part + ((size_t)hg * units_per_head + c) * g.Rpad, pre, nkr);
-    else
-      chunk_pass2<D, NRT>(smem, g, half, c * own, own, qg, rowc + (size_t)hg * g.Rpad, qreg, cr, !one_group, j0, tid,
-                          lane, wave, scores + (size_t)hg * g.L, pre, nkr);
-    // (every wave's reads of this chunk's rows are behind a barrier by now)
-    commit_chunk<D>(smem, pre, tid);
-    __syncthreads();
+    if (!plan.dynamic) break;
+    const int s = dyn0 + ctl[0] * RUN_UNITS;
+    if (s >= n_units) break;
+    run_u = s;
+    run_end = min(s + RUN_UNITS, n_units);
   }
+}
+
+// Sets the work counters of the two streaming passes to zero.
+__global__ void reset_counters_kernel(int* ctr) {
+  if (threadIdx.x < 2) ctr[threadIdx.x] = 0;
 }
 
 // Combine the (m, z) of all chunks of a head into c = M + log2 Z per score row.  One workgroup per
@@ -596,18 +644,37 @@ hipError_t launch_stream(const ScoreGeom& g, int pool, const uint16_t* q, const 
   const int half = (pool - 1) / 2;
   const int units2 = (g.L + CHUNK_ROWS - 2 * half - 1) / (CHUNK_ROWS - 2 * half);
   const long long nu1 = n_heads * g.nchunk, nu2 = n_heads * units2;
-  if (nu1 > 0x7fffffffLL || nu2 > 0x7fffffffLL) return hipErrorInvalidValue;
-  // consecutive units per workgroup, as few workgroups as keep every resident slot busy
-  const int upb1 = (int)((nu1 + resident - 1) / resident), upb2 = (int)((nu2 + resident - 1) / resident);
-  const int grid1 = (int)((nu1 + upb1 - 1) / upb1), grid2 = (int)((nu2 + upb2 - 1) / upb2);
-  hipLaunchKernelGGL((stream_kernel<D, NRT, 1>), dim3(grid1), dim3(THREADS), bytes, st, g, 0, g.nchunk, upb1, q, k,
-                     ws.part, (const float*)nullptr, (float*)nullptr, (int)nu1);
+  if (nu1 > 0x7fff0000LL || nu2 > 0x7fff0000LL) return hipErrorInvalidValue;
+  // Few units per resident workgroup: one fixed run each, as few workgroups as keep every slot busy.
+  // Many: 5/8 of the even share as the fixed first run, the rest claimed in short runs.
+  auto make_plan = [&](long long nu, int units_per_head, int* grid) {
+    StreamPlan p;
+    p.units_per_head = units_per_head;
+    p.n_units = (int)nu;
+    const int share = (int)((nu + resident - 1) / resident);
+    if (share < 4 * RUN_UNITS) {
+      p.static_units = share;
+      p.dynamic = 0;
+      *grid = (int)((nu + share - 1) / share);
+    } else {
+      p.static_units = (int)(nu / resident) * 5 / 8;
+      p.dynamic = 1;
+      *grid = resident;
+    }
+    return p;
+  };
+  int grid1 = 0, grid2 = 0;
+  const StreamPlan p1 = make_plan(nu1, g.nchunk, &grid1), p2 = make_plan(nu2, units2, &grid2);
+  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, ws.ctr);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL((stream_kernel<D, NRT, 1>), dim3(grid1), dim3(THREADS), bytes, st, g, 0, p1, q, k, ws.part,
+                     (const float*)nullptr, (float*)nullptr, ws.ctr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(row_constants_mfma_kernel, dim3((unsigned)n_heads, g.Rpad / 32), dim3(256), 0, st, g, ws.part,
                      ws.rowc);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL((stream_kernel<D, NRT, 2>), dim3(grid2), dim3(THREADS), bytes, st, g, half, units2, upb2, q,
-                     k, (float2*)nullptr, ws.rowc, scores, (int)nu2);
+  hipLaunchKernelGGL((stream_kernel<D, NRT, 2>), dim3(grid2), dim3(THREADS), bytes, st, g, half, p2, q, k,
+                     (float2*)nullptr, ws.rowc, scores, ws.ctr + 1);
   return hipGetLastError();
 }
 
