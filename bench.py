@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload: index into BASELINE.json configs (1-based)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-instances", type=int, default=2)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device tensor copy (a kernel of known traffic, "
+                         "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU (every KV head is independent; nothing is sharded or "
@@ -95,6 +98,12 @@ def main():
     def step():
         laq.laq_evict(q, k, v, budgets, cfg.pool, scores=scores, idx=idx, k_out=k_out, v_out=v_out, ws=ws)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -126,7 +135,8 @@ def main():
     achieved = ab["score"] / (stages["score"] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(cfg.name),
-                "kernel": "laq_score stage (statistics stream + row constants + normalise/pool stream)",
+                "kernel": "laq_score stage: stream_kernel<pass 1> + row_constants_mfma_kernel + "
+                          "stream_kernel<pass 2> (K counted once in the algorithmic bytes, read twice)",
                 "algorithmic_bytes_per_launch": ab["score"],
                 "ms_per_launch": round(stages["score"], 4)}
 
