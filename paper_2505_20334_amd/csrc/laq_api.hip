@@ -28,9 +28,12 @@ static bool make_geom(const laq_shape* s, ScoreGeom* g) {
 
 static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// chunks per head under the finest chunking any scoring path uses
+static size_t max_chunks(const ScoreGeom& g) { return ((size_t)g.L + MIN_CHUNK_ROWS - 1) / MIN_CHUNK_ROWS; }
+
 size_t workspace_bytes(const ScoreGeom& g) {
   const size_t heads = (size_t)g.n_inst * g.Hkv;
-  return round256(heads * g.nchunk * g.Rpad * sizeof(float2)) + round256(heads * g.Rpad * sizeof(float)) +
+  return round256(heads * max_chunks(g) * g.Rpad * sizeof(float2)) + round256(heads * g.Rpad * sizeof(float)) +
          round256(heads * g.L * sizeof(float)) + 256;
 }
 
@@ -39,7 +42,7 @@ Workspace carve_workspace(const ScoreGeom& g, void* ws) {
   char* base = static_cast<char*>(ws);
   Workspace w;
   w.part = reinterpret_cast<float2*>(base);
-  base += round256(heads * g.nchunk * g.Rpad * sizeof(float2));
+  base += round256(heads * max_chunks(g) * g.Rpad * sizeof(float2));
   w.rowc = reinterpret_cast<float*>(base);
   base += round256(heads * g.Rpad * sizeof(float));
   w.raw = reinterpret_cast<float*>(base);

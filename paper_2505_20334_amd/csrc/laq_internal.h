@@ -13,6 +13,13 @@ namespace laq {
 // Each scoring workgroup stages CHUNK_ROWS consecutive key rows of one KV head; a head is
 // covered by nchunk = ceil(L / CHUNK_ROWS) chunks.
 constexpr int CHUNK_ROWS = 256;
+// The matrix-core path stages MFMA_ROWS key rows per workgroup (its own, finer chunking of the
+// same per-chunk statistics); the workspace is sized for the finer of the two.
+#ifndef LAQ_MFMA_ROWS
+#define LAQ_MFMA_ROWS 256
+#endif
+constexpr int MFMA_ROWS = LAQ_MFMA_ROWS;
+constexpr int MIN_CHUNK_ROWS = MFMA_ROWS < CHUNK_ROWS ? MFMA_ROWS : CHUNK_ROWS;
 constexpr int MAX_POOL = 63;
 constexpr int MAX_INST_PER_LAUNCH = 256;   // size of the per-instance tables passed as kernel arguments
 

@@ -2,7 +2,7 @@
 //
 // For one KV head the logits of Eq. 4's observation window form a skinny product
 // S = Q_g K^T with R = G*W rows (the group's query heads x the cached window queries)
-// and L columns.  A workgroup of four waves holds CHUNK_ROWS key rows in LDS and walks
+// and L columns.  A workgroup of four waves holds MFMA_ROWS key rows in LDS and walks
 // them in 32-key tiles:
 //
 //   pass 1 (statistics):  D = K_tile * Q^T, so a lane owns one score row and 16 keys of
@@ -43,7 +43,12 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr float NEG_BIG = -1.0e30f;
 constexpr int WAVES = 4;
 constexpr int THREADS = WAVES * 64;
-constexpr int KTILES = CHUNK_ROWS / 32;
+constexpr int KTILES = MFMA_ROWS / 32;
+#ifndef LAQ_MFMA_BLOCKS
+#define LAQ_MFMA_BLOCKS 2
+#endif
+constexpr int MFMA_BLOCKS = LAQ_MFMA_BLOCKS;       // workgroups per compute unit the kernels are built for
+
 #ifndef LAQ_LDS_AHEAD
 #define LAQ_LDS_AHEAD 2
 #endif
@@ -55,14 +60,14 @@ template <int D> struct Tile {
   static constexpr int ROWB = D * 2 + 16;
   static constexpr int KSTEPS = D / 16;
   static constexpr int PIECES_PER_ROW = D / 8;                         // 16-byte pieces
-  static constexpr int PIECES_PER_THREAD = CHUNK_ROWS * PIECES_PER_ROW / THREADS;
-  static constexpr int K_BYTES = CHUNK_ROWS * ROWB;
+  static constexpr int PIECES_PER_THREAD = MFMA_ROWS * PIECES_PER_ROW / THREADS;
+  static constexpr int K_BYTES = MFMA_ROWS * ROWB;
 };
 
 template <int D, int NRT> struct Smem {
   static constexpr int OFF_STAT = Tile<D>::K_BYTES;                    // float2[THREADS] (pass 1) / float[256] (pass 2)
-  static constexpr int OFF_SLOT = OFF_STAT + THREADS * 8;              // float[NRT][CHUNK_ROWS]
-  static constexpr int OFF_CTL = OFF_SLOT + NRT * CHUNK_ROWS * 4;      // int: the workgroup's next run of units
+  static constexpr int OFF_SLOT = OFF_STAT + THREADS * 8;              // float[NRT][MFMA_ROWS]
+  static constexpr int OFF_CTL = OFF_SLOT + NRT * MFMA_ROWS * 4;      // int: the workgroup's next run of units
   static constexpr int BYTES = OFF_CTL + 16;
 };
 
@@ -82,7 +87,7 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// Key rows j0 .. j0+CHUNK_ROWS-1 (j0 >= 0) of one head travel HBM -> registers -> LDS in 16-byte
+// Key rows j0 .. j0+MFMA_ROWS-1 (j0 >= 0) of one head travel HBM -> registers -> LDS in 16-byte
 // pieces.  A thread owns one 16-byte column of PIECES_PER_THREAD consecutive rows, so its
 // loads differ only in an immediate offset and the 16 (8) lanes that share a row read it
 // contiguously.  The loads are buffer loads against a descriptor that spans exactly the head's
@@ -202,10 +207,10 @@ __device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg
   bf16x8 ring[LDS_AHEAD];
 #pragma unroll
   for (int n = 0; n < LDS_AHEAD; ++n) ring[n] = lds_operand(base + (n / KS) * 32 * T::ROWB + (n % KS) * 32);
-  f32x16 cur = zero, nxt = zero;
   // running maximum of the raw dot products (the logit scale is positive, so the order is the
   // same); m_run enters as "nothing seen yet"
   float raw_max = -3.0e38f;
+  f32x16 cur = zero, nxt = zero;
   static_for<0, NT + 1>([&](auto I) {
     constexpr int i = decltype(I)::value;
     float m_new = m_run, s = 0.f;
@@ -385,7 +390,7 @@ __device__ __forceinline__ void chunk_pass1(char* smem, const ScoreGeom& g, cons
   float2* stat = reinterpret_cast<float2*>(smem + S::OFF_STAT);
   const int slot = wave % NRT, ks = wave / NRT;
   const int ntile = g.Rpad / 32;
-  const bool plain_chunk = (j0 + CHUNK_ROWS - 1 <= g.P);    // no key beyond the prefix: no causal mask
+  const bool plain_chunk = (j0 + MFMA_ROWS - 1 <= g.P);    // no key beyond the prefix: no causal mask
   for (int rg = 0; rg * NRT < ntile; ++rg) {
     const int rt = rg * NRT + slot;
     float m_run = NEG_BIG, z_run = 0.f;
@@ -434,14 +439,14 @@ __device__ __forceinline__ void chunk_pass2(char* smem, const ScoreGeom& g, int 
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
   float* slots = reinterpret_cast<float*>(smem + S::OFF_SLOT);
-  float* raw = reinterpret_cast<float*>(smem + S::OFF_STAT);       // float[CHUNK_ROWS]
+  float* raw = reinterpret_cast<float*>(smem + S::OFF_STAT);       // float[MFMA_ROWS]
   const int slot = wave % NRT, ks = wave / NRT;
   const int ntile = g.Rpad / 32;
-  const bool plain_chunk = (j0 + CHUNK_ROWS - 1 <= g.P);
+  const bool plain_chunk = (j0 + MFMA_ROWS - 1 <= g.P);
   // every (slot, key tile) cell of the slot buffer belongs to exactly one wave; a slot whose first
   // row tile does not exist (fewer tiles than slots) is cleared by its wave instead
   if (slot >= ntile) {
-    for (int t = lane; t < TPW * 32; t += 64) slots[slot * CHUNK_ROWS + ks * TPW * 32 + t] = 0.f;
+    for (int t = lane; t < TPW * 32; t += 64) slots[slot * MFMA_ROWS + ks * TPW * 32 + t] = 0.f;
     fetch_chunk<D>(pre, nkr);
   }
   for (int rg = 0; rg * NRT < ntile; ++rg) {
@@ -452,7 +457,7 @@ __device__ __forceinline__ void chunk_pass2(char* smem, const ScoreGeom& g, int 
 #pragma unroll
         for (int i = 0; i < 16; ++i) cr[i] = c[rt * 32 + acc_row(i, lane >> 5)];
       }
-      float* myslot = slots + slot * CHUNK_ROWS;
+      float* myslot = slots + slot * MFMA_ROWS;
       if (plain_chunk) {
         if (rg == 0)
           pass2_pipe<D, TPW, true>(smem, qreg, ks * TPW, cr, g.scale2, lane, myslot, true, pre, nkr);
@@ -465,13 +470,16 @@ __device__ __forceinline__ void chunk_pass2(char* smem, const ScoreGeom& g, int 
     }
   }
   __syncthreads();                        // slots complete, key rows no longer read
-  float v = slots[tid];
+  float v = 0.f;
+  if (tid < MFMA_ROWS) {
+    v = slots[tid];
 #pragma unroll
-  for (int s = 1; s < NRT; ++s) v += slots[s * CHUNK_ROWS + tid];
-  raw[tid] = v;
+    for (int s = 1; s < NRT; ++s) v += slots[s * MFMA_ROWS + tid];
+    raw[tid] = v;
+  }
   __syncthreads();
   const int j = j0 + tid;
-  if (j >= own_lo && j < own_lo + own && j < g.L) {
+  if (tid < MFMA_ROWS && j >= own_lo && j < own_lo + own && j < g.L) {
     if (j < g.P && half > 0) {
       const int lo = max(j - half, 0) - j0, hi = min(j + half, g.P - 1) - j0;
       v = raw[lo];
@@ -504,7 +512,7 @@ struct StreamPlan {
 };
 
 template <int D, int NRT, int PASS>
-__global__ __launch_bounds__(THREADS, 2) void stream_kernel(ScoreGeom g, int half, StreamPlan plan,
+__global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom g, int half, StreamPlan plan,
                                                             const uint16_t* __restrict__ q,
                                                             const uint16_t* __restrict__ k,
                                                             float2* __restrict__ part,
@@ -512,7 +520,7 @@ __global__ __launch_bounds__(THREADS, 2) void stream_kernel(ScoreGeom g, int hal
                                                             float* __restrict__ scores, int* __restrict__ ctr) {
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int own = CHUNK_ROWS - 2 * half;
+  const int own = MFMA_ROWS - 2 * half;
   const bool one_group = (g.Rpad / 32 <= NRT);
   const int units_per_head = plan.units_per_head, n_units = plan.n_units;
   volatile int* ctl = reinterpret_cast<volatile int*>(smem + Smem<D, NRT>::OFF_CTL);
@@ -642,8 +650,11 @@ hipError_t launch_stream(const ScoreGeom& g, int pool, const uint16_t* q, const 
   }
   const long long n_heads = (long long)g.n_inst * g.Hkv;
   const int half = (pool - 1) / 2;
-  const int units2 = (g.L + CHUNK_ROWS - 2 * half - 1) / (CHUNK_ROWS - 2 * half);
-  const long long nu1 = n_heads * g.nchunk, nu2 = n_heads * units2;
+  const int units2 = (g.L + MFMA_ROWS - 2 * half - 1) / (MFMA_ROWS - 2 * half);
+  const int units1 = (g.L + MFMA_ROWS - 1) / MFMA_ROWS;
+  ScoreGeom gm = g;
+  gm.nchunk = units1;                      // this path's chunking of the statistics
+  const long long nu1 = n_heads * units1, nu2 = n_heads * units2;
   if (nu1 > 0x7fff0000LL || nu2 > 0x7fff0000LL) return hipErrorInvalidValue;
   // Few units per resident workgroup: one fixed run each, as few workgroups as keep every slot busy.
   // Many: 5/8 of the even share as the fixed first run, the rest claimed in short runs.
@@ -664,13 +675,13 @@ hipError_t launch_stream(const ScoreGeom& g, int pool, const uint16_t* q, const 
     return p;
   };
   int grid1 = 0, grid2 = 0;
-  const StreamPlan p1 = make_plan(nu1, g.nchunk, &grid1), p2 = make_plan(nu2, units2, &grid2);
+  const StreamPlan p1 = make_plan(nu1, units1, &grid1), p2 = make_plan(nu2, units2, &grid2);
   hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, ws.ctr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((stream_kernel<D, NRT, 1>), dim3(grid1), dim3(THREADS), bytes, st, g, 0, p1, q, k, ws.part,
                      (const float*)nullptr, (float*)nullptr, ws.ctr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(row_constants_mfma_kernel, dim3((unsigned)n_heads, g.Rpad / 32), dim3(256), 0, st, g, ws.part,
+  hipLaunchKernelGGL(row_constants_mfma_kernel, dim3((unsigned)n_heads, g.Rpad / 32), dim3(256), 0, st, gm, ws.part,
                      ws.rowc);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((stream_kernel<D, NRT, 2>), dim3(grid2), dim3(THREADS), bytes, st, g, half, p2, q, k,
@@ -692,7 +703,7 @@ hipError_t launch_for_rows(const ScoreGeom& g, int pool, const uint16_t* q, cons
 bool score_mfma_supported(const ScoreGeom& g, int dtype) {
   // the key loads address a head with 31-bit byte offsets (one chunk of slack past its end)
   return dtype == LAQ_BF16 && (g.d == 128 || g.d == 64) && g.R >= 16 &&
-         g.n_inst * (long long)g.Hkv <= 0x7fffffff && ((long long)g.L + CHUNK_ROWS) * g.d * 2 < 0x7fffffffLL;
+         g.n_inst * (long long)g.Hkv <= 0x7fffffff && ((long long)g.L + MFMA_ROWS) * g.d * 2 < 0x7fffffffLL;
 }
 
 // scores: pooled with kernel `pool` (pool == 1: raw)

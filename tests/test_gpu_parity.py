@@ -162,7 +162,7 @@ EDGE = [
     ("R48-three-tiles", torch.bfloat16, 12, 2, 128, 900, 8, 7, 64),
     ("R160-two-groups", torch.bfloat16, 10, 1, 128, 700, 16, 7, 64),
     ("R20-padded", torch.bfloat16, 5, 1, 128, 700, 4, 7, 64),
-    ("R1200-two-kernel-route", torch.bfloat16, 4, 1, 128, 700, 300, 7, 400),
+    ("R1200-many-row-groups", torch.bfloat16, 4, 1, 128, 700, 300, 7, 400),
     ("R288-nine-tiles", torch.bfloat16, 4, 1, 64, 1300, 72, 5, 200),
     ("d64-mfma", torch.bfloat16, 8, 2, 64, 1500, 8, 7, 128),
     ("d64-R64", torch.bfloat16, 16, 2, 64, 1500, 8, 7, 128),
@@ -185,14 +185,48 @@ def test_edge_cases(laq, name, dtype, Hq, Hkv, d, L, W, pool, budget):
     run_and_check(laq, q, k, v, [budget, max(W, budget - 3)], pool, name)
 
 
-def test_very_long_sequence_takes_two_kernel_route(laq):
-    # more chunks per head than resident workgroups (L > 128000): the single-read kernel does not apply
+def test_very_long_sequence(laq):
+    # one head of 513 chunks: more units than workgroups, all on one head
     g = torch.Generator().manual_seed(77)
     Hq, Hkv, d, L, W = 4, 1, 128, 131072 + 40, 8
     q = torch.randn(1, Hq, W, d, generator=g).bfloat16().to(DEV)
     k = torch.randn(1, Hkv, L, d, generator=g).bfloat16().to(DEV)
     v = torch.randn(1, Hkv, L, d, generator=g).bfloat16().to(DEV)
     run_and_check(laq, q, k, v, [1024], 7, "L131k")
+
+
+def test_many_heads_dynamic_runs_and_one_unit_tail(laq):
+    # 513 short heads = 8721 units per pass: enough for the streaming kernels to hand out the tail of
+    # the work in runs of 4 through their counter, and 8721 - 512*10 = 4*900 + 1 leaves a last run of
+    # one unit (on a device that holds 512 workgroups).  Sampled heads against the oracle, invariants
+    # on everything, and the same bits on a second call.
+    n, Hq, Hkv, d, L, W, pool, budget = 57, 18, 9, 128, 4100, 16, 7, 300
+    G = Hq // Hkv
+    gen = torch.Generator(device=DEV).manual_seed(2024)
+    q = (torch.randn(n, Hq, W, d, generator=gen, device=DEV) * 1.5).bfloat16()
+    k = torch.randn(n, Hkv, L, d, generator=gen, device=DEV).bfloat16()
+    v = torch.randn(n, Hkv, L, d, generator=gen, device=DEV).bfloat16()
+    budgets = [budget] * n
+    scores, idx, ko, vo = laq.laq_evict(q, k, v, budgets, pool)
+    raw = laq.laq_score(q, k, 1)
+    again = laq.laq_evict(q, k, v, budgets, pool)
+    torch.cuda.synchronize()
+    for x, y in zip((scores, idx, ko, vo), again):
+        assert torch.equal(x, y)
+    np.testing.assert_allclose(raw.double().sum(dim=2).cpu().numpy(), G * W, rtol=2e-4)
+    assert (scores >= raw).all() and (raw >= 0).all()
+    idx_l = split_packed(idx.cpu(), budgets, Hkv, L)
+    ko_l = split_packed(ko.cpu(), budgets, Hkv, L)
+    for (i, g) in [(0, 0), (22, 4), (39, 8), (56, 8)]:       # first, middle (static / claimed runs), very last head
+        print("many-heads sample", i, g, flush=True)
+        qc, kc = q[i, g * G:(g + 1) * G].cpu(), k[i, g:g + 1].cpu()
+        r = oracle.raw_scores(qc, kc)
+        pooled = oracle.maxpool(r, W, pool)
+        check_scores(raw[i, g].cpu(), r[0], k.dtype, "many-heads raw inst %d head %d" % (i, g))
+        check_scores(scores[i, g].cpu(), pooled[0], k.dtype, "many-heads inst %d head %d" % (i, g))
+        check_index_row(idx_l[i][g].numpy(), pooled[0].float().numpy(), W, budget, 1e-3, "many-heads")
+        assert torch.equal(oracle.select(scores[i, g:g + 1].cpu(), W, budget)[0], idx_l[i][g])
+        assert torch.equal(ko_l[i][g], k[i, g].cpu()[idx_l[i][g].long()])
 
 
 def test_per_instance_budgets_pack_correctly(laq):
