@@ -19,12 +19,12 @@
 // supplies row/column l%32 and the 8 consecutive reduction elements l/32), so the same
 // registers serve both passes with the operands swapped.
 //
-// Each pass is one launch of persistent workgroups that stream a run of consecutive chunks:
+// Each pass is one launch of persistent workgroups that stream runs of consecutive chunks:
 // while a chunk is being worked on in LDS, the next chunk's key rows are already on their way
-// into registers; Q and the row constants are loaded once per head.  Between the passes a small kernel combines the
-// per-chunk statistics of every head.  K is therefore read twice (see the design notes for
-// why a single-read variant, which must make all chunks of a head meet between the passes,
-// is slower on this part).
+// into registers; Q and the row constants are loaded once per head.  Between the passes a
+// small kernel combines the per-chunk statistics of every head.  K is therefore read twice.
+// (A single-read variant has to keep a head's keys on chip while all its chunks meet between
+// the passes; on this part that device-wide meeting costs more than the second read.)
 #include <type_traits>
 
 #include "laq_internal.h"
@@ -52,7 +52,7 @@ constexpr int MFMA_BLOCKS = LAQ_MFMA_BLOCKS;       // workgroups per compute uni
 #ifndef LAQ_LDS_AHEAD
 #define LAQ_LDS_AHEAD 2
 #endif
-constexpr int LDS_AHEAD = LAQ_LDS_AHEAD;          // must not exceed the MFMAs of one wave's share (>= 8)
+constexpr int LDS_AHEAD = LAQ_LDS_AHEAD;          // MFMA operands requested from LDS this many MFMAs ahead
 
 // LDS row stride: the key row plus 16 bytes, so that the 16 lanes of a 128-bit LDS read
 // phase (rows r .. r+15, same column) fall on 16 distinct 4-bank groups.
@@ -182,9 +182,9 @@ __device__ __forceinline__ void merge_stat(float& M, float& Z, float2 p) {
 // ---- software-pipelined passes for chunks without causally masked keys -----------------
 // The MFMA chain of key tile i+1 is issued one instruction at a time, each followed by a
 // slice of the VALU work of tile i, so that the matrix pipe and the vector ALU run
-// concurrently inside one wave; LDS operands are fetched LDS_AHEAD MFMAs ahead (the LDS pipe
-// is as busy as the matrix pipe here -- every MFMA consumes 1 KB of key rows -- so its latency
-// under load is several MFMA durations).  The scheduling fences pin that interleaving.
+// concurrently inside one wave; LDS operands are fetched LDS_AHEAD MFMAs ahead (deeper did
+// not measure faster: the loop is bound by VALU issue, about 89 issue slots per tile, not by
+// LDS latency).  The scheduling fences and value pins hold that interleaving.
 // With PREFETCH the wave also requests its share of the workgroup's next chunk, one 16-byte piece
 // per MFMA slot from the first slot on: the requests then trickle out at the rate the texture
 // path accepts them instead of blocking the wave in front of its arithmetic.
@@ -573,7 +573,9 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
       if (un >= run_end) {
         un = u;
         if (plan.dynamic) {
-          const int s = dyn0 + ctl[0] * RUN_UNITS;
+          // (read from LDS, hence a per-lane value to the compiler: made wave-uniform by hand, or
+          // every load through a descriptor derived from it is wrapped in a uniformity loop)
+          const int s = dyn0 + __builtin_amdgcn_readfirstlane(ctl[0]) * RUN_UNITS;
           if (s < n_units) un = s;
         }
       }
@@ -591,7 +593,7 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
       __syncthreads();
     }
     if (!plan.dynamic) break;
-    const int s = dyn0 + ctl[0] * RUN_UNITS;
+    const int s = dyn0 + __builtin_amdgcn_readfirstlane(ctl[0]) * RUN_UNITS;
     if (s >= n_units) break;
     run_u = s;
     run_end = min(s + RUN_UNITS, n_units);
@@ -633,15 +635,18 @@ template <int D, int NRT>
 hipError_t launch_stream(const ScoreGeom& g, int pool, const uint16_t* q, const uint16_t* k, float* scores,
                          const Workspace& ws, hipStream_t st) {
   constexpr int bytes = Smem<D, NRT>::BYTES;
-  static int resident = 0;                 // workgroups the device holds at once (queried once)
+  static int resident_of[64] = {0};        // workgroups each device holds at once (queried once per device)
+  int dev = 0;
+  hipError_t e;
+  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  int& resident = resident_of[dev];
   const void* f1 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 1>);
   const void* f2 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 2>);
-  hipError_t e;
   if (resident == 0) {
     if ((e = hipFuncSetAttribute(f1, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(f2, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
-    int dev = 0, cus = 0, n1 = 0, n2 = 0;
-    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    int cus = 0, n1 = 0, n2 = 0;
     if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
     if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, f1, THREADS, bytes)) != hipSuccess) return e;
     if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, f2, THREADS, bytes)) != hipSuccess) return e;
