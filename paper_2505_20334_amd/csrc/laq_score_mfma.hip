@@ -65,7 +65,7 @@ template <int D> struct Tile {
 };
 
 template <int D, int NRT> struct Smem {
-  static constexpr int OFF_STAT = Tile<D>::K_BYTES;                    // float2[THREADS] (pass 1) / float[256] (pass 2)
+  static constexpr int OFF_STAT = Tile<D>::K_BYTES;                    // float2[THREADS]: pass 1's per-thread statistics
   static constexpr int OFF_SLOT = OFF_STAT + THREADS * 8;              // float[NRT][MFMA_ROWS]
   static constexpr int OFF_CTL = OFF_SLOT + NRT * MFMA_ROWS * 4;      // int: the workgroup's next run of units
   static constexpr int BYTES = OFF_CTL + 16;
@@ -378,15 +378,18 @@ __device__ __forceinline__ void pass2_masked(const char* ldsK, const bf16x8 (&qr
 // after them), so the caller may overwrite the rows at once.  The row group that runs first
 // also requests the key rows of the workgroup's next chunk (nkr) into `pre`.
 
-// Pass 1 over the staged chunk (keys j0 .. j0+255): (m, z) of every score row goes to
-// out[0 .. Rpad).
+// Pass 1 over the staged chunk (keys j0 .. j0+MFMA_ROWS-1): (m, z) of every score row goes to
+// out[0 .. Rpad).  The statistics of the last row group are handed back instead (returns true if
+// this thread holds one, for out[idx_out]): the caller stores them after it has moved the next
+// chunk's rows into LDS, so that the wait for those rows is not also a wait for the store.
 template <int D, int NRT>
-__device__ __forceinline__ void chunk_pass1(char* smem, const ScoreGeom& g, const uint16_t* __restrict__ qg,
+__device__ __forceinline__ bool chunk_pass1(char* smem, const ScoreGeom& g, const uint16_t* __restrict__ qg,
                                             bf16x8 (&qreg)[Tile<D>::KSTEPS], bool reload, int j0, int tid, int lane,
-                                            int wave, float2* __restrict__ out,
+                                            int wave, float2* __restrict__ out, int& idx_out, float2& mz_out,
                                             u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
+  bool pending = false;
   float2* stat = reinterpret_cast<float2*>(smem + S::OFF_STAT);
   const int slot = wave % NRT, ks = wave / NRT;
   const int ntile = g.Rpad / 32;
@@ -421,25 +424,33 @@ __device__ __forceinline__ void chunk_pass1(char* smem, const ScoreGeom& g, cons
           merge_stat(M, Z, stat[wv * 64 + n]);
           merge_stat(M, Z, stat[wv * 64 + 32 + n]);
         }
-        out[(rg * NRT + s) * 32 + n] = make_float2(M, Z);
+        if ((rg + 1) * NRT < ntile) {
+          out[(rg * NRT + s) * 32 + n] = make_float2(M, Z);
+        } else {
+          pending = true;
+          idx_out = (rg * NRT + s) * 32 + n;
+          mz_out = make_float2(M, Z);
+        }
       }
     }
   }
+  return pending;
 }
 
 // Pass 2 over the staged chunk (staged row t is key j0 + t; the keys own_lo .. own_lo+own-1 are
 // this chunk's to write, the rows around them are the pooling halo): raw scores of all staged
-// rows, max-pool, owned rows written.  c points at the head's row constants.
+// rows, max-pool.  Returns whether this thread has an owned key (index j_out) and its pooled score
+// (v_out); the caller stores it after it has moved the next chunk's rows into LDS, so that the
+// wait for those rows is not also a wait for the store.  c points at the head's row constants.
 template <int D, int NRT>
-__device__ __forceinline__ void chunk_pass2(char* smem, const ScoreGeom& g, int half, int own_lo, int own,
+__device__ __forceinline__ bool chunk_pass2(char* smem, const ScoreGeom& g, int half, int own_lo, int own,
                                             const uint16_t* __restrict__ qg, const float* __restrict__ c,
                                             bf16x8 (&qreg)[Tile<D>::KSTEPS], float (&cr)[16], bool reload, int j0,
-                                            int tid, int lane, int wave, float* __restrict__ scores_head,
+                                            int tid, int lane, int wave, int& j_out, float& v_out,
                                             u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
   float* slots = reinterpret_cast<float*>(smem + S::OFF_SLOT);
-  float* raw = reinterpret_cast<float*>(smem + S::OFF_STAT);       // float[MFMA_ROWS]
   const int slot = wave % NRT, ks = wave / NRT;
   const int ntile = g.Rpad / 32;
   const bool plain_chunk = (j0 + MFMA_ROWS - 1 <= g.P);
@@ -470,23 +481,28 @@ __device__ __forceinline__ void chunk_pass2(char* smem, const ScoreGeom& g, int 
     }
   }
   __syncthreads();                        // slots complete, key rows no longer read
-  float v = 0.f;
-  if (tid < MFMA_ROWS) {
-    v = slots[tid];
-#pragma unroll
-    for (int s = 1; s < NRT; ++s) v += slots[s * MFMA_ROWS + tid];
-    raw[tid] = v;
-  }
-  __syncthreads();
+  // raw score of staged row t = sum of the row-tile slots; an owned prefix key takes the maximum of
+  // the raw scores in its pooling window straight from the slots (no second barrier)
   const int j = j0 + tid;
-  if (tid < MFMA_ROWS && j >= own_lo && j < own_lo + own && j < g.L) {
+  j_out = j;
+  v_out = 0.f;
+  const bool owned = tid < MFMA_ROWS && j >= own_lo && j < own_lo + own && j < g.L;
+  if (owned) {
+    int lo = tid, hi = tid;
     if (j < g.P && half > 0) {
-      const int lo = max(j - half, 0) - j0, hi = min(j + half, g.P - 1) - j0;
-      v = raw[lo];
-      for (int i = lo + 1; i <= hi; ++i) v = fmaxf(v, raw[i]);
+      lo = max(j - half, 0) - j0;
+      hi = min(j + half, g.P - 1) - j0;
     }
-    scores_head[j] = v;
+    float v = 0.f;                        // scores are sums of probabilities, never negative
+    for (int i = lo; i <= hi; ++i) {
+      float r = slots[i];
+#pragma unroll
+      for (int s = 1; s < NRT; ++s) r += slots[s * MFMA_ROWS + i];
+      v = fmaxf(v, r);
+    }
+    v_out = v;
   }
+  return owned;
 }
 
 // ---- the two streaming kernels ---------------------------------------------------------------
@@ -581,15 +597,22 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
       }
       const int hn = un / units_per_head, cn = un - hn * units_per_head;
       const KeyRows nkr = key_rows<D>(k + (size_t)hn * g.L * D, max(cn * own - half, 0), g.L, tid);
+      bool owned = false;
+      int j_out = 0;
+      float v_out = 0.f;
+      float2 mz_out = make_float2(0.f, 0.f);
+      float2* part_unit = part + ((size_t)hg * units_per_head + c) * g.Rpad;
       if (PASS == 1)
-        chunk_pass1<D, NRT>(smem, g, qg, qreg, !one_group, j0, tid, lane, wave,
-                            part + ((size_t)hg * units_per_head + c) * g.Rpad, pre, nkr);
+        owned = chunk_pass1<D, NRT>(smem, g, qg, qreg, !one_group, j0, tid, lane, wave, part_unit, j_out, mz_out,
+                                    pre, nkr);
       else
-        chunk_pass2<D, NRT>(smem, g, half, c * own, own, qg, rowc + (size_t)hg * g.Rpad, qreg, cr, !one_group, j0,
-                            tid, lane, wave, scores + (size_t)hg * g.L, pre, nkr);
+        owned = chunk_pass2<D, NRT>(smem, g, half, c * own, own, qg, rowc + (size_t)hg * g.Rpad, qreg, cr,
+                                    !one_group, j0, tid, lane, wave, j_out, v_out, pre, nkr);
       // (every wave's reads of this chunk's rows are behind a barrier by now)
       if (plan.dynamic && first && !single && tid == 0) ctl[0] = claimed;
       commit_chunk<D>(smem, pre, tid);
+      if (PASS == 1 && owned) part_unit[j_out] = mz_out;
+      if (PASS == 2 && owned) scores[(size_t)hg * g.L + j_out] = v_out;
       __syncthreads();
     }
     if (!plan.dynamic) break;
