@@ -494,11 +494,24 @@ __device__ __forceinline__ bool chunk_pass2(char* smem, const ScoreGeom& g, int 
       hi = min(j + half, g.P - 1) - j0;
     }
     float v = 0.f;                        // scores are sums of probabilities, never negative
-    for (int i = lo; i <= hi; ++i) {
+    auto raw_at = [&](int i) {
       float r = slots[i];
 #pragma unroll
       for (int s = 1; s < NRT; ++s) r += slots[s * MFMA_ROWS + i];
-      v = fmaxf(v, r);
+      return r;
+    };
+    if (lo == hi) {
+      v = raw_at(tid);
+    } else if (half <= 3) {
+      // the usual window of up to 7: all reads issued at once (positions clamped into the window
+      // repeat a value, which a maximum does not mind) instead of a chain of LDS round trips
+      float r[7];
+#pragma unroll
+      for (int o = 0; o < 7; ++o) r[o] = raw_at(min(max(tid + o - 3, lo), hi));
+#pragma unroll
+      for (int o = 0; o < 7; ++o) v = fmaxf(v, r[o]);
+    } else {
+      for (int i = lo; i <= hi; ++i) v = fmaxf(v, raw_at(i));
     }
     v_out = v;
   }
