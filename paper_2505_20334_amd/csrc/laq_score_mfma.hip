@@ -569,6 +569,8 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
   __syncthreads();
 
   int hg_loaded = -1;
+  // (head, chunk) of the current unit, kept incrementally: a division only where a run starts
+  int hg = run_u / units_per_head, c = run_u - hg * units_per_head;
   for (;;) {
     int claimed = 0;                      // thread 0: the run claimed while this one is worked on
     for (int u = run_u; u < run_end; ++u) {
@@ -581,10 +583,9 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
           __syncthreads();
         }
       }
-      const int hg = u / units_per_head, c = u - hg * units_per_head;
-      const int inst = hg / g.Hkv, head = hg - inst * g.Hkv;
       const int j0 = max(c * own - half, 0);       // first staged key (the head's first chunk has no left halo)
-      const uint16_t* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * D;
+      // the G query heads of KV head hg are consecutive: rows hg*R .. hg*R+R-1 of Q (R = G*W)
+      const uint16_t* qg = q + (size_t)hg * g.R * D;
       const bool reload = !one_group || hg != hg_loaded;
       hg_loaded = hg;
       if (one_group && reload) {
@@ -598,17 +599,21 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
       }
       // the unit after this one: the next of the run, else the first of the claimed run, else (nothing
       // left) this unit again, which is harmless and keeps the loads in flight the same everywhere
-      int un = u + 1;
-      if (un >= run_end) {
-        un = u;
-        if (plan.dynamic) {
-          // (read from LDS, hence a per-lane value to the compiler: made wave-uniform by hand, or
-          // every load through a descriptor derived from it is wrapped in a uniformity loop)
-          const int s = dyn0 + __builtin_amdgcn_readfirstlane(ctl[0]) * RUN_UNITS;
-          if (s < n_units) un = s;
+      int hn = hg, cn = c;
+      if (u + 1 < run_end) {
+        if (++cn == units_per_head) {
+          cn = 0;
+          ++hn;
+        }
+      } else if (plan.dynamic) {
+        // (read from LDS, hence a per-lane value to the compiler: made wave-uniform by hand, or
+        // every load through a descriptor derived from it is wrapped in a uniformity loop)
+        const int s = dyn0 + __builtin_amdgcn_readfirstlane(ctl[0]) * RUN_UNITS;
+        if (s < n_units) {
+          hn = s / units_per_head;
+          cn = s - hn * units_per_head;
         }
       }
-      const int hn = un / units_per_head, cn = un - hn * units_per_head;
       const KeyRows nkr = key_rows<D>(k + (size_t)hn * g.L * D, max(cn * own - half, 0), g.L, tid);
       bool owned = false;
       int j_out = 0;
@@ -627,11 +632,13 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
       if (PASS == 1 && owned) part_unit[j_out] = mz_out;
       if (PASS == 2 && owned) scores[(size_t)hg * g.L + j_out] = v_out;
       __syncthreads();
+      hg = hn;                            // what was prefetched is what comes next
+      c = cn;
     }
     if (!plan.dynamic) break;
     const int s = dyn0 + __builtin_amdgcn_readfirstlane(ctl[0]) * RUN_UNITS;
     if (s >= n_units) break;
-    run_u = s;
+    run_u = s;                            // (hg, c) already point at unit s
     run_end = min(s + RUN_UNITS, n_units);
   }
 }
