@@ -16,7 +16,7 @@ from __future__ import annotations
 import ctypes
 import os
 import subprocess
-from typing import Optional, Tuple
+from typing import Optional, Sequence, Tuple
 
 import torch
 
@@ -44,7 +44,7 @@ def _load() -> ctypes.CDLL:
         lib = ctypes.CDLL(_LIB)
         c_int, c_dbl, c_vp = ctypes.c_int, ctypes.c_double, ctypes.c_void_p
         lib.laq_oracle_raw_scores.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int,
-                                              c_dbl, c_vp]
+                                              c_vp, c_dbl, c_vp]
         lib.laq_oracle_raw_scores.restype = c_int
         lib.laq_oracle_maxpool.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp]
         lib.laq_oracle_maxpool.restype = c_int
@@ -70,23 +70,33 @@ def _cpu(t: torch.Tensor) -> torch.Tensor:
     return t.contiguous()
 
 
-def raw_scores(q_win: torch.Tensor, k: torch.Tensor, scale: float = 0.0) -> torch.Tensor:
-    """Steps 1-4 for one instance: q_win [Hq, W, d], k [Hkv, L, d] -> raw [Hkv, L] fp64."""
+def raw_scores(q_win: torch.Tensor, k: torch.Tensor, scale: float = 0.0,
+               q_pos: Optional[Sequence[int]] = None) -> torch.Tensor:
+    """Steps 1-4 for one instance: q_win [Hq, W, d], k [Hkv, L, d] -> raw [Hkv, L] fp64.
+
+    q_pos: position of each of the W window queries in the key sequence (query w sees keys
+    j <= q_pos[w]); None = the trailing window, q_pos[w] = L - W + w."""
     q_win, k = _cpu(q_win), _cpu(k)
     Hq, W, d = q_win.shape
     Hkv, L, d2 = k.shape
     if d != d2 or q_win.dtype != k.dtype:
         raise ValueError("q_win / k mismatch")
     raw = torch.empty(Hkv, L, dtype=torch.float64)
+    pos = None
+    if q_pos is not None:
+        if len(q_pos) != W:
+            raise ValueError("q_pos needs one entry per window query")
+        pos = (ctypes.c_int32 * W)(*[int(x) for x in q_pos])
     rc = _load().laq_oracle_raw_scores(q_win.data_ptr(), k.data_ptr(), _dtype_code(k),
-                                       Hq, Hkv, d, L, W, float(scale), raw.data_ptr())
+                                       Hq, Hkv, d, L, W, pos, float(scale), raw.data_ptr())
     if rc != 0:
         raise ValueError("laq_oracle_raw_scores rejected its arguments")
     return raw
 
 
 def maxpool(raw: torch.Tensor, W: int, pool: int) -> torch.Tensor:
-    """Step 5: raw [Hkv, L] fp64 -> pooled [Hkv, L] fp64 (prefix pooled, window columns copied)."""
+    """Step 5: raw [Hkv, L] fp64 -> pooled [Hkv, L] fp64; W = trailing keys always retained
+    (prefix [0, L-W) pooled, the rest copied)."""
     raw = _cpu(raw.double())
     Hkv, L = raw.shape
     out = torch.empty_like(raw)
@@ -97,7 +107,8 @@ def maxpool(raw: torch.Tensor, W: int, pool: int) -> torch.Tensor:
 
 
 def select(scores_f32: torch.Tensor, W: int, budget: int) -> torch.Tensor:
-    """Step 6: scores [Hkv, L] fp32 -> idx [Hkv, min(budget, L)] int32, ascending."""
+    """Step 6: scores [Hkv, L] fp32 -> idx [Hkv, min(budget, L)] int32, ascending; W = trailing
+    keys always retained."""
     if scores_f32.dtype != torch.float32:
         raise TypeError("selection is decided on fp32 scores")
     s = _cpu(scores_f32)
@@ -124,10 +135,11 @@ def compact(src: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
 
 
 def evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], budget: int,
-          pool: int, scale: float = 0.0
+          pool: int, scale: float = 0.0, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None
           ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, Optional[torch.Tensor]]:
-    """Whole path for one instance: returns (pooled fp64 [Hkv, L], idx, k', v')."""
-    W = q_win.shape[1]
-    pooled = maxpool(raw_scores(q_win, k, scale), W, pool)
+    """Whole path for one instance: returns (pooled fp64 [Hkv, L], idx, k', v').
+    keep = trailing keys always retained (None: the number of window queries)."""
+    W = q_win.shape[1] if keep is None else int(keep)
+    pooled = maxpool(raw_scores(q_win, k, scale, q_pos), W, pool)
     idx = select(pooled.float(), W, budget)
     return pooled, idx, compact(k, idx), (compact(v, idx) if v is not None else None)

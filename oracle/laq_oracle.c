@@ -27,6 +27,15 @@
  *      ("ArgSort(...)[:B]" of Eq. 4);
  *   7. the compacted cache is K and V restricted to those rows.
  *
+ * General observation window (Sec. 4.3, Eq. 5, "LAQ++": local window queries
+ * joined with the lookahead Q-cache): each of the W queries carries its own
+ * position q_pos[w] in the key sequence and sees keys j <= q_pos[w]; a
+ * lookahead query, generated after the whole prompt, has q_pos >= L-1 and
+ * sees every key.  The number of trailing keys that are always retained
+ * (`keep`, the local window's own tokens; may be 0) is then independent of W;
+ * ranking and pooling run over the prefix [0, L - keep).  The layout above is
+ * the special case q_pos[w] = L - W + w, keep = W.
+ *
  * Readings where the paper is silent (softmax before the sum, 1/sqrt(d) scale,
  * max- rather than average-pooling, GQA sum, budget including the window,
  * tie-break) are listed in the design notes of the repository.
@@ -57,17 +66,21 @@ static double load_elem(const void *base, int dtype, size_t i)
 
 /*
  * Steps 1-4.  q: [Hq, W, d], k: [Hkv, L, d] in `dtype`; raw: [Hkv, L] doubles.
- * scale <= 0 selects 1/sqrt(d).  Returns 0, or -1 on bad arguments.
+ * q_pos: W positions (query w sees keys j <= q_pos[w]; values beyond L-1 mean
+ * "every key"), or NULL for the trailing window q_pos[w] = L - W + w (needs
+ * W <= L).  scale <= 0 selects 1/sqrt(d).  Returns 0, or -1 on bad arguments.
  */
 int laq_oracle_raw_scores(const void *q, const void *k, int dtype,
                           int Hq, int Hkv, int d, int L, int W,
-                          double scale, double *raw)
+                          const int32_t *q_pos, double scale, double *raw)
 {
     if (!q || !k || !raw || Hq <= 0 || Hkv <= 0 || d <= 0 || L <= 0 || W <= 0 ||
-        W > L || Hq % Hkv != 0 || (dtype != ORACLE_F32 && dtype != ORACLE_BF16))
+        (!q_pos && W > L) || Hq % Hkv != 0 || (dtype != ORACLE_F32 && dtype != ORACLE_BF16))
         return -1;
+    if (q_pos)
+        for (int w = 0; w < W; ++w)
+            if (q_pos[w] < 0) return -1;
     const int G = Hq / Hkv;
-    const int P = L - W;
     if (scale <= 0.0)
         scale = 1.0 / sqrt((double)d);
 
@@ -81,7 +94,9 @@ int laq_oracle_raw_scores(const void *q, const void *k, int dtype,
     for (int h = 0; h < Hq; ++h) {
         const int g = h / G;
         for (int w = 0; w < W; ++w) {
-            const int vis = P + w + 1;            /* keys 0 .. P+w are visible */
+            int last = q_pos ? q_pos[w] : L - W + w;   /* last visible key */
+            if (last > L - 1) last = L - 1;
+            const int vis = last + 1;
             for (int c = 0; c < d; ++c)
                 qrow[c] = load_elem(q, dtype, ((size_t)h * W + w) * d + c);
             double M = -INFINITY;
@@ -109,14 +124,15 @@ int laq_oracle_raw_scores(const void *q, const void *k, int dtype,
 
 /*
  * Step 5.  raw, pooled: [Hkv, L] doubles (may not alias).  pool is odd >= 1.
- * The max runs over the part of the window that lies inside the prefix [0, P);
- * columns j >= P are copied.
+ * keep = number of trailing keys that are always retained (0 <= keep <= L);
+ * P = L - keep.  The max runs over the part of the pooling window that lies
+ * inside the prefix [0, P); columns j >= P are copied.
  */
-int laq_oracle_maxpool(const double *raw, int Hkv, int L, int W, int pool, double *pooled)
+int laq_oracle_maxpool(const double *raw, int Hkv, int L, int keep, int pool, double *pooled)
 {
-    if (!raw || !pooled || Hkv <= 0 || L <= 0 || W <= 0 || W > L || pool < 1 || pool % 2 == 0)
+    if (!raw || !pooled || Hkv <= 0 || L <= 0 || keep < 0 || keep > L || pool < 1 || pool % 2 == 0)
         return -1;
-    const int P = L - W, half = (pool - 1) / 2;
+    const int P = L - keep, half = (pool - 1) / 2;
     for (int g = 0; g < Hkv; ++g) {
         const double *r = raw + (size_t)g * L;
         double *o = pooled + (size_t)g * L;
@@ -153,14 +169,16 @@ static int int32_cmp(const void *a, const void *b)
 
 /*
  * Step 6.  scores: [Hkv, L] fp32 (the precision in which the library takes the
- * decision); idx: [Hkv, Bk] with Bk = min(budget, L).  budget >= W required.
+ * decision); idx: [Hkv, Bk] with Bk = min(budget, L).  keep = number of
+ * trailing keys always retained (0 <= keep <= L, budget >= keep); P = L - keep.
  * A full sort of the prefix by (score descending, index ascending); the first
- * budget - W entries are kept, re-sorted ascending, and followed by P .. L-1.
+ * Bk - keep entries are kept, re-sorted ascending, and followed by P .. L-1.
  */
-int laq_oracle_select(const float *scores, int Hkv, int L, int W, int budget, int32_t *idx)
+int laq_oracle_select(const float *scores, int Hkv, int L, int keep, int budget, int32_t *idx)
 {
-    if (!scores || !idx || Hkv <= 0 || L <= 0 || W <= 0 || W > L || budget < W)
+    if (!scores || !idx || Hkv <= 0 || L <= 0 || keep < 0 || keep > L || budget < keep)
         return -1;
+    const int W = keep;
     const int P = L - W;
     const int Bk = budget < L ? budget : L;
     const int ksel = Bk - W;

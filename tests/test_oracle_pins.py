@@ -383,3 +383,138 @@ def test_pyramid_budget_schedule_endpoints_and_monotone():
     assert all(x > y for x, y in zip(b, b[1:]))
     assert budgets_for(CONFIGS[4]) == b
     assert budgets_for(CONFIGS[5]) == [256] * 256
+
+
+# ----------------------------------------------------------------------------
+# general observation window (Sec. 4.3, Eq. 5): explicit query positions and an
+# independent count of retained trailing keys
+# ----------------------------------------------------------------------------
+def brute_raw_pos(q, k, q_pos, scale=None):
+    """Explicit attention with per-query last visible key, in pure Python loops."""
+    q = q.double().tolist()
+    k = k.double().tolist()
+    Hq, W, d = len(q), len(q[0]), len(q[0][0])
+    Hkv, L = len(k), len(k[0])
+    G = Hq // Hkv
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    raw = [[0.0] * L for _ in range(Hkv)]
+    for h in range(Hq):
+        g = h // G
+        for w in range(W):
+            last = min(q_pos[w], L - 1)
+            s = [scale * sum(a * b for a, b in zip(q[h][w], k[g][j])) for j in range(last + 1)]
+            m = max(s)
+            e = [math.exp(x - m) for x in s]
+            z = sum(e)
+            for j in range(last + 1):
+                raw[g][j] += e[j] / z
+    return np.array(raw)
+
+
+def test_explicit_positions_equal_to_the_default_give_the_same_bits():
+    g = torch.Generator().manual_seed(21)
+    q, k = torch.randn(4, 5, 16, generator=g), torch.randn(2, 40, 16, generator=g)
+    a = oracle.raw_scores(q, k)
+    b = oracle.raw_scores(q, k, q_pos=[35 + w for w in range(5)])
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_positions_match_python_loops(seed):
+    g = torch.Generator().manual_seed(100 + seed)
+    Hq, Hkv, d, L, W = 4, 2, 8, 23, 6
+    q, k = torch.randn(Hq, W, d, generator=g), torch.randn(Hkv, L, d, generator=g)
+    pos = torch.randint(0, L + 5, (W,), generator=g).tolist()       # some beyond L-1, maybe 0
+    pos[0] = 0                                                        # a query that sees one key only
+    got = oracle.raw_scores(q, k, q_pos=pos).numpy()
+    np.testing.assert_allclose(got, brute_raw_pos(q, k, pos), rtol=1e-12, atol=1e-15)
+    # a query that sees one key puts its whole mass there; nothing lands beyond the furthest position
+    assert got[:, 0].min() >= Hq // Hkv - 1e-12
+    far = min(max(pos), L - 1)
+    assert (got[:, far + 1:] == 0).all()
+
+
+def test_lookahead_queries_see_every_key_library_softmax():
+    # queries generated after the prompt (pure LAQ): no mask at all -> plain softmax, any position >= L-1
+    g = torch.Generator().manual_seed(5)
+    Hq, Hkv, d, L, W = 6, 3, 32, 77, 4
+    q, k = torch.randn(Hq, W, d, generator=g), torch.randn(Hkv, L, d, generator=g)
+    for pos in ([L - 1] * W, [L + 3, L, 10 * L, L - 1]):
+        got = oracle.raw_scores(q, k, q_pos=pos)
+        kk = k.double().repeat_interleave(Hq // Hkv, dim=0)
+        att = torch.softmax(torch.einsum("hwc,hjc->hwj", q.double(), kk) / math.sqrt(d), dim=2)
+        want = att.reshape(Hkv, Hq // Hkv, W, L).sum(dim=(1, 2))
+        torch.testing.assert_close(got, want, rtol=1e-12, atol=1e-15)
+        torch.testing.assert_close(got.sum(dim=1), torch.full((Hkv,), float(Hq // Hkv * W), dtype=torch.float64))
+
+
+def test_joined_window_is_the_sum_of_its_parts():
+    # Eq. 5: local window queries joined with lookahead queries; every row is its own softmax, so
+    # the score of the union is the sum of the two runs
+    g = torch.Generator().manual_seed(6)
+    Hq, Hkv, d, L = 4, 2, 16, 50
+    q_loc, q_la = torch.randn(Hq, 3, d, generator=g), torch.randn(Hq, 5, d, generator=g)
+    k = torch.randn(Hkv, L, d, generator=g)
+    pos_loc, pos_la = [L - 3, L - 2, L - 1], [L + i for i in range(5)]
+    both = oracle.raw_scores(torch.cat([q_loc, q_la], dim=1), k, q_pos=pos_loc + pos_la)
+    parts = oracle.raw_scores(q_loc, k, q_pos=pos_loc) + oracle.raw_scores(q_la, k, q_pos=pos_la)
+    torch.testing.assert_close(both, parts, rtol=1e-13, atol=1e-15)
+    # the local part alone is the default layout
+    assert torch.equal(oracle.raw_scores(q_loc, k, q_pos=pos_loc), oracle.raw_scores(q_loc, k))
+
+
+def test_query_order_does_not_matter_when_positions_travel_with_the_queries():
+    g = torch.Generator().manual_seed(8)
+    q, k = torch.randn(2, 6, 8, generator=g), torch.randn(2, 30, 8, generator=g)
+    pos = [3, 29, 11, 40, 0, 17]
+    perm = [4, 2, 0, 5, 1, 3]
+    a = oracle.raw_scores(q, k, q_pos=pos)
+    b = oracle.raw_scores(q[:, perm], k, q_pos=[pos[i] for i in perm])
+    torch.testing.assert_close(a, b, rtol=1e-13, atol=1e-15)
+
+
+def test_negative_position_and_wrong_length_are_rejected():
+    q, k = torch.randn(2, 3, 8), torch.randn(1, 10, 8)
+    with pytest.raises(ValueError):
+        oracle.raw_scores(q, k, q_pos=[1, -1, 2])
+    with pytest.raises(ValueError):
+        oracle.raw_scores(q, k, q_pos=[1, 2])
+    with pytest.raises(ValueError):
+        oracle.raw_scores(torch.randn(2, 12, 8), k)          # default layout needs W <= L
+    oracle.raw_scores(torch.randn(2, 12, 8), k, q_pos=[9] * 12)   # explicit positions do not
+
+
+@pytest.mark.parametrize("keep", [0, 1, 4, 12])
+def test_keep_count_in_pool_and_select_vs_brute(keep):
+    g = torch.Generator().manual_seed(30 + keep)
+    raw = torch.rand(2, 12, generator=g, dtype=torch.float64)
+    raw[0, 5] = raw[0, 2]                                         # a tie
+    pooled = oracle.maxpool(raw, keep, 3)
+    np.testing.assert_array_equal(pooled.numpy(), brute_pool(raw.numpy(), keep, 3))
+    for budget in (keep, keep + 1, 7, 12, 20):
+        if budget < max(keep, 1):
+            continue
+        got = oracle.select(pooled.float(), keep, budget)
+        want = brute_select(pooled.float().numpy(), keep, budget)
+        np.testing.assert_array_equal(got.numpy(), want)
+        assert got.shape[1] == min(budget, 12)
+        if keep:
+            assert got[:, -keep:].tolist() == [list(range(12 - keep, 12))] * 2
+
+
+def test_keep_zero_is_plain_topk_library():
+    g = torch.Generator().manual_seed(31)
+    s = torch.randn(3, 200, generator=g)                          # distinct values: order is unique
+    got = oracle.select(s, 0, 17)
+    want = torch.sort(torch.topk(s, 17, dim=1).indices, dim=1).values.int()
+    assert torch.equal(got, want)
+
+
+def test_select_rejects_budget_below_keep_and_keep_above_length():
+    s = torch.rand(1, 10)
+    with pytest.raises(ValueError):
+        oracle.select(s, 4, 3)
+    with pytest.raises(ValueError):
+        oracle.select(s, 11, 11)
+    with pytest.raises(ValueError):
+        oracle.maxpool(s.double(), -1, 3)
