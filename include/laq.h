@@ -56,10 +56,24 @@ typedef struct laq_shape {
   int32_t Hq;      /* query heads, multiple of Hkv */
   int32_t Hkv;     /* KV heads */
   int32_t d;       /* head size, multiple of 8, <= 256 */
-  int32_t L;       /* key rows per KV head (prefix + window) */
-  int32_t W;       /* window queries per query head, 1 <= W <= L */
+  int32_t L;       /* key rows per KV head */
+  int32_t W;       /* observation-window queries per query head, >= 1 */
   int32_t dtype;   /* laq_dtype of q_win, k, v, k_out, v_out */
   float scale;     /* logit scale; <= 0 selects 1/sqrt(d) */
+  /*
+   * General observation window (Sec. 4.3, Eq. 5: local window queries joined with the
+   * lookahead Q-cache).  Both fields are optional; a zeroed q_pos with keep = -1 is the
+   * trailing-window layout in which the W queries belong to the last W keys.
+   *   q_pos  HOST array [W] or NULL.  q_pos[w] >= 0 is the position of query w in the key
+   *          sequence: it attends to keys j <= q_pos[w]; a lookahead query, generated after
+   *          the prompt, has q_pos[w] >= L-1 and sees every key.  NULL: q_pos[w] = L-W+w
+   *          (needs W <= L).  At most 512 entries (LAQ_ERR_UNSUPPORTED beyond).
+   *   keep   number of trailing keys that are always retained and take no part in ranking
+   *          and pooling (the local window's own tokens), 0 <= keep <= L; negative: W
+   *          (needs W <= L).  Every budget must be >= keep.
+   */
+  const int32_t *q_pos;
+  int32_t keep;
 } laq_shape;
 
 /* Bytes of device scratch that laq_score / laq_evict need for this shape (0 on a bad shape). */
@@ -67,7 +81,7 @@ size_t laq_workspace_bytes(const laq_shape *shape);
 
 /*
  * Importance scores (Eq. 4's sum over the Q-cache, taken on attention scores).
- *   q_win  [n_inst, Hq, W, d]   window (lookahead) queries
+ *   q_win  [n_inst, Hq, W, d]   observation-window queries (Q-cache, local window, or both)
  *   k      [n_inst, Hkv, L, d]  key cache (streamed twice: softmax statistics, then normalised scores)
  *   scores [n_inst, Hkv, L]     fp32 out.  For each KV head g and key j:
  *            raw[g,j] = sum over the G heads of the group and the W queries of

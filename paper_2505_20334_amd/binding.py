@@ -28,7 +28,8 @@ class LaqError(RuntimeError):
 class _Shape(ctypes.Structure):
     _fields_ = [("n_inst", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("L", ctypes.c_int32), ("W", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("q_pos", ctypes.POINTER(ctypes.c_int32)), ("keep", ctypes.c_int32)]
 
 
 def lib_path() -> str:
@@ -88,8 +89,17 @@ def _stream(stream) -> int:
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
-def _shape(n: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: int, scale: float) -> _Shape:
-    return _Shape(n, Hq, Hkv, d, L, W, dtype, float(scale))
+def _shape(n: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: int, scale: float,
+           q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None) -> _Shape:
+    """q_pos: position of every window query in the key sequence (None: the trailing window);
+    keep: trailing keys always retained (None: W).  The position array stays alive with the struct."""
+    sh = _Shape(n, Hq, Hkv, d, L, W, dtype, float(scale), None, -1 if keep is None else int(keep))
+    if q_pos is not None:
+        if len(q_pos) != W:
+            raise ValueError("q_pos needs one entry per window query")
+        sh._q_pos_keepalive = (ctypes.c_int32 * W)(*[int(x) for x in q_pos])
+        sh.q_pos = ctypes.cast(sh._q_pos_keepalive, ctypes.POINTER(ctypes.c_int32))
+    return sh
 
 
 def _budget_array(budget: Sequence[int], n: int):
@@ -107,16 +117,17 @@ def packed_rows(budget: Sequence[int], Hkv: int, L: int) -> Tuple[int, List[int]
     return row, starts
 
 
-def laq_workspace_bytes(n_inst: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: torch.dtype) -> int:
+def laq_workspace_bytes(n_inst: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: torch.dtype,
+                        q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None) -> int:
     code = LAQ_F32 if dtype == torch.float32 else LAQ_BF16
-    sh = _shape(n_inst, Hq, Hkv, d, L, W, code, 0.0)
+    sh = _shape(n_inst, Hq, Hkv, d, L, W, code, 0.0, q_pos, keep)
     return int(load_library().laq_workspace_bytes(ctypes.byref(sh)))
 
 
-def _workspace(q_win, k, ws):
+def _workspace(q_win, k, ws, q_pos=None, keep=None):
     n, Hq, W, d = q_win.shape
     _, Hkv, L, _ = k.shape
-    need = laq_workspace_bytes(n, Hq, Hkv, d, L, W, k.dtype)
+    need = laq_workspace_bytes(n, Hq, Hkv, d, L, W, k.dtype, q_pos, keep)
     if ws is None:
         ws = torch.empty(need, dtype=torch.uint8, device=k.device)
     return ws, ws.numel() * ws.element_size()
@@ -124,8 +135,9 @@ def _workspace(q_win, k, ws):
 
 def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale: float = 0.0,
               scores: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
-              stream=None) -> torch.Tensor:
-    """q_win [n, Hq, W, d], k [n, Hkv, L, d] -> scores [n, Hkv, L] fp32 (pooled if pool_kernel > 1)."""
+              stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None) -> torch.Tensor:
+    """q_win [n, Hq, W, d], k [n, Hkv, L, d] -> scores [n, Hkv, L] fp32 (pooled if pool_kernel > 1).
+    q_pos / keep: the general observation window of laq_shape (None: trailing window)."""
     lib = load_library()
     _dev(q_win, "q_win"), _dev(k, "k")
     n, Hq, W, d = q_win.shape
@@ -134,8 +146,8 @@ def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale:
         raise ValueError("q_win / k mismatch")
     if scores is None:
         scores = torch.empty(n, Hkv, L, dtype=torch.float32, device=k.device)
-    ws, ws_bytes = _workspace(q_win, k, ws)
-    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale)
+    ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep)
     rc = lib.laq_score(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), int(pool_kernel), scores.data_ptr(),
                        ws.data_ptr(), ws_bytes, _stream(stream))
     if rc != 0:
@@ -143,9 +155,10 @@ def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale:
     return scores
 
 
-def laq_select(scores: torch.Tensor, budget: Sequence[int], pool_kernel: int, W: int,
+def laq_select(scores: torch.Tensor, budget: Sequence[int], pool_kernel: int, keep: int,
                idx: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """scores [n, Hkv, L] fp32 -> packed idx (int32, see packed_rows)."""
+    """scores [n, Hkv, L] fp32 -> packed idx (int32, see packed_rows); keep = trailing keys always
+    retained (the window size W in the trailing-window layout)."""
     lib = load_library()
     _dev(scores, "scores")
     if scores.dtype != torch.float32:
@@ -154,7 +167,7 @@ def laq_select(scores: torch.Tensor, budget: Sequence[int], pool_kernel: int, W:
     total, _ = packed_rows(budget, Hkv, L)
     if idx is None:
         idx = torch.empty(total, dtype=torch.int32, device=scores.device)
-    sh = _shape(n, Hkv, Hkv, 8, L, W, LAQ_F32, 0.0)
+    sh = _shape(n, Hkv, Hkv, 8, L, 1, LAQ_F32, 0.0, None, keep)
     rc = lib.laq_select(ctypes.byref(sh), scores.data_ptr(), _budget_array(budget, n), int(pool_kernel),
                         idx.data_ptr(), _stream(stream))
     if rc != 0:
@@ -162,9 +175,10 @@ def laq_select(scores: torch.Tensor, budget: Sequence[int], pool_kernel: int, W:
     return idx
 
 
-def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, budget: Sequence[int], W: int,
+def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, budget: Sequence[int], keep: int,
                 k_out: Optional[torch.Tensor] = None, v_out: Optional[torch.Tensor] = None, stream=None):
-    """k, v [n, Hkv, L, d] + packed idx -> packed k_out, v_out [rows, d]."""
+    """k, v [n, Hkv, L, d] + packed idx -> packed k_out, v_out [rows, d]; keep as in laq_select
+    (only used to check the budgets)."""
     lib = load_library()
     _dev(k, "k"), _dev(idx, "idx")
     n, Hkv, L, d = k.shape
@@ -177,7 +191,7 @@ def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, b
             raise ValueError("k / v mismatch")
         if v_out is None:
             v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
-    sh = _shape(n, Hkv, Hkv, d, L, W, _dtype_code(k), 0.0)
+    sh = _shape(n, Hkv, Hkv, d, L, 1, _dtype_code(k), 0.0, None, keep)
     rc = lib.laq_compact(ctypes.byref(sh), k.data_ptr(), v.data_ptr() if v is not None else None,
                          idx.data_ptr(), _budget_array(budget, n), k_out.data_ptr(),
                          v_out.data_ptr() if v is not None else None, _stream(stream))
@@ -188,7 +202,7 @@ def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, b
 
 def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], budget: Sequence[int],
               pool_kernel: int, scale: float = 0.0, scores=None, idx=None, k_out=None, v_out=None, ws=None,
-              stream=None):
+              stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None):
     """Whole path on one stream: returns (scores, idx, k_out, v_out); layouts as in the three calls."""
     lib = load_library()
     _dev(q_win, "q_win"), _dev(k, "k")
@@ -207,8 +221,8 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
         _dev(v, "v")
         if v_out is None:
             v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
-    ws, ws_bytes = _workspace(q_win, k, ws)
-    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale)
+    ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep)
     rc = lib.laq_evict(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), v.data_ptr() if v is not None else None,
                        _budget_array(budget, n), int(pool_kernel), scores.data_ptr(), idx.data_ptr(),
                        k_out.data_ptr(), v_out.data_ptr() if v is not None else None, ws.data_ptr(), ws_bytes,

@@ -9,21 +9,42 @@ namespace laq {
 
 static bool pool_ok(int pool) { return pool >= 1 && pool <= MAX_POOL && (pool % 2) == 1; }
 
-static bool make_geom(const laq_shape* s, ScoreGeom* g) {
-  if (!s) return false;
-  if (s->n_inst < 1 || s->Hq < 1 || s->Hkv < 1 || s->d < 8 || s->d > 256 || (s->d % 8) != 0) return false;
-  if (s->L < 1 || s->W < 1 || s->W > s->L || (s->Hq % s->Hkv) != 0) return false;
-  if (s->dtype != LAQ_F32 && s->dtype != LAQ_BF16) return false;
-  if (!(s->scale == s->scale) || isinf(s->scale)) return false;
+// Geometry of a call.  Returns LAQ_OK, LAQ_ERR_INVALID or LAQ_ERR_UNSUPPORTED; fills the query
+// position table (qp may be null for calls that do not score) when positions are explicit.
+static int make_geom(const laq_shape* s, ScoreGeom* g, QueryPos* qp = nullptr) {
+  if (!s) return LAQ_ERR_INVALID;
+  if (s->n_inst < 1 || s->Hq < 1 || s->Hkv < 1 || s->d < 8 || s->d > 256 || (s->d % 8) != 0) return LAQ_ERR_INVALID;
+  if (s->L < 1 || s->W < 1 || (s->Hq % s->Hkv) != 0) return LAQ_ERR_INVALID;
+  if ((!s->q_pos || s->keep < 0) && s->W > s->L) return LAQ_ERR_INVALID;   // trailing-window defaults need W <= L
+  if (s->keep > s->L) return LAQ_ERR_INVALID;
+  if (s->dtype != LAQ_F32 && s->dtype != LAQ_BF16) return LAQ_ERR_INVALID;
+  if (!(s->scale == s->scale) || isinf(s->scale)) return LAQ_ERR_INVALID;
   g->n_inst = s->n_inst; g->Hq = s->Hq; g->Hkv = s->Hkv; g->d = s->d; g->L = s->L; g->W = s->W;
   g->G = s->Hq / s->Hkv;
   g->R = g->G * s->W;
-  g->P = s->L - s->W;
+  g->keep = s->keep < 0 ? s->W : s->keep;
+  g->P = s->L - g->keep;
+  g->pos0 = s->L - s->W;
+  g->explicit_pos = s->q_pos ? 1 : 0;
+  g->qmin = g->pos0;
+  if (s->q_pos) {
+    if (s->W > MAX_QPOS) return LAQ_ERR_UNSUPPORTED;
+    int qmin = s->L - 1;
+    for (int w = 0; w < s->W; ++w) {
+      if (s->q_pos[w] < 0) return LAQ_ERR_INVALID;
+      const int last = s->q_pos[w] < s->L - 1 ? s->q_pos[w] : s->L - 1;
+      if (qp) qp->last[w] = last;
+      if (last < qmin) qmin = last;
+    }
+    g->qmin = qmin;
+  } else if (qp && s->W <= MAX_QPOS) {
+    for (int w = 0; w < s->W; ++w) qp->last[w] = g->pos0 + w;
+  }
   g->Rpad = (g->R + 31) / 32 * 32;
   g->nchunk = (s->L + CHUNK_ROWS - 1) / CHUNK_ROWS;
   const float sc = s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d);
   g->scale2 = sc * 1.44269504088896340736f;
-  return true;
+  return LAQ_OK;
 }
 
 static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -67,26 +88,30 @@ static int fill_table(const laq_shape* s, const int32_t* budget, int i0, int n, 
   return bk_max;
 }
 
-static bool budgets_ok(const laq_shape* s, const int32_t* budget) {
+static bool budgets_ok(const laq_shape* s, const ScoreGeom& g, const int32_t* budget) {
   if (!budget) return false;
   for (int i = 0; i < s->n_inst; ++i)
-    if (budget[i] < s->W) return false;
+    if (budget[i] < g.keep || budget[i] < 1) return false;
   return true;
 }
 
 static int score_impl(const laq_shape* shape, const void* q_win, const void* k, int pool, float* scores,
                       void* ws, size_t ws_bytes, hipStream_t st) {
   ScoreGeom g;
-  if (!make_geom(shape, &g) || !pool_ok(pool) || !q_win || !k || !scores) return LAQ_ERR_INVALID;
+  QueryPos qp;
+  memset(&qp, 0, sizeof qp);
+  const int rc = make_geom(shape, &g, &qp);
+  if (rc != LAQ_OK) return rc;
+  if (!pool_ok(pool) || !q_win || !k || !scores) return LAQ_ERR_INVALID;
   if (!ws || ws_bytes < workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
   if (g.Hkv > 65535 || g.n_inst > 65535 || (long long)g.Hkv * g.n_inst > 0x7fffffffLL) return LAQ_ERR_UNSUPPORTED;
   const Workspace w = carve_workspace(g, ws);
   hipError_t e;
   if (score_mfma_supported(g, shape->dtype)) {
-    e = launch_score_mfma(g, pool, q_win, k, scores, w, st);         // pooling fused into pass 2
+    e = launch_score_mfma(g, qp, pool, q_win, k, scores, w, st);     // pooling fused into pass 2
   } else {
     float* raw = pool > 1 ? w.raw : scores;
-    e = launch_score_generic(g, shape->dtype, q_win, k, raw, w, st);
+    e = launch_score_generic(g, qp, shape->dtype, q_win, k, raw, w, st);
     if (e == hipSuccess && pool > 1) e = launch_pool(g, pool, raw, scores, st);
   }
   return e == hipSuccess ? LAQ_OK : LAQ_ERR_DEVICE;
@@ -95,8 +120,9 @@ static int score_impl(const laq_shape* shape, const void* q_win, const void* k, 
 static int select_impl(const laq_shape* shape, const float* scores, const int32_t* budget, int pool,
                        int32_t* idx, hipStream_t st) {
   ScoreGeom g;
-  if (!make_geom(shape, &g) || !pool_ok(pool) || !scores || !idx || !budgets_ok(shape, budget))
-    return LAQ_ERR_INVALID;
+  const int rc = make_geom(shape, &g);
+  if (rc != LAQ_OK) return rc;
+  if (!pool_ok(pool) || !scores || !idx || !budgets_ok(shape, g, budget)) return LAQ_ERR_INVALID;
   if (g.Hkv > 65535) return LAQ_ERR_UNSUPPORTED;
   int64_t row = 0;
   for (int i0 = 0; i0 < shape->n_inst; i0 += MAX_INST_PER_LAUNCH) {
@@ -104,7 +130,7 @@ static int select_impl(const laq_shape* shape, const float* scores, const int32_
     InstTable tab;
     memset(&tab, 0, sizeof tab);
     fill_table(shape, budget, i0, n, row, &tab, &row);
-    if (launch_select(n, i0, g.Hkv, g.L, g.W, pool, scores, tab, idx, st) != hipSuccess) return LAQ_ERR_DEVICE;
+    if (launch_select(n, i0, g.Hkv, g.L, g.keep, pool, scores, tab, idx, st) != hipSuccess) return LAQ_ERR_DEVICE;
   }
   return LAQ_OK;
 }
@@ -112,7 +138,9 @@ static int select_impl(const laq_shape* shape, const float* scores, const int32_
 static int compact_impl(const laq_shape* shape, const void* k, const void* v, const int32_t* idx,
                         const int32_t* budget, void* k_out, void* v_out, hipStream_t st) {
   ScoreGeom g;
-  if (!make_geom(shape, &g) || !k || !k_out || !idx || !budgets_ok(shape, budget)) return LAQ_ERR_INVALID;
+  const int rc = make_geom(shape, &g);
+  if (rc != LAQ_OK) return rc;
+  if (!k || !k_out || !idx || !budgets_ok(shape, g, budget)) return LAQ_ERR_INVALID;
   if ((v == nullptr) != (v_out == nullptr)) return LAQ_ERR_INVALID;
   const int row_bytes = g.d * (shape->dtype == LAQ_F32 ? 4 : 2);
   int64_t row = 0;
@@ -133,7 +161,7 @@ extern "C" {
 
 size_t laq_workspace_bytes(const laq_shape* shape) {
   laq::ScoreGeom g;
-  if (!laq::make_geom(shape, &g)) return 0;
+  if (laq::make_geom(shape, &g) != LAQ_OK) return 0;
   return laq::workspace_bytes(g);
 }
 
@@ -157,8 +185,10 @@ int laq_evict(const laq_shape* shape, const void* q_win, const void* k, const vo
               size_t ws_bytes, void* stream) {
   // validate everything first so that a rejected call has enqueued nothing
   laq::ScoreGeom g;
-  if (!laq::make_geom(shape, &g) || !laq::pool_ok(pool_kernel) || !q_win || !k || !scores || !idx || !k_out ||
-      !laq::budgets_ok(shape, budget) || ((v == nullptr) != (v_out == nullptr)))
+  const int rc0 = laq::make_geom(shape, &g);
+  if (rc0 != LAQ_OK) return rc0;
+  if (!laq::pool_ok(pool_kernel) || !q_win || !k || !scores || !idx || !k_out ||
+      !laq::budgets_ok(shape, g, budget) || ((v == nullptr) != (v_out == nullptr)))
     return LAQ_ERR_INVALID;
   if (!ws || ws_bytes < laq::workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);

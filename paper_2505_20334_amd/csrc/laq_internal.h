@@ -23,13 +23,31 @@ constexpr int MIN_CHUNK_ROWS = MFMA_ROWS < CHUNK_ROWS ? MFMA_ROWS : CHUNK_ROWS;
 constexpr int MAX_POOL = 63;
 constexpr int MAX_INST_PER_LAUNCH = 256;   // size of the per-instance tables passed as kernel arguments
 
+constexpr int MAX_QPOS = 512;              // explicit query positions a call may carry
+
 struct ScoreGeom {
   int n_inst, Hq, Hkv, d, L, W;
-  int G, R, P;
+  int G, R;
+  int keep;      // trailing keys always retained
+  int P;         // L - keep: the prefix that is ranked and pooled
   int Rpad;      // R rounded up to a multiple of 32
   int nchunk;    // ceil(L / CHUNK_ROWS)
+  int pos0;      // trailing-window layout: query w sees keys j <= pos0 + w (pos0 = L - W)
+  int explicit_pos;   // 1: positions come from the QueryPos table instead
+  int qmin;      // smallest last-visible key over the W queries: keys up to here need no mask
   float scale2;  // scale * log2(e): logits are kept in base-2 units
 };
+
+// Last key each window query sees (already clamped to L-1); passed by value to the kernels.
+// Filled for every call with W <= MAX_QPOS (also with the trailing-window positions), so that the
+// matrix-core kernels only ever look positions up; longer trailing windows take the generic path,
+// which computes them.
+struct QueryPos {
+  int32_t last[MAX_QPOS];
+};
+__device__ __forceinline__ int last_visible_key(const ScoreGeom& g, const QueryPos& qp, int w) {
+  return g.explicit_pos ? qp.last[w] : g.pos0 + w;
+}
 
 // Workspace carving: [partials | row constants | raw scores]
 //   part:  float2 (m, z) per (instance, KV head, chunk, padded row): softmax statistics of a chunk
@@ -54,14 +72,14 @@ struct InstTable {
 };
 
 // launchers (each returns hipGetLastError() after its last launch); `raw` receives unpooled scores
-hipError_t launch_score_generic(const ScoreGeom& g, int dtype, const void* q, const void* k, float* raw,
-                                const Workspace& ws, hipStream_t st);
+hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, int dtype, const void* q, const void* k,
+                                float* raw, const Workspace& ws, hipStream_t st);
 hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStream_t st);
 bool score_mfma_supported(const ScoreGeom& g, int dtype);
-hipError_t launch_score_mfma(const ScoreGeom& g, int pool, const void* q, const void* k, float* scores,
-                             const Workspace& ws, hipStream_t st);
+hipError_t launch_score_mfma(const ScoreGeom& g, const QueryPos& qp, int pool, const void* q, const void* k,
+                             float* scores, const Workspace& ws, hipStream_t st);
 hipError_t launch_pool(const ScoreGeom& g, int pool, const float* raw, float* pooled, hipStream_t st);
-hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int W, int pool, const float* scores,
+hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int keep, int pool, const float* scores,
                          const InstTable& tab, int32_t* idx, hipStream_t st);
 hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, int bk_max, const void* k,
                           const void* v, const int32_t* idx, const InstTable& tab, void* k_out, void* v_out,

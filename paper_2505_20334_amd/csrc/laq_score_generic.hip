@@ -37,7 +37,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // One workgroup per (chunk, KV head, instance); thread t owns key chunk * 256 + t.
 template <typename T>
-__global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, const T* __restrict__ q,
+__global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, QueryPos qp,
+                                                                   const T* __restrict__ q,
                                                                    const T* __restrict__ k,
                                                                    float2* __restrict__ part) {
   __shared__ float red[4];
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, 
 
   for (int r = 0; r < g.R; ++r) {
     const int w = r % g.W;
-    const bool vis = owned && (j <= g.P + w);
+    const bool vis = owned && (j <= last_visible_key(g, qp, w));
     float s = vis ? g.scale2 * dot_row(qg + (size_t)r * g.d, krow, g.d) : NEG_BIG;
     float m = wave_max(s);
     if (lane == 0) red[wave] = m;
@@ -68,7 +69,8 @@ __global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, 
 }
 
 template <typename T>
-__global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, const T* __restrict__ q,
+__global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, QueryPos qp,
+                                                                  const T* __restrict__ q,
                                                                   const T* __restrict__ k,
                                                                   const float* __restrict__ rowc,
                                                                   float* __restrict__ raw) {
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, c
   float acc = 0.f;
   for (int r = 0; r < g.R; ++r) {
     const int w = r % g.W;
-    if (j <= g.P + w) acc += exp2f(g.scale2 * dot_row(qg + (size_t)r * g.d, krow, g.d) - c[r]);
+    if (j <= last_visible_key(g, qp, w)) acc += exp2f(g.scale2 * dot_row(qg + (size_t)r * g.d, krow, g.d) - c[r]);
   }
   raw[((size_t)inst * g.Hkv + head) * g.L + j] = acc;
 }
@@ -134,14 +136,14 @@ hipError_t launch_pool(const ScoreGeom& g, int pool, const float* raw, float* po
   return hipGetLastError();
 }
 
-hipError_t launch_score_generic(const ScoreGeom& g, int dtype, const void* q, const void* k, float* raw,
-                                const Workspace& ws, hipStream_t st) {
+hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, int dtype, const void* q, const void* k,
+                                float* raw, const Workspace& ws, hipStream_t st) {
   dim3 grid(g.nchunk, g.Hkv, g.n_inst), block(CHUNK_ROWS);
   if (dtype == LAQ_F32) {
-    hipLaunchKernelGGL(stats_generic_kernel<float>, grid, block, 0, st, g, (const float*)q, (const float*)k,
+    hipLaunchKernelGGL(stats_generic_kernel<float>, grid, block, 0, st, g, qp, (const float*)q, (const float*)k,
                        ws.part);
   } else {
-    hipLaunchKernelGGL(stats_generic_kernel<uint16_t>, grid, block, 0, st, g, (const uint16_t*)q,
+    hipLaunchKernelGGL(stats_generic_kernel<uint16_t>, grid, block, 0, st, g, qp, (const uint16_t*)q,
                        (const uint16_t*)k, ws.part);
   }
   hipError_t e = hipGetLastError();
@@ -149,10 +151,10 @@ hipError_t launch_score_generic(const ScoreGeom& g, int dtype, const void* q, co
   e = launch_row_constants(g, ws, st);
   if (e != hipSuccess) return e;
   if (dtype == LAQ_F32) {
-    hipLaunchKernelGGL(norm_generic_kernel<float>, grid, block, 0, st, g, (const float*)q, (const float*)k,
+    hipLaunchKernelGGL(norm_generic_kernel<float>, grid, block, 0, st, g, qp, (const float*)q, (const float*)k,
                        ws.rowc, raw);
   } else {
-    hipLaunchKernelGGL(norm_generic_kernel<uint16_t>, grid, block, 0, st, g, (const uint16_t*)q,
+    hipLaunchKernelGGL(norm_generic_kernel<uint16_t>, grid, block, 0, st, g, qp, (const uint16_t*)q,
                        (const uint16_t*)k, ws.rowc, raw);
   }
   return hipGetLastError();

@@ -306,20 +306,21 @@ __device__ __forceinline__ void pass2_pipe(const char* ldsK, const bf16x8 (&qreg
   });
 }
 
-// ---- per-tile passes for chunks that touch the causal region (the last chunks of a head) ----
-// A masked logit enters as -inf through the accumulator's initial value.
+// ---- per-tile passes for chunks with keys that some window query does not see ----------------
+// (with the trailing-window layout: the last chunks of a head).  Query w of the window sees keys
+// j <= last_visible_key(w); a masked logit enters as -inf through the accumulator's initial value.
 template <int D>
 __device__ __forceinline__ void pass1_masked(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS],
-                                             const ScoreGeom& g, int rt, int kt0, int kt1, int j0, int lane,
-                                             float& m_run, float& z_run) {
+                                             const ScoreGeom& g, const QueryPos& qp, int rt, int kt0, int kt1,
+                                             int j0, int lane, float& m_run, float& z_run) {
   const int hf = lane >> 5;
   const int w = (rt * 32 + (lane & 31)) % g.W;
-  const int t_hi = g.P + w - j0;          // last staged row this lane's score row may see
+  const int t_hi = qp.last[w] - j0;       // last staged row this lane's score row may see
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int kt = kt0; kt < kt1; ++kt) {
     const int t0 = kt * 32;
     f32x16 acc;
-    if (j0 + t0 + 31 > g.P) {
+    if (j0 + t0 + 31 > g.qmin) {
       f32x16 bias;
 #pragma unroll
       for (int i = 0; i < 16; ++i) bias[i] = (t0 + acc_row(i, hf) <= t_hi) ? 0.f : -INFINITY;
@@ -341,20 +342,20 @@ __device__ __forceinline__ void pass1_masked(const char* ldsK, const bf16x8 (&qr
 
 template <int D>
 __device__ __forceinline__ void pass2_masked(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS],
-                                             const ScoreGeom& g, const float (&c)[16], int rt, int kt0, int kt1,
-                                             int j0, int lane, float* slotbuf, bool first) {
+                                             const ScoreGeom& g, const QueryPos& qp, const float (&c)[16], int rt,
+                                             int kt0, int kt1, int j0, int lane, float* slotbuf, bool first) {
   const int hf = lane >> 5, n = lane & 31;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int kt = kt0; kt < kt1; ++kt) {
     const int t0 = kt * 32;
     f32x16 acc;
-    if (j0 + t0 + 31 > g.P) {
+    if (j0 + t0 + 31 > g.qmin) {
       f32x16 bias;
       const int j = j0 + t0 + n;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int w = (rt * 32 + acc_row(i, hf)) % g.W;
-        bias[i] = (j <= g.P + w) ? 0.f : -INFINITY;
+        bias[i] = (j <= qp.last[w]) ? 0.f : -INFINITY;
       }
       acc = tile_product<D, false>(ldsK, kt, lane, qreg, bias);
     } else {
@@ -383,7 +384,8 @@ __device__ __forceinline__ void pass2_masked(const char* ldsK, const bf16x8 (&qr
 // this thread holds one, for out[idx_out]): the caller stores them after it has moved the next
 // chunk's rows into LDS, so that the wait for those rows is not also a wait for the store.
 template <int D, int NRT>
-__device__ __forceinline__ bool chunk_pass1(char* smem, const ScoreGeom& g, const uint16_t* __restrict__ qg,
+__device__ __forceinline__ bool chunk_pass1(char* smem, const ScoreGeom& g, const QueryPos& qp,
+                                            const uint16_t* __restrict__ qg,
                                             bf16x8 (&qreg)[Tile<D>::KSTEPS], bool reload, int j0, int tid, int lane,
                                             int wave, float2* __restrict__ out, int& idx_out, float2& mz_out,
                                             u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
@@ -393,7 +395,7 @@ __device__ __forceinline__ bool chunk_pass1(char* smem, const ScoreGeom& g, cons
   float2* stat = reinterpret_cast<float2*>(smem + S::OFF_STAT);
   const int slot = wave % NRT, ks = wave / NRT;
   const int ntile = g.Rpad / 32;
-  const bool plain_chunk = (j0 + MFMA_ROWS - 1 <= g.P);    // no key beyond the prefix: no causal mask
+  const bool plain_chunk = (j0 + MFMA_ROWS - 1 <= g.qmin);  // every window query sees every key of the chunk
   for (int rg = 0; rg * NRT < ntile; ++rg) {
     const int rt = rg * NRT + slot;
     float m_run = NEG_BIG, z_run = 0.f;
@@ -407,7 +409,7 @@ __device__ __forceinline__ bool chunk_pass1(char* smem, const ScoreGeom& g, cons
           pass1_pipe<D, TPW, false>(smem, qreg, ks * TPW, g.scale2, lane, m_run, z_run, pre, nkr);
       } else {
         if (rg == 0) fetch_chunk<D>(pre, nkr);
-        pass1_masked<D>(smem, qreg, g, rt, ks * TPW, ks * TPW + TPW, j0, lane, m_run, z_run);
+        pass1_masked<D>(smem, qreg, g, qp, rt, ks * TPW, ks * TPW + TPW, j0, lane, m_run, z_run);
       }
     } else if (rg == 0) {
       fetch_chunk<D>(pre, nkr);                              // a wave without a row tile still fetches its share
@@ -443,7 +445,8 @@ __device__ __forceinline__ bool chunk_pass1(char* smem, const ScoreGeom& g, cons
 // (v_out); the caller stores it after it has moved the next chunk's rows into LDS, so that the
 // wait for those rows is not also a wait for the store.  c points at the head's row constants.
 template <int D, int NRT>
-__device__ __forceinline__ bool chunk_pass2(char* smem, const ScoreGeom& g, int half, int own_lo, int own,
+__device__ __forceinline__ bool chunk_pass2(char* smem, const ScoreGeom& g, const QueryPos& qp, int half,
+                                            int own_lo, int own,
                                             const uint16_t* __restrict__ qg, const float* __restrict__ c,
                                             bf16x8 (&qreg)[Tile<D>::KSTEPS], float (&cr)[16], bool reload, int j0,
                                             int tid, int lane, int wave, int& j_out, float& v_out,
@@ -453,7 +456,7 @@ __device__ __forceinline__ bool chunk_pass2(char* smem, const ScoreGeom& g, int 
   float* slots = reinterpret_cast<float*>(smem + S::OFF_SLOT);
   const int slot = wave % NRT, ks = wave / NRT;
   const int ntile = g.Rpad / 32;
-  const bool plain_chunk = (j0 + MFMA_ROWS - 1 <= g.P);
+  const bool plain_chunk = (j0 + MFMA_ROWS - 1 <= g.qmin);
   // every (slot, key tile) cell of the slot buffer belongs to exactly one wave; a slot whose first
   // row tile does not exist (fewer tiles than slots) is cleared by its wave instead
   if (slot >= ntile) {
@@ -476,7 +479,7 @@ __device__ __forceinline__ bool chunk_pass2(char* smem, const ScoreGeom& g, int 
           pass2_pipe<D, TPW, false>(smem, qreg, ks * TPW, cr, g.scale2, lane, myslot, false, pre, nkr);
       } else {
         if (rg == 0) fetch_chunk<D>(pre, nkr);
-        pass2_masked<D>(smem, qreg, g, cr, rt, ks * TPW, ks * TPW + TPW, j0, lane, myslot, rg == 0);
+        pass2_masked<D>(smem, qreg, g, qp, cr, rt, ks * TPW, ks * TPW + TPW, j0, lane, myslot, rg == 0);
       }
     }
   }
@@ -541,8 +544,9 @@ struct StreamPlan {
 };
 
 template <int D, int NRT, int PASS>
-__global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom g, int half, StreamPlan plan,
-                                                            const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom g, QueryPos qp, int half,
+                                                                      StreamPlan plan,
+                                                                      const uint16_t* __restrict__ q,
                                                             const uint16_t* __restrict__ k,
                                                             float2* __restrict__ part,
                                                             const float* __restrict__ rowc,
@@ -621,10 +625,10 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
       float2 mz_out = make_float2(0.f, 0.f);
       float2* part_unit = part + ((size_t)hg * units_per_head + c) * g.Rpad;
       if (PASS == 1)
-        owned = chunk_pass1<D, NRT>(smem, g, qg, qreg, !one_group, j0, tid, lane, wave, part_unit, j_out, mz_out,
+        owned = chunk_pass1<D, NRT>(smem, g, qp, qg, qreg, !one_group, j0, tid, lane, wave, part_unit, j_out, mz_out,
                                     pre, nkr);
       else
-        owned = chunk_pass2<D, NRT>(smem, g, half, c * own, own, qg, rowc + (size_t)hg * g.Rpad, qreg, cr,
+        owned = chunk_pass2<D, NRT>(smem, g, qp, half, c * own, own, qg, rowc + (size_t)hg * g.Rpad, qreg, cr,
                                     !one_group, j0, tid, lane, wave, j_out, v_out, pre, nkr);
       // (every wave's reads of this chunk's rows are behind a barrier by now)
       if (plan.dynamic && first && !single && tid == 0) ctl[0] = claimed;
@@ -675,8 +679,8 @@ __global__ __launch_bounds__(256) void row_constants_mfma_kernel(ScoreGeom g, co
 }
 
 template <int D, int NRT>
-hipError_t launch_stream(const ScoreGeom& g, int pool, const uint16_t* q, const uint16_t* k, float* scores,
-                         const Workspace& ws, hipStream_t st) {
+hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, int pool, const uint16_t* q, const uint16_t* k,
+                         float* scores, const Workspace& ws, hipStream_t st) {
   constexpr int bytes = Smem<D, NRT>::BYTES;
   static int resident_of[64] = {0};        // workgroups each device holds at once (queried once per device)
   int dev = 0;
@@ -726,41 +730,41 @@ hipError_t launch_stream(const ScoreGeom& g, int pool, const uint16_t* q, const 
   const StreamPlan p1 = make_plan(nu1, units1, &grid1), p2 = make_plan(nu2, units2, &grid2);
   hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, ws.ctr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL((stream_kernel<D, NRT, 1>), dim3(grid1), dim3(THREADS), bytes, st, g, 0, p1, q, k, ws.part,
+  hipLaunchKernelGGL((stream_kernel<D, NRT, 1>), dim3(grid1), dim3(THREADS), bytes, st, g, qp, 0, p1, q, k, ws.part,
                      (const float*)nullptr, (float*)nullptr, ws.ctr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(row_constants_mfma_kernel, dim3((unsigned)n_heads, g.Rpad / 32), dim3(256), 0, st, gm, ws.part,
                      ws.rowc);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL((stream_kernel<D, NRT, 2>), dim3(grid2), dim3(THREADS), bytes, st, g, half, p2, q, k,
+  hipLaunchKernelGGL((stream_kernel<D, NRT, 2>), dim3(grid2), dim3(THREADS), bytes, st, g, qp, half, p2, q, k,
                      (float2*)nullptr, ws.rowc, scores, ws.ctr + 1);
   return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_for_rows(const ScoreGeom& g, int pool, const uint16_t* q, const uint16_t* k, float* scores,
-                           const Workspace& ws, hipStream_t st) {
+hipError_t launch_for_rows(const ScoreGeom& g, const QueryPos& qp, int pool, const uint16_t* q, const uint16_t* k,
+                           float* scores, const Workspace& ws, hipStream_t st) {
   const int ntile = g.Rpad / 32;
-  if (ntile == 1) return launch_stream<D, 1>(g, pool, q, k, scores, ws, st);
-  if (ntile == 2) return launch_stream<D, 2>(g, pool, q, k, scores, ws, st);
-  return launch_stream<D, 4>(g, pool, q, k, scores, ws, st);
+  if (ntile == 1) return launch_stream<D, 1>(g, qp, pool, q, k, scores, ws, st);
+  if (ntile == 2) return launch_stream<D, 2>(g, qp, pool, q, k, scores, ws, st);
+  return launch_stream<D, 4>(g, qp, pool, q, k, scores, ws, st);
 }
 
 }  // namespace
 
 bool score_mfma_supported(const ScoreGeom& g, int dtype) {
   // the key loads address a head with 31-bit byte offsets (one chunk of slack past its end)
-  return dtype == LAQ_BF16 && (g.d == 128 || g.d == 64) && g.R >= 16 &&
+  return dtype == LAQ_BF16 && (g.d == 128 || g.d == 64) && g.R >= 16 && g.W <= MAX_QPOS &&
          g.n_inst * (long long)g.Hkv <= 0x7fffffff && ((long long)g.L + MFMA_ROWS) * g.d * 2 < 0x7fffffffLL;
 }
 
 // scores: pooled with kernel `pool` (pool == 1: raw)
-hipError_t launch_score_mfma(const ScoreGeom& g, int pool, const void* q, const void* k, float* scores,
-                             const Workspace& ws, hipStream_t st) {
+hipError_t launch_score_mfma(const ScoreGeom& g, const QueryPos& qp, int pool, const void* q, const void* k,
+                             float* scores, const Workspace& ws, hipStream_t st) {
   const uint16_t* qq = static_cast<const uint16_t*>(q);
   const uint16_t* kk = static_cast<const uint16_t*>(k);
-  if (g.d == 128) return launch_for_rows<128>(g, pool, qq, kk, scores, ws, st);
-  return launch_for_rows<64>(g, pool, qq, kk, scores, ws, st);
+  if (g.d == 128) return launch_for_rows<128>(g, qp, pool, qq, kk, scores, ws, st);
+  return launch_for_rows<64>(g, qp, pool, qq, kk, scores, ws, st);
 }
 
 }  // namespace laq

@@ -4,7 +4,7 @@
 // are mapped to order-preserving 32-bit keys; four most-significant-digit-first passes
 // over 8-bit digits find the key T of the k-th largest score and how many keys equal to
 // T still fit (ties go to the lower position).  A last sweep emits, in ascending
-// position order, every key above T plus the first `want` keys equal to T, then the W
+// position order, every key above T plus the first `want` keys equal to T, then the `keep`
 // window positions.  Keys live in registers (each wave owns a contiguous segment of the
 // prefix, 64 consecutive positions per register row) for prefixes up to 32768; longer
 // prefixes re-read the scores from memory in every pass.
@@ -39,7 +39,7 @@ __device__ __forceinline__ int lanes_below(uint64_t m) {
 // ITEMS > 0: keys of the wave's segment are held in ITEMS registers per lane.
 // ITEMS == 0: keys are recomputed from memory on every sweep (any prefix length).
 template <int ITEMS>
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int W, int pool,
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int keep, int pool,
                                                              const float* __restrict__ scores, InstTable tab,
                                                              int inst0, int32_t* __restrict__ idx) {
   __shared__ int hist[256];
@@ -48,13 +48,13 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int
 
   const int head = blockIdx.x, li = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int P = L - W, half = (pool - 1) / 2;
+  const int P = L - keep, half = (pool - 1) / 2;
   const int bk = tab.bk[li];
-  const int ksel = bk - W;
+  const int ksel = bk - keep;
   const float* s = scores + ((size_t)(inst0 + li) * Hkv + head) * L;
   int32_t* out = idx + (tab.row0[li] + (int64_t)head * bk);
 
-  for (int w = tid; w < W; w += SEL_THREADS) out[ksel + w] = P + w;
+  for (int w = tid; w < keep; w += SEL_THREADS) out[ksel + w] = P + w;
   if (ksel <= 0) return;
   if (ksel >= P) {
     for (int j = tid; j < P; j += SEL_THREADS) out[j] = j;
@@ -156,22 +156,22 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int
 }
 
 template <int ITEMS>
-hipError_t launch_one(int n_inst, int inst0, int Hkv, int L, int W, int pool, const float* scores,
+hipError_t launch_one(int n_inst, int inst0, int Hkv, int L, int keep, int pool, const float* scores,
                       const InstTable& tab, int32_t* idx, hipStream_t st) {
-  hipLaunchKernelGGL(select_kernel<ITEMS>, dim3(Hkv, n_inst), dim3(SEL_THREADS), 0, st, Hkv, L, W, pool, scores,
+  hipLaunchKernelGGL(select_kernel<ITEMS>, dim3(Hkv, n_inst), dim3(SEL_THREADS), 0, st, Hkv, L, keep, pool, scores,
                      tab, inst0, idx);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int W, int pool, const float* scores,
+hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int keep, int pool, const float* scores,
                          const InstTable& tab, int32_t* idx, hipStream_t st) {
-  const int P = L - W;
-  if (P <= 2 * SEL_THREADS) return launch_one<2>(n_inst, inst0, Hkv, L, W, pool, scores, tab, idx, st);
-  if (P <= 8 * SEL_THREADS) return launch_one<8>(n_inst, inst0, Hkv, L, W, pool, scores, tab, idx, st);
-  if (P <= 32 * SEL_THREADS) return launch_one<32>(n_inst, inst0, Hkv, L, W, pool, scores, tab, idx, st);
-  return launch_one<0>(n_inst, inst0, Hkv, L, W, pool, scores, tab, idx, st);
+  const int P = L - keep;
+  if (P <= 2 * SEL_THREADS) return launch_one<2>(n_inst, inst0, Hkv, L, keep, pool, scores, tab, idx, st);
+  if (P <= 8 * SEL_THREADS) return launch_one<8>(n_inst, inst0, Hkv, L, keep, pool, scores, tab, idx, st);
+  if (P <= 32 * SEL_THREADS) return launch_one<32>(n_inst, inst0, Hkv, L, keep, pool, scores, tab, idx, st);
+  return launch_one<0>(n_inst, inst0, Hkv, L, keep, pool, scores, tab, idx, st);
 }
 
 }  // namespace laq

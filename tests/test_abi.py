@@ -47,9 +47,14 @@ def test_workspace_bytes_grows_with_shape():
 
 
 def _shape(**kw):
-    base = dict(n_inst=1, Hq=8, Hkv=2, d=128, L=512, W=8, dtype=1, scale=0.0)
+    base = dict(n_inst=1, Hq=8, Hkv=2, d=128, L=512, W=8, dtype=1, scale=0.0, q_pos=None, keep=-1)
     base.update(kw)
     return binding._Shape(*[base[f] for f, _ in binding._Shape._fields_])
+
+
+def _positions(values):
+    arr = (ctypes.c_int32 * len(values))(*values)
+    return ctypes.cast(arr, ctypes.POINTER(ctypes.c_int32)), arr
 
 
 def test_bad_arguments_are_rejected_without_a_gpu():
@@ -76,6 +81,32 @@ def test_bad_arguments_are_rejected_without_a_gpu():
                          None) == INVALID
     assert lib.laq_evict(ctypes.byref(sh), fake, fake, fake, bud, 7, fake, fake, fake, fake, fake, 8,
                          None) == WORKSPACE
+
+
+def test_general_window_arguments_are_checked_without_a_gpu():
+    lib = laq.load_library()
+    fake = ctypes.c_void_p(0x1000)
+    INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
+    bud = (ctypes.c_int32 * 1)(64)
+    # explicit positions: any W >= 1, entries >= 0, at most 512 of them
+    p_ok, keep1 = _positions([511, 600, 0, 3, 3, 3, 3, 3])
+    ok = _shape(q_pos=p_ok, keep=0)
+    assert lib.laq_score(ctypes.byref(ok), fake, fake, 7, fake, fake, 16, None) == WORKSPACE      # accepted up to here
+    p_neg, keep2 = _positions([5, -1, 0, 3, 3, 3, 3, 3])
+    assert lib.laq_score(ctypes.byref(_shape(q_pos=p_neg, keep=0)), fake, fake, 7, fake, fake, 1 << 30,
+                         None) == INVALID
+    p_many, keep3 = _positions([1] * 600)
+    assert lib.laq_score(ctypes.byref(_shape(W=600, q_pos=p_many, keep=8)), fake, fake, 7, fake, fake, 1 << 30,
+                         None) == UNSUPPORTED
+    assert lib.laq_score(ctypes.byref(_shape(W=600, q_pos=p_many, keep=-1)), fake, fake, 7, fake, fake, 1 << 30,
+                         None) == INVALID                                                       # keep defaults to W > L
+    assert lib.laq_score(ctypes.byref(_shape(keep=513)), fake, fake, 7, fake, fake, 1 << 30, None) == INVALID
+    # budgets are checked against keep (every call below is rejected before anything is launched)
+    assert lib.laq_select(ctypes.byref(_shape(keep=100)), fake, bud, 7, fake, None) == INVALID    # 64 < keep
+    assert lib.laq_select(ctypes.byref(_shape(keep=0)), fake, (ctypes.c_int32 * 1)(0), 7, fake, None) == INVALID
+    assert laq.laq_workspace_bytes(1, 8, 2, 128, 512, 600, torch.bfloat16) == 0
+    assert laq.laq_workspace_bytes(1, 8, 2, 128, 512, 600, torch.bfloat16, q_pos=[1] * 600, keep=4) == 0   # > 512 positions
+    assert laq.laq_workspace_bytes(1, 8, 2, 128, 512, 300, torch.bfloat16, q_pos=[1] * 300, keep=4) > 0
 
 
 def test_packed_rows():

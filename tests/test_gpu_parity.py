@@ -296,3 +296,89 @@ def test_explicit_scale(laq):
     q = torch.randn(1, 8, 8, 128, generator=g).bfloat16().to(DEV)
     k = torch.randn(1, 2, 500, 128, generator=g).bfloat16().to(DEV)
     run_and_check(laq, q, k, None, [64], 7, "scale", scale=0.02)
+
+
+# ---- general observation window (Eq. 5): explicit query positions, independent keep count ----
+def run_general(laq, q, k, v, budgets, pool, q_pos, keep, what, heads=None):
+    n, Hq, W, d = q.shape
+    _, Hkv, L, _ = k.shape
+    G = Hq // Hkv
+    print("case:", what, "n=%d Hq=%d Hkv=%d d=%d L=%d W=%d pool=%d keep=%d" % (n, Hq, Hkv, d, L, W, pool, keep),
+          flush=True)
+    scores, idx, ko, vo = laq.laq_evict(q, k, v, budgets, pool, q_pos=q_pos, keep=keep)
+    s3 = laq.laq_score(q, k, pool, q_pos=q_pos, keep=keep)
+    i3 = laq.laq_select(s3, budgets, 1, keep)
+    k3, v3 = laq.laq_compact(k, v, i3, budgets, keep)
+    raw = laq.laq_score(q, k, 1, q_pos=q_pos, keep=keep)
+    i_alt = laq.laq_select(raw, budgets, pool, keep)
+    torch.cuda.synchronize()
+    assert torch.equal(s3, scores) and torch.equal(i3, idx) and torch.equal(k3, ko) and torch.equal(v3, vo)
+    assert torch.equal(i_alt, idx)
+    idx_l = split_packed(idx.cpu(), budgets, Hkv, L)
+    ko_l = split_packed(ko.cpu(), budgets, Hkv, L)
+    vo_l = split_packed(vo.cpu(), budgets, Hkv, L)
+    qc, kc, vc, sc, rc = q.cpu(), k.cpu(), v.cpu(), scores.cpu(), raw.cpu()
+    for i in range(n):
+        for g in (range(Hkv) if heads is None else heads):
+            o_raw = oracle.raw_scores(qc[i, g * G:(g + 1) * G], kc[i, g:g + 1], q_pos=q_pos)
+            pooled = oracle.maxpool(o_raw, keep, pool)
+            check_scores(rc[i, g], o_raw[0], k.dtype, "%s raw inst %d head %d" % (what, i, g))
+            check_scores(sc[i, g], pooled[0], k.dtype, "%s inst %d head %d" % (what, i, g))
+            check_index_row(idx_l[i][g].numpy(), pooled[0].float().numpy(), keep, budgets[i], RTOL[k.dtype],
+                            "%s inst %d head %d" % (what, i, g))
+            assert torch.equal(oracle.select(sc[i, g:g + 1], keep, budgets[i])[0], idx_l[i][g])
+            rows = idx_l[i][g].long()
+            assert torch.equal(ko_l[i][g], kc[i, g, rows]) and torch.equal(vo_l[i][g], vc[i, g, rows])
+    return scores, idx
+
+
+def _qkv(seed, n, Hq, Hkv, d, L, W, dtype=torch.bfloat16):
+    g = torch.Generator().manual_seed(seed)
+    q = (torch.randn(n, Hq, W, d, generator=g) * 1.5).to(dtype).to(DEV)
+    k = torch.randn(n, Hkv, L, d, generator=g).to(dtype).to(DEV)
+    v = torch.randn(n, Hkv, L, d, generator=g).to(dtype).to(DEV)
+    return q, k, v
+
+
+GENERAL = [
+    # name, dtype, Hq, Hkv, d, L, W, pool, budget, keep, positions (callable of L, W)
+    ("lookahead-only", torch.bfloat16, 8, 2, 128, 1000, 8, 7, 100, 0, lambda L, W: [L + i for i in range(W)]),
+    ("lookahead-keep-local-8", torch.bfloat16, 8, 2, 128, 1000, 8, 7, 100, 8, lambda L, W: [L - 1] * W),
+    ("lookahead-no-ragged-chunk", torch.bfloat16, 8, 2, 128, 1024, 8, 7, 64, 0, lambda L, W: [L + 7] * W),
+    ("joined-8-local-8-lookahead", torch.bfloat16, 16, 4, 128, 2000, 16, 7, 128, 8,
+     lambda L, W: [L - 8 + i for i in range(8)] + [L + i for i in range(8)]),
+    ("scattered-positions-three-tiles", torch.bfloat16, 12, 2, 128, 900, 8, 5, 64, 4,
+     lambda L, W: [0, 5, 255, 256, 511, 700, L - 1, 3 * L]),
+    ("scattered-fp32-generic", torch.float32, 4, 2, 64, 500, 6, 3, 40, 2, lambda L, W: [499, 0, 17, 300, 1000, 256]),
+    ("d64-joined", torch.bfloat16, 8, 2, 64, 1500, 16, 7, 128, 8,
+     lambda L, W: [L - 8 + i for i in range(8)] + [L - 1] * 8),
+    ("keep-everything", torch.bfloat16, 8, 2, 128, 300, 8, 7, 300, 300, lambda L, W: [L] * W),
+    ("many-queries-more-than-keys", torch.bfloat16, 4, 2, 128, 40, 64, 3, 20, 0, lambda L, W: [w % 40 for w in range(W)]),
+]
+
+
+@pytest.mark.parametrize("name,dtype,Hq,Hkv,d,L,W,pool,budget,keep,pos", GENERAL, ids=[e[0] for e in GENERAL])
+def test_general_window(laq, name, dtype, Hq, Hkv, d, L, W, pool, budget, keep, pos):
+    q, k, v = _qkv(len(name) * 77 + L, 2, Hq, Hkv, d, L, W, dtype)
+    run_general(laq, q, k, v, [budget, max(keep, budget - 3, 1)], pool, pos(L, W), keep, name)
+
+
+def test_explicit_trailing_positions_give_the_default_bits(laq):
+    q, k, v = _qkv(5, 2, 8, 2, 128, 1300, 8)
+    L, W = 1300, 8
+    a = laq.laq_evict(q, k, v, [100, 90], 7)
+    b = laq.laq_evict(q, k, v, [100, 90], 7, q_pos=[L - W + w for w in range(W)], keep=W)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_joined_window_full_size_sampled(laq):
+    # the 32k shape with the paper's main setting of 8 local window queries + 8 lookahead queries
+    n, Hq, Hkv, d, L, W, pool, keep = 4, 32, 8, 128, 32768, 16, 7, 8
+    gen = torch.Generator(device=DEV).manual_seed(99)
+    q = (torch.randn(n, Hq, W, d, generator=gen, device=DEV) * 1.5).bfloat16()
+    k = torch.randn(n, Hkv, L, d, generator=gen, device=DEV).bfloat16()
+    v = torch.randn(n, Hkv, L, d, generator=gen, device=DEV).bfloat16()
+    pos = [L - 8 + i for i in range(8)] + [L + i for i in range(8)]
+    run_general(laq, q, k, v, [1024, 512, 256, 128], pool, pos, keep, "joined-32k", heads=[3])
