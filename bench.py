@@ -54,6 +54,10 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload: index into BASELINE.json configs (1-based)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-instances", type=int, default=2)
+    ap.add_argument("--window", choices=["trailing", "lookahead", "joined"], default="trailing",
+                    help="observation window: the config's trailing window (default, the headline workload); "
+                         "8 lookahead queries that see every key, nothing kept (Eq. 4); or 8 local window "
+                         "queries joined with 8 lookahead queries, 8 keys kept (Eq. 5)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device tensor copy (a kernel of known traffic, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -77,6 +81,16 @@ def main():
     cfg = CONFIGS[args.config]
     budgets = budgets_for(cfg)
     n = cfg.n_inst
+    q_pos, keep, workload = None, None, cfg.name
+    if args.window != "trailing":
+        import dataclasses
+        if args.window == "lookahead":
+            cfg = dataclasses.replace(cfg, W=8)
+            q_pos, keep = [cfg.L + i for i in range(8)], 0
+        else:
+            cfg = dataclasses.replace(cfg, W=16)
+            q_pos, keep = [cfg.L - 8 + i for i in range(8)] + [cfg.L + i for i in range(8)], 8
+        workload = "%s+%s-window" % (cfg.name, args.window)
 
     # ---- inputs, generated on the device, resident before any timing ----
     dt = cfg.torch_dtype
@@ -92,11 +106,13 @@ def main():
     idx = torch.empty(total_rows, dtype=torch.int32, device=dev)
     k_out = torch.empty(total_rows, cfg.d, dtype=dt, device=dev)
     v_out = torch.empty(total_rows, cfg.d, dtype=dt, device=dev)
-    ws = torch.empty(laq.laq_workspace_bytes(n, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, cfg.W, dt), dtype=torch.uint8,
-                     device=dev)
+    ws = torch.empty(laq.laq_workspace_bytes(n, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, cfg.W, dt, q_pos, keep),
+                     dtype=torch.uint8, device=dev)
+    keep_rows = cfg.W if keep is None else keep
 
     def step():
-        laq.laq_evict(q, k, v, budgets, cfg.pool, scores=scores, idx=idx, k_out=k_out, v_out=v_out, ws=ws)
+        laq.laq_evict(q, k, v, budgets, cfg.pool, scores=scores, idx=idx, k_out=k_out, v_out=v_out, ws=ws,
+                      q_pos=q_pos, keep=keep)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -121,11 +137,11 @@ def main():
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
     for _ in range(reps):
         ev[0].record()
-        laq.laq_score(q, k, cfg.pool, scores=scores, ws=ws)
+        laq.laq_score(q, k, cfg.pool, scores=scores, ws=ws, q_pos=q_pos, keep=keep)
         ev[1].record()
-        laq.laq_select(scores, budgets, 1, cfg.W, idx=idx)
+        laq.laq_select(scores, budgets, 1, keep_rows, idx=idx)
         ev[2].record()
-        laq.laq_compact(k, v, idx, budgets, cfg.W, k_out=k_out, v_out=v_out)
+        laq.laq_compact(k, v, idx, budgets, keep_rows, k_out=k_out, v_out=v_out)
         ev[3].record()
         torch.cuda.synchronize()
         stages["score"] += ev[0].elapsed_time(ev[1]) / reps
@@ -134,7 +150,7 @@ def main():
     ab = algorithmic_bytes(cfg, budgets)
     achieved = ab["score"] / (stages["score"] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(cfg.name),
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(workload),
                 "kernel": "laq_score stage: stream_kernel<pass 1> + row_constants_mfma_kernel + "
                           "stream_kernel<pass 2> (K counted once in the algorithmic bytes, read twice)",
                 "algorithmic_bytes_per_launch": ab["score"],
@@ -145,7 +161,7 @@ def main():
         "value": round(value, 1), "unit": "key-tokens/s/layer", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name, "cfg_id": cfg.cfg_id, "instances": n, "Hq": cfg.Hq, "Hkv": cfg.Hkv,
+        "config": {"workload": workload, "cfg_id": cfg.cfg_id, "instances": n, "Hq": cfg.Hq, "Hkv": cfg.Hkv,
                    "d": cfg.d, "L": cfg.L, "W": cfg.W, "pool": cfg.pool, "budget": cfg.budget},
         "whole_path": {"algorithmic_GBs": round(ab["total"] / (ms_per_step * 1e-3) / 1e9, 1),
                        "frac_of_hbm_peak": round(ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -162,7 +178,7 @@ def main():
         for i in ids:
             qi, ki, vi = q[i].cpu(), k[i].cpu(), v[i].cpu()
             c0 = time.perf_counter()
-            oracle.evict(qi, ki, vi, budgets[i], cfg.pool)
+            oracle.evict(qi, ki, vi, budgets[i], cfg.pool, q_pos=q_pos, keep=keep)
             t_cpu += time.perf_counter() - c0
         out["cpu_baseline"] = {"value": round(len(ids) * cfg.L / t_cpu, 1), "unit": "key-tokens/s/layer",
                                "cores": 1, "kind": "oracle",

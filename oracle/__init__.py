@@ -48,6 +48,10 @@ def _load() -> ctypes.CDLL:
         lib.laq_oracle_raw_scores.restype = c_int
         lib.laq_oracle_maxpool.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp]
         lib.laq_oracle_maxpool.restype = c_int
+        lib.laq_oracle_avgpool.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp]
+        lib.laq_oracle_avgpool.restype = c_int
+        lib.laq_oracle_sink_recent.argtypes = [c_int, c_int, c_int, c_int, c_vp]
+        lib.laq_oracle_sink_recent.restype = c_int
         lib.laq_oracle_select.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp]
         lib.laq_oracle_select.restype = c_int
         lib.laq_oracle_compact.argtypes = [c_vp, c_int, c_int, ctypes.c_size_t, c_vp, c_int, c_vp]
@@ -106,6 +110,29 @@ def maxpool(raw: torch.Tensor, W: int, pool: int) -> torch.Tensor:
     return out
 
 
+def avgpool(raw: torch.Tensor, W: int, pool: int) -> torch.Tensor:
+    """Step 5, average variant (Sec. 5.1): window mean with zeros outside the prefix [0, L-W);
+    the trailing W columns are copied."""
+    raw = _cpu(raw.double())
+    Hkv, L = raw.shape
+    out = torch.empty_like(raw)
+    rc = _load().laq_oracle_avgpool(raw.data_ptr(), Hkv, L, W, pool, out.data_ptr())
+    if rc != 0:
+        raise ValueError("laq_oracle_avgpool rejected its arguments")
+    return out
+
+
+def sink_recent(Hkv: int, L: int, n_sink: int, budget: int) -> torch.Tensor:
+    """Score-free stage-1 eviction (Sec. 4.2, StreamingLLM form): idx [Hkv, min(budget, L)] int32 =
+    the first n_sink positions and the most recent ones."""
+    Bk = min(int(budget), L)
+    idx = torch.empty(Hkv, Bk, dtype=torch.int32)
+    rc = _load().laq_oracle_sink_recent(Hkv, L, int(n_sink), int(budget), idx.data_ptr())
+    if rc != 0:
+        raise ValueError("laq_oracle_sink_recent rejected its arguments")
+    return idx
+
+
 def select(scores_f32: torch.Tensor, W: int, budget: int) -> torch.Tensor:
     """Step 6: scores [Hkv, L] fp32 -> idx [Hkv, min(budget, L)] int32, ascending; W = trailing
     keys always retained."""
@@ -135,11 +162,14 @@ def compact(src: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
 
 
 def evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], budget: int,
-          pool: int, scale: float = 0.0, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None
-          ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, Optional[torch.Tensor]]:
+          pool: int, scale: float = 0.0, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
+          pool_mode: str = "max") -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, Optional[torch.Tensor]]:
     """Whole path for one instance: returns (pooled fp64 [Hkv, L], idx, k', v').
-    keep = trailing keys always retained (None: the number of window queries)."""
+    keep = trailing keys always retained (None: the number of window queries); pool_mode "max" or
+    "avg"."""
     W = q_win.shape[1] if keep is None else int(keep)
-    pooled = maxpool(raw_scores(q_win, k, scale, q_pos), W, pool)
+    if pool_mode not in ("max", "avg"):
+        raise ValueError("pool_mode is 'max' or 'avg'")
+    pooled = (maxpool if pool_mode == "max" else avgpool)(raw_scores(q_win, k, scale, q_pos), W, pool)
     idx = select(pooled.float(), W, budget)
     return pooled, idx, compact(k, idx), (compact(v, idx) if v is not None else None)

@@ -36,6 +36,15 @@
  * ranking and pooling run over the prefix [0, L - keep).  The layout above is
  * the special case q_pos[w] = L - W + w, keep = W.
  *
+ * Stage-1 eviction (Sec. 4.2 "Lookahead": the low-budget eviction that
+ * precedes the lookahead decoding uses an existing method): the observation-
+ * window procedure above with the prompt suffix as window is that method in
+ * its SnapKV form; Sec. 5.1 describes its pooling as an average, provided here
+ * as laq_oracle_avgpool (window mean with zeros outside the prefix, i.e. the
+ * sum over the clipped window divided by the kernel size).  The StreamingLLM
+ * form keeps the first tokens of the sequence ("sinks") and the most recent
+ * ones and needs no scores: laq_oracle_sink_recent.
+ *
  * Readings where the paper is silent (softmax before the sum, 1/sqrt(d) scale,
  * max- rather than average-pooling, GQA sum, budget including the window,
  * tie-break) are listed in the design notes of the repository.
@@ -43,7 +52,9 @@
  * Pins (tests marked "not gpu"): brute-force attention matrices on tiny inputs,
  * row-sum and non-negativity invariants, the closed form for identical keys,
  * the W=1/G=1/pool=1 reduction to ArgSort(q K^T), GQA additivity, key-shift
- * invariance, hand-computed pooling cases, exhaustive top-k, planted keys.
+ * invariance, hand-computed pooling cases, exhaustive top-k, planted keys;
+ * the average pool against a library average-pooling routine, its column-sum
+ * identity and hand cases; the sink+recent list against set-built brute force.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -147,6 +158,56 @@ int laq_oracle_maxpool(const double *raw, int Hkv, int L, int keep, int pool, do
         }
         for (int j = P; j < L; ++j)
             o[j] = r[j];
+    }
+    return 0;
+}
+
+/*
+ * Step 5, average variant (Sec. 5.1 describes the observation-window baseline's
+ * pooling as an average).  Same arguments as laq_oracle_maxpool.  The mean is
+ * taken over the full kernel with zeros standing in for positions outside the
+ * prefix [0, P): pooled[j] = (sum of raw[i], |i-j| <= (pool-1)/2, 0 <= i < P) / pool.
+ * Columns j >= P are copied.
+ */
+int laq_oracle_avgpool(const double *raw, int Hkv, int L, int keep, int pool, double *pooled)
+{
+    if (!raw || !pooled || Hkv <= 0 || L <= 0 || keep < 0 || keep > L || pool < 1 || pool % 2 == 0)
+        return -1;
+    const int P = L - keep, half = (pool - 1) / 2;
+    for (int g = 0; g < Hkv; ++g) {
+        const double *r = raw + (size_t)g * L;
+        double *o = pooled + (size_t)g * L;
+        for (int j = 0; j < P; ++j) {
+            double acc = 0.0;
+            for (int i = j - half; i <= j + half; ++i)
+                if (i >= 0 && i < P) acc += r[i];
+            o[j] = acc / (double)pool;
+        }
+        for (int j = P; j < L; ++j)
+            o[j] = r[j];
+    }
+    return 0;
+}
+
+/*
+ * Score-free stage-1 eviction in the StreamingLLM form (Sec. 2.1, Sec. 4.2):
+ * every head keeps the first n_sink positions and the most recent ones, Bk =
+ * min(budget, L) in all (budget >= 1).  idx: [Hkv, Bk], ascending.  When n_sink >= Bk the
+ * list is the first Bk positions.
+ */
+int laq_oracle_sink_recent(int Hkv, int L, int n_sink, int budget, int32_t *idx)
+{
+    if (!idx || Hkv <= 0 || L <= 0 || n_sink < 0 || budget < 1)
+        return -1;
+    const int Bk = budget < L ? budget : L;
+    const int s = n_sink < Bk ? n_sink : Bk;
+    const int recent = Bk - s;
+    for (int g = 0; g < Hkv; ++g) {
+        int32_t *out = idx + (size_t)g * Bk;
+        for (int t = 0; t < s; ++t)
+            out[t] = t;
+        for (int t = 0; t < recent; ++t)
+            out[s + t] = L - recent + t;
     }
     return 0;
 }

@@ -518,3 +518,103 @@ def test_select_rejects_budget_below_keep_and_keep_above_length():
         oracle.select(s, 11, 11)
     with pytest.raises(ValueError):
         oracle.maxpool(s.double(), -1, 3)
+
+
+# ----------------------------------------------------------------------------
+# Stage-1 eviction variants (Sec. 4.2; Sec. 5.1 for the average pool): pins
+@pytest.mark.parametrize("pool", [1, 3, 5, 7, 9])
+def test_avgpool_vs_library_routine_and_exact_fractions(pool):
+    g = torch.Generator().manual_seed(100 + pool)
+    raw = torch.randint(0, 50, (3, 41), generator=g).double()      # small integers: sums are exact
+    got = oracle.avgpool(raw, 0, pool)
+    lib = torch.nn.functional.avg_pool1d(raw.unsqueeze(0), pool, stride=1, padding=pool // 2,
+                                         count_include_pad=True)[0]
+    np.testing.assert_allclose(got.numpy(), lib.numpy(), rtol=1e-15, atol=0)
+    half = pool // 2
+    for j in (0, 1, 20, 39, 40):                                    # exact rational arithmetic
+        lo, hi = max(0, j - half), min(40, j + half)
+        want = Fraction(int(raw[1, lo:hi + 1].sum().item()), pool)
+        assert Fraction(got[1, j].item()) == Fraction(float(want))
+    if pool == 1:
+        assert torch.equal(got, raw)
+
+
+def test_avgpool_hand_cases_and_prefix_domain():
+    raw = torch.tensor([[3.0, 0.0, 6.0, 9.0, 0.0, 3.0, 1000.0, 2000.0]], dtype=torch.float64)
+    got = oracle.avgpool(raw, 2, 3).numpy()[0]                      # prefix = first 6, last 2 copied
+    # zeros stand in beyond both ends of the prefix; the kept columns never leak into it
+    assert got.tolist() == [1.0, 3.0, 5.0, 5.0, 4.0, 1.0, 1000.0, 2000.0]
+    const = torch.full((1, 20), 7.0, dtype=torch.float64)
+    got = oracle.avgpool(const, 0, 7).numpy()[0]
+    np.testing.assert_allclose(got[3:17], 7.0, rtol=1e-15)
+    np.testing.assert_allclose(got[:3], [7.0 * c / 7 for c in (4, 5, 6)], rtol=1e-15)
+    np.testing.assert_allclose(got[17:], [7.0 * c / 7 for c in (6, 5, 4)], rtol=1e-15)
+
+
+def test_avgpool_column_sum_identity_and_linearity():
+    g = torch.Generator().manual_seed(77)
+    a = torch.rand(2, 64, generator=g, dtype=torch.float64)
+    b = torch.rand(2, 64, generator=g, dtype=torch.float64)
+    keep, pool, half = 5, 7, 3
+    P = 64 - keep
+    pa = oracle.avgpool(a, keep, pool)
+    # entry i of the prefix lies in min(i, half) + min(P-1-i, half) + 1 windows
+    cover = torch.tensor([min(i, half) + min(P - 1 - i, half) + 1 for i in range(P)], dtype=torch.float64)
+    np.testing.assert_allclose(pa[:, :P].sum(1).numpy(), ((a[:, :P] * cover).sum(1) / pool).numpy(), rtol=1e-13)
+    pab = oracle.avgpool(2.0 * a + b, keep, pool)
+    np.testing.assert_allclose(pab.numpy(), (2.0 * pa + oracle.avgpool(b, keep, pool)).numpy(), rtol=1e-13)
+    # an isolated spike spreads into a plateau of height 1/pool
+    s = torch.zeros(1, 40, dtype=torch.float64)
+    s[0, 20] = 1.0
+    sp = oracle.avgpool(s, 4, 7).numpy()[0]
+    assert sp[17:24].tolist() == [1.0 / 7] * 7 and sp[16] == 0 and sp[24] == 0
+    with pytest.raises(ValueError):
+        oracle.avgpool(s, 4, 4)
+
+
+def test_avgpool_differs_from_maxpool_in_selection_on_a_planted_case():
+    # one tall spike next to a broad shoulder: the max pool keeps the spike's neighbourhood,
+    # the average keeps the shoulder's centre
+    raw = torch.zeros(1, 30, dtype=torch.float64)
+    raw[0, 5] = 1.0
+    raw[0, 18:23] = 0.5
+    top_max = oracle.select(oracle.maxpool(raw, 0, 5).float(), 0, 1)
+    top_avg = oracle.select(oracle.avgpool(raw, 0, 5).float(), 0, 1)
+    assert top_max.tolist() == [[3]]          # plateau 3..7 of height 1, lowest index wins
+    assert top_avg.tolist() == [[20]]         # 5 * 0.5 / 5 = 0.5 > 1 / 5
+
+
+@pytest.mark.parametrize("L,n_sink,budget", [(10, 2, 5), (10, 0, 4), (10, 4, 4), (10, 6, 4), (10, 3, 10),
+                                             (10, 3, 25), (1, 4, 1), (257, 4, 64), (10, 2, 1)])
+def test_sink_recent_vs_set_construction(L, n_sink, budget):
+    got = oracle.sink_recent(3, L, n_sink, budget)
+    Bk = min(budget, L)
+    s = min(n_sink, Bk)
+    want = sorted(set(range(s)) | set(range(L - (Bk - s), L)))
+    assert got.shape == (3, Bk)
+    assert got.tolist() == [want] * 3
+    assert len(set(want)) == Bk
+
+
+def test_sink_recent_hand_case_and_rejection():
+    assert oracle.sink_recent(1, 10, 2, 5).tolist() == [[0, 1, 7, 8, 9]]
+    assert oracle.sink_recent(2, 6, 4, 100).tolist() == [list(range(6))] * 2
+    with pytest.raises(ValueError):
+        oracle.sink_recent(1, 10, -1, 5)
+    with pytest.raises(ValueError):
+        oracle.sink_recent(1, 10, 2, 0)
+
+
+def test_evict_with_average_pool_is_pool_then_select():
+    cfg = CONFIGS[1]
+    q, k, v, _ = make_instance(cfg, 0, 0)
+    pooled, idx, k2, v2 = oracle.evict(q, k, v, 64, 7, pool_mode="avg")
+    raw = oracle.raw_scores(q, k)
+    assert torch.equal(pooled, oracle.avgpool(raw, cfg.W, 7))
+    assert torch.equal(idx, oracle.select(pooled.float(), cfg.W, 64))
+    # total prefix mass shrinks only through the zero padding at the two ends
+    P = cfg.L - cfg.W
+    assert (pooled[:, :P].sum(1) <= raw[:, :P].sum(1) * (1 + 1e-12)).all()
+    np.testing.assert_allclose(pooled[:, 3:P - 3].numpy(),
+                               torch.nn.functional.avg_pool1d(raw[:, :P].unsqueeze(0), 7, stride=1)[0].numpy(),
+                               rtol=1e-13)
