@@ -58,6 +58,9 @@ def main():
                     help="observation window: the config's trailing window (default, the headline workload); "
                          "8 lookahead queries that see every key, nothing kept (Eq. 4); or 8 local window "
                          "queries joined with 8 lookahead queries, 8 keys kept (Eq. 5)")
+    ap.add_argument("--pool-mode", choices=["max", "avg"], default="max",
+                    help="sequence pooling: max (default, the headline workload) or the average of the "
+                         "stage-1 eviction variant (Sec. 5.1)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device tensor copy (a kernel of known traffic, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -91,6 +94,8 @@ def main():
             cfg = dataclasses.replace(cfg, W=16)
             q_pos, keep = [cfg.L - 8 + i for i in range(8)] + [cfg.L + i for i in range(8)], 8
         workload = "%s+%s-window" % (cfg.name, args.window)
+    if args.pool_mode != "max":
+        workload += "+%s-pool" % args.pool_mode
 
     # ---- inputs, generated on the device, resident before any timing ----
     dt = cfg.torch_dtype
@@ -112,7 +117,7 @@ def main():
 
     def step():
         laq.laq_evict(q, k, v, budgets, cfg.pool, scores=scores, idx=idx, k_out=k_out, v_out=v_out, ws=ws,
-                      q_pos=q_pos, keep=keep)
+                      q_pos=q_pos, keep=keep, pool_mode=args.pool_mode)
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -137,7 +142,7 @@ def main():
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
     for _ in range(reps):
         ev[0].record()
-        laq.laq_score(q, k, cfg.pool, scores=scores, ws=ws, q_pos=q_pos, keep=keep)
+        laq.laq_score(q, k, cfg.pool, scores=scores, ws=ws, q_pos=q_pos, keep=keep, pool_mode=args.pool_mode)
         ev[1].record()
         laq.laq_select(scores, budgets, 1, keep_rows, idx=idx)
         ev[2].record()
@@ -178,7 +183,7 @@ def main():
         for i in ids:
             qi, ki, vi = q[i].cpu(), k[i].cpu(), v[i].cpu()
             c0 = time.perf_counter()
-            oracle.evict(qi, ki, vi, budgets[i], cfg.pool, q_pos=q_pos, keep=keep)
+            oracle.evict(qi, ki, vi, budgets[i], cfg.pool, q_pos=q_pos, keep=keep, pool_mode=args.pool_mode)
             t_cpu += time.perf_counter() - c0
         out["cpu_baseline"] = {"value": round(len(ids) * cfg.L / t_cpu, 1), "unit": "key-tokens/s/layer",
                                "cores": 1, "kind": "oracle",

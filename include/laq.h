@@ -42,6 +42,10 @@ extern "C" {
 
 typedef enum { LAQ_F32 = 0, LAQ_BF16 = 1 } laq_dtype;
 
+/* Sequence pooling of the raw scores: the maximum (default) or the average that Sec. 5.1
+ * names for the observation-window baseline used as stage-1 eviction (Sec. 4.2). */
+typedef enum { LAQ_POOL_MAX = 0, LAQ_POOL_AVG = 1 } laq_pool_mode;
+
 enum {
   LAQ_OK = 0,
   LAQ_ERR_INVALID = -1,     /* null pointer, bad shape, budget < W, even pool kernel ... */
@@ -74,6 +78,12 @@ typedef struct laq_shape {
    */
   const int32_t *q_pos;
   int32_t keep;
+  /*
+   * laq_pool_mode of every pool_kernel > 1 below (0 = LAQ_POOL_MAX).  LAQ_POOL_AVG replaces
+   * the window maximum by (sum of raw[g,i], |i-j| <= (p-1)/2, 0 <= i < P) / p, i.e. the window
+   * mean with zeros outside the prefix, summed in fp32 in ascending i.
+   */
+  int32_t pool_mode;
 } laq_shape;
 
 /* Bytes of device scratch that laq_score / laq_evict need for this shape (0 on a bad shape). */
@@ -89,7 +99,8 @@ size_t laq_workspace_bytes(const laq_shape *shape);
  *          With pool_kernel == 1 scores = raw.  With an odd pool_kernel p > 1 the prefix
  *          columns hold max(raw[g,i] : |i-j| <= (p-1)/2, 0 <= i < P) (the sequence pooling
  *          of the observation-window procedure, Sec. 2.1 / 5.1) and the W window columns
- *          keep raw.  Max is exact and the raw scores do not depend on pool_kernel, so
+ *          keep raw (LAQ_POOL_AVG: the window mean instead, see laq_shape).  The raw scores
+ *          do not depend on pool_kernel and both places pool with the same arithmetic, so
  *          laq_score(p) + laq_select(1) and laq_score(1) + laq_select(p) give the same indices.
  *   ws / ws_bytes  device scratch of at least laq_workspace_bytes(shape)
  * Supported: dtype BF16 or F32; any Hq/Hkv/W/L within the limits of laq_shape;
@@ -102,8 +113,8 @@ int laq_score(const laq_shape *shape, const void *q_win, const void *k, int pool
  * Per-KV-head selection ("ArgSort(...)[:B]" of Eq. 4) under a per-instance budget.
  *   scores [n_inst, Hkv, L] fp32, non-negative (as laq_score writes them)
  *   budget [n_inst] HOST array, budget[i] >= W.  Bk(i) = min(budget[i], L).
- *   pool_kernel  odd >= 1; p > 1 applies the max-pool described above to the prefix
- *                columns before ranking (use 1 if laq_score already pooled)
+ *   pool_kernel  odd >= 1; p > 1 applies the pooling described above (shape->pool_mode) to
+ *                the prefix columns before ranking (use 1 if laq_score already pooled)
  *   idx    int32 out, packed: instance i starts at element sum_{i'<i} Hkv * Bk(i') and
  *          holds [Hkv, Bk(i)].  Each row: the Bk - W prefix positions with the largest
  *          pooled score (ties to the lower position), ascending, then P .. L-1.
@@ -111,6 +122,19 @@ int laq_score(const laq_shape *shape, const void *q_win, const void *k, int pool
  */
 int laq_select(const laq_shape *shape, const float *scores, const int32_t *budget,
                int pool_kernel, int32_t *idx, void *stream);
+
+/*
+ * Score-free stage-1 eviction in the StreamingLLM form (Sec. 2.1; Sec. 4.2 allows it as the
+ * low-budget eviction that precedes the lookahead decoding): every KV head keeps the first
+ * n_sink positions and the most recent ones.
+ *   budget [n_inst] HOST array, budget[i] >= 1.  Bk(i) = min(budget[i], L).
+ *   n_sink >= 0.  s = min(n_sink, Bk): a row is 0 .. s-1 followed by L-(Bk-s) .. L-1.
+ *   idx    int32 out, packed exactly as laq_select packs it (feed it to laq_compact with a
+ *          shape whose keep is 0).
+ * Takes plain sizes: n_inst, Hkv, L >= 1, Hkv <= 65535.  Uses no workspace.
+ */
+int laq_select_sink_recent(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t *budget,
+                           int32_t n_sink, int32_t *idx, void *stream);
 
 /*
  * Cache compaction: gather the retained rows.

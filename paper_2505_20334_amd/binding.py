@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(_PKG, "liblaq.so")
 _lib: Optional[ctypes.CDLL] = None
 
 LAQ_F32, LAQ_BF16 = 0, 1
+LAQ_POOL_MAX, LAQ_POOL_AVG = 0, 1
 
 
 class LaqError(RuntimeError):
@@ -29,7 +30,8 @@ class _Shape(ctypes.Structure):
     _fields_ = [("n_inst", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("L", ctypes.c_int32), ("W", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
-                ("q_pos", ctypes.POINTER(ctypes.c_int32)), ("keep", ctypes.c_int32)]
+                ("q_pos", ctypes.POINTER(ctypes.c_int32)), ("keep", ctypes.c_int32),
+                ("pool_mode", ctypes.c_int32)]
 
 
 def lib_path() -> str:
@@ -53,6 +55,8 @@ def load_library() -> ctypes.CDLL:
     lib.laq_score.restype = i32
     lib.laq_select.argtypes = [sp, vp, ctypes.POINTER(ctypes.c_int32), i32, vp, vp]
     lib.laq_select.restype = i32
+    lib.laq_select_sink_recent.argtypes = [i32, i32, i32, ctypes.POINTER(ctypes.c_int32), i32, vp, vp]
+    lib.laq_select_sink_recent.restype = i32
     lib.laq_compact.argtypes = [sp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp, vp, vp]
     lib.laq_compact.restype = i32
     lib.laq_evict.argtypes = [sp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), i32, vp, vp, vp, vp, vp, sz, vp]
@@ -90,10 +94,14 @@ def _stream(stream) -> int:
 
 
 def _shape(n: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: int, scale: float,
-           q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None) -> _Shape:
+           q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None, pool_mode: str = "max") -> _Shape:
     """q_pos: position of every window query in the key sequence (None: the trailing window);
-    keep: trailing keys always retained (None: W).  The position array stays alive with the struct."""
-    sh = _Shape(n, Hq, Hkv, d, L, W, dtype, float(scale), None, -1 if keep is None else int(keep))
+    keep: trailing keys always retained (None: W); pool_mode "max" or "avg".  The position array
+    stays alive with the struct."""
+    if pool_mode not in ("max", "avg"):
+        raise ValueError("pool_mode is 'max' or 'avg'")
+    sh = _Shape(n, Hq, Hkv, d, L, W, dtype, float(scale), None, -1 if keep is None else int(keep),
+                LAQ_POOL_AVG if pool_mode == "avg" else LAQ_POOL_MAX)
     if q_pos is not None:
         if len(q_pos) != W:
             raise ValueError("q_pos needs one entry per window query")
@@ -135,9 +143,11 @@ def _workspace(q_win, k, ws, q_pos=None, keep=None):
 
 def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale: float = 0.0,
               scores: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
-              stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None) -> torch.Tensor:
+              stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
+              pool_mode: str = "max") -> torch.Tensor:
     """q_win [n, Hq, W, d], k [n, Hkv, L, d] -> scores [n, Hkv, L] fp32 (pooled if pool_kernel > 1).
-    q_pos / keep: the general observation window of laq_shape (None: trailing window)."""
+    q_pos / keep: the general observation window of laq_shape (None: trailing window); pool_mode:
+    "max" or "avg" (laq_pool_mode)."""
     lib = load_library()
     _dev(q_win, "q_win"), _dev(k, "k")
     n, Hq, W, d = q_win.shape
@@ -147,7 +157,7 @@ def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale:
     if scores is None:
         scores = torch.empty(n, Hkv, L, dtype=torch.float32, device=k.device)
     ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
-    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode)
     rc = lib.laq_score(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), int(pool_kernel), scores.data_ptr(),
                        ws.data_ptr(), ws_bytes, _stream(stream))
     if rc != 0:
@@ -156,9 +166,9 @@ def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale:
 
 
 def laq_select(scores: torch.Tensor, budget: Sequence[int], pool_kernel: int, keep: int,
-               idx: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+               idx: Optional[torch.Tensor] = None, stream=None, pool_mode: str = "max") -> torch.Tensor:
     """scores [n, Hkv, L] fp32 -> packed idx (int32, see packed_rows); keep = trailing keys always
-    retained (the window size W in the trailing-window layout)."""
+    retained (the window size W in the trailing-window layout); pool_mode as in laq_score."""
     lib = load_library()
     _dev(scores, "scores")
     if scores.dtype != torch.float32:
@@ -167,11 +177,29 @@ def laq_select(scores: torch.Tensor, budget: Sequence[int], pool_kernel: int, ke
     total, _ = packed_rows(budget, Hkv, L)
     if idx is None:
         idx = torch.empty(total, dtype=torch.int32, device=scores.device)
-    sh = _shape(n, Hkv, Hkv, 8, L, 1, LAQ_F32, 0.0, None, keep)
+    sh = _shape(n, Hkv, Hkv, 8, L, 1, LAQ_F32, 0.0, None, keep, pool_mode)
     rc = lib.laq_select(ctypes.byref(sh), scores.data_ptr(), _budget_array(budget, n), int(pool_kernel),
                         idx.data_ptr(), _stream(stream))
     if rc != 0:
         raise LaqError(rc, "laq_select")
+    return idx
+
+
+def laq_select_sink_recent(n_inst: int, Hkv: int, L: int, budget: Sequence[int], n_sink: int,
+                           idx: Optional[torch.Tensor] = None, device=None, stream=None) -> torch.Tensor:
+    """Score-free stage-1 list: packed idx (as laq_select packs it) holding, per KV head, the first
+    n_sink positions and the most recent ones.  `device` places a newly made idx (default cuda:0)."""
+    lib = load_library()
+    total, _ = packed_rows(budget, Hkv, L)
+    if idx is None:
+        idx = torch.empty(total, dtype=torch.int32, device=device if device is not None else "cuda:0")
+    _dev(idx, "idx")
+    if idx.dtype != torch.int32 or idx.numel() < total:
+        raise ValueError("idx must be int32 with at least %d entries" % total)
+    rc = lib.laq_select_sink_recent(int(n_inst), int(Hkv), int(L), _budget_array(budget, n_inst), int(n_sink),
+                                    idx.data_ptr(), _stream(stream))
+    if rc != 0:
+        raise LaqError(rc, "laq_select_sink_recent")
     return idx
 
 
@@ -202,7 +230,8 @@ def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, b
 
 def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], budget: Sequence[int],
               pool_kernel: int, scale: float = 0.0, scores=None, idx=None, k_out=None, v_out=None, ws=None,
-              stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None):
+              stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
+              pool_mode: str = "max"):
     """Whole path on one stream: returns (scores, idx, k_out, v_out); layouts as in the three calls."""
     lib = load_library()
     _dev(q_win, "q_win"), _dev(k, "k")
@@ -222,7 +251,7 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
         if v_out is None:
             v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
     ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
-    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode)
     rc = lib.laq_evict(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), v.data_ptr() if v is not None else None,
                        _budget_array(budget, n), int(pool_kernel), scores.data_ptr(), idx.data_ptr(),
                        k_out.data_ptr(), v_out.data_ptr() if v is not None else None, ws.data_ptr(), ws_bytes,

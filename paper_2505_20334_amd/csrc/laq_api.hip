@@ -8,6 +8,7 @@
 namespace laq {
 
 static bool pool_ok(int pool) { return pool >= 1 && pool <= MAX_POOL && (pool % 2) == 1; }
+static bool pool_avg(const laq_shape* s) { return s->pool_mode == LAQ_POOL_AVG; }
 
 // Geometry of a call.  Returns LAQ_OK, LAQ_ERR_INVALID or LAQ_ERR_UNSUPPORTED; fills the query
 // position table (qp may be null for calls that do not score) when positions are explicit.
@@ -18,6 +19,7 @@ static int make_geom(const laq_shape* s, ScoreGeom* g, QueryPos* qp = nullptr) {
   if ((!s->q_pos || s->keep < 0) && s->W > s->L) return LAQ_ERR_INVALID;   // trailing-window defaults need W <= L
   if (s->keep > s->L) return LAQ_ERR_INVALID;
   if (s->dtype != LAQ_F32 && s->dtype != LAQ_BF16) return LAQ_ERR_INVALID;
+  if (s->pool_mode != LAQ_POOL_MAX && s->pool_mode != LAQ_POOL_AVG) return LAQ_ERR_INVALID;
   if (!(s->scale == s->scale) || isinf(s->scale)) return LAQ_ERR_INVALID;
   g->n_inst = s->n_inst; g->Hq = s->Hq; g->Hkv = s->Hkv; g->d = s->d; g->L = s->L; g->W = s->W;
   g->G = s->Hq / s->Hkv;
@@ -73,15 +75,15 @@ Workspace carve_workspace(const ScoreGeom& g, void* ws) {
 }
 
 // Fill the per-instance table for instances [i0, i0+n) and return the largest Bk among them.
-static int fill_table(const laq_shape* s, const int32_t* budget, int i0, int n, int64_t row_base,
+static int fill_table(int Hkv, int L, const int32_t* budget, int i0, int n, int64_t row_base,
                       InstTable* tab, int64_t* rows_after) {
   int bk_max = 0;
   int64_t row = row_base;
   for (int i = 0; i < n; ++i) {
-    const int bk = budget[i0 + i] < s->L ? budget[i0 + i] : s->L;
+    const int bk = budget[i0 + i] < L ? budget[i0 + i] : L;
     tab->bk[i] = bk;
     tab->row0[i] = row;
-    row += (int64_t)s->Hkv * bk;
+    row += (int64_t)Hkv * bk;
     if (bk > bk_max) bk_max = bk;
   }
   *rows_after = row;
@@ -105,14 +107,17 @@ static int score_impl(const laq_shape* shape, const void* q_win, const void* k, 
   if (!pool_ok(pool) || !q_win || !k || !scores) return LAQ_ERR_INVALID;
   if (!ws || ws_bytes < workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
   if (g.Hkv > 65535 || g.n_inst > 65535 || (long long)g.Hkv * g.n_inst > 0x7fffffffLL) return LAQ_ERR_UNSUPPORTED;
+  if ((g.L + 255) / 256 > 65535) return LAQ_ERR_UNSUPPORTED;      // grid limit of the pooling kernel
   const Workspace w = carve_workspace(g, ws);
   hipError_t e;
-  if (score_mfma_supported(g, shape->dtype)) {
-    e = launch_score_mfma(g, qp, pool, q_win, k, scores, w, st);     // pooling fused into pass 2
+  const bool avg = pool_avg(shape) && pool > 1;
+  if (score_mfma_supported(g, shape->dtype) && !avg) {
+    e = launch_score_mfma(g, qp, pool, q_win, k, scores, w, st);     // max pooling fused into pass 2
   } else {
     float* raw = pool > 1 ? w.raw : scores;
-    e = launch_score_generic(g, qp, shape->dtype, q_win, k, raw, w, st);
-    if (e == hipSuccess && pool > 1) e = launch_pool(g, pool, raw, scores, st);
+    e = score_mfma_supported(g, shape->dtype) ? launch_score_mfma(g, qp, 1, q_win, k, raw, w, st)
+                                              : launch_score_generic(g, qp, shape->dtype, q_win, k, raw, w, st);
+    if (e == hipSuccess && pool > 1) e = launch_pool(g, pool, avg, raw, scores, st);
   }
   return e == hipSuccess ? LAQ_OK : LAQ_ERR_DEVICE;
 }
@@ -129,8 +134,8 @@ static int select_impl(const laq_shape* shape, const float* scores, const int32_
     const int n = shape->n_inst - i0 < MAX_INST_PER_LAUNCH ? shape->n_inst - i0 : MAX_INST_PER_LAUNCH;
     InstTable tab;
     memset(&tab, 0, sizeof tab);
-    fill_table(shape, budget, i0, n, row, &tab, &row);
-    if (launch_select(n, i0, g.Hkv, g.L, g.keep, pool, scores, tab, idx, st) != hipSuccess) return LAQ_ERR_DEVICE;
+    fill_table(g.Hkv, g.L, budget, i0, n, row, &tab, &row);
+    if (launch_select(n, i0, g.Hkv, g.L, g.keep, pool, pool_avg(shape), scores, tab, idx, st) != hipSuccess) return LAQ_ERR_DEVICE;
   }
   return LAQ_OK;
 }
@@ -148,9 +153,26 @@ static int compact_impl(const laq_shape* shape, const void* k, const void* v, co
     const int n = shape->n_inst - i0 < MAX_INST_PER_LAUNCH ? shape->n_inst - i0 : MAX_INST_PER_LAUNCH;
     InstTable tab;
     memset(&tab, 0, sizeof tab);
-    const int bk_max = fill_table(shape, budget, i0, n, row, &tab, &row);
+    const int bk_max = fill_table(g.Hkv, g.L, budget, i0, n, row, &tab, &row);
     if (launch_compact(n, i0, g.Hkv, g.L, row_bytes, bk_max, k, v, idx, tab, k_out, v_out, st) != hipSuccess)
       return LAQ_ERR_DEVICE;
+  }
+  return LAQ_OK;
+}
+
+static int sink_recent_impl(int n_inst, int Hkv, int L, const int32_t* budget, int n_sink, int32_t* idx,
+                            hipStream_t st) {
+  if (n_inst < 1 || Hkv < 1 || L < 1 || n_sink < 0 || !budget || !idx) return LAQ_ERR_INVALID;
+  for (int i = 0; i < n_inst; ++i)
+    if (budget[i] < 1) return LAQ_ERR_INVALID;
+  if (Hkv > 65535) return LAQ_ERR_UNSUPPORTED;
+  int64_t row = 0;
+  for (int i0 = 0; i0 < n_inst; i0 += MAX_INST_PER_LAUNCH) {
+    const int n = n_inst - i0 < MAX_INST_PER_LAUNCH ? n_inst - i0 : MAX_INST_PER_LAUNCH;
+    InstTable tab;
+    memset(&tab, 0, sizeof tab);
+    fill_table(Hkv, L, budget, i0, n, row, &tab, &row);
+    if (launch_sink_recent(n, Hkv, L, n_sink, tab, idx, st) != hipSuccess) return LAQ_ERR_DEVICE;
   }
   return LAQ_OK;
 }
@@ -173,6 +195,11 @@ int laq_score(const laq_shape* shape, const void* q_win, const void* k, int pool
 int laq_select(const laq_shape* shape, const float* scores, const int32_t* budget, int pool_kernel,
                int32_t* idx, void* stream) {
   return laq::select_impl(shape, scores, budget, pool_kernel, idx, static_cast<hipStream_t>(stream));
+}
+
+int laq_select_sink_recent(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t* budget, int32_t n_sink,
+                           int32_t* idx, void* stream) {
+  return laq::sink_recent_impl(n_inst, Hkv, L, budget, n_sink, idx, static_cast<hipStream_t>(stream));
 }
 
 int laq_compact(const laq_shape* shape, const void* k, const void* v, const int32_t* idx,

@@ -71,6 +71,22 @@ struct InstTable {
   int64_t row0[MAX_INST_PER_LAUNCH];    // first packed output row (sum of Hkv * Bk of earlier instances)
 };
 
+// Pooled score at prefix position pos, the one arithmetic every pooling site uses: the
+// maximum over the part of the window inside [0, P), or (avg) the fp32 sum over it in
+// ascending position divided by the kernel size 2*half+1 (zeros outside the prefix).
+__device__ __forceinline__ float pool_window(const float* __restrict__ s, int pos, int P, int half, bool avg) {
+  if (half == 0) return s[pos];
+  const int lo = max(pos - half, 0), hi = min(pos + half, P - 1);
+  if (avg) {
+    float acc = 0.f;
+    for (int i = lo; i <= hi; ++i) acc += s[i];
+    return acc / (float)(2 * half + 1);
+  }
+  float v = s[pos];
+  for (int i = lo; i <= hi; ++i) v = fmaxf(v, s[i]);
+  return v;
+}
+
 // launchers (each returns hipGetLastError() after its last launch); `raw` receives unpooled scores
 hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, int dtype, const void* q, const void* k,
                                 float* raw, const Workspace& ws, hipStream_t st);
@@ -78,9 +94,11 @@ hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStre
 bool score_mfma_supported(const ScoreGeom& g, int dtype);
 hipError_t launch_score_mfma(const ScoreGeom& g, const QueryPos& qp, int pool, const void* q, const void* k,
                              float* scores, const Workspace& ws, hipStream_t st);
-hipError_t launch_pool(const ScoreGeom& g, int pool, const float* raw, float* pooled, hipStream_t st);
-hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int keep, int pool, const float* scores,
+hipError_t launch_pool(const ScoreGeom& g, int pool, bool avg, const float* raw, float* pooled, hipStream_t st);
+hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int keep, int pool, bool avg, const float* scores,
                          const InstTable& tab, int32_t* idx, hipStream_t st);
+hipError_t launch_sink_recent(int n_inst, int Hkv, int L, int n_sink, const InstTable& tab, int32_t* idx,
+                              hipStream_t st);
 hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, int bk_max, const void* k,
                           const void* v, const int32_t* idx, const InstTable& tab, void* k_out, void* v_out,
                           hipStream_t st);

@@ -88,18 +88,14 @@ __global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, Q
   raw[((size_t)inst * g.Hkv + head) * g.L + j] = acc;
 }
 
-// pooled[j] = max(raw[i] : |i - j| <= half, 0 <= i < P) for prefix keys; window columns are copied
-__global__ __launch_bounds__(256) void pool_kernel(int L, int P, int half, const float* __restrict__ raw,
+// pooled[j] = max (or mean) of raw[i], |i - j| <= half, 0 <= i < P, for prefix keys; the kept
+// trailing columns are copied
+__global__ __launch_bounds__(256) void pool_kernel(int L, int P, int half, bool avg, const float* __restrict__ raw,
                                                    float* __restrict__ pooled) {
-  const int j = blockIdx.x * 256 + threadIdx.x;
+  const int j = blockIdx.y * 256 + threadIdx.x;      // grid.x walks the (instance, KV head) pairs
   if (j >= L) return;
-  const float* r = raw + (size_t)blockIdx.y * L;
-  float v = r[j];
-  if (j < P) {
-    const int lo = max(j - half, 0), hi = min(j + half, P - 1);
-    for (int i = lo; i <= hi; ++i) v = fmaxf(v, r[i]);
-  }
-  pooled[(size_t)blockIdx.y * L + j] = v;
+  const float* r = raw + (size_t)blockIdx.x * L;
+  pooled[(size_t)blockIdx.x * L + j] = j < P ? pool_window(r, j, P, half, avg) : r[j];
 }
 
 }  // namespace
@@ -130,9 +126,9 @@ hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStre
   return hipGetLastError();
 }
 
-hipError_t launch_pool(const ScoreGeom& g, int pool, const float* raw, float* pooled, hipStream_t st) {
-  dim3 grid((g.L + 255) / 256, g.n_inst * g.Hkv);
-  hipLaunchKernelGGL(pool_kernel, grid, dim3(256), 0, st, g.L, g.P, (pool - 1) / 2, raw, pooled);
+hipError_t launch_pool(const ScoreGeom& g, int pool, bool avg, const float* raw, float* pooled, hipStream_t st) {
+  dim3 grid(g.n_inst * g.Hkv, (g.L + 255) / 256);
+  hipLaunchKernelGGL(pool_kernel, grid, dim3(256), 0, st, g.L, g.P, (pool - 1) / 2, avg, raw, pooled);
   return hipGetLastError();
 }
 

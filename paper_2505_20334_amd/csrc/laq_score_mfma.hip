@@ -41,6 +41,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float NEG_BIG = -1.0e30f;
+constexpr int MAX_HALF = (MAX_POOL - 1) / 2;
 constexpr int WAVES = 4;
 constexpr int THREADS = WAVES * 64;
 constexpr int KTILES = MFMA_ROWS / 32;
@@ -65,7 +66,8 @@ template <int D> struct Tile {
 };
 
 template <int D, int NRT> struct Smem {
-  static constexpr int OFF_STAT = Tile<D>::K_BYTES;                    // float2[THREADS]: pass 1's per-thread statistics
+  static constexpr int OFF_STAT = Tile<D>::K_BYTES;                    // float2[THREADS]: pass 1's per-thread statistics;
+                                                                       // pass 2: the chunk's raw scores with a zero margin
   static constexpr int OFF_SLOT = OFF_STAT + THREADS * 8;              // float[NRT][MFMA_ROWS]
   static constexpr int OFF_CTL = OFF_SLOT + NRT * MFMA_ROWS * 4;      // int: the workgroup's next run of units
   static constexpr int BYTES = OFF_CTL + 16;
@@ -439,17 +441,23 @@ __device__ __forceinline__ bool chunk_pass1(char* smem, const ScoreGeom& g, cons
   return pending;
 }
 
-// Pass 2 over the staged chunk (staged row t is key j0 + t; the keys own_lo .. own_lo+own-1 are
-// this chunk's to write, the rows around them are the pooling halo): raw scores of all staged
-// rows, max-pool.  Returns whether this thread has an owned key (index j_out) and its pooled score
-// (v_out); the caller stores it after it has moved the next chunk's rows into LDS, so that the
-// wait for those rows is not also a wait for the store.  c points at the head's row constants.
+// Pass 2 over the staged chunk (staged row t is key j0 + t, j0 a multiple of the chunk size): raw
+// scores of its rows.  Returns whether this thread has a score to store (index j_out, raw value
+// v_out); the caller stores it after it has moved the next chunk's rows into LDS, so that the wait
+// for those rows is not also a wait for the store.  With pool_out set the stored value is the
+// maximum over the key's pooling window instead, which pooled_score() takes from the copy of the
+// raw scores left in LDS once the caller has passed a barrier.  A prefix key whose pooling window
+// reaches into a neighbouring chunk is left out here: with `edges` set, the raw scores of the
+// chunk's first and last 2*half rows are handed back as well (slot e_out of the chunk's edge
+// record, value r_out, when the function sets edge_out) and pool_boundaries_kernel pools those
+// keys from the records.  c points at the head's row constants.
 template <int D, int NRT>
 __device__ __forceinline__ bool chunk_pass2(char* smem, const ScoreGeom& g, const QueryPos& qp, int half,
-                                            int own_lo, int own,
+                                            bool edges,
                                             const uint16_t* __restrict__ qg, const float* __restrict__ c,
                                             bf16x8 (&qreg)[Tile<D>::KSTEPS], float (&cr)[16], bool reload, int j0,
                                             int tid, int lane, int wave, int& j_out, float& v_out,
+                                            bool& pool_out, bool& edge_out, int& e_out, float& r_out,
                                             u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
@@ -484,46 +492,73 @@ __device__ __forceinline__ bool chunk_pass2(char* smem, const ScoreGeom& g, cons
     }
   }
   __syncthreads();                        // slots complete, key rows no longer read
-  // raw score of staged row t = sum of the row-tile slots; an owned prefix key takes the maximum of
-  // the raw scores in its pooling window straight from the slots (no second barrier)
+  // raw score of staged row t = sum of the row-tile slots
   const int j = j0 + tid;
   j_out = j;
   v_out = 0.f;
-  const bool owned = tid < MFMA_ROWS && j >= own_lo && j < own_lo + own && j < g.L;
-  if (owned) {
-    int lo = tid, hi = tid;
-    if (j < g.P && half > 0) {
-      lo = max(j - half, 0) - j0;
-      hi = min(j + half, g.P - 1) - j0;
-    }
-    float v = 0.f;                        // scores are sums of probabilities, never negative
-    auto raw_at = [&](int i) {
-      float r = slots[i];
+  edge_out = false;
+  e_out = 0;
+  r_out = 0.f;
+  bool owned = tid < MFMA_ROWS && j < g.L;
+  float v = 0.f;
+  if (tid < MFMA_ROWS) {
+    v = slots[tid];
 #pragma unroll
-      for (int s = 1; s < NRT; ++s) r += slots[s * MFMA_ROWS + i];
-      return r;
-    };
-    if (lo == hi) {
-      v = raw_at(tid);
-    } else if (half <= 3) {
-      // the usual window of up to 7: all reads issued at once (positions clamped into the window
-      // repeat a value, which a maximum does not mind) instead of a chain of LDS round trips
-      float r[7];
-#pragma unroll
-      for (int o = 0; o < 7; ++o) r[o] = raw_at(min(max(tid + o - 3, lo), hi));
-#pragma unroll
-      for (int o = 0; o < 7; ++o) v = fmaxf(v, r[o]);
-    } else {
-      for (int i = lo; i <= hi; ++i) v = fmaxf(v, raw_at(i));
-    }
-    v_out = v;
+    for (int s = 1; s < NRT; ++s) v += slots[s * MFMA_ROWS + tid];
   }
+  pool_out = false;
+  if (half > 0) {
+    // Pooling reads the raw scores through a copy with MAX_HALF zeros on either side (the zeros
+    // were written when the kernel started), in which the keys outside the prefix are zero too:
+    // scores are sums of probabilities, never negative, so a zero stands for "not in the window"
+    // and every window position can be read without a bounds test.  The copy is complete at the
+    // caller's next barrier; pooled_score() reads it then.
+    float* rawbuf = reinterpret_cast<float*>(smem + S::OFF_STAT) + MAX_HALF;
+    if (tid < MFMA_ROWS) rawbuf[tid] = j < g.P ? v : 0.f;
+    if (owned) {
+      if (edges) {
+        r_out = v;
+        if (tid < 2 * half) {
+          edge_out = true;
+          e_out = tid;
+        } else if (tid >= MFMA_ROWS - 2 * half) {
+          edge_out = true;
+          e_out = tid - (MFMA_ROWS - 4 * half);
+        }
+      }
+      if (j < g.P) {
+        if ((j0 > 0 && tid < half) || min(j + half, g.P - 1) >= j0 + MFMA_ROWS)
+          owned = false;                  // the window reaches into a neighbouring chunk
+        else
+          pool_out = true;
+      }
+    }
+  }
+  v_out = v;
   return owned;
+}
+
+// Maximum of the raw scores in the pooling window of staged row tid, from the zero-margined copy
+// that chunk_pass2 left in LDS (call after a barrier that follows it).
+template <int D, int NRT>
+__device__ __forceinline__ float pooled_score(const char* smem, int half, int tid, float v) {
+  const float* rawbuf = reinterpret_cast<const float*>(smem + Smem<D, NRT>::OFF_STAT) + MAX_HALF;
+  if (half == 3) {
+    float r[7];                           // the usual kernel of 7: all reads issued at once
+#pragma unroll
+    for (int o = 0; o < 7; ++o) r[o] = rawbuf[tid + o - 3];
+#pragma unroll
+    for (int o = 0; o < 7; ++o) v = fmaxf(v, r[o]);
+  } else {
+    for (int o = -half; o <= half; ++o) v = fmaxf(v, rawbuf[tid + o]);
+  }
+  return v;
 }
 
 // ---- the two streaming kernels ---------------------------------------------------------------
 // PASS 1: units are (head, chunk of 256 keys); writes part[head][chunk][row].
-// PASS 2: units are (head, chunk owning 256 - 2*half keys); reads rowc[head][row], writes scores.
+// PASS 2: units are (head, chunk of 256 keys); reads rowc[head][row], writes scores and, through
+//         `part`, the edge records float[head][chunk][4*half] of the pooling across chunk boundaries.
 //
 // A workgroup works through runs of consecutive units, i.e. it walks along one head, so Q and
 // the row constants are loaded once per head and the only per-unit traffic is the key rows.  Its
@@ -553,7 +588,6 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
                                                             float* __restrict__ scores, int* __restrict__ ctr) {
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int own = MFMA_ROWS - 2 * half;
   const bool one_group = (g.Rpad / 32 <= NRT);
   const int units_per_head = plan.units_per_head, n_units = plan.n_units;
   volatile int* ctl = reinterpret_cast<volatile int*>(smem + Smem<D, NRT>::OFF_CTL);
@@ -565,9 +599,13 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
   u32x4 pre[Tile<D>::PIECES_PER_THREAD];
   bf16x8 qreg[Tile<D>::KSTEPS];
   float cr[16];
+  if (PASS == 2 && tid < 2 * MAX_HALF) {  // zero margins of the raw-score copy that pooling reads
+    float* margin = reinterpret_cast<float*>(smem + Smem<D, NRT>::OFF_STAT);
+    margin[tid < MAX_HALF ? tid : MFMA_ROWS + tid] = 0.f;
+  }
   {
     const int hg = run_u / units_per_head, c = run_u - hg * units_per_head;
-    fetch_chunk<D>(pre, key_rows<D>(k + (size_t)hg * g.L * D, max(c * own - half, 0), g.L, tid));
+    fetch_chunk<D>(pre, key_rows<D>(k + (size_t)hg * g.L * D, c * MFMA_ROWS, g.L, tid));
     commit_chunk<D>(smem, pre, tid);
   }
   __syncthreads();
@@ -587,7 +625,7 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
           __syncthreads();
         }
       }
-      const int j0 = max(c * own - half, 0);       // first staged key (the head's first chunk has no left halo)
+      const int j0 = c * MFMA_ROWS;                // first staged key
       // the G query heads of KV head hg are consecutive: rows hg*R .. hg*R+R-1 of Q (R = G*W)
       const uint16_t* qg = q + (size_t)hg * g.R * D;
       const bool reload = !one_group || hg != hg_loaded;
@@ -618,24 +656,30 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
           cn = s - hn * units_per_head;
         }
       }
-      const KeyRows nkr = key_rows<D>(k + (size_t)hn * g.L * D, max(cn * own - half, 0), g.L, tid);
-      bool owned = false;
-      int j_out = 0;
-      float v_out = 0.f;
+      const KeyRows nkr = key_rows<D>(k + (size_t)hn * g.L * D, cn * MFMA_ROWS, g.L, tid);
+      bool owned = false, edge_out = false, pool_out = false;
+      int j_out = 0, e_out = 0;
+      float v_out = 0.f, r_out = 0.f;
       float2 mz_out = make_float2(0.f, 0.f);
       float2* part_unit = part + ((size_t)hg * units_per_head + c) * g.Rpad;
       if (PASS == 1)
         owned = chunk_pass1<D, NRT>(smem, g, qp, qg, qreg, !one_group, j0, tid, lane, wave, part_unit, j_out, mz_out,
                                     pre, nkr);
       else
-        owned = chunk_pass2<D, NRT>(smem, g, qp, half, c * own, own, qg, rowc + (size_t)hg * g.Rpad, qreg, cr,
-                                    !one_group, j0, tid, lane, wave, j_out, v_out, pre, nkr);
+        owned = chunk_pass2<D, NRT>(smem, g, qp, half, half > 0 && units_per_head > 1, qg,
+                                    rowc + (size_t)hg * g.Rpad, qreg, cr, !one_group, j0, tid, lane, wave, j_out,
+                                    v_out, pool_out, edge_out, e_out, r_out, pre, nkr);
       // (every wave's reads of this chunk's rows are behind a barrier by now)
       if (plan.dynamic && first && !single && tid == 0) ctl[0] = claimed;
       commit_chunk<D>(smem, pre, tid);
       if (PASS == 1 && owned) part_unit[j_out] = mz_out;
-      if (PASS == 2 && owned) scores[(size_t)hg * g.L + j_out] = v_out;
+      if (PASS == 2 && owned && !pool_out) scores[(size_t)hg * g.L + j_out] = v_out;
+      if (PASS == 2 && edge_out)
+        reinterpret_cast<float*>(part)[((size_t)hg * units_per_head + c) * (4 * half) + e_out] = r_out;
       __syncthreads();
+      // (pooling comes after the barrier that completes the raw-score copy; the copy is next
+      // written behind the next unit's first barrier, which every wave passes after these reads)
+      if (PASS == 2 && pool_out) scores[(size_t)hg * g.L + j_out] = pooled_score<D, NRT>(smem, half, tid, v_out);
       hg = hn;                            // what was prefetched is what comes next
       c = cn;
     }
@@ -678,6 +722,30 @@ __global__ __launch_bounds__(256) void row_constants_mfma_kernel(ScoreGeom g, co
   }
 }
 
+// Pooled scores of the prefix keys whose pooling window crosses a boundary between two chunks of
+// pass 2, from the edge records (per chunk: raw scores of its first 2*half rows, then of its last
+// 2*half rows).  The boundary before chunk c lies at key b = c * chunk size and the keys
+// b-half .. b+half-1 are pooled here, one per thread; blockIdx.x is the head.
+__global__ __launch_bounds__(256) void pool_boundaries_kernel(int L, int P, int half, int nchunk,
+                                                               const float* __restrict__ edge,
+                                                               float* __restrict__ scores) {
+  const int hg = blockIdx.x;
+  const int rec = 4 * half, per = 2 * half;
+  const int it = blockIdx.y * 256 + threadIdx.x;
+  if (it >= (nchunk - 1) * per) return;
+  const int c = it / per + 1;
+  const int b = c * MFMA_ROWS;
+  const int j = b - half + it % per;
+  if (j >= P) return;
+  // raw score of key i, b - 2*half <= i < b + 2*half, is e[i]: the tail of chunk c-1's record is
+  // followed in memory by the head of chunk c's
+  const float* e = edge + ((size_t)hg * nchunk + c - 1) * rec + per - (b - per);
+  const int hi = min(j + half, P - 1);
+  float v = 0.f;
+  for (int i = j - half; i <= hi; ++i) v = fmaxf(v, e[i]);
+  scores[(size_t)hg * L + j] = v;
+}
+
 template <int D, int NRT>
 hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, int pool, const uint16_t* q, const uint16_t* k,
                          float* scores, const Workspace& ws, hipStream_t st) {
@@ -702,8 +770,8 @@ hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, int pool, const
   }
   const long long n_heads = (long long)g.n_inst * g.Hkv;
   const int half = (pool - 1) / 2;
-  const int units2 = (g.L + MFMA_ROWS - 2 * half - 1) / (MFMA_ROWS - 2 * half);
   const int units1 = (g.L + MFMA_ROWS - 1) / MFMA_ROWS;
+  const int units2 = units1;
   ScoreGeom gm = g;
   gm.nchunk = units1;                      // this path's chunking of the statistics
   const long long nu1 = n_heads * units1, nu2 = n_heads * units2;
@@ -736,9 +804,18 @@ hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, int pool, const
   hipLaunchKernelGGL(row_constants_mfma_kernel, dim3((unsigned)n_heads, g.Rpad / 32), dim3(256), 0, st, gm, ws.part,
                      ws.rowc);
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  // (the edge records, at most 124 floats per 256-key chunk and only written when a head has more
+  // than one chunk, fit the workspace's raw-score area of L floats per head)
   hipLaunchKernelGGL((stream_kernel<D, NRT, 2>), dim3(grid2), dim3(THREADS), bytes, st, g, qp, half, p2, q, k,
-                     (float2*)nullptr, ws.rowc, scores, ws.ctr + 1);
-  return hipGetLastError();
+                     reinterpret_cast<float2*>(ws.raw), ws.rowc, scores, ws.ctr + 1);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (half > 0 && units2 > 1) {
+    const int items = (units2 - 1) * 2 * half;
+    hipLaunchKernelGGL(pool_boundaries_kernel, dim3((unsigned)n_heads, (items + 255) / 256), dim3(256), 0, st, g.L,
+                       g.P, half, units2, (const float*)ws.raw, scores);
+    return hipGetLastError();
+  }
+  return hipSuccess;
 }
 
 template <int D>

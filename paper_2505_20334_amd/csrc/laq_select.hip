@@ -22,16 +22,6 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);   // larger float <=> larger key
 }
 
-// pooled score at prefix position pos (max over the part of the window inside [0, P))
-__device__ __forceinline__ float pooled_at(const float* __restrict__ s, int pos, int P, int half) {
-  float v = s[pos];
-  if (half > 0) {
-    const int lo = max(pos - half, 0), hi = min(pos + half, P - 1);
-    for (int i = lo; i <= hi; ++i) v = fmaxf(v, s[i]);
-  }
-  return v;
-}
-
 __device__ __forceinline__ int lanes_below(uint64_t m) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
 }
@@ -39,7 +29,7 @@ __device__ __forceinline__ int lanes_below(uint64_t m) {
 // ITEMS > 0: keys of the wave's segment are held in ITEMS registers per lane.
 // ITEMS == 0: keys are recomputed from memory on every sweep (any prefix length).
 template <int ITEMS>
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int keep, int pool,
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int keep, int pool, bool avg,
                                                              const float* __restrict__ scores, InstTable tab,
                                                              int inst0, int32_t* __restrict__ idx) {
   __shared__ int hist[256];
@@ -61,6 +51,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int
     return;
   }
 
+  constexpr int UNROLL = ITEMS > 0 ? ITEMS : 1;     // register-resident keys: full unrolling; memory path: none
   const int items = (ITEMS > 0) ? ITEMS : (P + SEL_THREADS - 1) / SEL_THREADS;
   const int seg0 = wave * items * 64;          // first position of this wave's segment
 
@@ -69,13 +60,13 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
       const int pos = seg0 + i * 64 + lane;
-      key[i] = (pos < P) ? order_key(pooled_at(s, pos, P, half)) : 0u;
+      key[i] = (pos < P) ? order_key(pool_window(s, pos, P, half, avg)) : 0u;
     }
   }
   auto key_of = [&](int i) -> uint32_t {
     if (ITEMS > 0) return key[i];
     const int pos = seg0 + i * 64 + lane;
-    return (pos < P) ? order_key(pooled_at(s, pos, P, half)) : 0u;
+    return (pos < P) ? order_key(pool_window(s, pos, P, half, avg)) : 0u;
   };
 
   // ---- radix passes: find the key of the ksel-th largest score ----
@@ -86,7 +77,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
     int cur = -1, cnt = 0;            // run-length aggregation: one atomic per run of equal digits
-#pragma unroll
+#pragma unroll UNROLL
     for (int i = 0; i < items; ++i) {
       const uint32_t kv = key_of(i);
       if ((kv & mask) == prefix) {
@@ -132,7 +123,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int
 
   // ---- emission in ascending position order ----
   int wg = 0, we = 0;
-#pragma unroll
+#pragma unroll UNROLL
   for (int i = 0; i < items; ++i) {
     const uint32_t kv = key_of(i);
     wg += __popcll(__ballot(kv > T));
@@ -142,7 +133,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int
   __syncthreads();
   int run_gt = 0, run_eq = 0;
   for (int v = 0; v < wave; ++v) { run_gt += wtot_gt[v]; run_eq += wtot_eq[v]; }
-#pragma unroll
+#pragma unroll UNROLL
   for (int i = 0; i < items; ++i) {
     const uint32_t kv = key_of(i);
     const bool gt = kv > T, eq = kv == T;
@@ -156,22 +147,40 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int
 }
 
 template <int ITEMS>
-hipError_t launch_one(int n_inst, int inst0, int Hkv, int L, int keep, int pool, const float* scores,
+hipError_t launch_one(int n_inst, int inst0, int Hkv, int L, int keep, int pool, bool avg, const float* scores,
                       const InstTable& tab, int32_t* idx, hipStream_t st) {
-  hipLaunchKernelGGL(select_kernel<ITEMS>, dim3(Hkv, n_inst), dim3(SEL_THREADS), 0, st, Hkv, L, keep, pool, scores,
+  hipLaunchKernelGGL(select_kernel<ITEMS>, dim3(Hkv, n_inst), dim3(SEL_THREADS), 0, st, Hkv, L, keep, pool, avg, scores,
                      tab, inst0, idx);
   return hipGetLastError();
 }
 
+// Score-free list (Sec. 2.1, StreamingLLM form): row = 0 .. s-1, then the Bk - s most recent
+// positions, s = min(n_sink, Bk).  One workgroup per (KV head, instance).
+__global__ __launch_bounds__(256) void sink_recent_kernel(int Hkv, int L, int n_sink, InstTable tab,
+                                                          int32_t* __restrict__ idx) {
+  const int head = blockIdx.x, li = blockIdx.y;
+  const int bk = tab.bk[li];
+  const int s = min(n_sink, bk);
+  const int shift = L - bk;                 // recent entry at list slot t sits at position t + (L - Bk)
+  int32_t* out = idx + (tab.row0[li] + (int64_t)head * bk);
+  for (int t = threadIdx.x; t < bk; t += 256) out[t] = t < s ? t : t + shift;
+}
+
 }  // namespace
 
-hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int keep, int pool, const float* scores,
+hipError_t launch_sink_recent(int n_inst, int Hkv, int L, int n_sink, const InstTable& tab, int32_t* idx,
+                              hipStream_t st) {
+  hipLaunchKernelGGL(sink_recent_kernel, dim3(Hkv, n_inst), dim3(256), 0, st, Hkv, L, n_sink, tab, idx);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int keep, int pool, bool avg, const float* scores,
                          const InstTable& tab, int32_t* idx, hipStream_t st) {
   const int P = L - keep;
-  if (P <= 2 * SEL_THREADS) return launch_one<2>(n_inst, inst0, Hkv, L, keep, pool, scores, tab, idx, st);
-  if (P <= 8 * SEL_THREADS) return launch_one<8>(n_inst, inst0, Hkv, L, keep, pool, scores, tab, idx, st);
-  if (P <= 32 * SEL_THREADS) return launch_one<32>(n_inst, inst0, Hkv, L, keep, pool, scores, tab, idx, st);
-  return launch_one<0>(n_inst, inst0, Hkv, L, keep, pool, scores, tab, idx, st);
+  if (P <= 2 * SEL_THREADS) return launch_one<2>(n_inst, inst0, Hkv, L, keep, pool, avg, scores, tab, idx, st);
+  if (P <= 8 * SEL_THREADS) return launch_one<8>(n_inst, inst0, Hkv, L, keep, pool, avg, scores, tab, idx, st);
+  if (P <= 32 * SEL_THREADS) return launch_one<32>(n_inst, inst0, Hkv, L, keep, pool, avg, scores, tab, idx, st);
+  return launch_one<0>(n_inst, inst0, Hkv, L, keep, pool, avg, scores, tab, idx, st);
 }
 
 }  // namespace laq

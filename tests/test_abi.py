@@ -20,8 +20,8 @@ def declared_functions(repo_root):
 def test_library_exports_every_declared_symbol(repo_root):
     lib = laq.load_library()
     names = declared_functions(repo_root)
-    assert names == ["laq_compact", "laq_evict", "laq_score", "laq_select", "laq_strerror",
-                     "laq_workspace_bytes"]
+    assert names == ["laq_compact", "laq_evict", "laq_score", "laq_select", "laq_select_sink_recent",
+                     "laq_strerror", "laq_workspace_bytes"]
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -47,7 +47,7 @@ def test_workspace_bytes_grows_with_shape():
 
 
 def _shape(**kw):
-    base = dict(n_inst=1, Hq=8, Hkv=2, d=128, L=512, W=8, dtype=1, scale=0.0, q_pos=None, keep=-1)
+    base = dict(n_inst=1, Hq=8, Hkv=2, d=128, L=512, W=8, dtype=1, scale=0.0, q_pos=None, keep=-1, pool_mode=0)
     base.update(kw)
     return binding._Shape(*[base[f] for f, _ in binding._Shape._fields_])
 
@@ -107,6 +107,28 @@ def test_general_window_arguments_are_checked_without_a_gpu():
     assert laq.laq_workspace_bytes(1, 8, 2, 128, 512, 600, torch.bfloat16) == 0
     assert laq.laq_workspace_bytes(1, 8, 2, 128, 512, 600, torch.bfloat16, q_pos=[1] * 600, keep=4) == 0   # > 512 positions
     assert laq.laq_workspace_bytes(1, 8, 2, 128, 512, 300, torch.bfloat16, q_pos=[1] * 300, keep=4) > 0
+
+
+def test_stage_one_variants_are_checked_without_a_gpu():
+    lib = laq.load_library()
+    fake = ctypes.c_void_p(0x1000)
+    INVALID, UNSUPPORTED, WORKSPACE = -1, -2, -3
+    bud = (ctypes.c_int32 * 1)(64)
+    # pool mode: 0 (max) and 1 (average) pass the shape check, anything else does not
+    assert lib.laq_score(ctypes.byref(_shape(pool_mode=1)), fake, fake, 7, fake, fake, 16, None) == WORKSPACE
+    assert lib.laq_score(ctypes.byref(_shape(pool_mode=2)), fake, fake, 7, fake, fake, 1 << 30, None) == INVALID
+    assert lib.laq_select(ctypes.byref(_shape(pool_mode=-1)), fake, bud, 7, fake, None) == INVALID
+    # sink + recent list: every call below is rejected before anything is launched
+    assert lib.laq_select_sink_recent(0, 2, 512, bud, 4, fake, None) == INVALID
+    assert lib.laq_select_sink_recent(1, 0, 512, bud, 4, fake, None) == INVALID
+    assert lib.laq_select_sink_recent(1, 2, 0, bud, 4, fake, None) == INVALID
+    assert lib.laq_select_sink_recent(1, 2, 512, bud, -1, fake, None) == INVALID
+    assert lib.laq_select_sink_recent(1, 2, 512, None, 4, fake, None) == INVALID
+    assert lib.laq_select_sink_recent(1, 2, 512, bud, 4, None, None) == INVALID
+    assert lib.laq_select_sink_recent(1, 2, 512, (ctypes.c_int32 * 1)(0), 4, fake, None) == INVALID
+    assert lib.laq_select_sink_recent(1, 70000, 512, bud, 4, fake, None) == UNSUPPORTED
+    with pytest.raises(ValueError):
+        binding._shape(1, 8, 2, 128, 512, 8, 1, 0.0, pool_mode="median")
 
 
 def test_packed_rows():

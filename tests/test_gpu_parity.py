@@ -172,6 +172,15 @@ EDGE = [
     ("window-is-everything", torch.bfloat16, 8, 2, 128, 32, 32, 7, 32),
     ("P-eq-1", torch.bfloat16, 8, 2, 128, 9, 8, 7, 9),
     ("long-window", torch.bfloat16, 8, 2, 128, 900, 300, 7, 400),
+    # pooling windows that cross the 256-key chunk boundaries of pass 2
+    ("prefix-ends-on-chunk-boundary", torch.bfloat16, 8, 2, 128, 520, 8, 7, 64),
+    ("prefix-ends-one-past-boundary", torch.bfloat16, 8, 2, 128, 521, 8, 7, 64),
+    ("prefix-ends-one-before-boundary", torch.bfloat16, 8, 2, 128, 519, 8, 7, 64),
+    ("prefix-ends-inside-boundary-window", torch.bfloat16, 8, 2, 128, 267, 8, 7, 64),
+    ("pool63-four-chunks", torch.bfloat16, 8, 2, 128, 1024, 8, 63, 200),
+    ("pool63-boundary-window-clipped-by-prefix", torch.bfloat16, 8, 2, 128, 290, 8, 63, 100),
+    ("pool5-length-multiple-of-chunk", torch.bfloat16, 16, 2, 64, 768, 8, 5, 90),
+    ("pool3-R128", torch.bfloat16, 32, 2, 128, 600, 8, 3, 64),
 ]
 
 
@@ -183,6 +192,24 @@ def test_edge_cases(laq, name, dtype, Hq, Hkv, d, L, W, pool, budget):
     k = torch.randn(n, Hkv, L, d, generator=g).to(dtype).to(DEV)
     v = torch.randn(n, Hkv, L, d, generator=g).to(dtype).to(DEV)
     run_and_check(laq, q, k, v, [budget, max(W, budget - 3)], pool, name)
+
+
+def test_peaks_on_chunk_boundaries_spread_to_both_sides(laq):
+    # keys aligned with the window queries right before and after every 256-key boundary: their
+    # pooled plateau must reach across the boundary in both directions
+    g = torch.Generator().manual_seed(5)
+    Hq, Hkv, d, L, W = 8, 2, 128, 1100, 8
+    q = torch.randn(1, Hq, W, d, generator=g)
+    k = torch.randn(1, Hkv, L, d, generator=g) * 0.5
+    for b in (256, 512, 768, 1024):
+        k[0, 0, b - 1] = q[0, 0].mean(0) * 3.0
+        k[0, 1, b] = q[0, 4].mean(0) * 3.0
+    q, k = q.bfloat16().to(DEV), k.bfloat16().to(DEV)
+    v = torch.randn(1, Hkv, L, d, generator=g).bfloat16().to(DEV)
+    sc = run_and_check(laq, q, k, v, [80], 7, "boundary-peaks")[0].cpu()
+    for b in (256, 512, 768, 1024):
+        assert (sc[0, 0, b - 4:b + 3] == sc[0, 0, b - 1]).all()       # plateau of key b-1
+        assert (sc[0, 1, b - 3:b + 4] == sc[0, 1, b]).all()           # plateau of key b
 
 
 def test_very_long_sequence(laq):
@@ -299,18 +326,18 @@ def test_explicit_scale(laq):
 
 
 # ---- general observation window (Eq. 5): explicit query positions, independent keep count ----
-def run_general(laq, q, k, v, budgets, pool, q_pos, keep, what, heads=None):
+def run_general(laq, q, k, v, budgets, pool, q_pos, keep, what, heads=None, pool_mode="max"):
     n, Hq, W, d = q.shape
     _, Hkv, L, _ = k.shape
     G = Hq // Hkv
-    print("case:", what, "n=%d Hq=%d Hkv=%d d=%d L=%d W=%d pool=%d keep=%d" % (n, Hq, Hkv, d, L, W, pool, keep),
-          flush=True)
-    scores, idx, ko, vo = laq.laq_evict(q, k, v, budgets, pool, q_pos=q_pos, keep=keep)
-    s3 = laq.laq_score(q, k, pool, q_pos=q_pos, keep=keep)
-    i3 = laq.laq_select(s3, budgets, 1, keep)
+    print("case:", what, "n=%d Hq=%d Hkv=%d d=%d L=%d W=%d pool=%d(%s) keep=%d" % (
+        n, Hq, Hkv, d, L, W, pool, pool_mode, keep), flush=True)
+    scores, idx, ko, vo = laq.laq_evict(q, k, v, budgets, pool, q_pos=q_pos, keep=keep, pool_mode=pool_mode)
+    s3 = laq.laq_score(q, k, pool, q_pos=q_pos, keep=keep, pool_mode=pool_mode)
+    i3 = laq.laq_select(s3, budgets, 1, keep, pool_mode=pool_mode)
     k3, v3 = laq.laq_compact(k, v, i3, budgets, keep)
-    raw = laq.laq_score(q, k, 1, q_pos=q_pos, keep=keep)
-    i_alt = laq.laq_select(raw, budgets, pool, keep)
+    raw = laq.laq_score(q, k, 1, q_pos=q_pos, keep=keep, pool_mode=pool_mode)
+    i_alt = laq.laq_select(raw, budgets, pool, keep, pool_mode=pool_mode)
     torch.cuda.synchronize()
     assert torch.equal(s3, scores) and torch.equal(i3, idx) and torch.equal(k3, ko) and torch.equal(v3, vo)
     assert torch.equal(i_alt, idx)
@@ -321,7 +348,7 @@ def run_general(laq, q, k, v, budgets, pool, q_pos, keep, what, heads=None):
     for i in range(n):
         for g in (range(Hkv) if heads is None else heads):
             o_raw = oracle.raw_scores(qc[i, g * G:(g + 1) * G], kc[i, g:g + 1], q_pos=q_pos)
-            pooled = oracle.maxpool(o_raw, keep, pool)
+            pooled = (oracle.maxpool if pool_mode == "max" else oracle.avgpool)(o_raw, keep, pool)
             check_scores(rc[i, g], o_raw[0], k.dtype, "%s raw inst %d head %d" % (what, i, g))
             check_scores(sc[i, g], pooled[0], k.dtype, "%s inst %d head %d" % (what, i, g))
             check_index_row(idx_l[i][g].numpy(), pooled[0].float().numpy(), keep, budgets[i], RTOL[k.dtype],
@@ -382,3 +409,94 @@ def test_joined_window_full_size_sampled(laq):
     v = torch.randn(n, Hkv, L, d, generator=gen, device=DEV).bfloat16()
     pos = [L - 8 + i for i in range(8)] + [L + i for i in range(8)]
     run_general(laq, q, k, v, [1024, 512, 256, 128], pool, pos, keep, "joined-32k", heads=[3])
+
+
+# ---- stage-1 eviction variants (Sec. 4.2; Sec. 5.1 for the average pool) ----
+def _trailing(L, W):
+    return [L - W + w for w in range(W)]
+
+
+STAGE1_AVG = [
+    # name, dtype, Hq, Hkv, d, L, W, pool, budget
+    ("avg7-llama-like", torch.bfloat16, 8, 2, 128, 1000, 8, 7, 100),
+    ("avg7-two-row-tiles-d64", torch.bfloat16, 16, 2, 64, 1500, 8, 7, 128),
+    ("avg3-fp32-generic", torch.float32, 4, 2, 64, 500, 6, 3, 40),
+    ("avg1-is-raw", torch.bfloat16, 8, 2, 128, 700, 8, 1, 64),
+    ("avg9-prefix-shorter-than-kernel", torch.float32, 2, 1, 32, 12, 8, 9, 10),
+    ("avg63-widest-kernel", torch.bfloat16, 8, 2, 128, 600, 8, 63, 50),
+    ("avg5-budget-equals-window", torch.bfloat16, 8, 2, 128, 300, 8, 5, 8),
+]
+
+
+@pytest.mark.parametrize("name,dtype,Hq,Hkv,d,L,W,pool,budget", STAGE1_AVG, ids=[e[0] for e in STAGE1_AVG])
+def test_stage_one_average_pool(laq, name, dtype, Hq, Hkv, d, L, W, pool, budget):
+    q, k, v = _qkv(len(name) * 31 + L, 2, Hq, Hkv, d, L, W, dtype)
+    run_general(laq, q, k, v, [budget, max(W, budget - 3)], pool, _trailing(L, W), W, name, pool_mode="avg")
+
+
+def test_average_pool_default_layout_matches_explicit_layout_and_differs_from_max(laq):
+    q, k, v = _qkv(12, 1, 8, 2, 128, 900, 8)
+    a = laq.laq_evict(q, k, v, [64], 7, pool_mode="avg")
+    b = laq.laq_evict(q, k, v, [64], 7, q_pos=_trailing(900, 8), keep=8, pool_mode="avg")
+    m = laq.laq_evict(q, k, v, [64], 7)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    assert not torch.equal(a[0], m[0])
+    # the mean of seven non-negative scores never exceeds their maximum
+    assert (a[0][..., :892] <= m[0][..., :892] * (1 + 1e-6)).all()
+
+
+def test_average_pool_full_size_sampled(laq):
+    # stage-1 eviction at the 32k shape: prompt suffix as window, low budget, average pool
+    cfg = CONFIGS[4]
+    n = 2
+    q = torch.empty(n, cfg.Hq, cfg.W, cfg.d, dtype=cfg.torch_dtype, device=DEV)
+    k = torch.empty(n, cfg.Hkv, cfg.L, cfg.d, dtype=cfg.torch_dtype, device=DEV)
+    v = torch.empty_like(k)
+    for i in range(n):
+        qi, ki, vi, _ = make_instance(cfg, 0, i, device=DEV)
+        q[i].copy_(qi); k[i].copy_(ki); v[i].copy_(vi)
+    run_general(laq, q, k, v, [256, 128], cfg.pool, _trailing(cfg.L, cfg.W), cfg.W, "avg-32k", heads=[5],
+                pool_mode="avg")
+
+
+SINKS = [
+    # name, Hkv, L, n_sink, budgets
+    ("four-sinks", 8, 4096, 4, [256, 128, 64]),
+    ("no-sinks", 2, 1000, 0, [100]),
+    ("sinks-fill-the-budget", 2, 1000, 16, [16, 8, 17]),
+    ("budget-beyond-length", 3, 50, 4, [50, 80, 49]),
+    ("single-row", 1, 1, 4, [1]),
+    ("long-rows-many-strides", 2, 40000, 4, [30000, 1]),
+]
+
+
+@pytest.mark.parametrize("name,Hkv,L,n_sink,budgets", SINKS, ids=[e[0] for e in SINKS])
+def test_sink_recent_list_and_compaction(laq, name, Hkv, L, n_sink, budgets):
+    print("case:", name, "Hkv=%d L=%d n_sink=%d budgets=%s" % (Hkv, L, n_sink, budgets), flush=True)
+    n = len(budgets)
+    idx = laq.laq_select_sink_recent(n, Hkv, L, budgets, n_sink, device=DEV)
+    g = torch.Generator().manual_seed(L)
+    k = torch.randn(n, Hkv, L, 64, generator=g).bfloat16().to(DEV)
+    v = torch.randn(n, Hkv, L, 64, generator=g).bfloat16().to(DEV)
+    ko, vo = laq.laq_compact(k, v, idx, budgets, 0)
+    torch.cuda.synchronize()
+    idx_l = split_packed(idx.cpu(), budgets, Hkv, L)
+    ko_l = split_packed(ko.cpu(), budgets, Hkv, L)
+    vo_l = split_packed(vo.cpu(), budgets, Hkv, L)
+    for i in range(n):
+        want = oracle.sink_recent(Hkv, L, n_sink, budgets[i])
+        assert torch.equal(idx_l[i], want), "%s inst %d" % (name, i)
+        assert torch.equal(ko_l[i], oracle.compact(k[i].cpu(), want))
+        assert torch.equal(vo_l[i], oracle.compact(v[i].cpu(), want))
+
+
+def test_sink_recent_more_instances_than_one_launch_holds(laq):
+    n, Hkv, L = 600, 2, 300
+    budgets = [1 + (7 * i) % 320 for i in range(n)]
+    idx = laq.laq_select_sink_recent(n, Hkv, L, budgets, 3, device=DEV)
+    torch.cuda.synchronize()
+    for i, rows in enumerate(split_packed(idx.cpu(), budgets, Hkv, L)):
+        if i % 37 == 0 or i in (255, 256, 511, 512, 599):
+            assert torch.equal(rows, oracle.sink_recent(Hkv, L, 3, budgets[i])), i
