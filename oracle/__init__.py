@@ -52,6 +52,8 @@ def _load() -> ctypes.CDLL:
         lib.laq_oracle_avgpool.restype = c_int
         lib.laq_oracle_sink_recent.argtypes = [c_int, c_int, c_int, c_int, c_vp]
         lib.laq_oracle_sink_recent.restype = c_int
+        lib.laq_oracle_overlap.argtypes = [c_vp, c_int, c_vp, c_int, c_int, c_int, c_vp]
+        lib.laq_oracle_overlap.restype = c_int
         lib.laq_oracle_select.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp]
         lib.laq_oracle_select.restype = c_int
         lib.laq_oracle_compact.argtypes = [c_vp, c_int, c_int, ctypes.c_size_t, c_vp, c_int, c_vp]
@@ -131,6 +133,22 @@ def sink_recent(Hkv: int, L: int, n_sink: int, budget: int) -> torch.Tensor:
     if rc != 0:
         raise ValueError("laq_oracle_sink_recent rejected its arguments")
     return idx
+
+
+def overlap(pred: torch.Tensor, gold: torch.Tensor, L: int) -> torch.Tensor:
+    """Numerator of Eq. 3: pred [Hkv, n_pred], gold [Hkv, n_gold] int32 position lists (no repeats
+    within a row) -> int32 [Hkv] sizes of the row-wise intersections.  Recall = overlap / n_gold."""
+    pred, gold = _cpu(pred), _cpu(gold)
+    if pred.dtype != torch.int32 or gold.dtype != torch.int32 or pred.shape[0] != gold.shape[0]:
+        raise TypeError("overlap takes two int32 lists with the same number of rows")
+    Hkv = pred.shape[0]
+    out = torch.empty(Hkv, dtype=torch.int32)
+    rc = _load().laq_oracle_overlap(pred.data_ptr() if pred.numel() else out.data_ptr(), pred.shape[1],
+                                    gold.data_ptr() if gold.numel() else out.data_ptr(), gold.shape[1],
+                                    Hkv, int(L), out.data_ptr())
+    if rc != 0:
+        raise ValueError("laq_oracle_overlap rejected its arguments")
+    return out
 
 
 def select(scores_f32: torch.Tensor, W: int, budget: int) -> torch.Tensor:

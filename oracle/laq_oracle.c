@@ -45,6 +45,11 @@
  * form keeps the first tokens of the sequence ("sinks") and the most recent
  * ones and needs no scores: laq_oracle_sink_recent.
  *
+ * Recall of a selection (Sec. 3, Eq. 1-3): with M_gold the index set selected
+ * by one set of queries (the response tokens') and M_pred the set selected by
+ * another (an observation window's), Recall = |M_pred ∩ M_gold| / |M_gold| per
+ * KV head: laq_oracle_overlap counts the intersection.
+ *
  * Readings where the paper is silent (softmax before the sum, 1/sqrt(d) scale,
  * max- rather than average-pooling, GQA sum, budget including the window,
  * tie-break) are listed in the design notes of the repository.
@@ -54,7 +59,8 @@
  * the W=1/G=1/pool=1 reduction to ArgSort(q K^T), GQA additivity, key-shift
  * invariance, hand-computed pooling cases, exhaustive top-k, planted keys;
  * the average pool against a library average-pooling routine, its column-sum
- * identity and hand cases; the sink+recent list against set-built brute force.
+ * identity and hand cases; the sink+recent list against set-built brute force;
+ * the overlap count against Python set intersection, its symmetry and extremes.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -209,6 +215,38 @@ int laq_oracle_sink_recent(int Hkv, int L, int n_sink, int budget, int32_t *idx)
         for (int t = 0; t < recent; ++t)
             out[s + t] = L - recent + t;
     }
+    return 0;
+}
+
+/*
+ * Eq. 3's numerator.  pred: [Hkv, n_pred], gold: [Hkv, n_gold], entries in
+ * [0, L), each row without repeats (any order); overlap[g] = number of
+ * positions that row g of pred shares with row g of gold.  The recall of Eq. 3
+ * is overlap[g] / n_gold.
+ */
+int laq_oracle_overlap(const int32_t *pred, int n_pred, const int32_t *gold, int n_gold,
+                       int Hkv, int L, int32_t *overlap)
+{
+    if (!pred || !gold || !overlap || Hkv <= 0 || L <= 0 || n_pred < 0 || n_gold < 0)
+        return -1;
+    unsigned char *in_gold = (unsigned char *)malloc((size_t)L);
+    if (!in_gold) return -1;
+    for (int g = 0; g < Hkv; ++g) {
+        memset(in_gold, 0, (size_t)L);
+        for (int t = 0; t < n_gold; ++t) {
+            int32_t j = gold[(size_t)g * n_gold + t];
+            if (j < 0 || j >= L) { free(in_gold); return -1; }
+            in_gold[j] = 1;
+        }
+        int32_t count = 0;
+        for (int t = 0; t < n_pred; ++t) {
+            int32_t j = pred[(size_t)g * n_pred + t];
+            if (j < 0 || j >= L) { free(in_gold); return -1; }
+            count += in_gold[j];
+        }
+        overlap[g] = count;
+    }
+    free(in_gold);
     return 0;
 }
 

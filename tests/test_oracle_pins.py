@@ -618,3 +618,43 @@ def test_evict_with_average_pool_is_pool_then_select():
     np.testing.assert_allclose(pooled[:, 3:P - 3].numpy(),
                                torch.nn.functional.avg_pool1d(raw[:, :P].unsqueeze(0), 7, stride=1)[0].numpy(),
                                rtol=1e-13)
+
+
+# ----------------------------------------------------------------------------
+# Recall of a selection (Sec. 3, Eq. 1-3): pins of the overlap count
+@pytest.mark.parametrize("seed", range(4))
+def test_overlap_vs_python_sets_and_symmetry(seed):
+    rng = np.random.default_rng(seed)
+    Hkv, L, n_pred, n_gold = 3, 97, 20 + seed, 31
+    pred = np.stack([rng.permutation(L)[:n_pred] for _ in range(Hkv)]).astype(np.int32)
+    gold = np.stack([rng.permutation(L)[:n_gold] for _ in range(Hkv)]).astype(np.int32)
+    got = oracle.overlap(torch.from_numpy(pred), torch.from_numpy(gold), L)
+    want = [len(set(pred[g].tolist()) & set(gold[g].tolist())) for g in range(Hkv)]
+    assert got.tolist() == want
+    assert oracle.overlap(torch.from_numpy(gold), torch.from_numpy(pred), L).tolist() == want
+
+
+def test_overlap_extremes_and_hand_case():
+    a = torch.tensor([[0, 2, 4, 6, 8]], dtype=torch.int32)
+    assert oracle.overlap(a, a, 10).tolist() == [5]                                   # recall 1
+    assert oracle.overlap(a, torch.tensor([[1, 3, 5, 7, 9]], dtype=torch.int32), 10).tolist() == [0]
+    assert oracle.overlap(a, torch.tensor([[8, 7, 2]], dtype=torch.int32), 10).tolist() == [2]
+    assert oracle.overlap(a, torch.arange(10, dtype=torch.int32)[None], 10).tolist() == [5]
+    with pytest.raises(ValueError):
+        oracle.overlap(a, torch.tensor([[10]], dtype=torch.int32), 10)               # position out of range
+
+
+def test_recall_of_a_window_against_all_queries_behaves_as_eq3_says():
+    # M_gold from many queries, M_pred from a subset of them: recall is 1 when the subset is the
+    # whole set and, on this planted instance, stays high for the subset because both see the
+    # planted keys
+    cfg = CONFIGS[1]
+    q, k, _, _ = make_instance(cfg, 0, 0)
+    L = cfg.L
+    see_all = [L] * cfg.W
+    gold = oracle.select(oracle.maxpool(oracle.raw_scores(q, k, q_pos=see_all), 0, 7).float(), 0, 64)
+    pred_all = oracle.select(oracle.maxpool(oracle.raw_scores(q, k, q_pos=see_all), 0, 7).float(), 0, 64)
+    assert oracle.overlap(pred_all, gold, L).tolist() == [64] * cfg.Hkv
+    pred_half = oracle.select(oracle.maxpool(oracle.raw_scores(q[:, :4], k, q_pos=see_all[:4]), 0, 7).float(), 0, 64)
+    ov = oracle.overlap(pred_half, gold, L)
+    assert (ov >= 32).all() and (ov <= 64).all()
