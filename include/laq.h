@@ -137,6 +137,22 @@ int laq_select_sink_recent(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t
                            int32_t n_sink, int32_t *idx, void *stream);
 
 /*
+ * Recall of one selection against another (Sec. 3, Eq. 1-3): with M_gold the positions selected
+ * by one set of queries (the response tokens') and M_pred those selected by another (an
+ * observation window's), Recall = |M_pred ∩ M_gold| / |M_gold| per KV head.
+ *   idx_pred, budget_pred   a packed index list and the HOST budget array it was made with
+ *   idx_gold, budget_gold   the same for the reference selection; budgets >= 1
+ *   Both lists as laq_select / laq_select_sink_recent write them: every row ascending, no
+ *   repeats (rows that are not ascending give an undefined count, nothing else).
+ *   overlap  int32 out [n_inst, Hkv]: size of the intersection
+ *   recall   fp32 out [n_inst, Hkv], may be NULL: overlap / min(budget_gold[i], L)
+ * Takes plain sizes: n_inst, Hkv, L >= 1, Hkv <= 65535.  Uses no workspace.
+ */
+int laq_recall(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t *idx_pred,
+               const int32_t *budget_pred, const int32_t *idx_gold, const int32_t *budget_gold,
+               int32_t *overlap, float *recall, void *stream);
+
+/*
  * Cache compaction: gather the retained rows.
  *   k, v         [n_inst, Hkv, L, d]; v (and v_out) may be NULL to compact K only
  *   idx, budget  as written by / passed to laq_select

@@ -57,6 +57,9 @@ def load_library() -> ctypes.CDLL:
     lib.laq_select.restype = i32
     lib.laq_select_sink_recent.argtypes = [i32, i32, i32, ctypes.POINTER(ctypes.c_int32), i32, vp, vp]
     lib.laq_select_sink_recent.restype = i32
+    bp = ctypes.POINTER(ctypes.c_int32)
+    lib.laq_recall.argtypes = [i32, i32, i32, vp, bp, vp, bp, vp, vp, vp]
+    lib.laq_recall.restype = i32
     lib.laq_compact.argtypes = [sp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp, vp, vp]
     lib.laq_compact.restype = i32
     lib.laq_evict.argtypes = [sp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), i32, vp, vp, vp, vp, vp, sz, vp]
@@ -201,6 +204,29 @@ def laq_select_sink_recent(n_inst: int, Hkv: int, L: int, budget: Sequence[int],
     if rc != 0:
         raise LaqError(rc, "laq_select_sink_recent")
     return idx
+
+
+def laq_recall(idx_pred: torch.Tensor, budget_pred: Sequence[int], idx_gold: torch.Tensor,
+               budget_gold: Sequence[int], Hkv: int, L: int, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Two packed index lists (as laq_select writes them) -> (overlap int32 [n, Hkv], recall fp32
+    [n, Hkv]) with recall = |pred ∩ gold| / |gold| per KV head."""
+    lib = load_library()
+    _dev(idx_pred, "idx_pred"), _dev(idx_gold, "idx_gold")
+    n = len(budget_pred)
+    if len(budget_gold) != n:
+        raise ValueError("the two budget arrays need one entry per instance each")
+    if idx_pred.dtype != torch.int32 or idx_gold.dtype != torch.int32:
+        raise TypeError("index lists are int32")
+    if idx_pred.numel() < packed_rows(budget_pred, Hkv, L)[0] or idx_gold.numel() < packed_rows(budget_gold, Hkv, L)[0]:
+        raise ValueError("an index list is shorter than its budgets say")
+    overlap = torch.empty(n, Hkv, dtype=torch.int32, device=idx_pred.device)
+    recall = torch.empty(n, Hkv, dtype=torch.float32, device=idx_pred.device)
+    rc = lib.laq_recall(n, int(Hkv), int(L), idx_pred.data_ptr(), _budget_array(budget_pred, n),
+                        idx_gold.data_ptr(), _budget_array(budget_gold, n), overlap.data_ptr(), recall.data_ptr(),
+                        _stream(stream))
+    if rc != 0:
+        raise LaqError(rc, "laq_recall")
+    return overlap, recall
 
 
 def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, budget: Sequence[int], keep: int,

@@ -177,6 +177,32 @@ static int sink_recent_impl(int n_inst, int Hkv, int L, const int32_t* budget, i
   return LAQ_OK;
 }
 
+static int recall_impl(int n_inst, int Hkv, int L, const int32_t* idx_pred, const int32_t* budget_pred,
+                       const int32_t* idx_gold, const int32_t* budget_gold, int32_t* overlap, float* recall,
+                       hipStream_t st) {
+  if (n_inst < 1 || Hkv < 1 || L < 1 || !idx_pred || !budget_pred || !idx_gold || !budget_gold || !overlap)
+    return LAQ_ERR_INVALID;
+  for (int i = 0; i < n_inst; ++i)
+    if (budget_pred[i] < 1 || budget_gold[i] < 1) return LAQ_ERR_INVALID;
+  if (Hkv > 65535) return LAQ_ERR_UNSUPPORTED;
+  int64_t row_a = 0, row_b = 0;
+  for (int i0 = 0; i0 < n_inst; i0 += MAX_PAIR_PER_LAUNCH) {
+    const int n = n_inst - i0 < MAX_PAIR_PER_LAUNCH ? n_inst - i0 : MAX_PAIR_PER_LAUNCH;
+    PairTable tab;
+    memset(&tab, 0, sizeof tab);
+    for (int i = 0; i < n; ++i) {
+      tab.bk_a[i] = budget_pred[i0 + i] < L ? budget_pred[i0 + i] : L;
+      tab.bk_b[i] = budget_gold[i0 + i] < L ? budget_gold[i0 + i] : L;
+      tab.row_a[i] = row_a;
+      tab.row_b[i] = row_b;
+      row_a += (int64_t)Hkv * tab.bk_a[i];
+      row_b += (int64_t)Hkv * tab.bk_b[i];
+    }
+    if (launch_recall(n, i0, Hkv, tab, idx_pred, idx_gold, overlap, recall, st) != hipSuccess) return LAQ_ERR_DEVICE;
+  }
+  return LAQ_OK;
+}
+
 }  // namespace laq
 
 extern "C" {
@@ -200,6 +226,12 @@ int laq_select(const laq_shape* shape, const float* scores, const int32_t* budge
 int laq_select_sink_recent(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t* budget, int32_t n_sink,
                            int32_t* idx, void* stream) {
   return laq::sink_recent_impl(n_inst, Hkv, L, budget, n_sink, idx, static_cast<hipStream_t>(stream));
+}
+
+int laq_recall(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t* idx_pred, const int32_t* budget_pred,
+               const int32_t* idx_gold, const int32_t* budget_gold, int32_t* overlap, float* recall, void* stream) {
+  return laq::recall_impl(n_inst, Hkv, L, idx_pred, budget_pred, idx_gold, budget_gold, overlap, recall,
+                          static_cast<hipStream_t>(stream));
 }
 
 int laq_compact(const laq_shape* shape, const void* k, const void* v, const int32_t* idx,

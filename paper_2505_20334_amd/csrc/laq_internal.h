@@ -87,6 +87,13 @@ __device__ __forceinline__ float pool_window(const float* __restrict__ s, int po
   return v;
 }
 
+// Two packed index lists side by side, for up to MAX_PAIR_PER_LAUNCH instances.
+constexpr int MAX_PAIR_PER_LAUNCH = 128;
+struct PairTable {
+  int32_t bk_a[MAX_PAIR_PER_LAUNCH], bk_b[MAX_PAIR_PER_LAUNCH];       // row lengths
+  int64_t row_a[MAX_PAIR_PER_LAUNCH], row_b[MAX_PAIR_PER_LAUNCH];     // first packed row of the instance
+};
+
 // launchers (each returns hipGetLastError() after its last launch); `raw` receives unpooled scores
 hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, int dtype, const void* q, const void* k,
                                 float* raw, const Workspace& ws, hipStream_t st);
@@ -99,6 +106,8 @@ hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int keep, int po
                          const InstTable& tab, int32_t* idx, hipStream_t st);
 hipError_t launch_sink_recent(int n_inst, int Hkv, int L, int n_sink, const InstTable& tab, int32_t* idx,
                               hipStream_t st);
+hipError_t launch_recall(int n_inst, int inst0, int Hkv, const PairTable& tab, const int32_t* idx_pred,
+                         const int32_t* idx_gold, int32_t* overlap, float* recall, hipStream_t st);
 hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, int bk_max, const void* k,
                           const void* v, const int32_t* idx, const InstTable& tab, void* k_out, void* v_out,
                           hipStream_t st);

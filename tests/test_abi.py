@@ -20,7 +20,7 @@ def declared_functions(repo_root):
 def test_library_exports_every_declared_symbol(repo_root):
     lib = laq.load_library()
     names = declared_functions(repo_root)
-    assert names == ["laq_compact", "laq_evict", "laq_score", "laq_select", "laq_select_sink_recent",
+    assert names == ["laq_compact", "laq_evict", "laq_recall", "laq_score", "laq_select", "laq_select_sink_recent",
                      "laq_strerror", "laq_workspace_bytes"]
     for n in names:
         assert getattr(lib, n) is not None
@@ -129,6 +129,13 @@ def test_stage_one_variants_are_checked_without_a_gpu():
     assert lib.laq_select_sink_recent(1, 70000, 512, bud, 4, fake, None) == UNSUPPORTED
     with pytest.raises(ValueError):
         binding._shape(1, 8, 2, 128, 512, 8, 1, 0.0, pool_mode="median")
+    # recall of two lists: rejected before anything is launched
+    assert lib.laq_recall(0, 2, 512, fake, bud, fake, bud, fake, None, None) == INVALID
+    assert lib.laq_recall(1, 2, 512, None, bud, fake, bud, fake, None, None) == INVALID
+    assert lib.laq_recall(1, 2, 512, fake, bud, fake, None, fake, None, None) == INVALID
+    assert lib.laq_recall(1, 2, 512, fake, bud, fake, bud, None, None, None) == INVALID
+    assert lib.laq_recall(1, 2, 512, fake, (ctypes.c_int32 * 1)(0), fake, bud, fake, None, None) == INVALID
+    assert lib.laq_recall(1, 70000, 512, fake, bud, fake, bud, fake, None, None) == UNSUPPORTED
 
 
 def test_packed_rows():

@@ -500,3 +500,76 @@ def test_sink_recent_more_instances_than_one_launch_holds(laq):
     for i, rows in enumerate(split_packed(idx.cpu(), budgets, Hkv, L)):
         if i % 37 == 0 or i in (255, 256, 511, 512, 599):
             assert torch.equal(rows, oracle.sink_recent(Hkv, L, 3, budgets[i])), i
+
+
+# ---- recall of one selection against another (Sec. 3, Eq. 1-3) ----
+def _random_lists(seed, n, Hkv, L, budgets):
+    rng = np.random.default_rng(seed)
+    rows = []
+    for b in budgets:
+        bk = min(b, L)
+        rows.append(np.stack([np.sort(rng.permutation(L)[:bk]) for _ in range(Hkv)]).astype(np.int32))
+    return rows
+
+
+RECALL = [
+    # name, Hkv, L, pred budgets, gold budgets
+    ("equal-budgets", 4, 1000, [64, 128, 7], [64, 128, 7]),
+    ("different-budgets", 2, 500, [50, 500, 1], [80, 20, 499]),
+    ("budget-beyond-length", 2, 40, [100, 40], [39, 100]),
+    ("long-lists", 2, 40000, [30000, 2048], [2048, 30000]),
+    ("single-position", 1, 1, [1], [1]),
+]
+
+
+@pytest.mark.parametrize("name,Hkv,L,bp,bg", RECALL, ids=[e[0] for e in RECALL])
+def test_recall_of_random_lists(laq, name, Hkv, L, bp, bg):
+    print("case:", name, "Hkv=%d L=%d pred=%s gold=%s" % (Hkv, L, bp, bg), flush=True)
+    n = len(bp)
+    pred = _random_lists(len(name), n, Hkv, L, bp)
+    gold = _random_lists(len(name) + 1000, n, Hkv, L, bg)
+    p_dev = torch.from_numpy(np.concatenate([r.reshape(-1) for r in pred])).to(DEV)
+    g_dev = torch.from_numpy(np.concatenate([r.reshape(-1) for r in gold])).to(DEV)
+    overlap, recall = laq.laq_recall(p_dev, bp, g_dev, bg, Hkv, L)
+    same, one = laq.laq_recall(g_dev, bg, g_dev, bg, Hkv, L)
+    torch.cuda.synchronize()
+    for i in range(n):
+        want = oracle.overlap(torch.from_numpy(pred[i]), torch.from_numpy(gold[i]), L)
+        assert torch.equal(overlap[i].cpu(), want), "%s inst %d" % (name, i)
+        np.testing.assert_array_equal(recall[i].cpu().numpy(),
+                                      (want.float() / np.float32(min(bg[i], L))).numpy())
+        assert same[i].cpu().tolist() == [min(bg[i], L)] * Hkv and one[i].cpu().tolist() == [1.0] * Hkv
+
+
+def test_recall_more_instances_than_one_launch_holds(laq):
+    n, Hkv, L = 300, 2, 200
+    bp = [1 + (11 * i) % 210 for i in range(n)]
+    bg = [1 + (7 * i) % 190 for i in range(n)]
+    pred, gold = _random_lists(1, n, Hkv, L, bp), _random_lists(2, n, Hkv, L, bg)
+    p_dev = torch.from_numpy(np.concatenate([r.reshape(-1) for r in pred])).to(DEV)
+    g_dev = torch.from_numpy(np.concatenate([r.reshape(-1) for r in gold])).to(DEV)
+    overlap, _ = laq.laq_recall(p_dev, bp, g_dev, bg, Hkv, L)
+    torch.cuda.synchronize()
+    for i in list(range(0, n, 23)) + [127, 128, 255, 256, 299]:
+        assert torch.equal(overlap[i].cpu(), oracle.overlap(torch.from_numpy(pred[i]), torch.from_numpy(gold[i]), L)), i
+
+
+def test_recall_of_the_window_selection_against_the_selection_by_all_queries(laq):
+    # Eq. 1-3 end to end on the library's own selections: M_pred from the first 8 queries, M_gold
+    # from all 32 (every query placed after the prompt), 4k keys
+    q, k, v = _qkv(21, 2, 32, 8, 128, 4096, 32)
+    L, budgets = 4096, [256, 128]
+    see_all = [L] * 32
+    gold = laq.laq_evict(q, k, v, budgets, 7, q_pos=see_all, keep=0)[1]
+    pred = laq.laq_evict(q[:, :, :8].contiguous(), k, v, budgets, 7, q_pos=see_all[:8], keep=0)[1]
+    sinks = laq.laq_select_sink_recent(2, 8, L, budgets, 4, device=DEV)
+    ov, rec = laq.laq_recall(pred, budgets, gold, budgets, 8, L)
+    ov_s, rec_s = laq.laq_recall(sinks, budgets, gold, budgets, 8, L)
+    torch.cuda.synchronize()
+    pl, gl, sl = (split_packed(x.cpu(), budgets, 8, L) for x in (pred, gold, sinks))
+    for i in range(2):
+        assert torch.equal(ov[i].cpu(), oracle.overlap(pl[i], gl[i], L))
+        assert torch.equal(ov_s[i].cpu(), oracle.overlap(sl[i], gl[i], L))
+    assert (rec > 0).all() and (rec <= 1).all()
+    # scored selections agree far more with the reference than the score-free list does
+    assert rec.mean().item() > rec_s.mean().item()
