@@ -54,6 +54,11 @@ def _load() -> ctypes.CDLL:
         lib.laq_oracle_sink_recent.restype = c_int
         lib.laq_oracle_overlap.argtypes = [c_vp, c_int, c_vp, c_int, c_int, c_int, c_vp]
         lib.laq_oracle_overlap.restype = c_int
+        lib.laq_oracle_decode_attention.argtypes = [c_vp, c_vp, c_vp, c_int, c_int, c_int, c_int, c_int,
+                                                    ctypes.c_double, c_vp]
+        lib.laq_oracle_decode_attention.restype = c_int
+        lib.laq_oracle_qcache_store.argtypes = [c_vp, c_int, c_int, c_int, ctypes.c_size_t, c_int, c_vp]
+        lib.laq_oracle_qcache_store.restype = c_int
         lib.laq_oracle_select.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp]
         lib.laq_oracle_select.restype = c_int
         lib.laq_oracle_compact.argtypes = [c_vp, c_int, c_int, ctypes.c_size_t, c_vp, c_int, c_vp]
@@ -148,6 +153,35 @@ def overlap(pred: torch.Tensor, gold: torch.Tensor, L: int) -> torch.Tensor:
                                     Hkv, int(L), out.data_ptr())
     if rc != 0:
         raise ValueError("laq_oracle_overlap rejected its arguments")
+    return out
+
+
+def decode_attention(q: torch.Tensor, kc: torch.Tensor, vc: torch.Tensor, scale: float = 0.0) -> torch.Tensor:
+    """Single-token attention over a compacted cache (Sec. 4.3): q [Hq, d], kc / vc [Hkv, Bk, d]
+    -> out [Hq, d] fp64."""
+    q, kc, vc = _cpu(q), _cpu(kc), _cpu(vc)
+    if not (q.dtype == kc.dtype == vc.dtype) or kc.shape != vc.shape:
+        raise TypeError("q, kc, vc share a dtype and kc, vc a shape")
+    Hq, d = q.shape
+    Hkv, Bk, _ = kc.shape
+    out = torch.empty(Hq, d, dtype=torch.float64)
+    rc = _load().laq_oracle_decode_attention(q.data_ptr(), kc.data_ptr(), vc.data_ptr(), _dtype_code(kc),
+                                             Hq, Hkv, d, Bk, float(scale), out.data_ptr())
+    if rc != 0:
+        raise ValueError("laq_oracle_decode_attention rejected its arguments")
+    return out
+
+
+def qcache_store(q_cache: torch.Tensor, q_step: torch.Tensor, t: int) -> torch.Tensor:
+    """Q-cache capture (Sec. 4.2): returns a copy of q_cache [Hq, W, d] whose row t holds q_step [Hq, d]."""
+    q_step = _cpu(q_step)
+    out = _cpu(q_cache).clone()
+    Hq, W, d = out.shape
+    if q_step.shape != (Hq, d) or q_step.dtype != out.dtype:
+        raise TypeError("q_step is [Hq, d] in the cache's dtype")
+    rc = _load().laq_oracle_qcache_store(q_step.data_ptr(), Hq, W, d, out.element_size(), int(t), out.data_ptr())
+    if rc != 0:
+        raise ValueError("laq_oracle_qcache_store rejected its arguments")
     return out
 
 

@@ -50,6 +50,14 @@
  * another (an observation window's), Recall = |M_pred ∩ M_gold| / |M_gold| per
  * KV head: laq_oracle_overlap counts the intersection.
  *
+ * The step after the path (Sec. 4.3: after the re-eviction, generation goes on
+ * as standard autoregressive decoding): one new token's query attends to the
+ * retained rows of its KV head, out[h] = softmax_j(scale <q_h, K'_j>) V' with
+ * KV head h / G and no mask (every retained key precedes the new token):
+ * laq_oracle_decode_attention.  The step before it (Sec. 4.2: the lookahead
+ * decoding keeps its query states as the Q-cache) is a plain store of the
+ * step's queries into slot t of the cache: laq_oracle_qcache_store.
+ *
  * Readings where the paper is silent (softmax before the sum, 1/sqrt(d) scale,
  * max- rather than average-pooling, GQA sum, budget including the window,
  * tie-break) are listed in the design notes of the repository.
@@ -60,7 +68,10 @@
  * invariance, hand-computed pooling cases, exhaustive top-k, planted keys;
  * the average pool against a library average-pooling routine, its column-sum
  * identity and hand cases; the sink+recent list against set-built brute force;
- * the overlap count against Python set intersection, its symmetry and extremes.
+ * the overlap count against Python set intersection, its symmetry and extremes;
+ * decode attention against a library softmax-and-matmul, the mean of V for
+ * identical keys, a dominant key, GQA head mapping; the Q-cache store against
+ * tensor indexing.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -247,6 +258,64 @@ int laq_oracle_overlap(const int32_t *pred, int n_pred, const int32_t *gold, int
         overlap[g] = count;
     }
     free(in_gold);
+    return 0;
+}
+
+/*
+ * Single-token attention over a compacted cache (Sec. 4.3, the decoding that
+ * follows the re-eviction).  q: [Hq, d], kc, vc: [Hkv, Bk, d] in `dtype`;
+ * out: [Hq, d] doubles.  Query head h uses KV head h / (Hq / Hkv).
+ * scale <= 0 selects 1/sqrt(d).
+ */
+int laq_oracle_decode_attention(const void *q, const void *kc, const void *vc, int dtype,
+                                int Hq, int Hkv, int d, int Bk, double scale, double *out)
+{
+    if (!q || !kc || !vc || !out || Hq <= 0 || Hkv <= 0 || d <= 0 || Bk <= 0 || Hq % Hkv != 0 ||
+        (dtype != ORACLE_F32 && dtype != ORACLE_BF16))
+        return -1;
+    const int G = Hq / Hkv;
+    if (scale <= 0.0)
+        scale = 1.0 / sqrt((double)d);
+    double *p = (double *)malloc(sizeof(double) * (size_t)Bk);
+    if (!p) return -1;
+    for (int h = 0; h < Hq; ++h) {
+        const int g = h / G;
+        double M = -INFINITY;
+        for (int j = 0; j < Bk; ++j) {
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c)
+                acc += load_elem(q, dtype, (size_t)h * d + c) * load_elem(kc, dtype, ((size_t)g * Bk + j) * d + c);
+            p[j] = scale * acc;
+            if (p[j] > M) M = p[j];
+        }
+        double Z = 0.0;
+        for (int j = 0; j < Bk; ++j) {
+            p[j] = exp(p[j] - M);
+            Z += p[j];
+        }
+        for (int c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int j = 0; j < Bk; ++j)
+                acc += p[j] * load_elem(vc, dtype, ((size_t)g * Bk + j) * d + c);
+            out[(size_t)h * d + c] = acc / Z;
+        }
+    }
+    free(p);
+    return 0;
+}
+
+/*
+ * Q-cache capture (Sec. 4.2): the queries of lookahead step t, q_step [Hq, d],
+ * become row t of every head of the Q-cache [Hq, W, d]; elem_bytes is the
+ * element size.  A byte copy.
+ */
+int laq_oracle_qcache_store(const void *q_step, int Hq, int W, int d, size_t elem_bytes, int t, void *q_cache)
+{
+    if (!q_step || !q_cache || Hq <= 0 || W <= 0 || d <= 0 || t < 0 || t >= W || elem_bytes == 0)
+        return -1;
+    const size_t row = (size_t)d * elem_bytes;
+    for (int h = 0; h < Hq; ++h)
+        memcpy((char *)q_cache + ((size_t)h * W + t) * row, (const char *)q_step + (size_t)h * row, row);
     return 0;
 }
 

@@ -658,3 +658,71 @@ def test_recall_of_a_window_against_all_queries_behaves_as_eq3_says():
     pred_half = oracle.select(oracle.maxpool(oracle.raw_scores(q[:, :4], k, q_pos=see_all[:4]), 0, 7).float(), 0, 64)
     ov = oracle.overlap(pred_half, gold, L)
     assert (ov >= 32).all() and (ov <= 64).all()
+
+
+# ----------------------------------------------------------------------------
+# Decoding on the compacted cache (Sec. 4.3) and Q-cache capture (Sec. 4.2): pins
+@pytest.mark.parametrize("Hq,Hkv,d,Bk,dtype", [(4, 2, 16, 9, torch.float32), (8, 2, 64, 130, torch.bfloat16),
+                                               (3, 3, 8, 1, torch.float32), (6, 1, 32, 40, torch.bfloat16)])
+def test_decode_attention_vs_library_softmax_matmul(Hq, Hkv, d, Bk, dtype):
+    g = torch.Generator().manual_seed(Hq * 100 + Bk)
+    q = torch.randn(Hq, d, generator=g).to(dtype)
+    kc = torch.randn(Hkv, Bk, d, generator=g).to(dtype)
+    vc = torch.randn(Hkv, Bk, d, generator=g).to(dtype)
+    got = oracle.decode_attention(q, kc, vc)
+    G = Hq // Hkv
+    kk = kc.double().repeat_interleave(G, dim=0)                 # [Hq, Bk, d]: head h -> KV head h // G
+    vv = vc.double().repeat_interleave(G, dim=0)
+    p = torch.softmax(torch.einsum("hd,hjd->hj", q.double(), kk) / math.sqrt(d), dim=1)
+    want = torch.einsum("hj,hjd->hd", p, vv)
+    np.testing.assert_allclose(got.numpy(), want.numpy(), rtol=1e-11, atol=1e-13)
+    lib = torch.nn.functional.scaled_dot_product_attention(q.double()[:, None, :], kk, vv)[:, 0]
+    np.testing.assert_allclose(got.numpy(), lib.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_decode_attention_closed_forms():
+    g = torch.Generator().manual_seed(3)
+    q = torch.randn(4, 16, generator=g)
+    vc = torch.randn(2, 7, 16, generator=g)
+    same = torch.randn(2, 1, 16, generator=g).expand(2, 7, 16).contiguous()
+    got = oracle.decode_attention(q, same, vc)                   # identical keys: the mean of V
+    np.testing.assert_allclose(got[:2].numpy(), vc[0].double().mean(0).expand(2, 16).numpy(), rtol=1e-12)
+    np.testing.assert_allclose(got[2:].numpy(), vc[1].double().mean(0).expand(2, 16).numpy(), rtol=1e-12)
+    kc = torch.zeros(2, 7, 16)
+    kc[0, 3] = q[0] * 50.0                                       # one dominant key for head 0
+    got = oracle.decode_attention(q, kc, vc, scale=1.0)
+    np.testing.assert_allclose(got[0].numpy(), vc[0, 3].double().numpy(), rtol=1e-9, atol=1e-12)
+    # explicit scale is used: zero keys give uniform weights whatever the scale
+    got0 = oracle.decode_attention(q, torch.zeros(2, 7, 16), vc, scale=3.0)
+    np.testing.assert_allclose(got0[3].numpy(), vc[1].double().mean(0).numpy(), rtol=1e-12)
+    # permuting the retained rows (keys and values together) changes nothing
+    perm = torch.randperm(7, generator=g)
+    kr = torch.randn(2, 7, 16, generator=g)
+    a = oracle.decode_attention(q, kr, vc)
+    b = oracle.decode_attention(q, kr[:, perm].contiguous(), vc[:, perm].contiguous())
+    np.testing.assert_allclose(a.numpy(), b.numpy(), rtol=1e-12, atol=1e-14)
+    # extreme logits stay finite
+    big = oracle.decode_attention(q * 1e3, kr * 1e3, vc, scale=1.0)
+    assert np.isfinite(big.numpy()).all()
+
+
+def test_qcache_store_is_tensor_indexing():
+    g = torch.Generator().manual_seed(9)
+    cache = torch.randn(6, 8, 32, generator=g).bfloat16()
+    step = torch.randn(6, 32, generator=g).bfloat16()
+    for t in (0, 3, 7):
+        want = cache.clone()
+        want[:, t] = step
+        assert torch.equal(oracle.qcache_store(cache, step, t), want)
+    with pytest.raises(ValueError):
+        oracle.qcache_store(cache, step, 8)
+
+
+def test_eight_lookahead_steps_fill_the_qcache_that_scoring_reads():
+    # the Q-cache built step by step is the q_win tensor the re-eviction takes
+    g = torch.Generator().manual_seed(10)
+    steps = [torch.randn(4, 16, generator=g) for _ in range(8)]
+    cache = torch.zeros(4, 8, 16)
+    for t, s in enumerate(steps):
+        cache = oracle.qcache_store(cache, s, t)
+    assert torch.equal(cache, torch.stack(steps, dim=1))
