@@ -46,6 +46,70 @@ def read_traffic(workload):
     return None
 
 
+def bench_decode(args, torch, laq, cfg, budgets, dev):
+    """One new token per instance attends to its compacted cache (packed K', V' of the config's budgets)."""
+    n, dt = cfg.n_inst, cfg.torch_dtype
+    total, _ = laq.packed_rows(budgets, cfg.Hkv, cfg.L)
+    gen = torch.Generator(device=dev).manual_seed(1234)
+    kc = torch.randn(total, cfg.d, generator=gen, device=dev).to(dt)
+    vc = torch.randn(total, cfg.d, generator=gen, device=dev).to(dt)
+    q = torch.randn(n, cfg.Hq, cfg.d, generator=gen, device=dev).to(dt)
+    out_t = torch.empty(n, cfg.Hq, cfg.d, dtype=torch.float32, device=dev)
+
+    def step():
+        laq.laq_decode_attention(q, kc, vc, budgets, cfg.Hkv, cfg.L, out=out_t)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    reps = max(3, min(args.steps, 20))
+    ev[0].record()
+    for _ in range(reps):
+        step()
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms_kernel = ev[0].elapsed_time(ev[1]) / reps
+    ab = 2 * total * cfg.d * cfg.elem_bytes + q.numel() * cfg.elem_bytes + out_t.numel() * 4
+    achieved = ab / (ms_kernel * 1e-3) / 1e9
+    workload = cfg.name + "+decode"
+    out = {
+        "metric": "retained key-tokens attended/sec per layer (all heads)",
+        "value": round(total / cfg.Hkv / (ms_per_step * 1e-3), 1), "unit": "key-tokens/s/layer", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": workload, "cfg_id": cfg.cfg_id, "instances": n, "Hq": cfg.Hq, "Hkv": cfg.Hkv,
+                   "d": cfg.d, "L": cfg.L, "budget": cfg.budget, "packed_rows": total},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(workload),
+                     "kernel": "decode_kernel (K' and V' rows read once, q read, out written)",
+                     "algorithmic_bytes_per_launch": ab, "ms_per_launch": round(ms_kernel, 4)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        ids = list(range(n))                 # the oracle needs well under a second per instance here
+        _, starts = laq.packed_rows(budgets, cfg.Hkv, cfg.L)
+        t_cpu, rows = 0.0, 0
+        for i in ids:
+            bk = min(budgets[i], cfg.L)
+            ki = kc[starts[i]:starts[i] + cfg.Hkv * bk].reshape(cfg.Hkv, bk, cfg.d).cpu()
+            vi = vc[starts[i]:starts[i] + cfg.Hkv * bk].reshape(cfg.Hkv, bk, cfg.d).cpu()
+            qi = q[i].cpu()
+            c0 = time.perf_counter()
+            oracle.decode_attention(qi, ki, vi)
+            t_cpu += time.perf_counter() - c0
+            rows += bk
+        out["cpu_baseline"] = {"value": round(rows / t_cpu, 1), "unit": "key-tokens/s/layer", "cores": 1,
+                               "kind": "oracle", "sample": "all %d instances, %.2f s" % (n, t_cpu)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,7 +117,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="workload: index into BASELINE.json configs (1-based)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-instances", type=int, default=2)
+    ap.add_argument("--cpu-instances", type=int, default=5,
+                    help="instances the CPU oracle is timed on (spread over the layers; about 2-5 s each)")
+    ap.add_argument("--path", choices=["evict", "decode"], default="evict",
+                    help="evict (default): the re-eviction hot path, the headline workload; decode: one new "
+                         "token's attention over the compacted cache of the same config (Sec. 4.3)")
     ap.add_argument("--window", choices=["trailing", "lookahead", "joined"], default="trailing",
                     help="observation window: the config's trailing window (default, the headline workload); "
                          "8 lookahead queries that see every key, nothing kept (Eq. 4); or 8 local window "
@@ -84,6 +152,8 @@ def main():
     cfg = CONFIGS[args.config]
     budgets = budgets_for(cfg)
     n = cfg.n_inst
+    if args.path == "decode":
+        return bench_decode(args, torch, laq, cfg, budgets, dev)
     q_pos, keep, workload = None, None, cfg.name
     if args.window != "trailing":
         import dataclasses
@@ -177,8 +247,8 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
-        ids = sorted(set([0, n - 1][:args.cpu_instances])) if args.cpu_instances <= 2 else \
-            list(range(min(args.cpu_instances, n)))
+        m = max(1, min(args.cpu_instances, n))
+        ids = sorted(set(round(i * (n - 1) / max(m - 1, 1)) for i in range(m)))      # spread over the layers
         t_cpu = 0.0
         for i in ids:
             qi, ki, vi = q[i].cpu(), k[i].cpu(), v[i].cpu()

@@ -172,6 +172,32 @@ int laq_evict(const laq_shape *shape, const void *q_win, const void *k, const vo
               const int32_t *budget, int pool_kernel, float *scores, int32_t *idx,
               void *k_out, void *v_out, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Q-cache capture (Sec. 4.2: the lookahead decoding keeps its query states): store the queries of
+ * lookahead step t into the Q-cache that laq_score later reads as q_win.
+ *   q_step  [n_inst, Hq, d]     queries of the step, dtype shape->dtype
+ *   t       0 <= t < shape->W   slot of the step
+ *   q_cache [n_inst, Hq, W, d]  rows [.., t, :] are overwritten, the others left alone
+ * Reads n_inst, Hq, d, W, dtype of the shape (the remaining fields must still be valid).
+ */
+int laq_qcache_store(const laq_shape *shape, const void *q_step, int32_t t, void *q_cache,
+                     void *stream);
+
+/*
+ * Decoding on the compacted cache (Sec. 4.3: after the re-eviction, generation continues as
+ * standard autoregressive decoding): attention of one new token per instance over the retained
+ * rows, out[h] = softmax_j(scale * <q[h], K'[h/G, j]>) V'[h/G], no mask (every retained key
+ * precedes the new token).
+ *   q          [n_inst, Hq, d]  dtype shape->dtype
+ *   k_c, v_c   packed as laq_compact writes them: instance i holds [Hkv, Bk(i), d]
+ *   budget     HOST array [n_inst], >= 1; Bk(i) = min(budget[i], L)
+ *   out        fp32 [n_inst, Hq, d]
+ * Reads n_inst, Hq, Hkv, d, L, dtype, scale of the shape.  Uses no workspace.  The merge of
+ * partial sums follows a fixed order: two runs give identical bits.
+ */
+int laq_decode_attention(const laq_shape *shape, const void *q, const void *k_c, const void *v_c,
+                         const int32_t *budget, float *out, void *stream);
+
 /* Static description of an error code. */
 const char *laq_strerror(int code);
 

@@ -58,6 +58,10 @@ def load_library() -> ctypes.CDLL:
     lib.laq_select_sink_recent.argtypes = [i32, i32, i32, ctypes.POINTER(ctypes.c_int32), i32, vp, vp]
     lib.laq_select_sink_recent.restype = i32
     bp = ctypes.POINTER(ctypes.c_int32)
+    lib.laq_decode_attention.argtypes = [sp, vp, vp, vp, bp, vp, vp]
+    lib.laq_decode_attention.restype = i32
+    lib.laq_qcache_store.argtypes = [sp, vp, i32, vp, vp]
+    lib.laq_qcache_store.restype = i32
     lib.laq_recall.argtypes = [i32, i32, i32, vp, bp, vp, bp, vp, vp, vp]
     lib.laq_recall.restype = i32
     lib.laq_compact.argtypes = [sp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), vp, vp, vp]
@@ -227,6 +231,41 @@ def laq_recall(idx_pred: torch.Tensor, budget_pred: Sequence[int], idx_gold: tor
     if rc != 0:
         raise LaqError(rc, "laq_recall")
     return overlap, recall
+
+
+def laq_qcache_store(q_cache: torch.Tensor, q_step: torch.Tensor, t: int, stream=None) -> torch.Tensor:
+    """q_cache [n, Hq, W, d] (updated in place: rows [.., t, :] = q_step [n, Hq, d]); returns q_cache."""
+    lib = load_library()
+    _dev(q_cache, "q_cache"), _dev(q_step, "q_step")
+    n, Hq, W, d = q_cache.shape
+    if q_step.shape != (n, Hq, d) or q_step.dtype != q_cache.dtype:
+        raise ValueError("q_step is [n, Hq, d] in the cache's dtype")
+    sh = _shape(n, Hq, Hq, d, max(W, 1), W, _dtype_code(q_cache), 0.0, None, 0)
+    rc = lib.laq_qcache_store(ctypes.byref(sh), q_step.data_ptr(), int(t), q_cache.data_ptr(), _stream(stream))
+    if rc != 0:
+        raise LaqError(rc, "laq_qcache_store")
+    return q_cache
+
+
+def laq_decode_attention(q: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, budget: Sequence[int],
+                         Hkv: int, L: int, scale: float = 0.0, out: Optional[torch.Tensor] = None,
+                         stream=None) -> torch.Tensor:
+    """q [n, Hq, d] and the packed k_c, v_c [rows, d] of laq_compact -> out [n, Hq, d] fp32: one new
+    token's attention over the retained rows of its KV head."""
+    lib = load_library()
+    _dev(q, "q"), _dev(k_c, "k_c"), _dev(v_c, "v_c")
+    n, Hq, d = q.shape
+    total, _ = packed_rows(budget, Hkv, L)
+    if k_c.shape != (total, d) or v_c.shape != (total, d) or not (q.dtype == k_c.dtype == v_c.dtype):
+        raise ValueError("k_c / v_c must be the packed [rows, d] tensors of these budgets, in q's dtype")
+    if out is None:
+        out = torch.empty(n, Hq, d, dtype=torch.float32, device=q.device)
+    sh = _shape(n, Hq, Hkv, d, L, 1, _dtype_code(q), scale, None, 0)
+    rc = lib.laq_decode_attention(ctypes.byref(sh), q.data_ptr(), k_c.data_ptr(), v_c.data_ptr(),
+                                  _budget_array(budget, n), out.data_ptr(), _stream(stream))
+    if rc != 0:
+        raise LaqError(rc, "laq_decode_attention")
+    return out
 
 
 def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, budget: Sequence[int], keep: int,

@@ -177,6 +177,38 @@ static int sink_recent_impl(int n_inst, int Hkv, int L, const int32_t* budget, i
   return LAQ_OK;
 }
 
+static int decode_impl(const laq_shape* shape, const void* q, const void* kc, const void* vc,
+                       const int32_t* budget, float* out, hipStream_t st) {
+  ScoreGeom g;
+  const int rc = make_geom(shape, &g);
+  if (rc != LAQ_OK) return rc;
+  if (!q || !kc || !vc || !out || !budget) return LAQ_ERR_INVALID;
+  for (int i = 0; i < shape->n_inst; ++i)
+    if (budget[i] < 1) return LAQ_ERR_INVALID;
+  if (g.Hkv > 65535) return LAQ_ERR_UNSUPPORTED;
+  int64_t row = 0;
+  for (int i0 = 0; i0 < shape->n_inst; i0 += MAX_INST_PER_LAUNCH) {
+    const int n = shape->n_inst - i0 < MAX_INST_PER_LAUNCH ? shape->n_inst - i0 : MAX_INST_PER_LAUNCH;
+    InstTable tab;
+    memset(&tab, 0, sizeof tab);
+    fill_table(g.Hkv, g.L, budget, i0, n, row, &tab, &row);
+    if (launch_decode(n, i0, g.Hq, g.Hkv, g.d, shape->dtype, g.scale2, tab, q, kc, vc, out, st) != hipSuccess)
+      return LAQ_ERR_DEVICE;
+  }
+  return LAQ_OK;
+}
+
+static int qcache_store_impl(const laq_shape* shape, const void* q_step, int t, void* q_cache, hipStream_t st) {
+  ScoreGeom g;
+  const int rc = make_geom(shape, &g);
+  if (rc != LAQ_OK) return rc;
+  if (!q_step || !q_cache || t < 0 || t >= g.W) return LAQ_ERR_INVALID;
+  const int row_bytes = g.d * (shape->dtype == LAQ_F32 ? 4 : 2);
+  return launch_qcache_store((long long)g.n_inst * g.Hq, g.W, t, row_bytes, q_step, q_cache, st) == hipSuccess
+             ? LAQ_OK
+             : LAQ_ERR_DEVICE;
+}
+
 static int recall_impl(int n_inst, int Hkv, int L, const int32_t* idx_pred, const int32_t* budget_pred,
                        const int32_t* idx_gold, const int32_t* budget_gold, int32_t* overlap, float* recall,
                        hipStream_t st) {
@@ -226,6 +258,15 @@ int laq_select(const laq_shape* shape, const float* scores, const int32_t* budge
 int laq_select_sink_recent(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t* budget, int32_t n_sink,
                            int32_t* idx, void* stream) {
   return laq::sink_recent_impl(n_inst, Hkv, L, budget, n_sink, idx, static_cast<hipStream_t>(stream));
+}
+
+int laq_decode_attention(const laq_shape* shape, const void* q, const void* k_c, const void* v_c,
+                         const int32_t* budget, float* out, void* stream) {
+  return laq::decode_impl(shape, q, k_c, v_c, budget, out, static_cast<hipStream_t>(stream));
+}
+
+int laq_qcache_store(const laq_shape* shape, const void* q_step, int32_t t, void* q_cache, void* stream) {
+  return laq::qcache_store_impl(shape, q_step, t, q_cache, static_cast<hipStream_t>(stream));
 }
 
 int laq_recall(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t* idx_pred, const int32_t* budget_pred,

@@ -1,0 +1,270 @@
+// The steps around the re-eviction (Sec. 4.2 / 4.3): storing the queries of a lookahead step into
+// the Q-cache, and the attention of one new token over the compacted cache that decoding
+// continues on.
+//
+// Decode attention is bound by reading K' and V' once.  One workgroup serves up to four query
+// heads that share a KV head (they share every key and value row it reads).  A row is read by a
+// group of `pp` adjacent lanes, 8 elements each, so a wave's loads cover whole rows contiguously;
+// the lane groups of the workgroup take the rows round-robin, four rows per turn; each group
+// keeps its own running (max, sum, weighted value sum) per query head.  The groups of a wave are merged across lanes, the waves through
+// LDS, in a fixed order (the results do not depend on timing).
+#include "laq_internal.h"
+
+namespace laq {
+
+namespace {
+
+constexpr int DEC_ROWS = 4;               // rows per lane group and turn
+constexpr int DEC_MANY_WORKGROUPS = 1024;
+constexpr float DEC_NEG_BIG = -1.0e30f;
+
+// Eight consecutive elements of a row: raw bits as loaded, widened to fp32 at the point of use.
+struct Piece8F32 { float4 a, b; };
+struct Piece8BF16 { uint4 r; };
+
+__device__ __forceinline__ void fetch8(const float* p, Piece8F32& x) {
+  x.a = *reinterpret_cast<const float4*>(p);
+  x.b = *reinterpret_cast<const float4*>(p + 4);
+}
+__device__ __forceinline__ void fetch8(const uint16_t* p, Piece8BF16& x) { x.r = *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void clear8(Piece8F32& x) { x.a = x.b = make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ void clear8(Piece8BF16& x) { x.r = make_uint4(0u, 0u, 0u, 0u); }
+
+__device__ __forceinline__ void widen8(const Piece8F32& x, float (&f)[8]) {
+  f[0] = x.a.x; f[1] = x.a.y; f[2] = x.a.z; f[3] = x.a.w;
+  f[4] = x.b.x; f[5] = x.b.y; f[6] = x.b.z; f[7] = x.b.w;
+}
+__device__ __forceinline__ void widen8(const Piece8BF16& x, float (&f)[8]) {   // bf16 = the high half of fp32
+  f[0] = __uint_as_float(x.r.x << 16); f[1] = __uint_as_float(x.r.x & 0xffff0000u);
+  f[2] = __uint_as_float(x.r.y << 16); f[3] = __uint_as_float(x.r.y & 0xffff0000u);
+  f[4] = __uint_as_float(x.r.z << 16); f[5] = __uint_as_float(x.r.z & 0xffff0000u);
+  f[6] = __uint_as_float(x.r.w << 16); f[7] = __uint_as_float(x.r.w & 0xffff0000u);
+}
+
+template <typename T> struct PieceOf;
+template <> struct PieceOf<float> { using type = Piece8F32; };
+template <> struct PieceOf<uint16_t> { using type = Piece8BF16; };
+
+// LDS layout: m[DEC_WAVES][GB], z[DEC_WAVES][GB], acc[DEC_WAVES][GB][d].  PREFETCH: the next turn's
+// rows are requested before the current turn's arithmetic (more registers, fewer resident waves).
+template <int GB, typename T, int DEC_THREADS, bool PREFETCH>
+__global__ __launch_bounds__(DEC_THREADS) void decode_kernel(int Hq, int Hkv, int d, int pp, float scale2,
+                                                             InstTable tab, int inst0, const T* __restrict__ q,
+                                                             const T* __restrict__ kc, const T* __restrict__ vc,
+                                                             float* __restrict__ out) {
+  using Piece = typename PieceOf<T>::type;
+  constexpr int DEC_WAVES = DEC_THREADS / 64;
+  extern __shared__ float sm[];
+  const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
+  const int head = blockIdx.x / nbatch, g0 = (blockIdx.x % nbatch) * GB;
+  const int li = blockIdx.y, inst = inst0 + li;
+  const int bk = tab.bk[li];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int dc = tid % pp, ks = tid / pp, nks = DEC_THREADS / pp;
+  const bool active = dc * 8 < d;
+  const T* K = kc + (tab.row0[li] + (int64_t)head * bk) * d + dc * 8;
+  const T* V = vc + (tab.row0[li] + (int64_t)head * bk) * d + dc * 8;
+
+  float qv[GB][8], acc[GB][8], m[GB], z[GB];
+#pragma unroll
+  for (int g = 0; g < GB; ++g) {
+    m[g] = DEC_NEG_BIG;
+    z[g] = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) qv[g][c] = acc[g][c] = 0.f;
+    if (active && g0 + g < G) {
+      Piece qp;
+      fetch8(q + ((size_t)inst * Hq + (size_t)head * G + g0 + g) * d + dc * 8, qp);
+      widen8(qp, qv[g]);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) qv[g][c] *= scale2;      // logits in base-2 units
+    }
+  }
+
+  const int turns = ((bk + nks - 1) / nks + DEC_ROWS - 1) / DEC_ROWS;
+  // rows ks + nks * (t * DEC_ROWS + u), u < DEC_ROWS, of turn t; rows beyond the cache read as zeros
+  auto fetch_turn = [&](int t, Piece (&kp)[DEC_ROWS], Piece (&vp)[DEC_ROWS]) {
+#pragma unroll
+    for (int u = 0; u < DEC_ROWS; ++u) {
+      const int j = ks + nks * (t * DEC_ROWS + u);
+      clear8(kp[u]);
+      clear8(vp[u]);
+      if (active && j < bk) {
+        fetch8(K + (size_t)j * d, kp[u]);
+        fetch8(V + (size_t)j * d, vp[u]);
+      }
+    }
+  };
+  Piece kp[DEC_ROWS], vp[DEC_ROWS], kn[DEC_ROWS], vn[DEC_ROWS];
+  if (PREFETCH) fetch_turn(0, kp, vp);
+  for (int t = 0; t < turns; ++t) {
+    if (!PREFETCH) fetch_turn(t, kp, vp);
+    if (PREFETCH && t + 1 < turns) fetch_turn(t + 1, kn, vn);   // travels during this turn's arithmetic
+    bool valid[DEC_ROWS];
+#pragma unroll
+    for (int u = 0; u < DEC_ROWS; ++u) valid[u] = ks + nks * (t * DEC_ROWS + u) < bk;
+    float s[DEC_ROWS][GB];
+#pragma unroll
+    for (int u = 0; u < DEC_ROWS; ++u) {
+      float kf[8];
+      widen8(kp[u], kf);
+#pragma unroll
+      for (int g = 0; g < GB; ++g) {
+        float dot = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) dot = fmaf(qv[g][c], kf[c], dot);
+        s[u][g] = dot;
+      }
+    }
+    // every lane of a group gets the complete logits of the group's rows
+    for (int o = 1; o < pp; o <<= 1) {
+#pragma unroll
+      for (int u = 0; u < DEC_ROWS; ++u)
+#pragma unroll
+        for (int g = 0; g < GB; ++g) s[u][g] += __shfl_xor(s[u][g], o);
+    }
+    float p[DEC_ROWS][GB];
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+      float m_new = m[g];
+#pragma unroll
+      for (int u = 0; u < DEC_ROWS; ++u)
+        if (valid[u]) m_new = fmaxf(m_new, s[u][g]);
+      const float a = __builtin_amdgcn_exp2f(m[g] - m_new);
+      float zsum = 0.f;
+#pragma unroll
+      for (int u = 0; u < DEC_ROWS; ++u) {
+        p[u][g] = valid[u] ? __builtin_amdgcn_exp2f(s[u][g] - m_new) : 0.f;
+        zsum += p[u][g];
+      }
+      z[g] = fmaf(z[g], a, zsum);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[g][c] *= a;
+      m[g] = m_new;
+    }
+#pragma unroll
+    for (int u = 0; u < DEC_ROWS; ++u) {
+      float vf[8];
+      widen8(vp[u], vf);
+#pragma unroll
+      for (int g = 0; g < GB; ++g)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[g][c] = fmaf(p[u][g], vf[c], acc[g][c]);
+    }
+    if (PREFETCH) {
+#pragma unroll
+      for (int u = 0; u < DEC_ROWS; ++u) {
+        kp[u] = kn[u];
+        vp[u] = vn[u];
+      }
+    }
+  }
+
+  // merge the lane groups of a wave: after the last step the wave's first group holds the result
+  for (int o = pp; o < 64; o <<= 1) {
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+      const float m_o = __shfl_xor(m[g], o), z_o = __shfl_xor(z[g], o);
+      const float M = fmaxf(m[g], m_o);
+      const float a = __builtin_amdgcn_exp2f(m[g] - M), b = __builtin_amdgcn_exp2f(m_o - M);
+      z[g] = fmaf(z[g], a, z_o * b);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[g][c] = fmaf(acc[g][c], a, __shfl_xor(acc[g][c], o) * b);
+      m[g] = M;
+    }
+  }
+  float* sm_m = sm;
+  float* sm_z = sm + DEC_WAVES * GB;
+  float* sm_acc = sm + 2 * DEC_WAVES * GB;
+  if (lane < pp) {
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+      if (lane == 0) {
+        sm_m[wave * GB + g] = m[g];
+        sm_z[wave * GB + g] = z[g];
+      }
+      if (active) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) sm_acc[((size_t)wave * GB + g) * d + dc * 8 + c] = acc[g][c];
+      }
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < GB * d; e += DEC_THREADS) {
+    const int g = e / d, c = e - g * d;
+    if (g0 + g >= G) continue;
+    float M = DEC_NEG_BIG;
+#pragma unroll
+    for (int w = 0; w < DEC_WAVES; ++w) M = fmaxf(M, sm_m[w * GB + g]);
+    float Z = 0.f, O = 0.f;
+#pragma unroll
+    for (int w = 0; w < DEC_WAVES; ++w) {
+      const float wgt = __builtin_amdgcn_exp2f(sm_m[w * GB + g] - M);
+      Z = fmaf(sm_z[w * GB + g], wgt, Z);
+      O = fmaf(sm_acc[((size_t)w * GB + g) * d + c], wgt, O);
+    }
+    out[((size_t)inst * Hq + (size_t)head * G + g0 + g) * d + c] = O / Z;
+  }
+}
+
+// q_cache[inst][h][t][:] = q_step[inst][h][:], 16 bytes per thread
+__global__ __launch_bounds__(256) void qcache_store_kernel(long long rows, int W, int t, int pieces,
+                                                           const uint4* __restrict__ q_step,
+                                                           uint4* __restrict__ q_cache) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows * pieces) return;
+  const long long row = i / pieces;
+  const int piece = (int)(i - row * pieces);
+  q_cache[(row * W + t) * pieces + piece] = q_step[i];
+}
+
+template <int GB, typename T, int THREADS, bool PREFETCH>
+hipError_t launch_decode_as(int n_inst, int inst0, int Hq, int Hkv, int d, float scale2, const InstTable& tab,
+                            const void* q, const void* kc, const void* vc, float* out, hipStream_t st) {
+  int pp = 8;                               // lanes per row: a power of two that covers d / 8 pieces
+  while (pp * 8 < d) pp <<= 1;
+  const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
+  const size_t lds = (size_t)(THREADS / 64) * GB * (d + 2) * sizeof(float);
+  hipLaunchKernelGGL((decode_kernel<GB, T, THREADS, PREFETCH>), dim3(Hkv * nbatch, n_inst), dim3(THREADS), lds, st, Hq,
+                     Hkv, d, pp, scale2, tab, inst0, static_cast<const T*>(q), static_cast<const T*>(kc),
+                     static_cast<const T*>(vc), out);
+  return hipGetLastError();
+}
+
+// Few workgroups (long caches, few heads): large workgroups that keep two turns of rows in flight.
+// Many workgroups: small ones without the second set of row registers, so that more of them are
+// resident at once.
+template <int GB, typename T>
+hipError_t launch_decode_for(int n_inst, int inst0, int Hq, int Hkv, int d, float scale2, const InstTable& tab,
+                             const void* q, const void* kc, const void* vc, float* out, hipStream_t st) {
+  const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
+  if ((long long)Hkv * nbatch * n_inst >= DEC_MANY_WORKGROUPS)
+    return launch_decode_as<GB, T, 256, false>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+  return launch_decode_as<GB, T, 512, true>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+}
+
+}  // namespace
+
+hipError_t launch_decode(int n_inst, int inst0, int Hq, int Hkv, int d, int dtype, float scale2, const InstTable& tab,
+                         const void* q, const void* kc, const void* vc, float* out, hipStream_t st) {
+  const int G = Hq / Hkv;
+  if (dtype == LAQ_BF16) {
+    if (G == 1) return launch_decode_for<1, uint16_t>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+    if (G == 2) return launch_decode_for<2, uint16_t>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+    return launch_decode_for<4, uint16_t>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+  }
+  if (G == 1) return launch_decode_for<1, float>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+  if (G == 2) return launch_decode_for<2, float>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+  return launch_decode_for<4, float>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+}
+
+hipError_t launch_qcache_store(long long rows, int W, int t, int row_bytes, const void* q_step, void* q_cache,
+                               hipStream_t st) {
+  const int pieces = row_bytes / 16;
+  const long long total = rows * pieces;
+  hipLaunchKernelGGL(qcache_store_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, rows, W, t, pieces,
+                     static_cast<const uint4*>(q_step), static_cast<uint4*>(q_cache));
+  return hipGetLastError();
+}
+
+}  // namespace laq

@@ -108,6 +108,10 @@ hipError_t launch_sink_recent(int n_inst, int Hkv, int L, int n_sink, const Inst
                               hipStream_t st);
 hipError_t launch_recall(int n_inst, int inst0, int Hkv, const PairTable& tab, const int32_t* idx_pred,
                          const int32_t* idx_gold, int32_t* overlap, float* recall, hipStream_t st);
+hipError_t launch_decode(int n_inst, int inst0, int Hq, int Hkv, int d, int dtype, float scale2, const InstTable& tab,
+                         const void* q, const void* kc, const void* vc, float* out, hipStream_t st);
+hipError_t launch_qcache_store(long long rows, int W, int t, int row_bytes, const void* q_step, void* q_cache,
+                               hipStream_t st);
 hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, int bk_max, const void* k,
                           const void* v, const int32_t* idx, const InstTable& tab, void* k_out, void* v_out,
                           hipStream_t st);

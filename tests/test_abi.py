@@ -20,7 +20,7 @@ def declared_functions(repo_root):
 def test_library_exports_every_declared_symbol(repo_root):
     lib = laq.load_library()
     names = declared_functions(repo_root)
-    assert names == ["laq_compact", "laq_evict", "laq_recall", "laq_score", "laq_select", "laq_select_sink_recent",
+    assert names == ["laq_compact", "laq_decode_attention", "laq_evict", "laq_qcache_store", "laq_recall", "laq_score", "laq_select", "laq_select_sink_recent",
                      "laq_strerror", "laq_workspace_bytes"]
     for n in names:
         assert getattr(lib, n) is not None
@@ -136,6 +136,25 @@ def test_stage_one_variants_are_checked_without_a_gpu():
     assert lib.laq_recall(1, 2, 512, fake, bud, fake, bud, None, None, None) == INVALID
     assert lib.laq_recall(1, 2, 512, fake, (ctypes.c_int32 * 1)(0), fake, bud, fake, None, None) == INVALID
     assert lib.laq_recall(1, 70000, 512, fake, bud, fake, bud, fake, None, None) == UNSUPPORTED
+
+
+def test_decode_side_calls_are_checked_without_a_gpu():
+    lib = laq.load_library()
+    fake = ctypes.c_void_p(0x1000)
+    INVALID = -1
+    bud = (ctypes.c_int32 * 1)(64)
+    sh = _shape(keep=0)
+    assert lib.laq_decode_attention(ctypes.byref(sh), None, fake, fake, bud, fake, None) == INVALID
+    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, None, bud, fake, None) == INVALID
+    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, fake, None, fake, None) == INVALID
+    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, fake, bud, None, None) == INVALID
+    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, fake, (ctypes.c_int32 * 1)(0), fake, None) == INVALID
+    assert lib.laq_decode_attention(ctypes.byref(_shape(Hq=7)), fake, fake, fake, bud, fake, None) == INVALID
+    assert lib.laq_qcache_store(ctypes.byref(sh), None, 0, fake, None) == INVALID
+    assert lib.laq_qcache_store(ctypes.byref(sh), fake, 0, None, None) == INVALID
+    assert lib.laq_qcache_store(ctypes.byref(sh), fake, -1, fake, None) == INVALID
+    assert lib.laq_qcache_store(ctypes.byref(sh), fake, 8, fake, None) == INVALID      # W = 8 slots: 0..7
+    assert lib.laq_qcache_store(ctypes.byref(_shape(d=12)), fake, 0, fake, None) == INVALID
 
 
 def test_packed_rows():

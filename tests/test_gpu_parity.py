@@ -573,3 +573,103 @@ def test_recall_of_the_window_selection_against_the_selection_by_all_queries(laq
     assert (rec > 0).all() and (rec <= 1).all()
     # scored selections agree far more with the reference than the score-free list does
     assert rec.mean().item() > rec_s.mean().item()
+
+
+# ---- the steps around the path: Q-cache capture (Sec. 4.2), decoding on the compacted cache (Sec. 4.3) ----
+def check_decode(got_f32, q, kc, vc, dtype, what, scale=0.0):
+    """|got - want| <= rtol * sum_j p_j |v_j| element by element (the scale of the sum that the
+    rounding errors of the weights act on), want and the bound from the oracle."""
+    want = oracle.decode_attention(q, kc, vc, scale)
+    bound = oracle.decode_attention(q, kc, vc.abs(), scale) * RTOL[dtype] + 1e-30
+    err = (got_f32.double() - want).abs()
+    assert torch.isfinite(got_f32).all(), what
+    assert (err <= bound).all(), "%s: worst err/bound %.3f" % (what, float((err / bound).max()))
+
+
+DECODE = [
+    # name, dtype, Hq, Hkv, d, L, budgets
+    ("mistral-like", torch.bfloat16, 32, 8, 128, 4096, [128, 2048, 5000]),
+    ("G1", torch.bfloat16, 4, 4, 128, 600, [77]),
+    ("G2", torch.bfloat16, 8, 4, 128, 600, [300, 1]),
+    ("G3-masked-head-slot", torch.bfloat16, 6, 2, 128, 500, [100]),
+    ("G8-two-head-batches", torch.bfloat16, 16, 2, 128, 700, [256]),
+    ("G6-ragged-second-batch", torch.bfloat16, 6, 1, 64, 700, [100]),
+    ("d64", torch.bfloat16, 8, 2, 64, 900, [500]),
+    ("d96-idle-lanes", torch.bfloat16, 4, 2, 96, 400, [64]),
+    ("d256", torch.bfloat16, 4, 2, 256, 300, [300]),
+    ("d8", torch.bfloat16, 2, 2, 8, 100, [40]),
+    ("fp32", torch.float32, 8, 2, 128, 500, [64, 200]),
+    ("fp32-d40", torch.float32, 4, 2, 40, 300, [33]),
+    ("fewer-rows-than-lane-groups", torch.bfloat16, 8, 2, 128, 50, [3, 15, 16, 17]),
+    ("long-cache", torch.bfloat16, 8, 2, 128, 33000, [33000]),
+]
+
+
+@pytest.mark.parametrize("name,dtype,Hq,Hkv,d,L,budgets", DECODE, ids=[e[0] for e in DECODE])
+def test_decode_attention_on_packed_cache(laq, name, dtype, Hq, Hkv, d, L, budgets):
+    print("case:", name, "Hq=%d Hkv=%d d=%d L=%d budgets=%s" % (Hq, Hkv, d, L, budgets), flush=True)
+    n = len(budgets)
+    g = torch.Generator().manual_seed(len(name) * 13 + d)
+    total, _ = laq.packed_rows(budgets, Hkv, L)
+    q = (torch.randn(n, Hq, d, generator=g) * 1.5).to(dtype)
+    kc = torch.randn(total, d, generator=g).to(dtype)
+    vc = torch.randn(total, d, generator=g).to(dtype)
+    out = laq.laq_decode_attention(q.to(DEV), kc.to(DEV), vc.to(DEV), budgets, Hkv, L)
+    again = laq.laq_decode_attention(q.to(DEV), kc.to(DEV), vc.to(DEV), budgets, Hkv, L)
+    torch.cuda.synchronize()
+    assert torch.equal(out, again)
+    k_l, v_l = split_packed(kc, budgets, Hkv, L), split_packed(vc, budgets, Hkv, L)
+    for i in range(n):
+        check_decode(out[i].cpu(), q[i], k_l[i].contiguous(), v_l[i].contiguous(), dtype, "%s inst %d" % (name, i))
+
+
+def test_decode_attention_extreme_logits_and_scale(laq):
+    g = torch.Generator().manual_seed(8)
+    q = (torch.randn(1, 8, 128, generator=g) * 30).bfloat16()
+    kc = (torch.randn(2 * 200, 128, generator=g) * 30).bfloat16()
+    vc = torch.randn(2 * 200, 128, generator=g).bfloat16()
+    for scale in (0.0, 1.0, 0.01):
+        out = laq.laq_decode_attention(q.to(DEV), kc.to(DEV), vc.to(DEV), [200], 2, 200, scale=scale)
+        torch.cuda.synchronize()
+        check_decode(out[0].cpu(), q[0], kc.view(2, 200, 128), vc.view(2, 200, 128), torch.bfloat16,
+                     "scale %g" % scale, scale)
+
+
+def test_evict_then_decode_on_the_compacted_cache(laq):
+    cfg = CONFIGS[2]
+    q, k, v, budgets, _ = make_batch(cfg, device=DEV)
+    _, idx, ko, vo = laq.laq_evict(q, k, v, budgets, cfg.pool)
+    gen = torch.Generator(device=DEV).manual_seed(4)
+    q_new = torch.randn(q.shape[0], cfg.Hq, cfg.d, generator=gen, device=DEV).to(k.dtype)
+    out = laq.laq_decode_attention(q_new, ko, vo, budgets, cfg.Hkv, cfg.L)
+    torch.cuda.synchronize()
+    k_l = split_packed(ko.cpu(), budgets, cfg.Hkv, cfg.L)
+    v_l = split_packed(vo.cpu(), budgets, cfg.Hkv, cfg.L)
+    for i in range(q.shape[0]):
+        check_decode(out[i].cpu(), q_new[i].cpu(), k_l[i].contiguous(), v_l[i].contiguous(), k.dtype, "inst %d" % i)
+
+
+def test_qcache_capture_feeds_scoring(laq):
+    n, Hq, Hkv, d, L, W = 2, 8, 2, 128, 700, 8
+    g = torch.Generator().manual_seed(6)
+    steps = [torch.randn(n, Hq, d, generator=g).bfloat16() for _ in range(W)]
+    k = torch.randn(n, Hkv, L, d, generator=g).bfloat16().to(DEV)
+    cache = torch.full((n, Hq, W, d), 7.0, dtype=torch.bfloat16, device=DEV)
+    ref = torch.full((n, Hq, W, d), 7.0, dtype=torch.bfloat16)
+    for t in (3, 0, 7, 1, 2, 6, 5, 4):                             # any order; a slot only changes its own rows
+        laq.laq_qcache_store(cache, steps[t].to(DEV), t)
+        for i in range(n):
+            ref[i] = oracle.qcache_store(ref[i], steps[t][i], t)
+        torch.cuda.synchronize()
+        assert torch.equal(cache.cpu(), ref)
+    assert torch.equal(cache.cpu(), torch.stack(steps, dim=2))
+    pos = [L + t for t in range(W)]
+    a = laq.laq_score(cache, k, 7, q_pos=pos, keep=0)
+    b = laq.laq_score(torch.stack(steps, dim=2).to(DEV), k, 7, q_pos=pos, keep=0)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    cache32 = torch.zeros(1, 3, 4, 40, device=DEV)
+    step32 = torch.randn(1, 3, 40, generator=g)
+    laq.laq_qcache_store(cache32, step32.to(DEV), 2)
+    torch.cuda.synchronize()
+    assert torch.equal(cache32[:, :, 2].cpu(), step32) and cache32[:, :, :2].abs().sum() == 0
