@@ -673,3 +673,41 @@ def test_qcache_capture_feeds_scoring(laq):
     laq.laq_qcache_store(cache32, step32.to(DEV), 2)
     torch.cuda.synchronize()
     assert torch.equal(cache32[:, :, 2].cpu(), step32) and cache32[:, :, :2].abs().sum() == 0
+
+
+# ---- the path under stream capture ----
+def test_evict_replays_from_a_captured_graph(laq):
+    """laq_evict enqueues kernels only (no allocation, no synchronisation, no memset node), so a
+    caller may capture it into a graph; every replay must give the eager bits, also after the
+    inputs changed in place and with eager work in between."""
+    cfg = dataclasses.replace(CONFIGS[2], L=3000)
+    q, k, v, budgets, _ = make_batch(cfg, device=DEV)
+    n = q.shape[0]
+    total, _ = laq.packed_rows(budgets, cfg.Hkv, cfg.L)
+    scores = torch.empty(n, cfg.Hkv, cfg.L, dtype=torch.float32, device=DEV)
+    idx = torch.empty(total, dtype=torch.int32, device=DEV)
+    ko = torch.empty(total, cfg.d, dtype=k.dtype, device=DEV)
+    vo = torch.empty_like(ko)
+    ws = torch.empty(laq.laq_workspace_bytes(n, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, cfg.W, k.dtype), dtype=torch.uint8,
+                     device=DEV)
+
+    def run():
+        laq.laq_evict(q, k, v, budgets, cfg.pool, scores=scores, idx=idx, k_out=ko, v_out=vo, ws=ws)
+
+    run()                                            # first call sets the kernels' attributes (not capturable)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    gen = torch.Generator(device=DEV).manual_seed(3)
+    for rep in range(4):
+        if rep:
+            k.copy_(torch.randn(k.shape, generator=gen, device=DEV).to(k.dtype))      # new inputs, same buffers
+        eager = [t.clone() for t in laq.laq_evict(q, k, v, budgets, cfg.pool)]
+        for t in (scores, idx, ko, vo):
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((scores, idx, ko, vo), eager):
+            assert torch.equal(got, want), "replay %d" % rep
