@@ -12,8 +12,9 @@
 //   pass 2 (normalise + sum + pool): D = Q * K_tile^T, so a lane owns one key and 16 rows;
 //           with the row constants c = M + log2 Z the probabilities exp2(s - c) are summed over
 //           the rows in-lane, across the two lane halves with one cross-lane add and across row
-//           tiles through LDS.  A pass-2 chunk carries a halo of (pool-1)/2 keys on each side,
-//           so the sequence max-pool of every owned key is local to the workgroup.
+//           tiles through LDS.  The sequence max-pool of every key whose window lies inside
+//           the chunk is taken right there; the few keys next to a chunk boundary are pooled
+//           by a small kernel afterwards, from raw scores that the chunks leave for it.
 //
 // The A and B operands of the 32x32x16 instruction have the same lane layout (lane l
 // supplies row/column l%32 and the 8 consecutive reduction elements l/32), so the same
