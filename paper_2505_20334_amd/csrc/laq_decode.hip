@@ -5,7 +5,7 @@
 // Decode attention is bound by reading K' and V' once.  One workgroup serves up to four query
 // heads that share a KV head (they share every key and value row it reads).  A row is read by a
 // group of `pp` adjacent lanes, 8 elements each, so a wave's loads cover whole rows contiguously;
-// the lane groups of the workgroup take the rows round-robin, four rows per turn; each group
+// the lane groups of the workgroup take the rows round-robin, several rows per turn; each group
 // keeps its own running (max, sum, weighted value sum) per query head.  The groups of a wave are merged across lanes, the waves through
 // LDS, in a fixed order (the results do not depend on timing).
 #include "laq_internal.h"
@@ -14,7 +14,6 @@ namespace laq {
 
 namespace {
 
-constexpr int DEC_ROWS = 4;               // rows per lane group and turn
 constexpr int DEC_MANY_WORKGROUPS = 1024;
 constexpr float DEC_NEG_BIG = -1.0e30f;
 
@@ -41,19 +40,38 @@ __device__ __forceinline__ void widen8(const Piece8BF16& x, float (&f)[8]) {   /
   f[6] = __uint_as_float(x.r.w << 16); f[7] = __uint_as_float(x.r.w & 0xffff0000u);
 }
 
+// Sum over the PP (8, 16 or 32) adjacent lanes of a group, result in every lane.  Data-parallel
+// lane permutations within a row of 16 lanes: swap neighbours, swap pairs, then mirror the 8 and
+// the 16 lanes (the halves already agree, so a mirror reaches the other half's sum).
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+template <int PP>
+__device__ __forceinline__ float group_sum(float x) {
+  x += dpp_move<0xB1>(x);                   // quad_perm [1,0,3,2]
+  x += dpp_move<0x4E>(x);                   // quad_perm [2,3,0,1]
+  x += dpp_move<0x141>(x);                  // row_half_mirror
+  if (PP >= 16) x += dpp_move<0x140>(x);    // row_mirror
+  if (PP >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
 template <typename T> struct PieceOf;
 template <> struct PieceOf<float> { using type = Piece8F32; };
 template <> struct PieceOf<uint16_t> { using type = Piece8BF16; };
 
-// LDS layout: m[DEC_WAVES][GB], z[DEC_WAVES][GB], acc[DEC_WAVES][GB][d].  PREFETCH: the next turn's
-// rows are requested before the current turn's arithmetic (more registers, fewer resident waves).
-template <int GB, typename T, int DEC_THREADS, bool PREFETCH>
-__global__ __launch_bounds__(DEC_THREADS) void decode_kernel(int Hq, int Hkv, int d, int pp, float scale2,
+// LDS layout: m[DEC_WAVES][GB], z[DEC_WAVES][GB], acc[DEC_WAVES][GB][d].  DEC_ROWS: rows per lane
+// group and turn.  PREFETCH: the next turn's rows are requested before the current turn's
+// arithmetic (more registers, fewer resident waves).
+template <int GB, typename T, int DEC_THREADS, int DEC_ROWS, bool PREFETCH, int PP>
+__global__ __launch_bounds__(DEC_THREADS) void decode_kernel(int Hq, int Hkv, int d, float scale2,
                                                              InstTable tab, int inst0, const T* __restrict__ q,
                                                              const T* __restrict__ kc, const T* __restrict__ vc,
                                                              float* __restrict__ out) {
   using Piece = typename PieceOf<T>::type;
   constexpr int DEC_WAVES = DEC_THREADS / 64;
+  constexpr int pp = PP;                   // lanes per row
   extern __shared__ float sm[];
   const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
   const int head = blockIdx.x / nbatch, g0 = (blockIdx.x % nbatch) * GB;
@@ -117,12 +135,10 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(int Hq, int Hkv, in
       }
     }
     // every lane of a group gets the complete logits of the group's rows
-    for (int o = 1; o < pp; o <<= 1) {
 #pragma unroll
-      for (int u = 0; u < DEC_ROWS; ++u)
+    for (int u = 0; u < DEC_ROWS; ++u)
 #pragma unroll
-        for (int g = 0; g < GB; ++g) s[u][g] += __shfl_xor(s[u][g], o);
-    }
+      for (int g = 0; g < GB; ++g) s[u][g] = group_sum<PP>(s[u][g]);
     float p[DEC_ROWS][GB];
 #pragma unroll
     for (int g = 0; g < GB; ++g) {
@@ -218,17 +234,26 @@ __global__ __launch_bounds__(256) void qcache_store_kernel(long long rows, int W
   q_cache[(row * W + t) * pieces + piece] = q_step[i];
 }
 
-template <int GB, typename T, int THREADS, bool PREFETCH>
-hipError_t launch_decode_as(int n_inst, int inst0, int Hq, int Hkv, int d, float scale2, const InstTable& tab,
+template <int GB, typename T, int THREADS, int ROWS, bool PREFETCH, int PP>
+hipError_t launch_decode_pp(int n_inst, int inst0, int Hq, int Hkv, int d, float scale2, const InstTable& tab,
                             const void* q, const void* kc, const void* vc, float* out, hipStream_t st) {
-  int pp = 8;                               // lanes per row: a power of two that covers d / 8 pieces
-  while (pp * 8 < d) pp <<= 1;
   const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
   const size_t lds = (size_t)(THREADS / 64) * GB * (d + 2) * sizeof(float);
-  hipLaunchKernelGGL((decode_kernel<GB, T, THREADS, PREFETCH>), dim3(Hkv * nbatch, n_inst), dim3(THREADS), lds, st, Hq,
-                     Hkv, d, pp, scale2, tab, inst0, static_cast<const T*>(q), static_cast<const T*>(kc),
+  hipLaunchKernelGGL((decode_kernel<GB, T, THREADS, ROWS, PREFETCH, PP>), dim3(Hkv * nbatch, n_inst), dim3(THREADS), lds,
+                     st, Hq, Hkv, d, scale2, tab, inst0, static_cast<const T*>(q), static_cast<const T*>(kc),
                      static_cast<const T*>(vc), out);
   return hipGetLastError();
+}
+
+// lanes per row: the power of two (at least 8) that covers the row's d / 8 pieces
+template <int GB, typename T, int THREADS, int ROWS, bool PREFETCH>
+hipError_t launch_decode_as(int n_inst, int inst0, int Hq, int Hkv, int d, float scale2, const InstTable& tab,
+                            const void* q, const void* kc, const void* vc, float* out, hipStream_t st) {
+  if (d <= 64)
+    return launch_decode_pp<GB, T, THREADS, ROWS, PREFETCH, 8>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+  if (d <= 128)
+    return launch_decode_pp<GB, T, THREADS, ROWS, PREFETCH, 16>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+  return launch_decode_pp<GB, T, THREADS, ROWS, PREFETCH, 32>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
 }
 
 // Few workgroups (long caches, few heads): large workgroups that keep two turns of rows in flight.
@@ -239,8 +264,8 @@ hipError_t launch_decode_for(int n_inst, int inst0, int Hq, int Hkv, int d, floa
                              const void* q, const void* kc, const void* vc, float* out, hipStream_t st) {
   const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
   if ((long long)Hkv * nbatch * n_inst >= DEC_MANY_WORKGROUPS)
-    return launch_decode_as<GB, T, 256, false>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
-  return launch_decode_as<GB, T, 512, true>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+    return launch_decode_as<GB, T, 256, 4, false>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+  return launch_decode_as<GB, T, 512, (sizeof(T) == 2 ? 8 : 4), true>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
 }
 
 }  // namespace

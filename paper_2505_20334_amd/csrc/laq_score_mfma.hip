@@ -26,6 +26,7 @@
 // small kernel combines the per-chunk statistics of every head.  K is therefore read twice.
 // (A single-read variant has to keep a head's keys on chip while all its chunks meet between
 // the passes; on this part that device-wide meeting costs more than the second read.)
+#include <atomic>
 #include <type_traits>
 
 #include "laq_internal.h"
@@ -751,12 +752,14 @@ template <int D, int NRT>
 hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, int pool, const uint16_t* q, const uint16_t* k,
                          float* scores, const Workspace& ws, hipStream_t st) {
   constexpr int bytes = Smem<D, NRT>::BYTES;
-  static int resident_of[64] = {0};        // workgroups each device holds at once (queried once per device)
+  // workgroups each device holds at once, queried on the first call per device (host threads that
+  // race here compute the same value)
+  static std::atomic<int> resident_of[64];
   int dev = 0;
   hipError_t e;
   if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
   if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  int& resident = resident_of[dev];
+  int resident = resident_of[dev].load(std::memory_order_acquire);
   const void* f1 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 1>);
   const void* f2 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 2>);
   if (resident == 0) {
@@ -768,6 +771,7 @@ hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, int pool, const
     if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, f2, THREADS, bytes)) != hipSuccess) return e;
     if (cus < 1 || n1 < 1 || n2 < 1) return hipErrorInvalidValue;
     resident = cus * (n1 < n2 ? n1 : n2);
+    resident_of[dev].store(resident, std::memory_order_release);
   }
   const long long n_heads = (long long)g.n_inst * g.Hkv;
   const int half = (pool - 1) / 2;
