@@ -89,13 +89,39 @@ __global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, Q
 }
 
 // pooled[j] = max (or mean) of raw[i], |i - j| <= half, 0 <= i < P, for prefix keys; the kept
-// trailing columns are copied
+// trailing columns are copied.  A workgroup stages POOL_TILE scores plus the window margins in
+// LDS, with zeros for positions outside the prefix: the scores are sums of probabilities, never
+// negative, so a zero leaves a maximum alone, and it leaves the ascending fp32 sum of the average
+// bit-identical to pool_window()'s sum over the clipped window.  grid.x walks the (instance, KV
+// head) pairs.
+constexpr int POOL_TILE = 1024;
 __global__ __launch_bounds__(256) void pool_kernel(int L, int P, int half, bool avg, const float* __restrict__ raw,
                                                    float* __restrict__ pooled) {
-  const int j = blockIdx.y * 256 + threadIdx.x;      // grid.x walks the (instance, KV head) pairs
-  if (j >= L) return;
+  __shared__ float tile[POOL_TILE + MAX_POOL - 1];
   const float* r = raw + (size_t)blockIdx.x * L;
-  pooled[(size_t)blockIdx.x * L + j] = j < P ? pool_window(r, j, P, half, avg) : r[j];
+  float* out = pooled + (size_t)blockIdx.x * L;
+  const int j0 = blockIdx.y * POOL_TILE;
+  for (int t = threadIdx.x; t < POOL_TILE + 2 * half; t += 256) {
+    const int i = j0 - half + t;
+    tile[t] = (i >= 0 && i < P) ? r[i] : 0.f;
+  }
+  __syncthreads();
+  const float kernel_size = (float)(2 * half + 1);
+  for (int t = threadIdx.x; t < POOL_TILE && j0 + t < L; t += 256) {
+    const int j = j0 + t;
+    float v;
+    if (j >= P) {
+      v = r[j];
+    } else if (avg) {
+      float acc = 0.f;
+      for (int o = 0; o <= 2 * half; ++o) acc += tile[t + o];
+      v = acc / kernel_size;
+    } else {
+      v = tile[t + half];
+      for (int o = 0; o <= 2 * half; ++o) v = fmaxf(v, tile[t + o]);
+    }
+    out[j] = v;
+  }
 }
 
 }  // namespace
@@ -127,7 +153,7 @@ hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStre
 }
 
 hipError_t launch_pool(const ScoreGeom& g, int pool, bool avg, const float* raw, float* pooled, hipStream_t st) {
-  dim3 grid(g.n_inst * g.Hkv, (g.L + 255) / 256);
+  dim3 grid(g.n_inst * g.Hkv, (g.L + POOL_TILE - 1) / POOL_TILE);
   hipLaunchKernelGGL(pool_kernel, grid, dim3(256), 0, st, g.L, g.P, (pool - 1) / 2, avg, raw, pooled);
   return hipGetLastError();
 }
