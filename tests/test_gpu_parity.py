@@ -711,3 +711,30 @@ def test_evict_replays_from_a_captured_graph(laq):
         torch.cuda.synchronize()
         for got, want in zip((scores, idx, ko, vo), eager):
             assert torch.equal(got, want), "replay %d" % rep
+
+
+def test_more_instances_than_one_select_or_compact_launch_holds(laq):
+    # 300 small instances with varying budgets: select, compact and decode walk their per-launch
+    # tables of 256 instances twice; the packed offsets must carry over
+    n, Hq, Hkv, d, L, W = 300, 4, 2, 128, 300, 4
+    g = torch.Generator().manual_seed(44)
+    q = (torch.randn(n, Hq, W, d, generator=g) * 1.5).bfloat16().to(DEV)
+    k = torch.randn(n, Hkv, L, d, generator=g).bfloat16().to(DEV)
+    v = torch.randn(n, Hkv, L, d, generator=g).bfloat16().to(DEV)
+    budgets = [W + (13 * i) % 120 for i in range(n)]
+    scores, idx, ko, vo = laq.laq_evict(q, k, v, budgets, 7)
+    q_new = torch.randn(n, Hq, d, generator=g).bfloat16().to(DEV)
+    out = laq.laq_decode_attention(q_new, ko, vo, budgets, Hkv, L)
+    torch.cuda.synchronize()
+    idx_l = split_packed(idx.cpu(), budgets, Hkv, L)
+    ko_l, vo_l = split_packed(ko.cpu(), budgets, Hkv, L), split_packed(vo.cpu(), budgets, Hkv, L)
+    sc, kc, vc = scores.cpu(), k.cpu(), v.cpu()
+    for i in list(range(0, n, 41)) + [254, 255, 256, 257, 299]:
+        want = oracle.select(sc[i], W, budgets[i])
+        assert torch.equal(idx_l[i], want), i
+        assert torch.equal(ko_l[i], oracle.compact(kc[i], want)) and torch.equal(vo_l[i], oracle.compact(vc[i], want)), i
+        check_decode(out[i].cpu(), q_new[i].cpu(), ko_l[i].contiguous(), vo_l[i].contiguous(), torch.bfloat16,
+                     "inst %d" % i)
+    # scores of a sampled instance against the oracle end to end
+    pooled = oracle.evict(q[256].cpu(), kc[256], vc[256], budgets[256], 7)[0]
+    check_scores(sc[256], pooled, torch.bfloat16, "inst 256")
