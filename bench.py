@@ -129,6 +129,9 @@ def main():
     ap.add_argument("--pool-mode", choices=["max", "avg"], default="max",
                     help="sequence pooling: max (default, the headline workload) or the average of the "
                          "stage-1 eviction variant (Sec. 5.1)")
+    ap.add_argument("--layout", choices=["dense", "token-major"], default="dense",
+                    help="dense (default): k, v stored [n, Hkv, L, d]; token-major: stored [n, L, Hkv, d] and handed "
+                         "over as strided views")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device tensor copy (a kernel of known traffic, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -166,12 +169,18 @@ def main():
         workload = "%s+%s-window" % (cfg.name, args.window)
     if args.pool_mode != "max":
         workload += "+%s-pool" % args.pool_mode
+    if args.layout != "dense":
+        workload += "+%s" % args.layout
 
     # ---- inputs, generated on the device, resident before any timing ----
     dt = cfg.torch_dtype
     q = torch.empty(n, cfg.Hq, cfg.W, cfg.d, dtype=dt, device=dev)
-    k = torch.empty(n, cfg.Hkv, cfg.L, cfg.d, dtype=dt, device=dev)
-    v = torch.empty(n, cfg.Hkv, cfg.L, cfg.d, dtype=dt, device=dev)
+    if args.layout == "dense":
+        k = torch.empty(n, cfg.Hkv, cfg.L, cfg.d, dtype=dt, device=dev)
+        v = torch.empty(n, cfg.Hkv, cfg.L, cfg.d, dtype=dt, device=dev)
+    else:
+        k = torch.empty(n, cfg.L, cfg.Hkv, cfg.d, dtype=dt, device=dev).permute(0, 2, 1, 3)
+        v = torch.empty(n, cfg.L, cfg.Hkv, cfg.d, dtype=dt, device=dev).permute(0, 2, 1, 3)
     for i in range(n):
         seq, layer = divmod(i, cfg.n_layer)
         qi, ki, vi, _ = make_instance(cfg, seq, layer, device=dev)

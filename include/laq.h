@@ -18,7 +18,8 @@
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller; tensors are dense,
- *     row-major, innermost dimension contiguous.  `budget` is a HOST array.
+ *     row-major, innermost dimension contiguous (k and v may instead carry the strides of
+ *     laq_shape).  `budget` is a HOST array.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work on it and return; the caller synchronises.
  *   - The library allocates and frees no device memory and keeps no state between
@@ -84,6 +85,17 @@ typedef struct laq_shape {
    * mean with zeros outside the prefix, summed in fp32 in ascending i.
    */
   int32_t pool_mode;
+  /*
+   * Layout of k and v as laq_score, laq_compact and laq_evict read them: distances, in elements,
+   * between instances, KV heads and consecutive key rows; the d elements of a row are always
+   * contiguous.  All zero: the dense [n_inst, Hkv, L, d] of the conventions above.  A token-major
+   * cache [n_inst, L, Hkv, d] is {L*Hkv*d, d, Hkv*d}.  Each stride is a multiple of 16 bytes,
+   * kv_stride_row >= d, v has the strides of k, and rows must not overlap (not checked).  Outputs
+   * (scores, idx, k_out, v_out) keep their layouts.
+   */
+  int64_t kv_stride_inst;
+  int64_t kv_stride_head;
+  int64_t kv_stride_row;
 } laq_shape;
 
 /* Bytes of device scratch that laq_score / laq_evict need for this shape (0 on a bad shape). */

@@ -31,7 +31,8 @@ class _Shape(ctypes.Structure):
                 ("d", ctypes.c_int32), ("L", ctypes.c_int32), ("W", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("q_pos", ctypes.POINTER(ctypes.c_int32)), ("keep", ctypes.c_int32),
-                ("pool_mode", ctypes.c_int32)]
+                ("pool_mode", ctypes.c_int32), ("kv_stride_inst", ctypes.c_int64),
+                ("kv_stride_head", ctypes.c_int64), ("kv_stride_row", ctypes.c_int64)]
 
 
 def lib_path() -> str:
@@ -94,6 +95,18 @@ def _dev(t: torch.Tensor, name: str) -> torch.Tensor:
     return t
 
 
+def _kv(t: torch.Tensor, name: str) -> Tuple[int, int, int]:
+    """k / v [n, Hkv, L, d] on the GPU with contiguous rows; returns its (instance, head, row) strides in
+    elements ((0, 0, 0) for a dense tensor).  A view of a token-major cache, k_tm.permute(0, 2, 1, 3), is fine."""
+    if t.device.type != "cuda":
+        raise ValueError("%s must live on the GPU" % name)
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError("%s must be [n, Hkv, L, d] with contiguous rows" % name)
+    if t.is_contiguous():
+        return (0, 0, 0)
+    return (t.stride(0), t.stride(1), t.stride(2))
+
+
 def _stream(stream) -> int:
     if stream is None:
         return torch.cuda.current_stream().cuda_stream
@@ -101,14 +114,16 @@ def _stream(stream) -> int:
 
 
 def _shape(n: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: int, scale: float,
-           q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None, pool_mode: str = "max") -> _Shape:
+           q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None, pool_mode: str = "max",
+           kv_strides: Tuple[int, int, int] = (0, 0, 0)) -> _Shape:
     """q_pos: position of every window query in the key sequence (None: the trailing window);
     keep: trailing keys always retained (None: W); pool_mode "max" or "avg".  The position array
     stays alive with the struct."""
     if pool_mode not in ("max", "avg"):
         raise ValueError("pool_mode is 'max' or 'avg'")
     sh = _Shape(n, Hq, Hkv, d, L, W, dtype, float(scale), None, -1 if keep is None else int(keep),
-                LAQ_POOL_AVG if pool_mode == "avg" else LAQ_POOL_MAX)
+                LAQ_POOL_AVG if pool_mode == "avg" else LAQ_POOL_MAX, int(kv_strides[0]), int(kv_strides[1]),
+                int(kv_strides[2]))
     if q_pos is not None:
         if len(q_pos) != W:
             raise ValueError("q_pos needs one entry per window query")
@@ -156,7 +171,8 @@ def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale:
     q_pos / keep: the general observation window of laq_shape (None: trailing window); pool_mode:
     "max" or "avg" (laq_pool_mode)."""
     lib = load_library()
-    _dev(q_win, "q_win"), _dev(k, "k")
+    _dev(q_win, "q_win")
+    kvs = _kv(k, "k")
     n, Hq, W, d = q_win.shape
     n2, Hkv, L, d2 = k.shape
     if n != n2 or d != d2 or q_win.dtype != k.dtype:
@@ -164,7 +180,7 @@ def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale:
     if scores is None:
         scores = torch.empty(n, Hkv, L, dtype=torch.float32, device=k.device)
     ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
-    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs)
     rc = lib.laq_score(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), int(pool_kernel), scores.data_ptr(),
                        ws.data_ptr(), ws_bytes, _stream(stream))
     if rc != 0:
@@ -273,18 +289,18 @@ def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, b
     """k, v [n, Hkv, L, d] + packed idx -> packed k_out, v_out [rows, d]; keep as in laq_select
     (only used to check the budgets)."""
     lib = load_library()
-    _dev(k, "k"), _dev(idx, "idx")
+    _dev(idx, "idx")
+    kvs = _kv(k, "k")
     n, Hkv, L, d = k.shape
     total, _ = packed_rows(budget, Hkv, L)
     if k_out is None:
         k_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
     if v is not None:
-        _dev(v, "v")
-        if v.shape != k.shape or v.dtype != k.dtype:
-            raise ValueError("k / v mismatch")
+        if v.shape != k.shape or v.dtype != k.dtype or _kv(v, "v") != kvs:
+            raise ValueError("k / v mismatch (shape, dtype or strides)")
         if v_out is None:
             v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
-    sh = _shape(n, Hkv, Hkv, d, L, 1, _dtype_code(k), 0.0, None, keep)
+    sh = _shape(n, Hkv, Hkv, d, L, 1, _dtype_code(k), 0.0, None, keep, "max", kvs)
     rc = lib.laq_compact(ctypes.byref(sh), k.data_ptr(), v.data_ptr() if v is not None else None,
                          idx.data_ptr(), _budget_array(budget, n), k_out.data_ptr(),
                          v_out.data_ptr() if v is not None else None, _stream(stream))
@@ -299,7 +315,8 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
               pool_mode: str = "max"):
     """Whole path on one stream: returns (scores, idx, k_out, v_out); layouts as in the three calls."""
     lib = load_library()
-    _dev(q_win, "q_win"), _dev(k, "k")
+    _dev(q_win, "q_win")
+    kvs = _kv(k, "k")
     n, Hq, W, d = q_win.shape
     n2, Hkv, L, d2 = k.shape
     if n != n2 or d != d2 or q_win.dtype != k.dtype:
@@ -312,11 +329,12 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
     if k_out is None:
         k_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
     if v is not None:
-        _dev(v, "v")
+        if v.shape != k.shape or v.dtype != k.dtype or _kv(v, "v") != kvs:
+            raise ValueError("k / v mismatch (shape, dtype or strides)")
         if v_out is None:
             v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
     ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
-    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs)
     rc = lib.laq_evict(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), v.data_ptr() if v is not None else None,
                        _budget_array(budget, n), int(pool_kernel), scores.data_ptr(), idx.data_ptr(),
                        k_out.data_ptr(), v_out.data_ptr() if v is not None else None, ws.data_ptr(), ws_bytes,

@@ -49,6 +49,28 @@ static int make_geom(const laq_shape* s, ScoreGeom* g, QueryPos* qp = nullptr) {
   return LAQ_OK;
 }
 
+// Layout of k / v from the shape's strides (all zero: dense).  LAQ_ERR_INVALID on strides that are
+// not 16-byte multiples, overlap a row, or mix zero and non-zero.
+static int make_layout(const laq_shape* s, const ScoreGeom& g, KvLayout* lay) {
+  const int eb = s->dtype == LAQ_F32 ? 4 : 2;
+  const int64_t si = s->kv_stride_inst, sh = s->kv_stride_head, sr = s->kv_stride_row;
+  if (si == 0 && sh == 0 && sr == 0) {
+    lay->row = g.d;
+    lay->head = (int64_t)g.L * g.d;
+    lay->inst = (int64_t)g.Hkv * g.L * g.d;
+    lay->dense = 1;
+  } else {
+    if (sr < g.d || sh < 1 || si < 1 || (sr * eb) % 16 || (sh * eb) % 16 || (si * eb) % 16) return LAQ_ERR_INVALID;
+    if (sr * eb > 0x7fffffffLL) return LAQ_ERR_INVALID;
+    lay->row = sr;
+    lay->head = sh;
+    lay->inst = si;
+    lay->dense = (sr == g.d && sh == (int64_t)g.L * g.d && si == (int64_t)g.Hkv * g.L * g.d) ? 1 : 0;
+  }
+  lay->row_bytes = (int32_t)(lay->row * eb);
+  return LAQ_OK;
+}
+
 static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // chunks per head under the finest chunking any scoring path uses
@@ -104,6 +126,8 @@ static int score_impl(const laq_shape* shape, const void* q_win, const void* k, 
   memset(&qp, 0, sizeof qp);
   const int rc = make_geom(shape, &g, &qp);
   if (rc != LAQ_OK) return rc;
+  KvLayout lay;
+  if (make_layout(shape, g, &lay) != LAQ_OK) return LAQ_ERR_INVALID;
   if (!pool_ok(pool) || !q_win || !k || !scores) return LAQ_ERR_INVALID;
   if (!ws || ws_bytes < workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
   if (g.Hkv > 65535 || g.n_inst > 65535 || (long long)g.Hkv * g.n_inst > 0x7fffffffLL) return LAQ_ERR_UNSUPPORTED;
@@ -111,12 +135,13 @@ static int score_impl(const laq_shape* shape, const void* q_win, const void* k, 
   const Workspace w = carve_workspace(g, ws);
   hipError_t e;
   const bool avg = pool_avg(shape) && pool > 1;
-  if (score_mfma_supported(g, shape->dtype) && !avg) {
-    e = launch_score_mfma(g, qp, pool, q_win, k, scores, w, st);     // max pooling fused into pass 2
+  const bool mfma = score_mfma_supported(g, lay, shape->dtype);
+  if (mfma && !avg) {
+    e = launch_score_mfma(g, qp, lay, pool, q_win, k, scores, w, st);     // max pooling fused into pass 2
   } else {
     float* raw = pool > 1 ? w.raw : scores;
-    e = score_mfma_supported(g, shape->dtype) ? launch_score_mfma(g, qp, 1, q_win, k, raw, w, st)
-                                              : launch_score_generic(g, qp, shape->dtype, q_win, k, raw, w, st);
+    e = mfma ? launch_score_mfma(g, qp, lay, 1, q_win, k, raw, w, st)
+             : launch_score_generic(g, qp, lay, shape->dtype, q_win, k, raw, w, st);
     if (e == hipSuccess && pool > 1) e = launch_pool(g, pool, avg, raw, scores, st);
   }
   return e == hipSuccess ? LAQ_OK : LAQ_ERR_DEVICE;
@@ -147,6 +172,8 @@ static int compact_impl(const laq_shape* shape, const void* k, const void* v, co
   if (rc != LAQ_OK) return rc;
   if (!k || !k_out || !idx || !budgets_ok(shape, g, budget)) return LAQ_ERR_INVALID;
   if ((v == nullptr) != (v_out == nullptr)) return LAQ_ERR_INVALID;
+  KvLayout lay;
+  if (make_layout(shape, g, &lay) != LAQ_OK) return LAQ_ERR_INVALID;
   const int row_bytes = g.d * (shape->dtype == LAQ_F32 ? 4 : 2);
   int64_t row = 0;
   for (int i0 = 0; i0 < shape->n_inst; i0 += MAX_INST_PER_LAUNCH) {
@@ -154,7 +181,7 @@ static int compact_impl(const laq_shape* shape, const void* k, const void* v, co
     InstTable tab;
     memset(&tab, 0, sizeof tab);
     const int bk_max = fill_table(g.Hkv, g.L, budget, i0, n, row, &tab, &row);
-    if (launch_compact(n, i0, g.Hkv, g.L, row_bytes, bk_max, k, v, idx, tab, k_out, v_out, st) != hipSuccess)
+    if (launch_compact(n, i0, g.Hkv, g.L, row_bytes, lay, bk_max, k, v, idx, tab, k_out, v_out, st) != hipSuccess)
       return LAQ_ERR_DEVICE;
   }
   return LAQ_OK;
@@ -290,6 +317,8 @@ int laq_evict(const laq_shape* shape, const void* q_win, const void* k, const vo
   if (!laq::pool_ok(pool_kernel) || !q_win || !k || !scores || !idx || !k_out ||
       !laq::budgets_ok(shape, g, budget) || ((v == nullptr) != (v_out == nullptr)))
     return LAQ_ERR_INVALID;
+  laq::KvLayout lay;
+  if (laq::make_layout(shape, g, &lay) != LAQ_OK) return LAQ_ERR_INVALID;
   if (!ws || ws_bytes < laq::workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   int rc = laq::score_impl(shape, q_win, k, pool_kernel, scores, ws, ws_bytes, st);

@@ -87,6 +87,14 @@ __device__ __forceinline__ float pool_window(const float* __restrict__ s, int po
   return v;
 }
 
+// Where the rows of k and v lie: element strides between instances and KV heads, and between
+// consecutive key rows (row_bytes is the latter in bytes).  dense = [n_inst, Hkv, L, d].
+struct KvLayout {
+  int64_t inst, head, row;
+  int32_t row_bytes;
+  int32_t dense;
+};
+
 // Two packed index lists side by side, for up to MAX_PAIR_PER_LAUNCH instances.
 constexpr int MAX_PAIR_PER_LAUNCH = 128;
 struct PairTable {
@@ -95,12 +103,12 @@ struct PairTable {
 };
 
 // launchers (each returns hipGetLastError() after its last launch); `raw` receives unpooled scores
-hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, int dtype, const void* q, const void* k,
-                                float* raw, const Workspace& ws, hipStream_t st);
+hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int dtype, const void* q,
+                                const void* k, float* raw, const Workspace& ws, hipStream_t st);
 hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStream_t st);
-bool score_mfma_supported(const ScoreGeom& g, int dtype);
-hipError_t launch_score_mfma(const ScoreGeom& g, const QueryPos& qp, int pool, const void* q, const void* k,
-                             float* scores, const Workspace& ws, hipStream_t st);
+bool score_mfma_supported(const ScoreGeom& g, const KvLayout& lay, int dtype);
+hipError_t launch_score_mfma(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int pool, const void* q,
+                             const void* k, float* scores, const Workspace& ws, hipStream_t st);
 hipError_t launch_pool(const ScoreGeom& g, int pool, bool avg, const float* raw, float* pooled, hipStream_t st);
 hipError_t launch_select(int n_inst, int inst0, int Hkv, int L, int keep, int pool, bool avg, const float* scores,
                          const InstTable& tab, int32_t* idx, hipStream_t st);
@@ -112,8 +120,8 @@ hipError_t launch_decode(int n_inst, int inst0, int Hq, int Hkv, int d, int dtyp
                          const void* q, const void* kc, const void* vc, float* out, hipStream_t st);
 hipError_t launch_qcache_store(long long rows, int W, int t, int row_bytes, const void* q_step, void* q_cache,
                                hipStream_t st);
-hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, int bk_max, const void* k,
-                          const void* v, const int32_t* idx, const InstTable& tab, void* k_out, void* v_out,
-                          hipStream_t st);
+hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, const KvLayout& lay, int bk_max,
+                          const void* k, const void* v, const int32_t* idx, const InstTable& tab, void* k_out,
+                          void* v_out, hipStream_t st);
 
 }  // namespace laq

@@ -37,7 +37,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // One workgroup per (chunk, KV head, instance); thread t owns key chunk * 256 + t.
 template <typename T>
-__global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, QueryPos qp,
+__global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, QueryPos qp, KvLayout lay,
                                                                    const T* __restrict__ q,
                                                                    const T* __restrict__ k,
                                                                    float2* __restrict__ part) {
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int j = chunk * CHUNK_ROWS + t;
   const bool owned = j < g.L;
-  const T* krow = k + (((size_t)inst * g.Hkv + head) * g.L + (owned ? j : 0)) * g.d;
+  const T* krow = k + (size_t)inst * lay.inst + (size_t)head * lay.head + (size_t)(owned ? j : 0) * lay.row;
   const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d;
   float2* out = part + (((size_t)inst * g.Hkv + head) * g.nchunk + chunk) * g.Rpad;
 
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, 
 }
 
 template <typename T>
-__global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, QueryPos qp,
+__global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, QueryPos qp, KvLayout lay,
                                                                   const T* __restrict__ q,
                                                                   const T* __restrict__ k,
                                                                   const float* __restrict__ rowc,
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, Q
   const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
   const int j = chunk * CHUNK_ROWS + threadIdx.x;
   if (j >= g.L) return;
-  const T* krow = k + (((size_t)inst * g.Hkv + head) * g.L + j) * g.d;
+  const T* krow = k + (size_t)inst * lay.inst + (size_t)head * lay.head + (size_t)j * lay.row;
   const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d;
   const float* c = rowc + ((size_t)inst * g.Hkv + head) * g.Rpad;
   float acc = 0.f;
@@ -158,14 +158,14 @@ hipError_t launch_pool(const ScoreGeom& g, int pool, bool avg, const float* raw,
   return hipGetLastError();
 }
 
-hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, int dtype, const void* q, const void* k,
-                                float* raw, const Workspace& ws, hipStream_t st) {
+hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int dtype, const void* q,
+                                const void* k, float* raw, const Workspace& ws, hipStream_t st) {
   dim3 grid(g.nchunk, g.Hkv, g.n_inst), block(CHUNK_ROWS);
   if (dtype == LAQ_F32) {
-    hipLaunchKernelGGL(stats_generic_kernel<float>, grid, block, 0, st, g, qp, (const float*)q, (const float*)k,
+    hipLaunchKernelGGL(stats_generic_kernel<float>, grid, block, 0, st, g, qp, lay, (const float*)q, (const float*)k,
                        ws.part);
   } else {
-    hipLaunchKernelGGL(stats_generic_kernel<uint16_t>, grid, block, 0, st, g, qp, (const uint16_t*)q,
+    hipLaunchKernelGGL(stats_generic_kernel<uint16_t>, grid, block, 0, st, g, qp, lay, (const uint16_t*)q,
                        (const uint16_t*)k, ws.part);
   }
   hipError_t e = hipGetLastError();
@@ -173,10 +173,10 @@ hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, int dtyp
   e = launch_row_constants(g, ws, st);
   if (e != hipSuccess) return e;
   if (dtype == LAQ_F32) {
-    hipLaunchKernelGGL(norm_generic_kernel<float>, grid, block, 0, st, g, qp, (const float*)q, (const float*)k,
+    hipLaunchKernelGGL(norm_generic_kernel<float>, grid, block, 0, st, g, qp, lay, (const float*)q, (const float*)k,
                        ws.rowc, raw);
   } else {
-    hipLaunchKernelGGL(norm_generic_kernel<uint16_t>, grid, block, 0, st, g, qp, (const uint16_t*)q,
+    hipLaunchKernelGGL(norm_generic_kernel<uint16_t>, grid, block, 0, st, g, qp, lay, (const uint16_t*)q,
                        (const uint16_t*)k, ws.rowc, raw);
   }
   return hipGetLastError();

@@ -101,6 +101,15 @@ struct KeyRows {
   __amdgpu_buffer_rsrc_t rsrc;
   int voff;                // byte offset of this thread's first piece within the head
 };
+// The same for a cache whose rows are not adjacent (e.g. token-major [L, Hkv, d]): the distance
+// between rows is a run-time value, so the row offsets are added in registers instead of riding in
+// the immediate field.  They are added to the vector offset, which the range check covers (a
+// scalar offset operand would not be checked).  The descriptor ends with the head's last row.
+struct KeyRowsStrided {
+  __amdgpu_buffer_rsrc_t rsrc;
+  int voff;
+  int row_bytes;           // distance between consecutive key rows of the head
+};
 
 template <int D>
 __device__ __forceinline__ KeyRows key_rows(const uint16_t* khead, int j0, int L, int tid) {
@@ -112,21 +121,38 @@ __device__ __forceinline__ KeyRows key_rows(const uint16_t* khead, int j0, int L
 }
 
 template <int D>
+__device__ __forceinline__ KeyRowsStrided key_rows_strided(const uint16_t* khead, int j0, int L, int tid,
+                                                           int row_bytes) {
+  using T = Tile<D>;
+  KeyRowsStrided kr;
+  kr.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(khead), 0, (L - 1) * row_bytes + D * 2,
+                                              0x00020000);
+  kr.voff = (j0 + (tid / T::PIECES_PER_ROW) * T::PIECES_PER_THREAD) * row_bytes + (tid % T::PIECES_PER_ROW) * 16;
+  kr.row_bytes = row_bytes;
+  return kr;
+}
+
+template <int D>
 __device__ __forceinline__ u32x4 load_piece(const KeyRows& kr, int voff, int it) {
   return __builtin_amdgcn_raw_buffer_load_b128(kr.rsrc, voff + it * (D * 2), 0, 0);
+}
+template <int D>
+__device__ __forceinline__ u32x4 load_piece(const KeyRowsStrided& kr, int voff, int it) {
+  return __builtin_amdgcn_raw_buffer_load_b128(kr.rsrc, voff + it * kr.row_bytes, 0, 0);
 }
 
 // The thread's byte offset, made opaque to the optimiser at the point of use: the row
 // offsets added to it then stay next to their loads and fold into the instructions'
 // immediate fields, instead of being precomputed into one live register per piece.
-__device__ __forceinline__ int local_offset(const KeyRows& kr) {
+template <typename KR>
+__device__ __forceinline__ int local_offset(const KR& kr) {
   int v = kr.voff;
   asm volatile("" : "+v"(v));
   return v;
 }
 
-template <int D>
-__device__ __forceinline__ void fetch_chunk(u32x4 (&buf)[Tile<D>::PIECES_PER_THREAD], const KeyRows kr) {
+template <int D, typename KR>
+__device__ __forceinline__ void fetch_chunk(u32x4 (&buf)[Tile<D>::PIECES_PER_THREAD], const KR kr) {
   const int v = local_offset(kr);
 #pragma unroll
   for (int it = 0; it < Tile<D>::PIECES_PER_THREAD; ++it) buf[it] = load_piece<D>(kr, v, it);
@@ -197,10 +223,10 @@ __device__ __forceinline__ void merge_stat(float& M, float& Z, float2 p) {
 // read of its result)
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
-template <int D, int NT, bool PREFETCH>
+template <int D, int NT, bool PREFETCH, typename KR>
 __device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS], int kt0,
                                            float scale2, int lane, float& m_run, float& z_run,
-                                           u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
+                                           u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KR& nkr) {
   using T = Tile<D>;
   constexpr int KS = T::KSTEPS, N = NT * KS;
   static_assert(LDS_AHEAD <= N, "operand prefetch deeper than the wave's share of a chunk");
@@ -259,10 +285,10 @@ __device__ __forceinline__ void pass1_pipe(const char* ldsK, const bf16x8 (&qreg
 }
 
 // `first`: this call's sums start the chunk's slot buffer (they are stored); otherwise they are added.
-template <int D, int NT, bool PREFETCH>
+template <int D, int NT, bool PREFETCH, typename KR>
 __device__ __forceinline__ void pass2_pipe(const char* ldsK, const bf16x8 (&qreg)[Tile<D>::KSTEPS], int kt0,
                                            const float (&c)[16], float scale2, int lane, float* slotbuf, bool first,
-                                           u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
+                                           u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KR& nkr) {
   using T = Tile<D>;
   constexpr int KS = T::KSTEPS, N = NT * KS, PER = 16 / KS;
   static_assert(LDS_AHEAD <= N, "operand prefetch deeper than the wave's share of a chunk");
@@ -387,12 +413,12 @@ __device__ __forceinline__ void pass2_masked(const char* ldsK, const bf16x8 (&qr
 // out[0 .. Rpad).  The statistics of the last row group are handed back instead (returns true if
 // this thread holds one, for out[idx_out]): the caller stores them after it has moved the next
 // chunk's rows into LDS, so that the wait for those rows is not also a wait for the store.
-template <int D, int NRT>
+template <int D, int NRT, typename KR>
 __device__ __forceinline__ bool chunk_pass1(char* smem, const ScoreGeom& g, const QueryPos& qp,
                                             const uint16_t* __restrict__ qg,
                                             bf16x8 (&qreg)[Tile<D>::KSTEPS], bool reload, int j0, int tid, int lane,
                                             int wave, float2* __restrict__ out, int& idx_out, float2& mz_out,
-                                            u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
+                                            u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KR& nkr) {
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
   bool pending = false;
@@ -453,14 +479,14 @@ __device__ __forceinline__ bool chunk_pass1(char* smem, const ScoreGeom& g, cons
 // chunk's first and last 2*half rows are handed back as well (slot e_out of the chunk's edge
 // record, value r_out, when the function sets edge_out) and pool_boundaries_kernel pools those
 // keys from the records.  c points at the head's row constants.
-template <int D, int NRT>
+template <int D, int NRT, typename KR>
 __device__ __forceinline__ bool chunk_pass2(char* smem, const ScoreGeom& g, const QueryPos& qp, int half,
                                             bool edges,
                                             const uint16_t* __restrict__ qg, const float* __restrict__ c,
                                             bf16x8 (&qreg)[Tile<D>::KSTEPS], float (&cr)[16], bool reload, int j0,
                                             int tid, int lane, int wave, int& j_out, float& v_out,
                                             bool& pool_out, bool& edge_out, int& e_out, float& r_out,
-                                            u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KeyRows& nkr) {
+                                            u32x4 (&pre)[Tile<D>::PIECES_PER_THREAD], const KR& nkr) {
   using S = Smem<D, NRT>;
   constexpr int KSPLIT = WAVES / NRT, TPW = KTILES / KSPLIT;
   float* slots = reinterpret_cast<float*>(smem + S::OFF_SLOT);
@@ -580,9 +606,9 @@ struct StreamPlan {
   int dynamic;             // 1: the units from static_units * gridDim.x on are claimed through ctr
 };
 
-template <int D, int NRT, int PASS>
+template <int D, int NRT, int PASS, bool STRIDED>
 __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom g, QueryPos qp, int half,
-                                                                      StreamPlan plan,
+                                                                      StreamPlan plan, KvLayout lay,
                                                                       const uint16_t* __restrict__ q,
                                                             const uint16_t* __restrict__ k,
                                                             float2* __restrict__ part,
@@ -598,6 +624,17 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
   int run_end = min(run_u + plan.static_units, dyn0);
   if (run_u >= run_end) return;           // (host: never with a dynamic part, every workgroup has a first run)
 
+  // key rows of chunk c_ of head hg_ (STRIDED: `lay` gives the element strides between instances and
+  // heads and the byte distance between rows; otherwise the cache is dense and `lay` is not read)
+  auto rows_of = [&](int hg_, int c_) {
+    if constexpr (STRIDED) {
+      const int inst = hg_ / g.Hkv, head = hg_ - inst * g.Hkv;
+      return key_rows_strided<D>(k + (size_t)inst * lay.inst + (size_t)head * lay.head, c_ * MFMA_ROWS, g.L, tid,
+                                 lay.row_bytes);
+    } else {
+      return key_rows<D>(k + (size_t)hg_ * g.L * D, c_ * MFMA_ROWS, g.L, tid);
+    }
+  };
   u32x4 pre[Tile<D>::PIECES_PER_THREAD];
   bf16x8 qreg[Tile<D>::KSTEPS];
   float cr[16];
@@ -607,7 +644,7 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
   }
   {
     const int hg = run_u / units_per_head, c = run_u - hg * units_per_head;
-    fetch_chunk<D>(pre, key_rows<D>(k + (size_t)hg * g.L * D, c * MFMA_ROWS, g.L, tid));
+    fetch_chunk<D>(pre, rows_of(hg, c));
     commit_chunk<D>(smem, pre, tid);
   }
   __syncthreads();
@@ -658,7 +695,7 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
           cn = s - hn * units_per_head;
         }
       }
-      const KeyRows nkr = key_rows<D>(k + (size_t)hn * g.L * D, cn * MFMA_ROWS, g.L, tid);
+      const auto nkr = rows_of(hn, cn);
       bool owned = false, edge_out = false, pool_out = false;
       int j_out = 0, e_out = 0;
       float v_out = 0.f, r_out = 0.f;
@@ -748,9 +785,9 @@ __global__ __launch_bounds__(256) void pool_boundaries_kernel(int L, int P, int 
   scores[(size_t)hg * L + j] = v;
 }
 
-template <int D, int NRT>
-hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, int pool, const uint16_t* q, const uint16_t* k,
-                         float* scores, const Workspace& ws, hipStream_t st) {
+template <int D, int NRT, bool STRIDED>
+hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int pool, const uint16_t* q,
+                         const uint16_t* k, float* scores, const Workspace& ws, hipStream_t st) {
   constexpr int bytes = Smem<D, NRT>::BYTES;
   // workgroups each device holds at once, queried on the first call per device (host threads that
   // race here compute the same value)
@@ -760,8 +797,8 @@ hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, int pool, const
   if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
   if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   int resident = resident_of[dev].load(std::memory_order_acquire);
-  const void* f1 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 1>);
-  const void* f2 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 2>);
+  const void* f1 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 1, STRIDED>);
+  const void* f2 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 2, STRIDED>);
   if (resident == 0) {
     if ((e = hipFuncSetAttribute(f1, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(f2, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
@@ -803,7 +840,8 @@ hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, int pool, const
   const StreamPlan p1 = make_plan(nu1, units1, &grid1), p2 = make_plan(nu2, units2, &grid2);
   hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, ws.ctr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL((stream_kernel<D, NRT, 1>), dim3(grid1), dim3(THREADS), bytes, st, g, qp, 0, p1, q, k, ws.part,
+  hipLaunchKernelGGL((stream_kernel<D, NRT, 1, STRIDED>), dim3(grid1), dim3(THREADS), bytes, st, g, qp, 0, p1, lay, q, k,
+                     ws.part,
                      (const float*)nullptr, (float*)nullptr, ws.ctr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(row_constants_mfma_kernel, dim3((unsigned)n_heads, g.Rpad / 32), dim3(256), 0, st, gm, ws.part,
@@ -811,7 +849,7 @@ hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, int pool, const
   if ((e = hipGetLastError()) != hipSuccess) return e;
   // (the edge records, at most 124 floats per 256-key chunk and only written when a head has more
   // than one chunk, fit the workspace's raw-score area of L floats per head)
-  hipLaunchKernelGGL((stream_kernel<D, NRT, 2>), dim3(grid2), dim3(THREADS), bytes, st, g, qp, half, p2, q, k,
+  hipLaunchKernelGGL((stream_kernel<D, NRT, 2, STRIDED>), dim3(grid2), dim3(THREADS), bytes, st, g, qp, half, p2, lay, q, k,
                      reinterpret_cast<float2*>(ws.raw), ws.rowc, scores, ws.ctr + 1);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (half > 0 && units2 > 1) {
@@ -823,30 +861,33 @@ hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, int pool, const
   return hipSuccess;
 }
 
-template <int D>
-hipError_t launch_for_rows(const ScoreGeom& g, const QueryPos& qp, int pool, const uint16_t* q, const uint16_t* k,
-                           float* scores, const Workspace& ws, hipStream_t st) {
+template <int D, bool STRIDED>
+hipError_t launch_for_rows(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int pool, const uint16_t* q,
+                           const uint16_t* k, float* scores, const Workspace& ws, hipStream_t st) {
   const int ntile = g.Rpad / 32;
-  if (ntile == 1) return launch_stream<D, 1>(g, qp, pool, q, k, scores, ws, st);
-  if (ntile == 2) return launch_stream<D, 2>(g, qp, pool, q, k, scores, ws, st);
-  return launch_stream<D, 4>(g, qp, pool, q, k, scores, ws, st);
+  if (ntile == 1) return launch_stream<D, 1, STRIDED>(g, qp, lay, pool, q, k, scores, ws, st);
+  if (ntile == 2) return launch_stream<D, 2, STRIDED>(g, qp, lay, pool, q, k, scores, ws, st);
+  return launch_stream<D, 4, STRIDED>(g, qp, lay, pool, q, k, scores, ws, st);
 }
 
 }  // namespace
 
-bool score_mfma_supported(const ScoreGeom& g, int dtype) {
+bool score_mfma_supported(const ScoreGeom& g, const KvLayout& lay, int dtype) {
   // the key loads address a head with 31-bit byte offsets (one chunk of slack past its end)
   return dtype == LAQ_BF16 && (g.d == 128 || g.d == 64) && g.R >= 16 && g.W <= MAX_QPOS &&
-         g.n_inst * (long long)g.Hkv <= 0x7fffffff && ((long long)g.L + MFMA_ROWS) * g.d * 2 < 0x7fffffffLL;
+         g.n_inst * (long long)g.Hkv <= 0x7fffffff && ((long long)g.L + MFMA_ROWS) * lay.row_bytes < 0x7fffffffLL;
 }
 
-// scores: pooled with kernel `pool` (pool == 1: raw)
-hipError_t launch_score_mfma(const ScoreGeom& g, const QueryPos& qp, int pool, const void* q, const void* k,
-                             float* scores, const Workspace& ws, hipStream_t st) {
+hipError_t launch_score_mfma(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int pool, const void* q,
+                             const void* k, float* scores, const Workspace& ws, hipStream_t st) {
   const uint16_t* qq = static_cast<const uint16_t*>(q);
   const uint16_t* kk = static_cast<const uint16_t*>(k);
-  if (g.d == 128) return launch_for_rows<128>(g, qp, pool, qq, kk, scores, ws, st);
-  return launch_for_rows<64>(g, qp, pool, qq, kk, scores, ws, st);
+  if (lay.dense) {
+    if (g.d == 128) return launch_for_rows<128, false>(g, qp, lay, pool, qq, kk, scores, ws, st);
+    return launch_for_rows<64, false>(g, qp, lay, pool, qq, kk, scores, ws, st);
+  }
+  if (g.d == 128) return launch_for_rows<128, true>(g, qp, lay, pool, qq, kk, scores, ws, st);
+  return launch_for_rows<64, true>(g, qp, lay, pool, qq, kk, scores, ws, st);
 }
 
 }  // namespace laq

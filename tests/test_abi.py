@@ -47,7 +47,8 @@ def test_workspace_bytes_grows_with_shape():
 
 
 def _shape(**kw):
-    base = dict(n_inst=1, Hq=8, Hkv=2, d=128, L=512, W=8, dtype=1, scale=0.0, q_pos=None, keep=-1, pool_mode=0)
+    base = dict(n_inst=1, Hq=8, Hkv=2, d=128, L=512, W=8, dtype=1, scale=0.0, q_pos=None, keep=-1, pool_mode=0,
+                kv_stride_inst=0, kv_stride_head=0, kv_stride_row=0)
     base.update(kw)
     return binding._Shape(*[base[f] for f, _ in binding._Shape._fields_])
 
@@ -155,6 +156,25 @@ def test_decode_side_calls_are_checked_without_a_gpu():
     assert lib.laq_qcache_store(ctypes.byref(sh), fake, -1, fake, None) == INVALID
     assert lib.laq_qcache_store(ctypes.byref(sh), fake, 8, fake, None) == INVALID      # W = 8 slots: 0..7
     assert lib.laq_qcache_store(ctypes.byref(_shape(d=12)), fake, 0, fake, None) == INVALID
+
+
+def test_key_value_strides_are_checked_without_a_gpu():
+    lib = laq.load_library()
+    fake = ctypes.c_void_p(0x1000)
+    INVALID, WORKSPACE = -1, -3
+    bud = (ctypes.c_int32 * 1)(64)
+    token_major = _shape(kv_stride_inst=512 * 2 * 128, kv_stride_head=128, kv_stride_row=2 * 128)
+    assert lib.laq_score(ctypes.byref(token_major), fake, fake, 7, fake, fake, 16, None) == WORKSPACE     # accepted
+    for bad in (_shape(kv_stride_row=256),                                        # some strides zero, some not
+                _shape(kv_stride_inst=131072, kv_stride_head=128, kv_stride_row=64),     # rows overlap (< d)
+                _shape(kv_stride_inst=131072, kv_stride_head=100, kv_stride_row=256),    # not a 16-byte multiple
+                _shape(kv_stride_inst=-1, kv_stride_head=128, kv_stride_row=256)):
+        assert lib.laq_score(ctypes.byref(bad), fake, fake, 7, fake, fake, 1 << 30, None) == INVALID
+        assert lib.laq_compact(ctypes.byref(bad), fake, None, fake, bud, fake, None, None) == INVALID
+        assert lib.laq_evict(ctypes.byref(bad), fake, fake, fake, bud, 7, fake, fake, fake, fake, fake, 1 << 30,
+                             None) == INVALID
+    with pytest.raises(ValueError):
+        binding._kv(torch.zeros(1, 2, 8, 16)[..., ::2], "k")                      # host tensor is refused first
 
 
 def test_packed_rows():

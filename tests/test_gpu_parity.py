@@ -738,3 +738,65 @@ def test_more_instances_than_one_select_or_compact_launch_holds(laq):
     # scores of a sampled instance against the oracle end to end
     pooled = oracle.evict(q[256].cpu(), kc[256], vc[256], budgets[256], 7)[0]
     check_scores(sc[256], pooled, torch.bfloat16, "inst 256")
+
+
+# ---- key / value caches that are not dense [n, Hkv, L, d] ----
+def _token_major_view(t):
+    """The same values stored [n, L, Hkv, d], handed over as a strided [n, Hkv, L, d] view."""
+    return t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+
+
+def _padded_rows_view(t, pad=8):
+    """Rows stored with `pad` unused elements after each (row stride d + pad)."""
+    wide = torch.full(t.shape[:-1] + (t.shape[-1] + pad,), 7.0, dtype=t.dtype, device=t.device)
+    wide[..., :t.shape[-1]] = t
+    return wide[..., :t.shape[-1]]
+
+
+STRIDED = [
+    # name, dtype, Hq, Hkv, d, L, W, pool, budget
+    ("token-major-R32", torch.bfloat16, 8, 2, 128, 1000, 8, 7, 100),
+    ("token-major-R64-4k", torch.bfloat16, 16, 4, 128, 4096, 16, 7, 256),
+    ("token-major-R128", torch.bfloat16, 32, 8, 128, 1500, 32, 7, 200),
+    ("token-major-d64", torch.bfloat16, 8, 2, 64, 1500, 8, 7, 128),
+    ("token-major-one-chunk", torch.bfloat16, 8, 2, 128, 200, 8, 5, 64),
+    ("token-major-fp32-generic", torch.float32, 4, 2, 64, 500, 6, 3, 40),
+    ("token-major-R8-generic-bf16", torch.bfloat16, 2, 2, 128, 600, 4, 7, 50),
+]
+
+
+@pytest.mark.parametrize("name,dtype,Hq,Hkv,d,L,W,pool,budget", STRIDED, ids=[e[0] for e in STRIDED])
+def test_strided_caches_give_the_dense_bits(laq, name, dtype, Hq, Hkv, d, L, W, pool, budget):
+    q, k, v = _qkv(len(name) * 7 + L, 2, Hq, Hkv, d, L, W, dtype)
+    budgets = [budget, max(W, budget - 5)]
+    dense = laq.laq_evict(q, k, v, budgets, pool)
+    for how, view in (("token-major", _token_major_view), ("padded-rows", _padded_rows_view)):
+        print("case:", name, how, flush=True)
+        kv, vv = view(k), view(v)
+        assert not kv.is_contiguous() and torch.equal(kv, k)
+        got = laq.laq_evict(q, kv, vv, budgets, pool)
+        s3 = laq.laq_score(q, kv, pool)
+        k3, v3 = laq.laq_compact(kv, vv, dense[1], budgets, W)
+        torch.cuda.synchronize()
+        for a, b in zip(got, dense):
+            assert torch.equal(a, b), "%s %s" % (name, how)
+        assert torch.equal(s3, dense[0]) and torch.equal(k3, dense[2]) and torch.equal(v3, dense[3])
+
+
+def test_token_major_cache_against_the_oracle(laq):
+    q, k, v = _qkv(91, 2, 16, 4, 128, 2100, 16)
+    pos = [2100 - 8 + i for i in range(8)] + [2100 + i for i in range(8)]
+    run_general(laq, q, _token_major_view(k), _token_major_view(v), [128, 96], 7, pos, 8, "token-major-joined")
+    run_general(laq, q, _token_major_view(k), _token_major_view(v), [128, 96], 7, _trailing(2100, 16), 16,
+                "token-major-avg", pool_mode="avg")
+
+
+def test_token_major_full_size_sampled(laq):
+    # the 32k shape stored [n, L, Hkv, d]: rows of a head lie 2 KiB apart
+    n, Hq, Hkv, d, L, W = 2, 32, 8, 128, 32768, 32
+    gen = torch.Generator(device=DEV).manual_seed(17)
+    k_tm = torch.randn(n, L, Hkv, d, generator=gen, device=DEV).bfloat16()
+    v_tm = torch.randn(n, L, Hkv, d, generator=gen, device=DEV).bfloat16()
+    q = (torch.randn(n, Hq, W, d, generator=gen, device=DEV) * 1.5).bfloat16()
+    run_and_check(laq, q, k_tm.permute(0, 2, 1, 3), v_tm.permute(0, 2, 1, 3), [1024, 256], 7, "token-major-32k",
+                  heads=[6])
