@@ -22,8 +22,9 @@
  *     laq_shape).  `budget` is a HOST array.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work on it and return; the caller synchronises.
- *   - The library allocates and frees no device memory and keeps no state between
- *     calls; scratch memory comes in through `ws` (size from laq_workspace_bytes).
+ *   - The library allocates and frees no device memory and keeps no device state between
+ *     calls (on the host it remembers how many workgroups each device holds, looked up on
+ *     the first scoring call); scratch memory comes in through `ws` (laq_workspace_bytes).
  *   - Errors are reported by the return value (LAQ_OK = 0, negative otherwise), never
  *     by exception or abort.  Arguments are validated before anything is enqueued, so
  *     a call that returns LAQ_ERR_INVALID / _UNSUPPORTED / _WORKSPACE has done nothing.
