@@ -253,6 +253,21 @@ def main():
         "roofline": roofline,
     }
 
+    # quality probe in the spirit of Eq. 1-3 (untimed): how much of the selection made by all W window
+    # queries (placed after the prompt, nothing kept) is recovered by the first quarter of them
+    if args.window == "trailing" and cfg.W >= 4:
+        see_all = [cfg.L] * cfg.W
+        few = cfg.W // 4
+        gold = laq.laq_evict(q, k, v, budgets, cfg.pool, q_pos=see_all, keep=0, pool_mode=args.pool_mode)[1]
+        pred = laq.laq_evict(q[:, :, :few].contiguous(), k, v, budgets, cfg.pool, q_pos=see_all[:few], keep=0,
+                             pool_mode=args.pool_mode)[1]
+        _, rec = laq.laq_recall(pred, budgets, gold, budgets, cfg.Hkv, cfg.L)
+        torch.cuda.synchronize()
+        out["whole_path"]["recall_probe"] = {
+            "value": round(float(rec.mean().item()), 4),
+            "what": "mean over (instance, KV head) of |M_pred & M_gold| / |M_gold|: M_gold selected by all %d "
+                    "window queries, M_pred by the first %d, every query after the prompt, synthetic data" % (cfg.W, few)}
+
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
