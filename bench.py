@@ -55,9 +55,11 @@ def bench_decode(args, torch, laq, cfg, budgets, dev):
     vc = torch.randn(total, cfg.d, generator=gen, device=dev).to(dt)
     q = torch.randn(n, cfg.Hq, cfg.d, generator=gen, device=dev).to(dt)
     out_t = torch.empty(n, cfg.Hq, cfg.d, dtype=torch.float32, device=dev)
+    ws = torch.empty(max(16, laq.laq_decode_workspace_bytes(n, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, dt, budgets)),
+                     dtype=torch.uint8, device=dev)
 
     def step():
-        laq.laq_decode_attention(q, kc, vc, budgets, cfg.Hkv, cfg.L, out=out_t)
+        laq.laq_decode_attention(q, kc, vc, budgets, cfg.Hkv, cfg.L, out=out_t, ws=ws)
 
     for _ in range(args.warmup):
         step()
@@ -87,7 +89,7 @@ def bench_decode(args, torch, laq, cfg, budgets, dev):
                    "d": cfg.d, "L": cfg.L, "budget": cfg.budget, "packed_rows": total},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(workload),
-                     "kernel": "decode_kernel (K' and V' rows read once, q read, out written)",
+                     "kernel": "decode_kernel + merge_parts_kernel (K' and V' rows read once, q read, out written)",
                      "algorithmic_bytes_per_launch": ab, "ms_per_launch": round(ms_kernel, 4)},
     }
     if not args.no_cpu_baseline:

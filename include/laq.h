@@ -205,11 +205,18 @@ int laq_qcache_store(const laq_shape *shape, const void *q_step, int32_t t, void
  *   k_c, v_c   packed as laq_compact writes them: instance i holds [Hkv, Bk(i), d]
  *   budget     HOST array [n_inst], >= 1; Bk(i) = min(budget[i], L)
  *   out        fp32 [n_inst, Hq, d]
- * Reads n_inst, Hq, Hkv, d, L, dtype, scale of the shape.  Uses no workspace.  The merge of
- * partial sums follows a fixed order: two runs give identical bits.
+ *   ws / ws_bytes  optional device scratch (ws may be NULL).  With at least
+ *              laq_decode_workspace_bytes(shape, budget) bytes, a call with few instances and
+ *              heads spreads every cache of more than 512 rows over several workgroups and
+ *              merges their partial results; LAQ_ERR_WORKSPACE if ws is given but too small.
+ *              Without it every cache is read by one workgroup.
+ * Reads n_inst, Hq, Hkv, d, L, dtype, scale of the shape.  Partial sums are merged in a fixed
+ * order: two runs of the same call give identical bits (with and without ws the last bits of
+ * `out` may differ, the order of the sums being different).
  */
+size_t laq_decode_workspace_bytes(const laq_shape *shape, const int32_t *budget);
 int laq_decode_attention(const laq_shape *shape, const void *q, const void *k_c, const void *v_c,
-                         const int32_t *budget, float *out, void *stream);
+                         const int32_t *budget, float *out, void *ws, size_t ws_bytes, void *stream);
 
 /* Static description of an error code. */
 const char *laq_strerror(int code);

@@ -59,8 +59,10 @@ def load_library() -> ctypes.CDLL:
     lib.laq_select_sink_recent.argtypes = [i32, i32, i32, ctypes.POINTER(ctypes.c_int32), i32, vp, vp]
     lib.laq_select_sink_recent.restype = i32
     bp = ctypes.POINTER(ctypes.c_int32)
-    lib.laq_decode_attention.argtypes = [sp, vp, vp, vp, bp, vp, vp]
+    lib.laq_decode_attention.argtypes = [sp, vp, vp, vp, bp, vp, vp, sz, vp]
     lib.laq_decode_attention.restype = i32
+    lib.laq_decode_workspace_bytes.argtypes = [sp, bp]
+    lib.laq_decode_workspace_bytes.restype = sz
     lib.laq_qcache_store.argtypes = [sp, vp, i32, vp, vp]
     lib.laq_qcache_store.restype = i32
     lib.laq_recall.argtypes = [i32, i32, i32, vp, bp, vp, bp, vp, vp, vp]
@@ -265,9 +267,10 @@ def laq_qcache_store(q_cache: torch.Tensor, q_step: torch.Tensor, t: int, stream
 
 def laq_decode_attention(q: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, budget: Sequence[int],
                          Hkv: int, L: int, scale: float = 0.0, out: Optional[torch.Tensor] = None,
-                         stream=None) -> torch.Tensor:
+                         stream=None, ws: Optional[torch.Tensor] = None, split: bool = True) -> torch.Tensor:
     """q [n, Hq, d] and the packed k_c, v_c [rows, d] of laq_compact -> out [n, Hq, d] fp32: one new
-    token's attention over the retained rows of its KV head."""
+    token's attention over the retained rows of its KV head.  split: let the library spread long
+    caches over several workgroups (a workspace of laq_decode_workspace_bytes is made if ws is None)."""
     lib = load_library()
     _dev(q, "q"), _dev(k_c, "k_c"), _dev(v_c, "v_c")
     n, Hq, d = q.shape
@@ -277,11 +280,26 @@ def laq_decode_attention(q: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, 
     if out is None:
         out = torch.empty(n, Hq, d, dtype=torch.float32, device=q.device)
     sh = _shape(n, Hq, Hkv, d, L, 1, _dtype_code(q), scale, None, 0)
-    rc = lib.laq_decode_attention(ctypes.byref(sh), q.data_ptr(), k_c.data_ptr(), v_c.data_ptr(),
-                                  _budget_array(budget, n), out.data_ptr(), _stream(stream))
+    bud = _budget_array(budget, n)
+    if split and ws is None:
+        need = int(lib.laq_decode_workspace_bytes(ctypes.byref(sh), bud))
+        if need:
+            ws = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if not split:
+        ws = None
+    rc = lib.laq_decode_attention(ctypes.byref(sh), q.data_ptr(), k_c.data_ptr(), v_c.data_ptr(), bud, out.data_ptr(),
+                                  ws.data_ptr() if ws is not None else None,
+                                  ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream))
     if rc != 0:
         raise LaqError(rc, "laq_decode_attention")
     return out
+
+
+def laq_decode_workspace_bytes(n_inst: int, Hq: int, Hkv: int, d: int, L: int, dtype: torch.dtype,
+                               budget: Sequence[int]) -> int:
+    code = LAQ_F32 if dtype == torch.float32 else LAQ_BF16
+    sh = _shape(n_inst, Hq, Hkv, d, L, 1, code, 0.0, None, 0)
+    return int(load_library().laq_decode_workspace_bytes(ctypes.byref(sh), _budget_array(budget, n_inst)))
 
 
 def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, budget: Sequence[int], keep: int,

@@ -204,8 +204,39 @@ static int sink_recent_impl(int n_inst, int Hkv, int L, const int32_t* budget, i
   return LAQ_OK;
 }
 
+// Decode attention splits long caches over several workgroups when the call has few of them: a
+// cache of more than DECODE_SPLIT_ROWS rows becomes parts of at most that many rows, whose partial
+// results go through the workspace.  Without a workspace every cache is one part.
+constexpr int DECODE_SPLIT_ROWS = 512;
+constexpr int DECODE_SPLIT_BELOW_WORKGROUPS = 1024;
+
+static int decode_parts_of(const ScoreGeom& g, int bk, bool split) {
+  if (!split) return 1;
+  const int s = (bk + DECODE_SPLIT_ROWS - 1) / DECODE_SPLIT_ROWS;
+  return s < MAX_PARTS_PER_LAUNCH ? s : MAX_PARTS_PER_LAUNCH;
+}
+
+static bool decode_would_split(const laq_shape* shape, const ScoreGeom& g, const int32_t* budget) {
+  const int gb = decode_head_batch(g.Hq, g.Hkv), nbatch = (g.G + gb - 1) / gb;
+  if ((long long)g.Hkv * nbatch * g.n_inst >= DECODE_SPLIT_BELOW_WORKGROUPS) return false;
+  for (int i = 0; i < shape->n_inst; ++i)
+    if ((budget[i] < g.L ? budget[i] : g.L) > DECODE_SPLIT_ROWS) return true;
+  return false;
+}
+
+// bytes of partial results: one record of d + 2 floats per part, workgroup column and query-head slot,
+// for at most one launch's parts (launches reuse the area; they are ordered on the stream)
+static size_t decode_ws_bytes(const laq_shape* shape, const ScoreGeom& g, const int32_t* budget) {
+  if (!decode_would_split(shape, g, budget)) return 0;
+  long long parts = 0;
+  for (int i = 0; i < shape->n_inst; ++i) parts += decode_parts_of(g, budget[i] < g.L ? budget[i] : g.L, true);
+  if (parts > MAX_PARTS_PER_LAUNCH) parts = MAX_PARTS_PER_LAUNCH;
+  const int gb = decode_head_batch(g.Hq, g.Hkv), nbatch = (g.G + gb - 1) / gb;
+  return round256((size_t)parts * g.Hkv * nbatch * gb * (g.d + 2) * sizeof(float));
+}
+
 static int decode_impl(const laq_shape* shape, const void* q, const void* kc, const void* vc,
-                       const int32_t* budget, float* out, hipStream_t st) {
+                       const int32_t* budget, float* out, void* ws, size_t ws_bytes, hipStream_t st) {
   ScoreGeom g;
   const int rc = make_geom(shape, &g);
   if (rc != LAQ_OK) return rc;
@@ -213,16 +244,44 @@ static int decode_impl(const laq_shape* shape, const void* q, const void* kc, co
   for (int i = 0; i < shape->n_inst; ++i)
     if (budget[i] < 1) return LAQ_ERR_INVALID;
   if (g.Hkv > 65535) return LAQ_ERR_UNSUPPORTED;
+  const bool split = ws != nullptr && decode_would_split(shape, g, budget);
+  if (split && ws_bytes < decode_ws_bytes(shape, g, budget)) return LAQ_ERR_WORKSPACE;
+  float* partial = static_cast<float*>(ws);
+
+  DecodeParts tab;
+  int n_parts = 0;
+  bool any_split = false;
+  auto flush = [&]() -> bool {
+    if (n_parts == 0) return true;
+    if (launch_decode(n_parts, g.Hq, g.Hkv, g.d, shape->dtype, g.scale2, tab, q, kc, vc, out, partial, st) !=
+        hipSuccess)
+      return false;
+    if (any_split && launch_merge_parts(n_parts, g.Hq, g.Hkv, g.d, tab, partial, out, st) != hipSuccess) return false;
+    n_parts = 0;
+    any_split = false;
+    return true;
+  };
   int64_t row = 0;
-  for (int i0 = 0; i0 < shape->n_inst; i0 += MAX_INST_PER_LAUNCH) {
-    const int n = shape->n_inst - i0 < MAX_INST_PER_LAUNCH ? shape->n_inst - i0 : MAX_INST_PER_LAUNCH;
-    InstTable tab;
-    memset(&tab, 0, sizeof tab);
-    fill_table(g.Hkv, g.L, budget, i0, n, row, &tab, &row);
-    if (launch_decode(n, i0, g.Hq, g.Hkv, g.d, shape->dtype, g.scale2, tab, q, kc, vc, out, st) != hipSuccess)
-      return LAQ_ERR_DEVICE;
+  for (int i = 0; i < shape->n_inst; ++i) {
+    const int bk = budget[i] < g.L ? budget[i] : g.L;
+    const int S = decode_parts_of(g, bk, split);
+    if (n_parts + S > MAX_PARTS_PER_LAUNCH && !flush()) return LAQ_ERR_DEVICE;   // the parts of a cache stay together
+    const int per = (bk + S - 1) / S;
+    for (int p = 0; p < S; ++p) {
+      const int start = p * per;
+      tab.row0[n_parts] = row;
+      tab.bk[n_parts] = bk;
+      tab.start[n_parts] = start < bk ? start : bk;
+      tab.rows[n_parts] = start < bk ? (bk - start < per ? bk - start : per) : 0;
+      tab.inst[n_parts] = i;
+      tab.split[n_parts] = (int16_t)p;
+      tab.nsplit[n_parts] = (int16_t)S;
+      ++n_parts;
+    }
+    any_split = any_split || S > 1;
+    row += (int64_t)g.Hkv * bk;
   }
-  return LAQ_OK;
+  return flush() ? LAQ_OK : LAQ_ERR_DEVICE;
 }
 
 static int qcache_store_impl(const laq_shape* shape, const void* q_step, int t, void* q_cache, hipStream_t st) {
@@ -287,9 +346,17 @@ int laq_select_sink_recent(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t
   return laq::sink_recent_impl(n_inst, Hkv, L, budget, n_sink, idx, static_cast<hipStream_t>(stream));
 }
 
+size_t laq_decode_workspace_bytes(const laq_shape* shape, const int32_t* budget) {
+  laq::ScoreGeom g;
+  if (laq::make_geom(shape, &g) != LAQ_OK || !budget) return 0;
+  for (int i = 0; i < shape->n_inst; ++i)
+    if (budget[i] < 1) return 0;
+  return laq::decode_ws_bytes(shape, g, budget);
+}
+
 int laq_decode_attention(const laq_shape* shape, const void* q, const void* k_c, const void* v_c,
-                         const int32_t* budget, float* out, void* stream) {
-  return laq::decode_impl(shape, q, k_c, v_c, budget, out, static_cast<hipStream_t>(stream));
+                         const int32_t* budget, float* out, void* ws, size_t ws_bytes, void* stream) {
+  return laq::decode_impl(shape, q, k_c, v_c, budget, out, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 int laq_qcache_store(const laq_shape* shape, const void* q_step, int32_t t, void* q_cache, void* stream) {

@@ -63,25 +63,28 @@ template <> struct PieceOf<uint16_t> { using type = Piece8BF16; };
 
 // LDS layout: m[DEC_WAVES][GB], z[DEC_WAVES][GB], acc[DEC_WAVES][GB][d].  DEC_ROWS: rows per lane
 // group and turn.  PREFETCH: the next turn's rows are requested before the current turn's
-// arithmetic (more registers, fewer resident waves).
+// arithmetic (more registers, fewer resident waves).  A workgroup works on one part of a cache
+// (blockIdx.y): the whole cache writes `out`; one of several parts writes its unnormalised sums
+// O[d], then M and Z, per query head, to partial[part][blockIdx.x][g][d + 2] for merge_parts_kernel.
 template <int GB, typename T, int DEC_THREADS, int DEC_ROWS, bool PREFETCH, int PP>
 __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(int Hq, int Hkv, int d, float scale2,
-                                                             InstTable tab, int inst0, const T* __restrict__ q,
+                                                             DecodeParts tab, const T* __restrict__ q,
                                                              const T* __restrict__ kc, const T* __restrict__ vc,
-                                                             float* __restrict__ out) {
+                                                             float* __restrict__ out, float* __restrict__ partial) {
   using Piece = typename PieceOf<T>::type;
   constexpr int DEC_WAVES = DEC_THREADS / 64;
   constexpr int pp = PP;                   // lanes per row
   extern __shared__ float sm[];
   const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
   const int head = blockIdx.x / nbatch, g0 = (blockIdx.x % nbatch) * GB;
-  const int li = blockIdx.y, inst = inst0 + li;
-  const int bk = tab.bk[li];
+  const int li = blockIdx.y, inst = tab.inst[li];
+  const int bk = tab.rows[li];             // rows of this part
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int dc = tid % pp, ks = tid / pp, nks = DEC_THREADS / pp;
   const bool active = dc * 8 < d;
-  const T* K = kc + (tab.row0[li] + (int64_t)head * bk) * d + dc * 8;
-  const T* V = vc + (tab.row0[li] + (int64_t)head * bk) * d + dc * 8;
+  const int64_t first_row = tab.row0[li] + (int64_t)head * tab.bk[li] + tab.start[li];
+  const T* K = kc + first_row * d + dc * 8;
+  const T* V = vc + first_row * d + dc * 8;
 
   float qv[GB][8], acc[GB][8], m[GB], z[GB];
 #pragma unroll
@@ -219,7 +222,42 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(int Hq, int Hkv, in
       Z = fmaf(sm_z[w * GB + g], wgt, Z);
       O = fmaf(sm_acc[((size_t)w * GB + g) * d + c], wgt, O);
     }
-    out[((size_t)inst * Hq + (size_t)head * G + g0 + g) * d + c] = O / Z;
+    if (tab.nsplit[li] == 1) {
+      out[((size_t)inst * Hq + (size_t)head * G + g0 + g) * d + c] = O / Z;
+    } else {
+      float* rec = partial + (((size_t)li * gridDim.x + blockIdx.x) * GB + g) * (d + 2);
+      rec[c] = O;
+      if (c == 0) {
+        rec[d] = M;
+        rec[d + 1] = Z;
+      }
+    }
+  }
+}
+
+// out[inst][h] from the parts of a cache that was split: the part records are merged in part
+// order.  blockIdx.x = query head, blockIdx.y = part; the workgroup of a cache's first part does
+// the work (the parts of a cache are consecutive entries of the table).
+__global__ __launch_bounds__(128) void merge_parts_kernel(int Hq, int Hkv, int d, int gb, int blocks_x,
+                                                          DecodeParts tab, const float* __restrict__ partial,
+                                                          float* __restrict__ out) {
+  const int li = blockIdx.y, h = blockIdx.x;
+  const int S = tab.nsplit[li];
+  if (S == 1 || tab.split[li] != 0) return;
+  const int G = Hq / Hkv, nbatch = (G + gb - 1) / gb;
+  const int head = h / G, gq = h - head * G;
+  const int x = head * nbatch + gq / gb, g = gq % gb;
+  const size_t rec_floats = (size_t)(d + 2), part_floats = (size_t)blocks_x * gb * rec_floats;
+  const float* rec0 = partial + ((size_t)li * blocks_x + x) * gb * rec_floats + (size_t)g * rec_floats;
+  float M = DEC_NEG_BIG;
+  for (int s2 = 0; s2 < S; ++s2) M = fmaxf(M, rec0[s2 * part_floats + d]);
+  float Z = 0.f;
+  for (int s2 = 0; s2 < S; ++s2) Z = fmaf(rec0[s2 * part_floats + d + 1], __builtin_amdgcn_exp2f(rec0[s2 * part_floats + d] - M), Z);
+  for (int c = threadIdx.x; c < d; c += 128) {
+    float O = 0.f;
+    for (int s2 = 0; s2 < S; ++s2)
+      O = fmaf(rec0[s2 * part_floats + c], __builtin_amdgcn_exp2f(rec0[s2 * part_floats + d] - M), O);
+    out[((size_t)tab.inst[li] * Hq + h) * d + c] = O / Z;
   }
 }
 
@@ -235,52 +273,65 @@ __global__ __launch_bounds__(256) void qcache_store_kernel(long long rows, int W
 }
 
 template <int GB, typename T, int THREADS, int ROWS, bool PREFETCH, int PP>
-hipError_t launch_decode_pp(int n_inst, int inst0, int Hq, int Hkv, int d, float scale2, const InstTable& tab,
-                            const void* q, const void* kc, const void* vc, float* out, hipStream_t st) {
+hipError_t launch_decode_pp(int n_parts, int Hq, int Hkv, int d, float scale2, const DecodeParts& tab, const void* q,
+                            const void* kc, const void* vc, float* out, float* partial, hipStream_t st) {
   const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
   const size_t lds = (size_t)(THREADS / 64) * GB * (d + 2) * sizeof(float);
-  hipLaunchKernelGGL((decode_kernel<GB, T, THREADS, ROWS, PREFETCH, PP>), dim3(Hkv * nbatch, n_inst), dim3(THREADS), lds,
-                     st, Hq, Hkv, d, scale2, tab, inst0, static_cast<const T*>(q), static_cast<const T*>(kc),
-                     static_cast<const T*>(vc), out);
+  hipLaunchKernelGGL((decode_kernel<GB, T, THREADS, ROWS, PREFETCH, PP>), dim3(Hkv * nbatch, n_parts), dim3(THREADS), lds,
+                     st, Hq, Hkv, d, scale2, tab, static_cast<const T*>(q), static_cast<const T*>(kc),
+                     static_cast<const T*>(vc), out, partial);
   return hipGetLastError();
 }
 
 // lanes per row: the power of two (at least 8) that covers the row's d / 8 pieces
 template <int GB, typename T, int THREADS, int ROWS, bool PREFETCH>
-hipError_t launch_decode_as(int n_inst, int inst0, int Hq, int Hkv, int d, float scale2, const InstTable& tab,
-                            const void* q, const void* kc, const void* vc, float* out, hipStream_t st) {
+hipError_t launch_decode_as(int n_parts, int Hq, int Hkv, int d, float scale2, const DecodeParts& tab, const void* q,
+                            const void* kc, const void* vc, float* out, float* partial, hipStream_t st) {
   if (d <= 64)
-    return launch_decode_pp<GB, T, THREADS, ROWS, PREFETCH, 8>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+    return launch_decode_pp<GB, T, THREADS, ROWS, PREFETCH, 8>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
   if (d <= 128)
-    return launch_decode_pp<GB, T, THREADS, ROWS, PREFETCH, 16>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
-  return launch_decode_pp<GB, T, THREADS, ROWS, PREFETCH, 32>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+    return launch_decode_pp<GB, T, THREADS, ROWS, PREFETCH, 16>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
+  return launch_decode_pp<GB, T, THREADS, ROWS, PREFETCH, 32>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
 }
 
 // Few workgroups (long caches, few heads): large workgroups that keep two turns of rows in flight.
-// Many workgroups: small ones without the second set of row registers, so that more of them are
-// resident at once.
+// Many workgroups, or caches cut into parts (short row ranges, several parts per compute unit):
+// small ones without the second set of row registers, so that more of them are resident at once.
 template <int GB, typename T>
-hipError_t launch_decode_for(int n_inst, int inst0, int Hq, int Hkv, int d, float scale2, const InstTable& tab,
-                             const void* q, const void* kc, const void* vc, float* out, hipStream_t st) {
+hipError_t launch_decode_for(int n_parts, int Hq, int Hkv, int d, float scale2, const DecodeParts& tab, const void* q,
+                             const void* kc, const void* vc, float* out, float* partial, hipStream_t st) {
   const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
-  if ((long long)Hkv * nbatch * n_inst >= DEC_MANY_WORKGROUPS)
-    return launch_decode_as<GB, T, 256, 4, false>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
-  return launch_decode_as<GB, T, 512, (sizeof(T) == 2 ? 8 : 4), true>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+  if ((long long)Hkv * nbatch * n_parts >= DEC_MANY_WORKGROUPS || tab.nsplit[0] > 1 || tab.nsplit[n_parts - 1] > 1)
+    return launch_decode_as<GB, T, 256, 4, false>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
+  return launch_decode_as<GB, T, 512, (sizeof(T) == 2 ? 8 : 4), true>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
 }
 
 }  // namespace
 
-hipError_t launch_decode(int n_inst, int inst0, int Hq, int Hkv, int d, int dtype, float scale2, const InstTable& tab,
-                         const void* q, const void* kc, const void* vc, float* out, hipStream_t st) {
+int decode_head_batch(int Hq, int Hkv) {
+  const int G = Hq / Hkv;
+  return G == 1 ? 1 : (G == 2 ? 2 : 4);
+}
+
+hipError_t launch_merge_parts(int n_parts, int Hq, int Hkv, int d, const DecodeParts& tab, const float* partial,
+                              float* out, hipStream_t st) {
+  const int gb = decode_head_batch(Hq, Hkv), G = Hq / Hkv, nbatch = (G + gb - 1) / gb;
+  hipLaunchKernelGGL(merge_parts_kernel, dim3(Hq, n_parts), dim3(128), 0, st, Hq, Hkv, d, gb, Hkv * nbatch, tab, partial,
+                     out);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode(int n_parts, int Hq, int Hkv, int d, int dtype, float scale2, const DecodeParts& tab,
+                         const void* q, const void* kc, const void* vc, float* out, float* partial, hipStream_t st) {
   const int G = Hq / Hkv;
   if (dtype == LAQ_BF16) {
-    if (G == 1) return launch_decode_for<1, uint16_t>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
-    if (G == 2) return launch_decode_for<2, uint16_t>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
-    return launch_decode_for<4, uint16_t>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+    if (G == 1) return launch_decode_for<1, uint16_t>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
+    if (G == 2) return launch_decode_for<2, uint16_t>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
+    return launch_decode_for<4, uint16_t>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
   }
-  if (G == 1) return launch_decode_for<1, float>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
-  if (G == 2) return launch_decode_for<2, float>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
-  return launch_decode_for<4, float>(n_inst, inst0, Hq, Hkv, d, scale2, tab, q, kc, vc, out, st);
+  if (G == 1) return launch_decode_for<1, float>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
+  if (G == 2) return launch_decode_for<2, float>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
+  return launch_decode_for<4, float>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
 }
 
 hipError_t launch_qcache_store(long long rows, int W, int t, int row_bytes, const void* q_step, void* q_cache,

@@ -102,6 +102,19 @@ struct PairTable {
   int64_t row_a[MAX_PAIR_PER_LAUNCH], row_b[MAX_PAIR_PER_LAUNCH];     // first packed row of the instance
 };
 
+// Parts of compacted caches for decode attention, up to MAX_PARTS_PER_LAUNCH per launch: a cache
+// is one part, or several consecutive ones that are merged afterwards.
+constexpr int MAX_PARTS_PER_LAUNCH = 128;
+struct DecodeParts {
+  int64_t row0[MAX_PARTS_PER_LAUNCH];   // first packed row of the instance
+  int32_t bk[MAX_PARTS_PER_LAUNCH];     // rows per KV head of the instance
+  int32_t start[MAX_PARTS_PER_LAUNCH];  // first row of the part within a head's rows
+  int32_t rows[MAX_PARTS_PER_LAUNCH];   // rows of the part
+  int32_t inst[MAX_PARTS_PER_LAUNCH];   // instance
+  int16_t split[MAX_PARTS_PER_LAUNCH];  // index of the part within its cache
+  int16_t nsplit[MAX_PARTS_PER_LAUNCH]; // parts of its cache
+};
+
 // launchers (each returns hipGetLastError() after its last launch); `raw` receives unpooled scores
 hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int dtype, const void* q,
                                 const void* k, float* raw, const Workspace& ws, hipStream_t st);
@@ -116,8 +129,11 @@ hipError_t launch_sink_recent(int n_inst, int Hkv, int L, int n_sink, const Inst
                               hipStream_t st);
 hipError_t launch_recall(int n_inst, int inst0, int Hkv, const PairTable& tab, const int32_t* idx_pred,
                          const int32_t* idx_gold, int32_t* overlap, float* recall, hipStream_t st);
-hipError_t launch_decode(int n_inst, int inst0, int Hq, int Hkv, int d, int dtype, float scale2, const InstTable& tab,
-                         const void* q, const void* kc, const void* vc, float* out, hipStream_t st);
+int decode_head_batch(int Hq, int Hkv);   // query heads of a KV head that one decode workgroup serves
+hipError_t launch_decode(int n_parts, int Hq, int Hkv, int d, int dtype, float scale2, const DecodeParts& tab,
+                         const void* q, const void* kc, const void* vc, float* out, float* partial, hipStream_t st);
+hipError_t launch_merge_parts(int n_parts, int Hq, int Hkv, int d, const DecodeParts& tab, const float* partial,
+                              float* out, hipStream_t st);
 hipError_t launch_qcache_store(long long rows, int W, int t, int row_bytes, const void* q_step, void* q_cache,
                                hipStream_t st);
 hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, const KvLayout& lay, int bk_max,

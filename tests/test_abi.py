@@ -20,7 +20,7 @@ def declared_functions(repo_root):
 def test_library_exports_every_declared_symbol(repo_root):
     lib = laq.load_library()
     names = declared_functions(repo_root)
-    assert names == ["laq_compact", "laq_decode_attention", "laq_evict", "laq_qcache_store", "laq_recall", "laq_score", "laq_select", "laq_select_sink_recent",
+    assert names == ["laq_compact", "laq_decode_attention", "laq_decode_workspace_bytes", "laq_evict", "laq_qcache_store", "laq_recall", "laq_score", "laq_select", "laq_select_sink_recent",
                      "laq_strerror", "laq_workspace_bytes"]
     for n in names:
         assert getattr(lib, n) is not None
@@ -145,12 +145,18 @@ def test_decode_side_calls_are_checked_without_a_gpu():
     INVALID = -1
     bud = (ctypes.c_int32 * 1)(64)
     sh = _shape(keep=0)
-    assert lib.laq_decode_attention(ctypes.byref(sh), None, fake, fake, bud, fake, None) == INVALID
-    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, None, bud, fake, None) == INVALID
-    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, fake, None, fake, None) == INVALID
-    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, fake, bud, None, None) == INVALID
-    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, fake, (ctypes.c_int32 * 1)(0), fake, None) == INVALID
-    assert lib.laq_decode_attention(ctypes.byref(_shape(Hq=7)), fake, fake, fake, bud, fake, None) == INVALID
+    assert lib.laq_decode_attention(ctypes.byref(sh), None, fake, fake, bud, fake, None, 0, None) == INVALID
+    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, None, bud, fake, None, 0, None) == INVALID
+    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, fake, None, fake, None, 0, None) == INVALID
+    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, fake, bud, None, None, 0, None) == INVALID
+    assert lib.laq_decode_attention(ctypes.byref(sh), fake, fake, fake, (ctypes.c_int32 * 1)(0), fake, None, 0, None) == INVALID
+    assert lib.laq_decode_attention(ctypes.byref(_shape(Hq=7)), fake, fake, fake, bud, fake, None, 0, None) == INVALID
+    # a cache of more than 512 rows in a small call wants a workspace; one that is too small is refused
+    long_bud = (ctypes.c_int32 * 1)(2048)
+    big = _shape(keep=0, L=4096)
+    need = lib.laq_decode_workspace_bytes(ctypes.byref(big), long_bud)
+    assert need > 0 and lib.laq_decode_workspace_bytes(ctypes.byref(big), bud) == 0
+    assert lib.laq_decode_attention(ctypes.byref(big), fake, fake, fake, long_bud, fake, fake, need - 1, None) == -3
     assert lib.laq_qcache_store(ctypes.byref(sh), None, 0, fake, None) == INVALID
     assert lib.laq_qcache_store(ctypes.byref(sh), fake, 0, None, None) == INVALID
     assert lib.laq_qcache_store(ctypes.byref(sh), fake, -1, fake, None) == INVALID

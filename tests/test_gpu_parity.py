@@ -800,3 +800,30 @@ def test_token_major_full_size_sampled(laq):
     q = (torch.randn(n, Hq, W, d, generator=gen, device=DEV) * 1.5).bfloat16()
     run_and_check(laq, q, k_tm.permute(0, 2, 1, 3), v_tm.permute(0, 2, 1, 3), [1024, 256], 7, "token-major-32k",
                   heads=[6])
+
+
+def test_decode_with_and_without_splitting_long_caches(laq):
+    # 40 caches of up to 2300 rows in a small call: 150 parts, i.e. two launches of the part table;
+    # both ways of summing must meet the oracle's bound, and a repeated call gives the same bits
+    n, Hq, Hkv, d, L = 40, 8, 2, 128, 2300
+    budgets = [300 + 50 * i for i in range(n)]
+    g = torch.Generator().manual_seed(12)
+    total, _ = laq.packed_rows(budgets, Hkv, L)
+    q = (torch.randn(n, Hq, d, generator=g) * 1.5).bfloat16()
+    kc = torch.randn(total, d, generator=g).bfloat16()
+    vc = torch.randn(total, d, generator=g).bfloat16()
+    need = laq.laq_decode_workspace_bytes(n, Hq, Hkv, d, L, torch.bfloat16, budgets)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    a = laq.laq_decode_attention(q.to(DEV), kc.to(DEV), vc.to(DEV), budgets, Hkv, L, ws=ws)
+    a2 = laq.laq_decode_attention(q.to(DEV), kc.to(DEV), vc.to(DEV), budgets, Hkv, L, ws=ws)
+    b = laq.laq_decode_attention(q.to(DEV), kc.to(DEV), vc.to(DEV), budgets, Hkv, L, split=False)
+    torch.cuda.synchronize()
+    assert torch.equal(a, a2)
+    k_l, v_l = split_packed(kc, budgets, Hkv, L), split_packed(vc, budgets, Hkv, L)
+    for i in (0, 4, 5, 17, 33, 34, 39):
+        for got, how in ((a, "split"), (b, "one workgroup per cache")):
+            check_decode(got[i].cpu(), q[i], k_l[i].contiguous(), v_l[i].contiguous(), torch.bfloat16,
+                         "%s inst %d" % (how, i))
+    # many workgroups already: no splitting, no workspace wanted
+    assert laq.laq_decode_workspace_bytes(256, 32, 8, 128, 32768, torch.bfloat16, [2048] * 256) == 0
