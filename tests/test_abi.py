@@ -194,3 +194,12 @@ def test_binding_refuses_host_tensors():
     k = torch.zeros(1, 2, 512, 128, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         laq.laq_score(q, k, 7)
+
+
+def test_bench_refuses_more_than_one_gpu(repo_root):
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(repo_root, "bench.py"), "--gpus", "2"], capture_output=True,
+                         text=True, timeout=120)
+    assert res.returncode == 2
+    assert "single-GPU" in res.stderr and res.stdout.strip() == ""
