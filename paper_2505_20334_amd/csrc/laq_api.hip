@@ -247,6 +247,22 @@ static int decode_impl(const laq_shape* shape, const void* q, const void* kc, co
   const bool split = ws != nullptr && decode_would_split(shape, g, budget);
   if (split && ws_bytes < decode_ws_bytes(shape, g, budget)) return LAQ_ERR_WORKSPACE;
   float* partial = static_cast<float*>(ws);
+  if (!split) {                                      // every cache is one part: tables of whole instances
+    int64_t row = 0;
+    for (int i0 = 0; i0 < shape->n_inst; i0 += MAX_INST_PER_LAUNCH) {
+      const int n = shape->n_inst - i0 < MAX_INST_PER_LAUNCH ? shape->n_inst - i0 : MAX_INST_PER_LAUNCH;
+      DecodeWhole whole;
+      whole.inst0 = i0;
+      for (int i = 0; i < n; ++i) {
+        whole.bk[i] = budget[i0 + i] < g.L ? budget[i0 + i] : g.L;
+        whole.row0[i] = row;
+        row += (int64_t)g.Hkv * whole.bk[i];
+      }
+      if (launch_decode(n, g.Hq, g.Hkv, g.d, shape->dtype, g.scale2, whole, q, kc, vc, out, st) != hipSuccess)
+        return LAQ_ERR_DEVICE;
+    }
+    return LAQ_OK;
+  }
 
   DecodeParts tab;
   int n_parts = 0;

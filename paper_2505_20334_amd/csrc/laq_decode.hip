@@ -57,6 +57,25 @@ __device__ __forceinline__ float group_sum(float x) {
   return x;
 }
 
+// Product of two 8-element pieces.  bf16: four two-element dot-product instructions on the raw
+// pairs (products and sums in fp32), no widening; fp32: eight fused multiply-adds.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc, false);
+}
+__device__ __forceinline__ float dot8(const Piece8BF16& a, const Piece8BF16& b) {
+  float s = dot2_bf16(a.r.x, b.r.x, 0.f);
+  s = dot2_bf16(a.r.y, b.r.y, s);
+  s = dot2_bf16(a.r.z, b.r.z, s);
+  return dot2_bf16(a.r.w, b.r.w, s);
+}
+__device__ __forceinline__ float dot8(const Piece8F32& a, const Piece8F32& b) {
+  float s = a.a.x * b.a.x;
+  s = fmaf(a.a.y, b.a.y, s); s = fmaf(a.a.z, b.a.z, s); s = fmaf(a.a.w, b.a.w, s);
+  s = fmaf(a.b.x, b.b.x, s); s = fmaf(a.b.y, b.b.y, s); s = fmaf(a.b.z, b.b.z, s);
+  return fmaf(a.b.w, b.b.w, s);
+}
+
 template <typename T> struct PieceOf;
 template <> struct PieceOf<float> { using type = Piece8F32; };
 template <> struct PieceOf<uint16_t> { using type = Piece8BF16; };
@@ -66,9 +85,9 @@ template <> struct PieceOf<uint16_t> { using type = Piece8BF16; };
 // arithmetic (more registers, fewer resident waves).  A workgroup works on one part of a cache
 // (blockIdx.y): the whole cache writes `out`; one of several parts writes its unnormalised sums
 // O[d], then M and Z, per query head, to partial[part][blockIdx.x][g][d + 2] for merge_parts_kernel.
-template <int GB, typename T, int DEC_THREADS, int DEC_ROWS, bool PREFETCH, int PP>
+template <int GB, typename T, int DEC_THREADS, int DEC_ROWS, bool PREFETCH, int PP, typename TAB>
 __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(int Hq, int Hkv, int d, float scale2,
-                                                             DecodeParts tab, const T* __restrict__ q,
+                                                             TAB tab, const T* __restrict__ q,
                                                              const T* __restrict__ kc, const T* __restrict__ vc,
                                                              float* __restrict__ out, float* __restrict__ partial) {
   using Piece = typename PieceOf<T>::type;
@@ -77,29 +96,25 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(int Hq, int Hkv, in
   extern __shared__ float sm[];
   const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
   const int head = blockIdx.x / nbatch, g0 = (blockIdx.x % nbatch) * GB;
-  const int li = blockIdx.y, inst = tab.inst[li];
-  const int bk = tab.rows[li];             // rows of this part
+  const int li = blockIdx.y, inst = tab.inst_of(li);
+  const int bk = tab.part_rows(li);        // rows of this part
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int dc = tid % pp, ks = tid / pp, nks = DEC_THREADS / pp;
   const bool active = dc * 8 < d;
-  const int64_t first_row = tab.row0[li] + (int64_t)head * tab.bk[li] + tab.start[li];
+  const int64_t first_row = tab.base_row(li) + (int64_t)head * tab.cache_rows(li) + tab.first_row(li);
   const T* K = kc + first_row * d + dc * 8;
   const T* V = vc + first_row * d + dc * 8;
 
-  float qv[GB][8], acc[GB][8], m[GB], z[GB];
+  Piece qv[GB];                            // this lane's 8 elements of every query of the batch
+  float acc[GB][8], m[GB], z[GB];
 #pragma unroll
   for (int g = 0; g < GB; ++g) {
     m[g] = DEC_NEG_BIG;
     z[g] = 0.f;
 #pragma unroll
-    for (int c = 0; c < 8; ++c) qv[g][c] = acc[g][c] = 0.f;
-    if (active && g0 + g < G) {
-      Piece qp;
-      fetch8(q + ((size_t)inst * Hq + (size_t)head * G + g0 + g) * d + dc * 8, qp);
-      widen8(qp, qv[g]);
-#pragma unroll
-      for (int c = 0; c < 8; ++c) qv[g][c] *= scale2;      // logits in base-2 units
-    }
+    for (int c = 0; c < 8; ++c) acc[g][c] = 0.f;
+    clear8(qv[g]);
+    if (active && g0 + g < G) fetch8(q + ((size_t)inst * Hq + (size_t)head * G + g0 + g) * d + dc * 8, qv[g]);
   }
 
   const int turns = ((bk + nks - 1) / nks + DEC_ROWS - 1) / DEC_ROWS;
@@ -127,21 +142,14 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(int Hq, int Hkv, in
     float s[DEC_ROWS][GB];
 #pragma unroll
     for (int u = 0; u < DEC_ROWS; ++u) {
-      float kf[8];
-      widen8(kp[u], kf);
 #pragma unroll
-      for (int g = 0; g < GB; ++g) {
-        float dot = 0.f;
-#pragma unroll
-        for (int c = 0; c < 8; ++c) dot = fmaf(qv[g][c], kf[c], dot);
-        s[u][g] = dot;
-      }
+      for (int g = 0; g < GB; ++g) s[u][g] = dot8(qv[g], kp[u]);
     }
-    // every lane of a group gets the complete logits of the group's rows
+    // every lane of a group gets the complete logits of the group's rows, in base-2 units
 #pragma unroll
     for (int u = 0; u < DEC_ROWS; ++u)
 #pragma unroll
-      for (int g = 0; g < GB; ++g) s[u][g] = group_sum<PP>(s[u][g]);
+      for (int g = 0; g < GB; ++g) s[u][g] = group_sum<PP>(s[u][g]) * scale2;
     float p[DEC_ROWS][GB];
 #pragma unroll
     for (int g = 0; g < GB; ++g) {
@@ -222,7 +230,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_kernel(int Hq, int Hkv, in
       Z = fmaf(sm_z[w * GB + g], wgt, Z);
       O = fmaf(sm_acc[((size_t)w * GB + g) * d + c], wgt, O);
     }
-    if (tab.nsplit[li] == 1) {
+    if (tab.parts(li) == 1) {
       out[((size_t)inst * Hq + (size_t)head * G + g0 + g) * d + c] = O / Z;
     } else {
       float* rec = partial + (((size_t)li * gridDim.x + blockIdx.x) * GB + g) * (d + 2);
@@ -272,20 +280,20 @@ __global__ __launch_bounds__(256) void qcache_store_kernel(long long rows, int W
   q_cache[(row * W + t) * pieces + piece] = q_step[i];
 }
 
-template <int GB, typename T, int THREADS, int ROWS, bool PREFETCH, int PP>
-hipError_t launch_decode_pp(int n_parts, int Hq, int Hkv, int d, float scale2, const DecodeParts& tab, const void* q,
+template <int GB, typename T, int THREADS, int ROWS, bool PREFETCH, int PP, typename TAB>
+hipError_t launch_decode_pp(int n_parts, int Hq, int Hkv, int d, float scale2, const TAB& tab, const void* q,
                             const void* kc, const void* vc, float* out, float* partial, hipStream_t st) {
   const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
   const size_t lds = (size_t)(THREADS / 64) * GB * (d + 2) * sizeof(float);
-  hipLaunchKernelGGL((decode_kernel<GB, T, THREADS, ROWS, PREFETCH, PP>), dim3(Hkv * nbatch, n_parts), dim3(THREADS), lds,
+  hipLaunchKernelGGL((decode_kernel<GB, T, THREADS, ROWS, PREFETCH, PP, TAB>), dim3(Hkv * nbatch, n_parts), dim3(THREADS), lds,
                      st, Hq, Hkv, d, scale2, tab, static_cast<const T*>(q), static_cast<const T*>(kc),
                      static_cast<const T*>(vc), out, partial);
   return hipGetLastError();
 }
 
 // lanes per row: the power of two (at least 8) that covers the row's d / 8 pieces
-template <int GB, typename T, int THREADS, int ROWS, bool PREFETCH>
-hipError_t launch_decode_as(int n_parts, int Hq, int Hkv, int d, float scale2, const DecodeParts& tab, const void* q,
+template <int GB, typename T, int THREADS, int ROWS, bool PREFETCH, typename TAB>
+hipError_t launch_decode_as(int n_parts, int Hq, int Hkv, int d, float scale2, const TAB& tab, const void* q,
                             const void* kc, const void* vc, float* out, float* partial, hipStream_t st) {
   if (d <= 64)
     return launch_decode_pp<GB, T, THREADS, ROWS, PREFETCH, 8>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
@@ -297,11 +305,11 @@ hipError_t launch_decode_as(int n_parts, int Hq, int Hkv, int d, float scale2, c
 // Few workgroups (long caches, few heads): large workgroups that keep two turns of rows in flight.
 // Many workgroups, or caches cut into parts (short row ranges, several parts per compute unit):
 // small ones without the second set of row registers, so that more of them are resident at once.
-template <int GB, typename T>
-hipError_t launch_decode_for(int n_parts, int Hq, int Hkv, int d, float scale2, const DecodeParts& tab, const void* q,
+template <int GB, typename T, typename TAB>
+hipError_t launch_decode_for(int n_parts, int Hq, int Hkv, int d, float scale2, const TAB& tab, const void* q,
                              const void* kc, const void* vc, float* out, float* partial, hipStream_t st) {
   const int G = Hq / Hkv, nbatch = (G + GB - 1) / GB;
-  if ((long long)Hkv * nbatch * n_parts >= DEC_MANY_WORKGROUPS || tab.nsplit[0] > 1 || tab.nsplit[n_parts - 1] > 1)
+  if ((long long)Hkv * nbatch * n_parts >= DEC_MANY_WORKGROUPS || tab.parts(0) > 1 || tab.parts(n_parts - 1) > 1)
     return launch_decode_as<GB, T, 256, 4, false>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
   return launch_decode_as<GB, T, 512, (sizeof(T) == 2 ? 8 : 4), true>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
 }
@@ -321,8 +329,10 @@ hipError_t launch_merge_parts(int n_parts, int Hq, int Hkv, int d, const DecodeP
   return hipGetLastError();
 }
 
-hipError_t launch_decode(int n_parts, int Hq, int Hkv, int d, int dtype, float scale2, const DecodeParts& tab,
-                         const void* q, const void* kc, const void* vc, float* out, float* partial, hipStream_t st) {
+template <typename TAB>
+static hipError_t launch_decode_any(int n_parts, int Hq, int Hkv, int d, int dtype, float scale2, const TAB& tab,
+                                    const void* q, const void* kc, const void* vc, float* out, float* partial,
+                                    hipStream_t st) {
   const int G = Hq / Hkv;
   if (dtype == LAQ_BF16) {
     if (G == 1) return launch_decode_for<1, uint16_t>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
@@ -332,6 +342,16 @@ hipError_t launch_decode(int n_parts, int Hq, int Hkv, int d, int dtype, float s
   if (G == 1) return launch_decode_for<1, float>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
   if (G == 2) return launch_decode_for<2, float>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
   return launch_decode_for<4, float>(n_parts, Hq, Hkv, d, scale2, tab, q, kc, vc, out, partial, st);
+}
+
+hipError_t launch_decode(int n_parts, int Hq, int Hkv, int d, int dtype, float scale2, const DecodeParts& tab,
+                         const void* q, const void* kc, const void* vc, float* out, float* partial, hipStream_t st) {
+  return launch_decode_any(n_parts, Hq, Hkv, d, dtype, scale2, tab, q, kc, vc, out, partial, st);
+}
+
+hipError_t launch_decode(int n_inst, int Hq, int Hkv, int d, int dtype, float scale2, const DecodeWhole& tab,
+                         const void* q, const void* kc, const void* vc, float* out, hipStream_t st) {
+  return launch_decode_any(n_inst, Hq, Hkv, d, dtype, scale2, tab, q, kc, vc, out, (float*)nullptr, st);
 }
 
 hipError_t launch_qcache_store(long long rows, int W, int t, int row_bytes, const void* q_step, void* q_cache,

@@ -113,6 +113,24 @@ struct DecodeParts {
   int32_t inst[MAX_PARTS_PER_LAUNCH];   // instance
   int16_t split[MAX_PARTS_PER_LAUNCH];  // index of the part within its cache
   int16_t nsplit[MAX_PARTS_PER_LAUNCH]; // parts of its cache
+  __host__ __device__ int inst_of(int i) const { return inst[i]; }
+  __host__ __device__ int64_t base_row(int i) const { return row0[i]; }
+  __host__ __device__ int cache_rows(int i) const { return bk[i]; }
+  __host__ __device__ int first_row(int i) const { return start[i]; }
+  __host__ __device__ int part_rows(int i) const { return rows[i]; }
+  __host__ __device__ int parts(int i) const { return nsplit[i]; }
+};
+// The same view of a launch in which every cache is one part: instances inst0 .. of a call.
+struct DecodeWhole {
+  int64_t row0[MAX_INST_PER_LAUNCH];
+  int32_t bk[MAX_INST_PER_LAUNCH];
+  int32_t inst0;
+  __host__ __device__ int inst_of(int i) const { return inst0 + i; }
+  __host__ __device__ int64_t base_row(int i) const { return row0[i]; }
+  __host__ __device__ int cache_rows(int i) const { return bk[i]; }
+  __host__ __device__ int first_row(int) const { return 0; }
+  __host__ __device__ int part_rows(int i) const { return bk[i]; }
+  __host__ __device__ int parts(int) const { return 1; }
 };
 
 // launchers (each returns hipGetLastError() after its last launch); `raw` receives unpooled scores
@@ -132,6 +150,8 @@ hipError_t launch_recall(int n_inst, int inst0, int Hkv, const PairTable& tab, c
 int decode_head_batch(int Hq, int Hkv);   // query heads of a KV head that one decode workgroup serves
 hipError_t launch_decode(int n_parts, int Hq, int Hkv, int d, int dtype, float scale2, const DecodeParts& tab,
                          const void* q, const void* kc, const void* vc, float* out, float* partial, hipStream_t st);
+hipError_t launch_decode(int n_inst, int Hq, int Hkv, int d, int dtype, float scale2, const DecodeWhole& tab,
+                         const void* q, const void* kc, const void* vc, float* out, hipStream_t st);
 hipError_t launch_merge_parts(int n_parts, int Hq, int Hkv, int d, const DecodeParts& tab, const float* partial,
                               float* out, hipStream_t st);
 hipError_t launch_qcache_store(long long rows, int W, int t, int row_bytes, const void* q_step, void* q_cache,
