@@ -210,7 +210,7 @@ static int sink_recent_impl(int n_inst, int Hkv, int L, const int32_t* budget, i
 constexpr int DECODE_SPLIT_ROWS = 512;
 constexpr int DECODE_SPLIT_BELOW_WORKGROUPS = 1024;
 
-static int decode_parts_of(const ScoreGeom& g, int bk, bool split) {
+static int decode_parts_of(int bk, bool split) {
   if (!split) return 1;
   const int s = (bk + DECODE_SPLIT_ROWS - 1) / DECODE_SPLIT_ROWS;
   return s < MAX_PARTS_PER_LAUNCH ? s : MAX_PARTS_PER_LAUNCH;
@@ -229,7 +229,7 @@ static bool decode_would_split(const laq_shape* shape, const ScoreGeom& g, const
 static size_t decode_ws_bytes(const laq_shape* shape, const ScoreGeom& g, const int32_t* budget) {
   if (!decode_would_split(shape, g, budget)) return 0;
   long long parts = 0;
-  for (int i = 0; i < shape->n_inst; ++i) parts += decode_parts_of(g, budget[i] < g.L ? budget[i] : g.L, true);
+  for (int i = 0; i < shape->n_inst; ++i) parts += decode_parts_of(budget[i] < g.L ? budget[i] : g.L, true);
   if (parts > MAX_PARTS_PER_LAUNCH) parts = MAX_PARTS_PER_LAUNCH;
   const int gb = decode_head_batch(g.Hq, g.Hkv), nbatch = (g.G + gb - 1) / gb;
   return round256((size_t)parts * g.Hkv * nbatch * gb * (g.d + 2) * sizeof(float));
@@ -280,7 +280,7 @@ static int decode_impl(const laq_shape* shape, const void* q, const void* kc, co
   int64_t row = 0;
   for (int i = 0; i < shape->n_inst; ++i) {
     const int bk = budget[i] < g.L ? budget[i] : g.L;
-    const int S = decode_parts_of(g, bk, split);
+    const int S = decode_parts_of(bk, split);
     if (n_parts + S > MAX_PARTS_PER_LAUNCH && !flush()) return LAQ_ERR_DEVICE;   // the parts of a cache stay together
     const int per = (bk + S - 1) / S;
     for (int p = 0; p < S; ++p) {
