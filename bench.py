@@ -142,6 +142,8 @@ def main():
     ap.add_argument("--layout", choices=["dense", "token-major"], default="dense",
                     help="dense (default): k, v stored [n, Hkv, L, d]; token-major: stored [n, L, Hkv, d] and handed "
                          "over as strided views")
+    ap.add_argument("--no-probe", action="store_true",
+                    help="skip the untimed recall probe (keeps profiler runs to the timed kernels)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device tensor copy (a kernel of known traffic, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -265,7 +267,7 @@ def main():
 
     # quality probe in the spirit of Eq. 1-3 (untimed): how much of the selection made by all W window
     # queries (placed after the prompt, nothing kept) is recovered by the first quarter of them
-    if args.window == "trailing" and cfg.W >= 4:
+    if args.window == "trailing" and cfg.W >= 4 and not args.no_probe:
         see_all = [cfg.L] * cfg.W
         few = cfg.W // 4
         gold = laq.laq_evict(q, k, v, budgets, cfg.pool, q_pos=see_all, keep=0, pool_mode=args.pool_mode)[1]
