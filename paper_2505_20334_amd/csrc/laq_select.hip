@@ -16,6 +16,7 @@ namespace {
 
 constexpr int SEL_THREADS = 1024;
 constexpr int SEL_WAVES = SEL_THREADS / 64;
+constexpr int SEL_MANY_WORKGROUPS = 768;   // from here on two workgroups per compute unit pay off
 
 __device__ __forceinline__ uint32_t order_key(float f) {
   const uint32_t b = __float_as_uint(f);
@@ -28,8 +29,11 @@ __device__ __forceinline__ int lanes_below(uint64_t m) {
 
 // ITEMS > 0: keys of the wave's segment are held in ITEMS registers per lane.
 // ITEMS == 0: keys are recomputed from memory on every sweep (any prefix length).
-template <int ITEMS>
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int keep, int pool, bool avg,
+// WAVES_PER_SIMD = 4: one workgroup per compute unit, up to 128 registers per lane; 8: two workgroups
+// per compute unit on 64 registers (the 32-key variant then spills a few of them, which costs
+// 12 % when there is one workgroup per compute unit anyway and gains 30 % when there are many).
+template <int ITEMS, int WAVES_PER_SIMD>
+__global__ __launch_bounds__(SEL_THREADS, WAVES_PER_SIMD) void select_kernel(int Hkv, int L, int keep, int pool, bool avg,
                                                              const float* __restrict__ scores, InstTable tab,
                                                              int inst0, int32_t* __restrict__ idx) {
   __shared__ int hist[256];
@@ -149,8 +153,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(int Hkv, int L, int
 template <int ITEMS>
 hipError_t launch_one(int n_inst, int inst0, int Hkv, int L, int keep, int pool, bool avg, const float* scores,
                       const InstTable& tab, int32_t* idx, hipStream_t st) {
-  hipLaunchKernelGGL(select_kernel<ITEMS>, dim3(Hkv, n_inst), dim3(SEL_THREADS), 0, st, Hkv, L, keep, pool, avg, scores,
-                     tab, inst0, idx);
+  if ((long long)Hkv * n_inst >= SEL_MANY_WORKGROUPS)
+    hipLaunchKernelGGL((select_kernel<ITEMS, 8>), dim3(Hkv, n_inst), dim3(SEL_THREADS), 0, st, Hkv, L, keep, pool, avg,
+                       scores, tab, inst0, idx);
+  else
+    hipLaunchKernelGGL((select_kernel<ITEMS, 4>), dim3(Hkv, n_inst), dim3(SEL_THREADS), 0, st, Hkv, L, keep, pool, avg,
+                       scores, tab, inst0, idx);
   return hipGetLastError();
 }
 
