@@ -877,7 +877,7 @@ hipError_t launch_for_rows(const ScoreGeom& g, const QueryPos& qp, const KvLayou
 
 bool score_mfma_supported(const ScoreGeom& g, const KvLayout& lay, int dtype) {
   // the key loads address a head with 31-bit byte offsets (one chunk of slack past its end)
-  return dtype == LAQ_BF16 && (g.d == 128 || g.d == 64) && g.R >= 16 && g.W <= MAX_QPOS &&
+  return dtype == LAQ_BF16 && (g.d == 128 || g.d == 64) && g.W <= MAX_QPOS &&
          g.n_inst * (long long)g.Hkv <= 0x7fffffff && ((long long)g.L + MFMA_ROWS) * lay.row_bytes < 0x7fffffffLL;
 }
 

@@ -158,7 +158,7 @@ EDGE = [
     ("pool1", torch.bfloat16, 8, 2, 128, 777, 8, 1, 64),
     ("pool3", torch.bfloat16, 8, 2, 128, 777, 8, 3, 64),
     ("pool63", torch.bfloat16, 8, 2, 128, 777, 8, 63, 200),
-    ("W1-G1-generic", torch.bfloat16, 2, 2, 128, 600, 1, 7, 50),
+    ("W1-G1-one-score-row", torch.bfloat16, 2, 2, 128, 600, 1, 7, 50),
     ("R48-three-tiles", torch.bfloat16, 12, 2, 128, 900, 8, 7, 64),
     ("R160-two-groups", torch.bfloat16, 10, 1, 128, 700, 16, 7, 64),
     ("R20-padded", torch.bfloat16, 5, 1, 128, 700, 4, 7, 64),
@@ -761,7 +761,8 @@ STRIDED = [
     ("token-major-d64", torch.bfloat16, 8, 2, 64, 1500, 8, 7, 128),
     ("token-major-one-chunk", torch.bfloat16, 8, 2, 128, 200, 8, 5, 64),
     ("token-major-fp32-generic", torch.float32, 4, 2, 64, 500, 6, 3, 40),
-    ("token-major-R8-generic-bf16", torch.bfloat16, 2, 2, 128, 600, 4, 7, 50),
+    ("token-major-R4", torch.bfloat16, 2, 2, 128, 600, 4, 7, 50),
+    ("token-major-d96-generic-bf16", torch.bfloat16, 4, 2, 96, 400, 4, 7, 32),
 ]
 
 
@@ -827,3 +828,14 @@ def test_decode_with_and_without_splitting_long_caches(laq):
                          "%s inst %d" % (how, i))
     # many workgroups already: no splitting, no workspace wanted
     assert laq.laq_decode_workspace_bytes(256, 32, 8, 128, 32768, torch.bfloat16, [2048] * 256) == 0
+
+
+def test_two_lookahead_steps_full_size_sampled(laq):
+    # a Q-cache of two lookahead steps (the paper's low-latency setting) with four query heads per KV
+    # head: 8 score rows, a quarter of a 32-row tile, at the 32k shape
+    n, Hq, Hkv, d, L, W = 2, 32, 8, 128, 32768, 2
+    gen = torch.Generator(device=DEV).manual_seed(23)
+    q = (torch.randn(n, Hq, W, d, generator=gen, device=DEV) * 1.5).bfloat16()
+    k = torch.randn(n, Hkv, L, d, generator=gen, device=DEV).bfloat16()
+    v = torch.randn(n, Hkv, L, d, generator=gen, device=DEV).bfloat16()
+    run_general(laq, q, k, v, [512, 128], 7, [L, L + 1], 0, "two-steps-32k", heads=[2])
