@@ -1,91 +1,150 @@
-// Generic scoring path (plain fp32 FMA): any head size, any number of score rows,
-// fp32 or bf16 storage.  Used for fp32 inputs and for shapes the MFMA path does not
-// take (fewer than 16 score rows per KV head, unusual head sizes).
+// Generic scoring path (vector ALU, no matrix cores): any head size up to 256, any number of
+// score rows, fp32 or bf16 storage.  Used for fp32 inputs and for head sizes the MFMA path does
+// not take.
 //
-// Computes, per KV head, the window attention of Eq. 4's observation window in two
-// passes over the keys: (1) per-row softmax statistics of each 256-key chunk,
-// (2) after the statistics of all chunks are combined (row_constants_kernel), the
-// normalised sum over rows.  Also here: the sequence max-pool over raw scores.
+// Computes, per KV head, the window attention of Eq. 4's observation window in two passes over
+// the keys: (1) per-row softmax statistics of each 256-key chunk, (2) after the statistics of all
+// chunks are combined (row_constants_kernel), the normalised sum over rows.  Also here: the
+// sequence pooling over raw scores.
+//
+// Both passes give a key row to a group of PP adjacent lanes, 8 elements per lane, so that a
+// wave's loads cover whole rows contiguously; the 256 / PP groups of a workgroup take the 256 keys
+// of a chunk round-robin.  The score rows are walked in blocks of GEN_ROWS whose query pieces sit in
+// registers; the chunk's key rows are re-read from cache once per block.
 #include "laq_internal.h"
+#include "laq_lanegroup.h"
 
 namespace laq {
 
 namespace {
 
 constexpr float NEG_BIG = -1.0e30f;   // finite "minus infinity" for running maxima
+constexpr int GEN_ROWS = 8;           // score rows per register block
 
-__device__ __forceinline__ float ld_elem(const float* p, size_t i) { return p[i]; }
-__device__ __forceinline__ float ld_elem(const uint16_t* p, size_t i) {
-  return __uint_as_float((uint32_t)p[i] << 16);   // bf16 -> fp32 is exact
-}
-
-template <typename T>
-__device__ __forceinline__ float dot_row(const T* __restrict__ qrow, const T* __restrict__ krow, int d) {
-  float acc = 0.f;
-  for (int c = 0; c < d; ++c) acc = fmaf(ld_elem(qrow, c), ld_elem(krow, c), acc);
-  return acc;
-}
-
-__device__ __forceinline__ float wave_max(float v) {
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-  return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
-
-// One workgroup per (chunk, KV head, instance); thread t owns key chunk * 256 + t.
-template <typename T>
+// One workgroup per (chunk, KV head, instance).  part[chunk][r] = (m, z) of row r over the
+// chunk's visible keys.
+template <typename T, int PP>
 __global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, QueryPos qp, KvLayout lay,
                                                                    const T* __restrict__ q,
                                                                    const T* __restrict__ k,
                                                                    float2* __restrict__ part) {
-  __shared__ float red[4];
+  using Piece = typename PieceOf<T>::type;
+  constexpr int NG = CHUNK_ROWS / PP, KPG = CHUNK_ROWS / NG;     // lane groups; keys per group
+  __shared__ float2 red[NG][GEN_ROWS];
   const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int j = chunk * CHUNK_ROWS + t;
-  const bool owned = j < g.L;
-  const T* krow = k + (size_t)inst * lay.inst + (size_t)head * lay.head + (size_t)(owned ? j : 0) * lay.row;
-  const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d;
+  const int tid = threadIdx.x, dc = tid % PP, ks = tid / PP;
+  const bool active = dc * 8 < g.d;
+  const int j0 = chunk * CHUNK_ROWS;
+  const T* kbase = k + (size_t)inst * lay.inst + (size_t)head * lay.head + dc * 8;
+  const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d + dc * 8;
   float2* out = part + (((size_t)inst * g.Hkv + head) * g.nchunk + chunk) * g.Rpad;
 
-  for (int r = 0; r < g.R; ++r) {
-    const int w = r % g.W;
-    const bool vis = owned && (j <= last_visible_key(g, qp, w));
-    float s = vis ? g.scale2 * dot_row(qg + (size_t)r * g.d, krow, g.d) : NEG_BIG;
-    float m = wave_max(s);
-    if (lane == 0) red[wave] = m;
+  for (int r0 = 0; r0 < g.R; r0 += GEN_ROWS) {
+    Piece qv[GEN_ROWS];
+    int last[GEN_ROWS];
+    float m[GEN_ROWS], z[GEN_ROWS];
+#pragma unroll
+    for (int rb = 0; rb < GEN_ROWS; ++rb) {
+      clear8(qv[rb]);
+      m[rb] = NEG_BIG;
+      z[rb] = 0.f;
+      last[rb] = -1;                                   // rows beyond R see nothing
+      if (r0 + rb < g.R) {
+        last[rb] = last_visible_key(g, qp, (r0 + rb) % g.W);
+        if (active) fetch8(qg + (size_t)(r0 + rb) * g.d, qv[rb]);
+      }
+    }
+#pragma unroll 2
+    for (int kk = 0; kk < KPG; ++kk) {
+      const int j = j0 + ks + NG * kk;
+      Piece kp;
+      clear8(kp);
+      if (active && j < g.L) fetch8(kbase + (size_t)j * lay.row, kp);
+#pragma unroll
+      for (int rb = 0; rb < GEN_ROWS; ++rb) {
+        const float s = group_sum<PP>(dot8(qv[rb], kp)) * g.scale2;
+        if (j < g.L && j <= last[rb]) {
+          const float m_new = fmaxf(m[rb], s);
+          z[rb] = fmaf(z[rb], exp2f(m[rb] - m_new), exp2f(s - m_new));
+          m[rb] = m_new;
+        }
+      }
+    }
+    if (dc == 0) {
+#pragma unroll
+      for (int rb = 0; rb < GEN_ROWS; ++rb) red[ks][rb] = make_float2(m[rb], z[rb]);
+    }
     __syncthreads();
-    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    __syncthreads();
-    float e = vis ? exp2f(s - m) : 0.f;
-    e = wave_sum(e);
-    if (lane == 0) red[wave] = e;
-    __syncthreads();
-    if (t == 0) out[r] = make_float2(m, (red[0] + red[1]) + (red[2] + red[3]));
+    if (tid < GEN_ROWS && r0 + tid < g.R) {
+      float M = NEG_BIG, Z = 0.f;
+      for (int gidx = 0; gidx < NG; ++gidx) {           // fixed order
+        const float2 mz = red[gidx][tid];
+        const float Mn = fmaxf(M, mz.x);
+        Z = Z * exp2f(M - Mn) + mz.y * exp2f(mz.x - Mn);
+        M = Mn;
+      }
+      out[r0 + tid] = make_float2(M, Z);
+    }
     __syncthreads();
   }
 }
 
-template <typename T>
+// raw[j] = sum over the score rows of exp2(s - c[r]) for the keys of the chunk.
+template <typename T, int PP>
 __global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, QueryPos qp, KvLayout lay,
                                                                   const T* __restrict__ q,
                                                                   const T* __restrict__ k,
                                                                   const float* __restrict__ rowc,
                                                                   float* __restrict__ raw) {
+  using Piece = typename PieceOf<T>::type;
+  constexpr int NG = CHUNK_ROWS / PP, KPG = CHUNK_ROWS / NG;
   const int chunk = blockIdx.x, head = blockIdx.y, inst = blockIdx.z;
-  const int j = chunk * CHUNK_ROWS + threadIdx.x;
-  if (j >= g.L) return;
-  const T* krow = k + (size_t)inst * lay.inst + (size_t)head * lay.head + (size_t)j * lay.row;
-  const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d;
+  const int tid = threadIdx.x, dc = tid % PP, ks = tid / PP;
+  const bool active = dc * 8 < g.d;
+  const int j0 = chunk * CHUNK_ROWS;
+  const T* kbase = k + (size_t)inst * lay.inst + (size_t)head * lay.head + dc * 8;
+  const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d + dc * 8;
   const float* c = rowc + ((size_t)inst * g.Hkv + head) * g.Rpad;
-  float acc = 0.f;
-  for (int r = 0; r < g.R; ++r) {
-    const int w = r % g.W;
-    if (j <= last_visible_key(g, qp, w)) acc += exp2f(g.scale2 * dot_row(qg + (size_t)r * g.d, krow, g.d) - c[r]);
+  float acc[KPG];
+#pragma unroll
+  for (int kk = 0; kk < KPG; ++kk) acc[kk] = 0.f;
+
+  for (int r0 = 0; r0 < g.R; r0 += GEN_ROWS) {
+    Piece qv[GEN_ROWS];
+    int last[GEN_ROWS];
+    float cr[GEN_ROWS];
+#pragma unroll
+    for (int rb = 0; rb < GEN_ROWS; ++rb) {
+      clear8(qv[rb]);
+      last[rb] = -1;
+      cr[rb] = 0.f;
+      if (r0 + rb < g.R) {
+        last[rb] = last_visible_key(g, qp, (r0 + rb) % g.W);
+        cr[rb] = c[r0 + rb];
+        if (active) fetch8(qg + (size_t)(r0 + rb) * g.d, qv[rb]);
+      }
+    }
+#pragma unroll
+    for (int kk = 0; kk < KPG; ++kk) {
+      const int j = j0 + ks + NG * kk;
+      Piece kp;
+      clear8(kp);
+      if (active && j < g.L) fetch8(kbase + (size_t)j * lay.row, kp);
+#pragma unroll
+      for (int rb = 0; rb < GEN_ROWS; ++rb) {
+        const float s = group_sum<PP>(dot8(qv[rb], kp)) * g.scale2;
+        if (j <= last[rb]) acc[kk] += exp2f(s - cr[rb]);
+      }
+    }
   }
-  raw[((size_t)inst * g.Hkv + head) * g.L + j] = acc;
+  if (dc == 0) {
+    float* rw = raw + ((size_t)inst * g.Hkv + head) * g.L;
+#pragma unroll
+    for (int kk = 0; kk < KPG; ++kk) {
+      const int j = j0 + ks + NG * kk;
+      if (j < g.L) rw[j] = acc[kk];
+    }
+  }
 }
 
 // pooled[j] = max (or mean) of raw[i], |i - j| <= half, 0 <= i < P, for prefix keys; the kept
@@ -158,28 +217,33 @@ hipError_t launch_pool(const ScoreGeom& g, int pool, bool avg, const float* raw,
   return hipGetLastError();
 }
 
-hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int dtype, const void* q,
-                                const void* k, float* raw, const Workspace& ws, hipStream_t st) {
+template <typename T, int PP>
+static hipError_t launch_generic_pp(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, const T* q, const T* k,
+                                    float* raw, const Workspace& ws, hipStream_t st) {
   dim3 grid(g.nchunk, g.Hkv, g.n_inst), block(CHUNK_ROWS);
-  if (dtype == LAQ_F32) {
-    hipLaunchKernelGGL(stats_generic_kernel<float>, grid, block, 0, st, g, qp, lay, (const float*)q, (const float*)k,
-                       ws.part);
-  } else {
-    hipLaunchKernelGGL(stats_generic_kernel<uint16_t>, grid, block, 0, st, g, qp, lay, (const uint16_t*)q,
-                       (const uint16_t*)k, ws.part);
-  }
+  hipLaunchKernelGGL((stats_generic_kernel<T, PP>), grid, block, 0, st, g, qp, lay, q, k, ws.part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = launch_row_constants(g, ws, st);
-  if (e != hipSuccess) return e;
-  if (dtype == LAQ_F32) {
-    hipLaunchKernelGGL(norm_generic_kernel<float>, grid, block, 0, st, g, qp, lay, (const float*)q, (const float*)k,
-                       ws.rowc, raw);
-  } else {
-    hipLaunchKernelGGL(norm_generic_kernel<uint16_t>, grid, block, 0, st, g, qp, lay, (const uint16_t*)q,
-                       (const uint16_t*)k, ws.rowc, raw);
-  }
+  if ((e = launch_row_constants(g, ws, st)) != hipSuccess) return e;
+  hipLaunchKernelGGL((norm_generic_kernel<T, PP>), grid, block, 0, st, g, qp, lay, q, k, ws.rowc, raw);
   return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_generic_for(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, const void* q,
+                                     const void* k, float* raw, const Workspace& ws, hipStream_t st) {
+  const T* qq = static_cast<const T*>(q);
+  const T* kk = static_cast<const T*>(k);
+  const int pp = lanes_per_row(g.d);
+  if (pp == 8) return launch_generic_pp<T, 8>(g, qp, lay, qq, kk, raw, ws, st);
+  if (pp == 16) return launch_generic_pp<T, 16>(g, qp, lay, qq, kk, raw, ws, st);
+  return launch_generic_pp<T, 32>(g, qp, lay, qq, kk, raw, ws, st);
+}
+
+hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int dtype, const void* q,
+                                const void* k, float* raw, const Workspace& ws, hipStream_t st) {
+  if (dtype == LAQ_F32) return launch_generic_for<float>(g, qp, lay, q, k, raw, ws, st);
+  return launch_generic_for<uint16_t>(g, qp, lay, q, k, raw, ws, st);
 }
 
 }  // namespace laq
