@@ -117,7 +117,9 @@ size_t laq_workspace_bytes(const laq_shape *shape);
  *          laq_score(p) + laq_select(1) and laq_score(1) + laq_select(p) give the same indices.
  *   ws / ws_bytes  device scratch of at least laq_workspace_bytes(shape)
  * Supported: dtype BF16 or F32; any Hq/Hkv/W/L within the limits of laq_shape;
- * pool_kernel odd, 1 <= pool_kernel <= 63.
+ * pool_kernel odd, 1 <= pool_kernel <= 63.  BF16 with d = 64 or 128 and W <= 512 runs on the
+ * matrix cores (bound by reading K twice); everything else runs on a vector-ALU path with the
+ * same results to within the rounding of its fp32 sums, several times slower per key.
  */
 int laq_score(const laq_shape *shape, const void *q_win, const void *k, int pool_kernel,
               float *scores, void *ws, size_t ws_bytes, void *stream);
