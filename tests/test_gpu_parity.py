@@ -839,3 +839,38 @@ def test_two_lookahead_steps_full_size_sampled(laq):
     k = torch.randn(n, Hkv, L, d, generator=gen, device=DEV).bfloat16()
     v = torch.randn(n, Hkv, L, d, generator=gen, device=DEV).bfloat16()
     run_general(laq, q, k, v, [512, 128], 7, [L, L + 1], 0, "two-steps-32k", heads=[2])
+
+
+def _random_case(rng):
+    d = int(rng.choice([64, 128, 128, 128, 96, 32]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 4, 4, 5]))
+    W = int(rng.choice([1, 2, 3, 8, 8, 16, 33]))
+    L = int(rng.choice([rng.integers(1, 60), rng.integers(200, 300), rng.integers(500, 1100), rng.integers(1100, 2400)]))
+    pool = int(rng.choice([1, 3, 7, 7, 15]))
+    dtype = torch.float32 if (d == 32 or rng.random() < 0.15) else torch.bfloat16
+    mode = rng.choice(["trailing", "lookahead", "joined", "scattered"])
+    if mode == "trailing":
+        W = min(W, L)
+        pos, keep = [L - W + w for w in range(W)], W
+    elif mode == "lookahead":
+        pos, keep = [L + w for w in range(W)], int(rng.integers(0, min(L, 9)))
+    elif mode == "joined":
+        local = min(W // 2, L)
+        pos, keep = [L - local + w for w in range(local)] + [L + w for w in range(W - local)], local
+    else:
+        pos, keep = [int(x) for x in rng.integers(0, 2 * L, size=W)], int(rng.integers(0, min(L, 5) + 1))
+    budgets = [int(rng.integers(max(keep, 1), L + 20)), int(rng.integers(max(keep, 1), max(keep, 1) + 1 + L // 4))]
+    return dict(d=d, Hkv=Hkv, Hq=Hkv * G, W=W, L=L, pool=pool, dtype=dtype, pos=pos, keep=keep, budgets=budgets,
+                pool_mode="avg" if rng.random() < 0.2 else "max", strided=bool(rng.random() < 0.25))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_against_the_oracle(laq, seed):
+    c = _random_case(np.random.default_rng(1000 + seed))
+    q, k, v = _qkv(seed, 2, c["Hq"], c["Hkv"], c["d"], c["L"], c["W"], c["dtype"])
+    if c["strided"]:
+        k, v = _token_major_view(k), _token_major_view(v)
+    name = "random-%d d=%d G=%d mode=%s strided=%s dtype=%s" % (seed, c["d"], c["Hq"] // c["Hkv"], c["pool_mode"],
+                                                               c["strided"], c["dtype"])
+    run_general(laq, q, k, v, c["budgets"], c["pool"], c["pos"], c["keep"], name, pool_mode=c["pool_mode"])
