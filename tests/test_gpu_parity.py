@@ -874,3 +874,63 @@ def test_random_shapes_against_the_oracle(laq, seed):
     name = "random-%d d=%d G=%d mode=%s strided=%s dtype=%s" % (seed, c["d"], c["Hq"] // c["Hkv"], c["pool_mode"],
                                                                c["strided"], c["dtype"])
     run_general(laq, q, k, v, c["budgets"], c["pool"], c["pos"], c["keep"], name, pool_mode=c["pool_mode"])
+
+
+def test_three_stage_flow_with_synthetic_queries(laq):
+    """The calls in the order the method uses them (Sec. 4): stage-1 eviction to a low budget, eight
+    lookahead steps that decode on the small cache and leave their queries in the Q-cache, the
+    re-eviction of the full prefill cache with local window + Q-cache (Eq. 5), decoding on the
+    result.  The model's layers are not here: the queries of every step are synthetic draws.  Each
+    stage is checked against the oracle's version of the same step."""
+    n, Hq, Hkv, d, L, W_local, steps = 2, 16, 4, 128, 3000, 8, 8
+    g = torch.Generator().manual_seed(77)
+    k = torch.randn(n, Hkv, L, d, generator=g).bfloat16()
+    v = torch.randn(n, Hkv, L, d, generator=g).bfloat16()
+    q_local = (torch.randn(n, Hq, W_local, d, generator=g) * 1.5).bfloat16()       # queries of the last prompt tokens
+    kd, vd, qd = k.to(DEV), v.to(DEV), q_local.to(DEV)
+
+    # stage 1: observation-window eviction with the prompt suffix as window, low budget
+    low = [96, 64]
+    _, idx1, k1, v1 = laq.laq_evict(qd, kd, vd, low, 7)
+    # lookahead: eight decode steps on the small cache; their queries become the Q-cache
+    q_cache = torch.zeros(n, Hq, steps, d, dtype=torch.bfloat16, device=DEV)
+    ref_cache = torch.zeros(n, Hq, steps, d, dtype=torch.bfloat16)
+    outs = []
+    for t in range(steps):
+        q_t = (torch.randn(n, Hq, d, generator=g) * 1.5).bfloat16()
+        laq.laq_qcache_store(q_cache, q_t.to(DEV), t)
+        outs.append((q_t, laq.laq_decode_attention(q_t.to(DEV), k1, v1, low, Hkv, L)))
+        for i in range(n):
+            ref_cache[i] = oracle.qcache_store(ref_cache[i], q_t[i], t)
+    # re-eviction of the full cache: local window joined with the Q-cache, the local window's keys kept
+    q_win = torch.cat([qd, q_cache], dim=2)
+    pos = [L - W_local + w for w in range(W_local)] + [L + t for t in range(steps)]
+    budgets = [256, 128]
+    scores, idx2, k2, v2 = laq.laq_evict(q_win, kd, vd, budgets, 7, q_pos=pos, keep=W_local)
+    q_next = (torch.randn(n, Hq, d, generator=g) * 1.5).bfloat16()
+    out2 = laq.laq_decode_attention(q_next.to(DEV), k2, v2, budgets, Hkv, L)
+    _, recall = laq.laq_recall(idx1, low, idx2, budgets, Hkv, L)
+    torch.cuda.synchronize()
+
+    assert torch.equal(q_cache.cpu(), ref_cache)
+    k1_l, v1_l = split_packed(k1.cpu(), low, Hkv, L), split_packed(v1.cpu(), low, Hkv, L)
+    k2_l, v2_l = split_packed(k2.cpu(), budgets, Hkv, L), split_packed(v2.cpu(), budgets, Hkv, L)
+    idx1_l, idx2_l = split_packed(idx1.cpu(), low, Hkv, L), split_packed(idx2.cpu(), budgets, Hkv, L)
+    q_win_c = torch.cat([q_local, ref_cache], dim=2)
+    for i in range(n):
+        o_pooled1, o_idx1, o_k1, o_v1 = oracle.evict(q_local[i], k[i], v[i], low[i], 7)
+        o_pooled2, o_idx2, o_k2, o_v2 = oracle.evict(q_win_c[i], k[i], v[i], budgets[i], 7, q_pos=pos, keep=W_local)
+        check_scores(scores[i].cpu(), o_pooled2, torch.bfloat16, "re-eviction inst %d" % i)
+        for gh in range(Hkv):
+            check_index_row(idx1_l[i][gh].numpy(), o_pooled1[gh].float().numpy(), W_local, low[i], RTOL[torch.bfloat16],
+                            "stage-1 inst %d head %d" % (i, gh))
+            check_index_row(idx2_l[i][gh].numpy(), o_pooled2[gh].float().numpy(), W_local, budgets[i],
+                            RTOL[torch.bfloat16], "re-eviction inst %d head %d" % (i, gh))
+        assert torch.equal(k1_l[i], oracle.compact(k[i], idx1_l[i])) and torch.equal(v2_l[i], oracle.compact(v[i], idx2_l[i]))
+        for q_t, o_t in outs[::3]:
+            check_decode(o_t[i].cpu(), q_t[i], k1_l[i].contiguous(), v1_l[i].contiguous(), torch.bfloat16,
+                         "lookahead decode inst %d" % i)
+        check_decode(out2[i].cpu(), q_next[i], k2_l[i].contiguous(), v2_l[i].contiguous(), torch.bfloat16,
+                     "decode inst %d" % i)
+        assert torch.equal(recall[i].cpu() * min(budgets[i], L),
+                           oracle.overlap(idx1_l[i], idx2_l[i], L).float())
