@@ -25,6 +25,8 @@
  *   - The library allocates and frees no device memory and keeps no device state between
  *     calls (on the host it remembers how many workgroups each device holds, looked up on
  *     the first scoring call); scratch memory comes in through `ws` (laq_workspace_bytes).
+ *     Calls that may run at the same time (different streams) need a workspace each; calls
+ *     on one stream may share one.
  *   - Errors are reported by the return value (LAQ_OK = 0, negative otherwise), never
  *     by exception or abort.  Arguments are validated before anything is enqueued, so
  *     a call that returns LAQ_ERR_INVALID / _UNSUPPORTED / _WORKSPACE has done nothing.
