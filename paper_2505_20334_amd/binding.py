@@ -40,13 +40,19 @@ def lib_path() -> str:
 
 
 def load_library() -> ctypes.CDLL:
-    """Load the built library; raises if it has not been built (no fallback path exists)."""
+    """Load the built library (building it first if nothing is built); raises if that is impossible --
+    there is no fallback path."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(_LIB_PATH):
-        raise ImportError("liblaq.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
-                          "(or paper_2505_20334_amd/_build.py) first")
+        # nothing built yet: build once (hipcc); there is no other way to run, so a failure is final
+        try:
+            from . import _build
+            _build.build()
+        except Exception as exc:
+            raise ImportError("liblaq.so is not built and building it failed (%s): run "
+                              "`python -c 'import __graft_entry__ as g; g.build()'`" % exc)
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     sp = ctypes.POINTER(_Shape)
