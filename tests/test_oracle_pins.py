@@ -726,3 +726,14 @@ def test_eight_lookahead_steps_fill_the_qcache_that_scoring_reads():
     for t, s in enumerate(steps):
         cache = oracle.qcache_store(cache, s, t)
     assert torch.equal(cache, torch.stack(steps, dim=1))
+
+
+def test_sink_recent_writes_exactly_its_rows():
+    # more sinks than the budget holds: the list is the first Bk positions and nothing is written
+    # beyond the Hkv * Bk entries (checked through the C entry point with a guarded buffer)
+    lib = oracle._load()
+    Hkv, L, n_sink, budget = 3, 10, 6, 4
+    buf = torch.full((Hkv * budget + 8,), -7, dtype=torch.int32)
+    assert lib.laq_oracle_sink_recent(Hkv, L, n_sink, budget, buf.data_ptr()) == 0
+    assert buf[:Hkv * budget].view(Hkv, budget).tolist() == [[0, 1, 2, 3]] * Hkv
+    assert buf[Hkv * budget:].tolist() == [-7] * 8
