@@ -172,6 +172,7 @@ EDGE = [
     ("window-is-everything", torch.bfloat16, 8, 2, 128, 32, 32, 7, 32),
     ("P-eq-1", torch.bfloat16, 8, 2, 128, 9, 8, 7, 9),
     ("long-window", torch.bfloat16, 8, 2, 128, 900, 300, 7, 400),
+    ("window-of-600-queries-beyond-the-position-table", torch.bfloat16, 2, 1, 128, 700, 600, 7, 650),
     # pooling windows that cross the 256-key chunk boundaries of pass 2
     ("prefix-ends-on-chunk-boundary", torch.bfloat16, 8, 2, 128, 520, 8, 7, 64),
     ("prefix-ends-one-past-boundary", torch.bfloat16, 8, 2, 128, 521, 8, 7, 64),
