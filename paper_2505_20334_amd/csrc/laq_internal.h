@@ -52,8 +52,9 @@ __device__ __forceinline__ int last_visible_key(const ScoreGeom& g, const QueryP
 // Workspace carving: [partials | row constants | raw scores]
 //   part:  float2 (m, z) per (instance, KV head, chunk, padded row): softmax statistics of a chunk
 //   rowc:  float c = M + log2(Z) per (instance, KV head, padded row)
-//   raw:   float per (instance, KV head, key): unpooled scores, used by the generic path when
-//          pooling is requested
+//   raw:   float per (instance, KV head, key): unpooled scores in front of a separate pooling
+//          kernel (generic path, average pool); the MFMA path with the max pool keeps the edge
+//          records of its chunk boundaries here instead
 //   ctr:   two work counters (one per streaming pass of the MFMA path), reset by every call
 struct Workspace {
   float2* part;
