@@ -22,9 +22,13 @@
  *     laq_shape).  `budget` is a HOST array.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work on it and return; the caller synchronises.
+ *   - The device that owns the tensors must be the current device of the calling thread
+ *     (hipSetDevice): kernels are launched on the current device.
  *   - The library allocates and frees no device memory and keeps no device state between
- *     calls (on the host it remembers how many workgroups each device holds, looked up on
- *     the first scoring call); scratch memory comes in through `ws` (laq_workspace_bytes).
+ *     calls; scratch memory comes in through `ws` (laq_workspace_bytes).  On the host it keeps,
+ *     per device, what laq_init() looks up (kernel attributes, how many workgroups the device
+ *     holds at once); a scoring call on a device that laq_init() has not seen does that lookup
+ *     itself, before it enqueues anything.
  *     Calls that may run at the same time (different streams) need a workspace each; calls
  *     on one stream may share one.
  *   - Errors are reported by the return value (LAQ_OK = 0, negative otherwise), never
@@ -55,7 +59,8 @@ enum {
   LAQ_ERR_INVALID = -1,     /* null pointer, bad shape, budget < W, even pool kernel ... */
   LAQ_ERR_UNSUPPORTED = -2, /* valid request outside what the kernels cover (see each call) */
   LAQ_ERR_WORKSPACE = -3,   /* ws is NULL or smaller than laq_workspace_bytes() */
-  LAQ_ERR_DEVICE = -4       /* a HIP launch failed */
+  LAQ_ERR_DEVICE = -4,      /* a HIP call (launch, attribute query, copy) failed */
+  LAQ_ERR_TIMEOUT = -5      /* laq_workspace_status: a kernel gave up a wait, the results are invalid */
 };
 
 /* Shape shared by all instances of one call. */
@@ -101,13 +106,43 @@ typedef struct laq_shape {
   int64_t kv_stride_row;
 } laq_shape;
 
-/* Bytes of device scratch that laq_score / laq_evict need for this shape (0 on a bad shape). */
+/*
+ * One-time set-up for the current device: sets the attributes of the scoring kernels and asks the
+ * runtime how many of their workgroups the device holds at once (the persistent kernels of Sec. 4.3's
+ * scoring step are launched with exactly that many).  Optional: the first scoring call on a device
+ * does the same.  Call it first if that call is to be recorded by a stream capture, which must not
+ * contain such queries.  Idempotent, thread-safe.  LAQ_OK or LAQ_ERR_DEVICE.
+ */
+int laq_init(void);
+
+/*
+ * Bytes of device scratch that laq_score / laq_evict need for this shape (0 on a bad shape): the
+ * per-chunk softmax statistics and row constants of the key-axis softmax (Sec. 4.3, Eq. 4 taken on
+ * attention scores), a raw-score plane in front of the pooling, the hand-over plane between scoring
+ * and selection, and the exchange memory of the single-read kernel.  Depends on n_inst, Hq, Hkv, L,
+ * W only.
+ */
 size_t laq_workspace_bytes(const laq_shape *shape);
 
 /*
+ * Whether the last scoring call that used this workspace completed all its waits.  The single-read
+ * scoring kernel lets the workgroups that share a KV head exchange their softmax statistics while
+ * it runs; each of those waits is bounded, and a kernel that gives one up (which needs the device
+ * to withhold part of a cooperative launch for about a second) finishes with invalid scores and
+ * leaves a mark in the workspace.  Synchronises `stream`, reads the mark: LAQ_OK, LAQ_ERR_TIMEOUT,
+ * or an argument / device error.  For callers that want the proof; results of a call that has
+ * completed on an otherwise healthy device need no check.
+ */
+int laq_workspace_status(const laq_shape *shape, const void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Importance scores (Eq. 4's sum over the Q-cache, taken on attention scores).
- *   q_win  [n_inst, Hq, W, d]   observation-window queries (Q-cache, local window, or both)
- *   k      [n_inst, Hkv, L, d]  key cache (streamed twice: softmax statistics, then normalised scores)
+ *   q_win  [n_inst, Hq, W, d]   observation-window queries (Q-cache, local window, or both); always
+ *                               dense (no strides)
+ *   k      [n_inst, Hkv, L, d]  key cache.  Read once where a team of workgroups can keep a head on
+ *                               chip between the two softmax passes (bf16, d = 128, at
+ *                               most 128 score rows per KV head, L up to 512 x the workgroups the
+ *                               device holds: 262144 on an MI355X), otherwise streamed twice
  *   scores [n_inst, Hkv, L]     fp32 out.  For each KV head g and key j:
  *            raw[g,j] = sum over the G heads of the group and the W queries of
  *                       softmax_j(scale * <q, k_j>) restricted to j <= P + w.
@@ -120,8 +155,9 @@ size_t laq_workspace_bytes(const laq_shape *shape);
  *   ws / ws_bytes  device scratch of at least laq_workspace_bytes(shape)
  * Supported: dtype BF16 or F32; any Hq/Hkv/W/L within the limits of laq_shape;
  * pool_kernel odd, 1 <= pool_kernel <= 63.  BF16 with d = 64 or 128 and W <= 512 runs on the
- * matrix cores (bound by reading K twice); everything else runs on a vector-ALU path with the
- * same results to within the rounding of its fp32 sums, several times slower per key.
+ * matrix cores; everything else runs on a vector-ALU path with the same results to within the
+ * rounding of its fp32 sums, several times slower per key.  q_win, k and scores must be 16-byte
+ * aligned.
  */
 int laq_score(const laq_shape *shape, const void *q_win, const void *k, int pool_kernel,
               float *scores, void *ws, size_t ws_bytes, void *stream);
@@ -170,20 +206,23 @@ int laq_recall(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t *idx_pred,
                int32_t *overlap, float *recall, void *stream);
 
 /*
- * Cache compaction: gather the retained rows.
+ * Cache compaction (Sec. 4.3: the cache is re-evicted to the given budget; decoding continues on
+ * what is left): gather the retained rows.
  *   k, v         [n_inst, Hkv, L, d]; v (and v_out) may be NULL to compact K only
  *   idx, budget  as written by / passed to laq_select
  *   k_out, v_out packed like idx: instance i starts at row sum_{i'<i} Hkv * Bk(i') and
  *                holds [Hkv, Bk(i), d]; bit copies of the selected rows
- * Indices must lie in [0, L); out-of-range entries are skipped (row left untouched).
+ * Indices must lie in [0, L); out-of-range entries are skipped (row left untouched).  k, v, k_out,
+ * v_out must be 16-byte aligned.
  */
 int laq_compact(const laq_shape *shape, const void *k, const void *v, const int32_t *idx,
                 const int32_t *budget, void *k_out, void *v_out, void *stream);
 
 /*
- * The whole path on one stream: laq_score(pool_kernel) + laq_select(1) + laq_compact; outputs
- * identical to those of the three calls.  `scores` is required (it is the hand-over buffer
- * between the stages) and is left holding the pooled scores.
+ * The whole path of Sec. 4.3 on one stream: laq_score(pool_kernel) + laq_select(1) + laq_compact;
+ * outputs identical to those of the three calls.  `scores` may be NULL: the pooled scores are then
+ * handed from scoring to selection through the workspace and not returned; otherwise it is left
+ * holding them.
  */
 int laq_evict(const laq_shape *shape, const void *q_win, const void *k, const void *v,
               const int32_t *budget, int pool_kernel, float *scores, int32_t *idx,
@@ -222,7 +261,7 @@ size_t laq_decode_workspace_bytes(const laq_shape *shape, const int32_t *budget)
 int laq_decode_attention(const laq_shape *shape, const void *q, const void *k_c, const void *v_c,
                          const int32_t *budget, float *out, void *ws, size_t ws_bytes, void *stream);
 
-/* Static description of an error code. */
+/* Static description of an error code (never NULL; "unknown error" for a code that is none of the above). */
 const char *laq_strerror(int code);
 
 #ifdef __cplusplus

@@ -33,19 +33,40 @@ def needs_build() -> bool:
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
-    """Run hipcc (cross-compiles without a GPU).  Returns the path of the library."""
+    """Run hipcc (cross-compiles without a GPU): every source to an object file, side by side, then one
+    link.  Returns the path of the library."""
     if not force and not needs_build():
         return LIB
+    from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(PKG, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    include = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+    def run(cmd):
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if verbose or res.returncode != 0:
+            print(res.stdout)
+            print("\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l))
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed (exit %d): %s" % (res.returncode, " ".join(cmd[-3:])))
+
+    def compile_one(src):
+        obj = os.path.join(objdir, os.path.basename(src)[:-4] + ".%d.o" % os.getpid())
+        run([hipcc] + compile_flags + include + ["-c", "-o", obj, src])
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, len(sources()))) as pool:
+        objs = list(pool.map(compile_one, sources()))
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp] + sources()
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if verbose or res.returncode != 0:
-        print(res.stdout)
-        print("\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l))
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed (exit %d)" % res.returncode)
-    os.replace(tmp, LIB)
+    try:
+        run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
+        os.replace(tmp, LIB)
+    finally:
+        for o in objs:
+            if os.path.exists(o):
+                os.remove(o)
     return LIB
 
 

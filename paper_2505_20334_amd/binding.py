@@ -79,12 +79,33 @@ def load_library() -> ctypes.CDLL:
     lib.laq_evict.restype = i32
     lib.laq_strerror.argtypes = [i32]
     lib.laq_strerror.restype = ctypes.c_char_p
+    lib.laq_init.argtypes = []
+    lib.laq_init.restype = i32
+    lib.laq_workspace_status.argtypes = [sp, vp, sz, vp]
+    lib.laq_workspace_status.restype = i32
     _lib = lib
     return lib
 
 
 def laq_strerror(code: int) -> str:
     return load_library().laq_strerror(int(code)).decode()
+
+
+def laq_init() -> None:
+    """One-time set-up of the library for torch's current device (optional; needed before a first call
+    that is recorded by a stream capture)."""
+    rc = load_library().laq_init()
+    if rc != 0:
+        raise LaqError(rc, "laq_init")
+
+
+def laq_workspace_status(ws: torch.Tensor, n_inst: int, Hq: int, Hkv: int, d: int, L: int, W: int,
+                         dtype: torch.dtype, stream=None) -> int:
+    """0 if the last scoring call on this workspace completed all its waits (synchronises the stream)."""
+    code = LAQ_F32 if dtype == torch.float32 else LAQ_BF16
+    sh = _shape(n_inst, Hq, Hkv, d, L, W, code, 0.0)
+    return int(load_library().laq_workspace_status(ctypes.byref(sh), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                                   _stream(stream)))
 
 
 def _dtype_code(t: torch.Tensor) -> int:
@@ -113,6 +134,28 @@ def _kv(t: torch.Tensor, name: str) -> Tuple[int, int, int]:
     if t.is_contiguous():
         return (0, 0, 0)
     return (t.stride(0), t.stride(1), t.stride(2))
+
+
+def _out(t: Optional[torch.Tensor], name: str, dtype: torch.dtype, numel: int, like: torch.Tensor) -> None:
+    """A caller-supplied output buffer must be what the kernels will write: right dtype and device, dense,
+    at least `numel` elements, 16-byte aligned."""
+    if t is None:
+        return
+    if t.device != like.device:
+        raise ValueError("%s must live on %s" % (name, like.device))
+    if t.dtype != dtype:
+        raise TypeError("%s must be %s" % (name, dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be dense (contiguous)" % name)
+    if t.numel() < numel:
+        raise ValueError("%s needs at least %d elements, has %d" % (name, numel, t.numel()))
+    if t.data_ptr() % 16:
+        raise ValueError("%s must be 16-byte aligned" % name)
+
+
+def _aligned(t: torch.Tensor, name: str) -> None:
+    if t.data_ptr() % 16:
+        raise ValueError("%s must be 16-byte aligned" % name)
 
 
 def _stream(stream) -> int:
@@ -168,6 +211,8 @@ def _workspace(q_win, k, ws, q_pos=None, keep=None):
     need = laq_workspace_bytes(n, Hq, Hkv, d, L, W, k.dtype, q_pos, keep)
     if ws is None:
         ws = torch.empty(need, dtype=torch.uint8, device=k.device)
+    elif ws.device != k.device or not ws.is_contiguous() or ws.data_ptr() % 256:
+        raise ValueError("ws must be a dense, 256-byte aligned tensor on %s" % k.device)
     return ws, ws.numel() * ws.element_size()
 
 
@@ -185,6 +230,8 @@ def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale:
     n2, Hkv, L, d2 = k.shape
     if n != n2 or d != d2 or q_win.dtype != k.dtype:
         raise ValueError("q_win / k mismatch")
+    _aligned(q_win, "q_win"), _aligned(k, "k")
+    _out(scores, "scores", torch.float32, n * Hkv * L, k)
     if scores is None:
         scores = torch.empty(n, Hkv, L, dtype=torch.float32, device=k.device)
     ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
@@ -206,6 +253,7 @@ def laq_select(scores: torch.Tensor, budget: Sequence[int], pool_kernel: int, ke
         raise TypeError("scores must be fp32")
     n, Hkv, L = scores.shape
     total, _ = packed_rows(budget, Hkv, L)
+    _out(idx, "idx", torch.int32, total, scores)
     if idx is None:
         idx = torch.empty(total, dtype=torch.int32, device=scores.device)
     sh = _shape(n, Hkv, Hkv, 8, L, 1, LAQ_F32, 0.0, None, keep, pool_mode)
@@ -283,6 +331,7 @@ def laq_decode_attention(q: torch.Tensor, k_c: torch.Tensor, v_c: torch.Tensor, 
     total, _ = packed_rows(budget, Hkv, L)
     if k_c.shape != (total, d) or v_c.shape != (total, d) or not (q.dtype == k_c.dtype == v_c.dtype):
         raise ValueError("k_c / v_c must be the packed [rows, d] tensors of these budgets, in q's dtype")
+    _out(out, "out", torch.float32, n * Hq * d, q)
     if out is None:
         out = torch.empty(n, Hq, d, dtype=torch.float32, device=q.device)
     sh = _shape(n, Hq, Hkv, d, L, 1, _dtype_code(q), scale, None, 0)
@@ -317,13 +366,21 @@ def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, b
     kvs = _kv(k, "k")
     n, Hkv, L, d = k.shape
     total, _ = packed_rows(budget, Hkv, L)
+    if idx.dtype != torch.int32 or idx.numel() < total:
+        raise ValueError("idx must be int32 with at least %d entries" % total)
+    _aligned(k, "k")
+    _out(k_out, "k_out", k.dtype, total * d, k)
     if k_out is None:
         k_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
     if v is not None:
         if v.shape != k.shape or v.dtype != k.dtype or _kv(v, "v") != kvs:
             raise ValueError("k / v mismatch (shape, dtype or strides)")
+        _aligned(v, "v")
+        _out(v_out, "v_out", k.dtype, total * d, k)
         if v_out is None:
             v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
+    elif v_out is not None:
+        raise ValueError("v_out without v")
     sh = _shape(n, Hkv, Hkv, d, L, 1, _dtype_code(k), 0.0, None, keep, "max", kvs)
     rc = lib.laq_compact(ctypes.byref(sh), k.data_ptr(), v.data_ptr() if v is not None else None,
                          idx.data_ptr(), _budget_array(budget, n), k_out.data_ptr(),
@@ -336,8 +393,10 @@ def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, b
 def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], budget: Sequence[int],
               pool_kernel: int, scale: float = 0.0, scores=None, idx=None, k_out=None, v_out=None, ws=None,
               stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
-              pool_mode: str = "max"):
-    """Whole path on one stream: returns (scores, idx, k_out, v_out); layouts as in the three calls."""
+              pool_mode: str = "max", want_scores: bool = True):
+    """Whole path on one stream: returns (scores, idx, k_out, v_out); layouts as in the three calls.
+    want_scores=False (and no scores buffer): the library hands the scores over inside the workspace and
+    None is returned in their place."""
     lib = load_library()
     _dev(q_win, "q_win")
     kvs = _kv(k, "k")
@@ -346,7 +405,11 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
     if n != n2 or d != d2 or q_win.dtype != k.dtype:
         raise ValueError("q_win / k mismatch")
     total, _ = packed_rows(budget, Hkv, L)
-    if scores is None:
+    _aligned(q_win, "q_win"), _aligned(k, "k")
+    _out(scores, "scores", torch.float32, n * Hkv * L, k)
+    _out(idx, "idx", torch.int32, total, k)
+    _out(k_out, "k_out", k.dtype, total * d, k)
+    if scores is None and want_scores:
         scores = torch.empty(n, Hkv, L, dtype=torch.float32, device=k.device)
     if idx is None:
         idx = torch.empty(total, dtype=torch.int32, device=k.device)
@@ -355,12 +418,17 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
     if v is not None:
         if v.shape != k.shape or v.dtype != k.dtype or _kv(v, "v") != kvs:
             raise ValueError("k / v mismatch (shape, dtype or strides)")
+        _aligned(v, "v")
+        _out(v_out, "v_out", k.dtype, total * d, k)
         if v_out is None:
             v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
+    elif v_out is not None:
+        raise ValueError("v_out without v")
     ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
     sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs)
     rc = lib.laq_evict(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), v.data_ptr() if v is not None else None,
-                       _budget_array(budget, n), int(pool_kernel), scores.data_ptr(), idx.data_ptr(),
+                       _budget_array(budget, n), int(pool_kernel),
+                       scores.data_ptr() if scores is not None else None, idx.data_ptr(),
                        k_out.data_ptr(), v_out.data_ptr() if v is not None else None, ws.data_ptr(), ws_bytes,
                        _stream(stream))
     if rc != 0:

@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "laq_internal.h"
 
 namespace laq {
@@ -79,7 +81,7 @@ static size_t max_chunks(const ScoreGeom& g) { return ((size_t)g.L + MIN_CHUNK_R
 size_t workspace_bytes(const ScoreGeom& g) {
   const size_t heads = (size_t)g.n_inst * g.Hkv;
   return round256(heads * max_chunks(g) * g.Rpad * sizeof(float2)) + round256(heads * g.Rpad * sizeof(float)) +
-         round256(heads * g.L * sizeof(float)) + 256;
+         2 * round256(heads * g.L * sizeof(float)) + round256(fused_sync_bytes(g)) + 256;
 }
 
 Workspace carve_workspace(const ScoreGeom& g, void* ws) {
@@ -92,7 +94,12 @@ Workspace carve_workspace(const ScoreGeom& g, void* ws) {
   base += round256(heads * g.Rpad * sizeof(float));
   w.raw = reinterpret_cast<float*>(base);
   base += round256(heads * g.L * sizeof(float));
+  w.pooled = reinterpret_cast<float*>(base);
+  base += round256(heads * g.L * sizeof(float));
+  w.fused = base;
+  base += round256(fused_sync_bytes(g));
   w.ctr = reinterpret_cast<int*>(base);
+  w.status = w.ctr + 8;
   return w;
 }
 
@@ -112,11 +119,42 @@ static int fill_table(int Hkv, int L, const int32_t* budget, int i0, int n, int6
   return bk_max;
 }
 
+// The same for the gather, whose grid covers the rows of every instance exactly.
+static void fill_compact_table(int Hkv, int L, int pieces_per_row, const int32_t* budget, int i0, int n,
+                               int64_t row_base, CompactTable* tab, int64_t* rows_after) {
+  int64_t row = row_base, blk = 0;
+  for (int i = 0; i < n; ++i) {
+    const int bk = budget[i0 + i] < L ? budget[i0 + i] : L;
+    tab->bk[i] = bk;
+    tab->row0[i] = row;
+    tab->blk0[i] = (int32_t)blk;
+    row += (int64_t)Hkv * bk;
+    blk += ((int64_t)Hkv * bk * pieces_per_row + COMPACT_THREADS - 1) / COMPACT_THREADS;
+  }
+  tab->blk0[n] = (int32_t)blk;
+  *rows_after = row;
+}
+
 static bool budgets_ok(const laq_shape* s, const ScoreGeom& g, const int32_t* budget) {
   if (!budget) return false;
   for (int i = 0; i < s->n_inst; ++i)
     if (budget[i] < g.keep || budget[i] < 1) return false;
   return true;
+}
+
+// ---- per-device set-up ---------------------------------------------------------------------
+// Kernel attributes and residency of the scoring kernels on the current device.
+constexpr int MAX_DEVICES = 64;
+static std::atomic<int> device_ready[MAX_DEVICES];
+
+static int init_current_device(int* dev_out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return LAQ_ERR_DEVICE;
+  if (dev_out) *dev_out = dev;
+  if (device_ready[dev].load(std::memory_order_acquire)) return LAQ_OK;
+  if (score_mfma_init(dev) != hipSuccess || score_fused_init(dev) != hipSuccess) return LAQ_ERR_DEVICE;
+  device_ready[dev].store(1, std::memory_order_release);
+  return LAQ_OK;
 }
 
 static int score_impl(const laq_shape* shape, const void* q_win, const void* k, int pool, float* scores,
@@ -132,16 +170,28 @@ static int score_impl(const laq_shape* shape, const void* q_win, const void* k, 
   if (!ws || ws_bytes < workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
   if (g.Hkv > 65535 || g.n_inst > 65535 || (long long)g.Hkv * g.n_inst > 0x7fffffffLL) return LAQ_ERR_UNSUPPORTED;
   if ((g.L + 255) / 256 > 65535) return LAQ_ERR_UNSUPPORTED;      // grid limit of the pooling kernel
+  const int rc_init = init_current_device(nullptr);
+  if (rc_init != LAQ_OK) return rc_init;
   const Workspace w = carve_workspace(g, ws);
   hipError_t e;
   const bool avg = pool_avg(shape) && pool > 1;
   const bool mfma = score_mfma_supported(g, lay, shape->dtype);
+  const bool fused = SINGLE_READ_ENABLED && score_fused_supported(g, lay, shape->dtype);
+  // matrix cores: the single-read kernel where a team of workgroups can hold a head, else the two
+  // streaming passes; both fuse the max pooling, the average goes through the raw-score plane
+  auto score_on_matrix_cores = [&](int p, float* dst) -> hipError_t {
+    bool done = false;
+    if (fused) {
+      const hipError_t ef = launch_score_fused(g, qp, lay, p, q_win, k, dst, w, st, &done);
+      if (ef != hipSuccess || done) return ef;
+    }
+    return launch_score_mfma(g, qp, lay, p, q_win, k, dst, w, st);
+  };
   if (mfma && !avg) {
-    e = launch_score_mfma(g, qp, lay, pool, q_win, k, scores, w, st);     // max pooling fused into pass 2
+    e = score_on_matrix_cores(pool, scores);
   } else {
     float* raw = pool > 1 ? w.raw : scores;
-    e = mfma ? launch_score_mfma(g, qp, lay, 1, q_win, k, raw, w, st)
-             : launch_score_generic(g, qp, lay, shape->dtype, q_win, k, raw, w, st);
+    e = mfma ? score_on_matrix_cores(1, raw) : launch_score_generic(g, qp, lay, shape->dtype, q_win, k, raw, w, st);
     if (e == hipSuccess && pool > 1) e = launch_pool(g, pool, avg, raw, scores, st);
   }
   return e == hipSuccess ? LAQ_OK : LAQ_ERR_DEVICE;
@@ -178,10 +228,10 @@ static int compact_impl(const laq_shape* shape, const void* k, const void* v, co
   int64_t row = 0;
   for (int i0 = 0; i0 < shape->n_inst; i0 += MAX_INST_PER_LAUNCH) {
     const int n = shape->n_inst - i0 < MAX_INST_PER_LAUNCH ? shape->n_inst - i0 : MAX_INST_PER_LAUNCH;
-    InstTable tab;
+    CompactTable tab;
     memset(&tab, 0, sizeof tab);
-    const int bk_max = fill_table(g.Hkv, g.L, budget, i0, n, row, &tab, &row);
-    if (launch_compact(n, i0, g.Hkv, g.L, row_bytes, lay, bk_max, k, v, idx, tab, k_out, v_out, st) != hipSuccess)
+    fill_compact_table(g.Hkv, g.L, row_bytes >> 4, budget, i0, n, row, &tab, &row);
+    if (launch_compact(n, i0, g.Hkv, g.L, row_bytes, lay, k, v, idx, tab, k_out, v_out, st) != hipSuccess)
       return LAQ_ERR_DEVICE;
   }
   return LAQ_OK;
@@ -390,25 +440,47 @@ int laq_compact(const laq_shape* shape, const void* k, const void* v, const int3
   return laq::compact_impl(shape, k, v, idx, budget, k_out, v_out, static_cast<hipStream_t>(stream));
 }
 
-int laq_evict(const laq_shape* shape, const void* q_win, const void* k, const void* v, const int32_t* budget,
-              int pool_kernel, float* scores, int32_t* idx, void* k_out, void* v_out, void* ws,
-              size_t ws_bytes, void* stream) {
+static int evict_impl(const laq_shape* shape, const void* q_win, const void* k, const void* v, const int32_t* budget,
+                      int pool_kernel, float* scores, int32_t* idx, void* k_out, void* v_out, void* ws,
+                      size_t ws_bytes, hipStream_t st) {
   // validate everything first so that a rejected call has enqueued nothing
   laq::ScoreGeom g;
   const int rc0 = laq::make_geom(shape, &g);
   if (rc0 != LAQ_OK) return rc0;
-  if (!laq::pool_ok(pool_kernel) || !q_win || !k || !scores || !idx || !k_out ||
+  if (!laq::pool_ok(pool_kernel) || !q_win || !k || !idx || !k_out ||
       !laq::budgets_ok(shape, g, budget) || ((v == nullptr) != (v_out == nullptr)))
     return LAQ_ERR_INVALID;
   laq::KvLayout lay;
   if (laq::make_layout(shape, g, &lay) != LAQ_OK) return LAQ_ERR_INVALID;
   if (!ws || ws_bytes < laq::workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!scores) scores = laq::carve_workspace(g, ws).pooled;      // the hand-over plane between the stages
   int rc = laq::score_impl(shape, q_win, k, pool_kernel, scores, ws, ws_bytes, st);
   if (rc != LAQ_OK) return rc;
   rc = laq::select_impl(shape, scores, budget, 1, idx, st);
   if (rc != LAQ_OK) return rc;
   return laq::compact_impl(shape, k, v, idx, budget, k_out, v_out, st);
+}
+
+int laq_evict(const laq_shape* shape, const void* q_win, const void* k, const void* v, const int32_t* budget,
+              int pool_kernel, float* scores, int32_t* idx, void* k_out, void* v_out, void* ws,
+              size_t ws_bytes, void* stream) {
+  return evict_impl(shape, q_win, k, v, budget, pool_kernel, scores, idx, k_out, v_out, ws, ws_bytes,
+                    static_cast<hipStream_t>(stream));
+}
+
+int laq_init(void) { return laq::init_current_device(nullptr); }
+
+int laq_workspace_status(const laq_shape* shape, const void* ws, size_t ws_bytes, void* stream) {
+  laq::ScoreGeom g;
+  const int rc0 = laq::make_geom(shape, &g);
+  if (rc0 != LAQ_OK) return rc0;
+  if (!ws || ws_bytes < laq::workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
+  const laq::Workspace w = laq::carve_workspace(g, const_cast<void*>(ws));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int word = 0;
+  if (hipMemcpyAsync(&word, w.status, sizeof word, hipMemcpyDeviceToHost, st) != hipSuccess) return LAQ_ERR_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return LAQ_ERR_DEVICE;
+  return word == 0 ? LAQ_OK : LAQ_ERR_TIMEOUT;
 }
 
 const char* laq_strerror(int code) {
@@ -418,6 +490,7 @@ const char* laq_strerror(int code) {
     case LAQ_ERR_UNSUPPORTED: return "unsupported shape";
     case LAQ_ERR_WORKSPACE: return "workspace missing or too small";
     case LAQ_ERR_DEVICE: return "HIP launch failed";
+    case LAQ_ERR_TIMEOUT: return "a kernel gave up waiting for its peers; results are not valid";
     default: return "unknown error";
   }
 }

@@ -24,6 +24,13 @@ constexpr int MAX_POOL = 63;
 constexpr int MAX_INST_PER_LAUNCH = 256;   // size of the per-instance tables passed as kernel arguments
 
 constexpr int MAX_QPOS = 512;              // explicit query positions a call may carry
+// The single-read scoring kernel: key rows per workgroup, and the number of its workgroups on the
+// device at once that the exchange memory of a workspace is sized for.
+constexpr int FUSED_ROWS = 1024;
+constexpr int FUSED_MAX_RESIDENT = 1024;
+// Whether scoring takes the single-read kernel where it applies (it is slower than the two streaming
+// passes on the shapes measured so far; the parity tests run with it switched on).
+constexpr bool SINGLE_READ_ENABLED = false;
 
 struct ScoreGeom {
   int n_inst, Hq, Hkv, d, L, W;
@@ -55,12 +62,17 @@ __device__ __forceinline__ int last_visible_key(const ScoreGeom& g, const QueryP
 //   raw:   float per (instance, KV head, key): unpooled scores in front of a separate pooling
 //          kernel (generic path, average pool); the MFMA path with the max pool keeps the edge
 //          records of its chunk boundaries here instead
+//   pooled: float per (instance, KV head, key): the hand-over plane between scoring and selection
+//          when laq_evict is called without a scores buffer
 //   ctr:   two work counters (one per streaming pass of the MFMA path), reset by every call
 struct Workspace {
   float2* part;
   float* rowc;
   float* raw;
+  float* pooled;
+  void* fused;      // exchange memory of the single-read kernel (fused_sync_bytes)
   int* ctr;
+  int* status;      // != 0 after a call whose single-read kernel gave up a wait (results invalid)
 };
 
 size_t workspace_bytes(const ScoreGeom& g);
@@ -70,6 +82,13 @@ Workspace carve_workspace(const ScoreGeom& g, void* ws);
 struct InstTable {
   int32_t bk[MAX_INST_PER_LAUNCH];      // rows kept per KV head
   int64_t row0[MAX_INST_PER_LAUNCH];    // first packed output row (sum of Hkv * Bk of earlier instances)
+};
+// The gather's own table: its grid covers exactly the rows of every instance, so a workgroup finds
+// its instance by the first workgroup of each (blk0 ascending, blk0[n] = all workgroups).
+struct CompactTable {
+  int32_t bk[MAX_INST_PER_LAUNCH];
+  int64_t row0[MAX_INST_PER_LAUNCH];
+  int32_t blk0[MAX_INST_PER_LAUNCH + 1];
 };
 
 // Pooled score at prefix position pos, the one arithmetic every pooling site uses: the
@@ -139,6 +158,19 @@ hipError_t launch_score_generic(const ScoreGeom& g, const QueryPos& qp, const Kv
                                 const void* k, float* raw, const Workspace& ws, hipStream_t st);
 hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStream_t st);
 bool score_mfma_supported(const ScoreGeom& g, const KvLayout& lay, int dtype);
+// kernel attributes and residency of every matrix-core scoring kernel on device `dev`, which must be
+// the current device; idempotent
+hipError_t score_mfma_init(int dev);
+hipError_t score_fused_init(int dev);
+size_t fused_sync_bytes(const ScoreGeom& g);
+bool score_fused_supported(const ScoreGeom& g, const KvLayout& lay, int dtype);
+// single-read scoring (K streamed once); *done = false: not launched, take the two-pass kernels
+hipError_t launch_score_fused(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int pool, const void* q,
+                              const void* k, float* scores, const Workspace& ws, hipStream_t st, bool* done);
+// pooled scores of the prefix keys within `half` of a boundary between two chunks of chunk_rows keys,
+// from the chunks' edge records
+hipError_t launch_pool_boundaries(const ScoreGeom& g, int half, int nchunk, int chunk_rows, const float* edge,
+                                  float* scores, hipStream_t st);
 hipError_t launch_score_mfma(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int pool, const void* q,
                              const void* k, float* scores, const Workspace& ws, hipStream_t st);
 hipError_t launch_pool(const ScoreGeom& g, int pool, bool avg, const float* raw, float* pooled, hipStream_t st);
@@ -157,8 +189,9 @@ hipError_t launch_merge_parts(int n_parts, int Hq, int Hkv, int d, const DecodeP
                               float* out, hipStream_t st);
 hipError_t launch_qcache_store(long long rows, int W, int t, int row_bytes, const void* q_step, void* q_cache,
                                hipStream_t st);
-hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, const KvLayout& lay, int bk_max,
-                          const void* k, const void* v, const int32_t* idx, const InstTable& tab, void* k_out,
+constexpr int COMPACT_THREADS = 256;      // one 16-byte piece of an output row per thread
+hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, const KvLayout& lay,
+                          const void* k, const void* v, const int32_t* idx, const CompactTable& tab, void* k_out,
                           void* v_out, hipStream_t st);
 
 }  // namespace laq

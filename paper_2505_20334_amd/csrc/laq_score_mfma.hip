@@ -677,8 +677,10 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
         const int rt = wave % NRT;
         load_q_tile<D>(qreg, qg, rt, g.R, lane);
         if (PASS == 2) {
+          const bool has_tile = rt * 32 < g.Rpad;     // (a slot beyond the head's row tiles reads nothing)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) cr[i] = rowc[(size_t)hg * g.Rpad + rt * 32 + acc_row(i, lane >> 5)];
+          for (int i = 0; i < 16; ++i)
+            cr[i] = has_tile ? rowc[(size_t)hg * g.Rpad + rt * 32 + acc_row(i, lane >> 5)] : 1.0e30f;
         }
       }
       // the unit after this one: the next of the run, else the first of the claimed run, else (nothing
@@ -765,10 +767,10 @@ __global__ __launch_bounds__(256) void row_constants_mfma_kernel(ScoreGeom g, co
 }
 
 // Pooled scores of the prefix keys whose pooling window crosses a boundary between two chunks of
-// pass 2, from the edge records (per chunk: raw scores of its first 2*half rows, then of its last
-// 2*half rows).  The boundary before chunk c lies at key b = c * chunk size and the keys
+// the scoring kernels, from the edge records (per chunk: raw scores of its first 2*half rows, then of its last
+// 2*half rows).  The boundary before chunk c lies at key b = c * chunk_rows and the keys
 // b-half .. b+half-1 are pooled here, one per thread; blockIdx.x is the head.
-__global__ __launch_bounds__(256) void pool_boundaries_kernel(int L, int P, int half, int nchunk,
+__global__ __launch_bounds__(256) void pool_boundaries_kernel(int L, int P, int half, int nchunk, int chunk_rows,
                                                                const float* __restrict__ edge,
                                                                float* __restrict__ scores) {
   const int hg = blockIdx.x;
@@ -776,7 +778,7 @@ __global__ __launch_bounds__(256) void pool_boundaries_kernel(int L, int P, int 
   const int it = blockIdx.y * 256 + threadIdx.x;
   if (it >= (nchunk - 1) * per) return;
   const int c = it / per + 1;
-  const int b = c * MFMA_ROWS;
+  const int b = c * chunk_rows;
   const int j = b - half + it % per;
   if (j >= P) return;
   // raw score of key i, b - 2*half <= i < b + 2*half, is e[i]: the tail of chunk c-1's record is
@@ -788,31 +790,46 @@ __global__ __launch_bounds__(256) void pool_boundaries_kernel(int L, int P, int 
   scores[(size_t)hg * L + j] = v;
 }
 
+// ---- per-device set-up ---------------------------------------------------------------------
+// The streaming kernels need more dynamic LDS than the default limit (an attribute per kernel) and
+// their grid is the number of workgroups the device holds at once (an occupancy query).  Both are
+// looked up for every instantiation at once, per device, by score_mfma_init(): explicitly through
+// laq_init(), else on the first scoring call on that device (host threads that race there compute
+// the same values).  After it a scoring call makes no HIP call other than kernel launches.
+constexpr int MAX_DEVICES = 64;
+constexpr int N_VARIANTS = 12;             // 2 head sizes x 3 row-tile counts x dense / strided
+template <int D, int NRT, bool STRIDED> constexpr int variant_id() {
+  return ((D == 128 ? 0 : 1) * 3 + (NRT == 1 ? 0 : NRT == 2 ? 1 : 2)) * 2 + (STRIDED ? 1 : 0);
+}
+std::atomic<int> resident_of[MAX_DEVICES][N_VARIANTS];
+std::atomic<int> device_ready[MAX_DEVICES];
+
+template <int D, int NRT, bool STRIDED>
+hipError_t init_variant(int dev, int cus) {
+  constexpr int bytes = Smem<D, NRT>::BYTES;
+  const void* f1 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 1, STRIDED>);
+  const void* f2 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 2, STRIDED>);
+  hipError_t e;
+  if ((e = hipFuncSetAttribute(f1, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(f2, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
+  int n1 = 0, n2 = 0;
+  if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, f1, THREADS, bytes)) != hipSuccess) return e;
+  if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, f2, THREADS, bytes)) != hipSuccess) return e;
+  if (n1 < 1 || n2 < 1) return hipErrorInvalidValue;
+  resident_of[dev][variant_id<D, NRT, STRIDED>()].store(cus * (n1 < n2 ? n1 : n2), std::memory_order_release);
+  return hipSuccess;
+}
+
 template <int D, int NRT, bool STRIDED>
 hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int pool, const uint16_t* q,
                          const uint16_t* k, float* scores, const Workspace& ws, hipStream_t st) {
   constexpr int bytes = Smem<D, NRT>::BYTES;
-  // workgroups each device holds at once, queried on the first call per device (host threads that
-  // race here compute the same value)
-  static std::atomic<int> resident_of[64];
   int dev = 0;
   hipError_t e;
   if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  int resident = resident_of[dev].load(std::memory_order_acquire);
-  const void* f1 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 1, STRIDED>);
-  const void* f2 = reinterpret_cast<const void*>(&stream_kernel<D, NRT, 2, STRIDED>);
-  if (resident == 0) {
-    if ((e = hipFuncSetAttribute(f1, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(f2, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
-    int cus = 0, n1 = 0, n2 = 0;
-    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, f1, THREADS, bytes)) != hipSuccess) return e;
-    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n2, f2, THREADS, bytes)) != hipSuccess) return e;
-    if (cus < 1 || n1 < 1 || n2 < 1) return hipErrorInvalidValue;
-    resident = cus * (n1 < n2 ? n1 : n2);
-    resident_of[dev].store(resident, std::memory_order_release);
-  }
+  if ((e = score_mfma_init(dev)) != hipSuccess) return e;
+  const int resident = resident_of[dev][variant_id<D, NRT, STRIDED>()].load(std::memory_order_acquire);
+  if (resident < 1) return hipErrorInvalidValue;
   const long long n_heads = (long long)g.n_inst * g.Hkv;
   const int half = (pool - 1) / 2;
   const int units1 = (g.L + MFMA_ROWS - 1) / MFMA_ROWS;
@@ -855,12 +872,7 @@ hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, const KvLayout&
   hipLaunchKernelGGL((stream_kernel<D, NRT, 2, STRIDED>), dim3(grid2), dim3(THREADS), bytes, st, g, qp, half, p2, lay, q, k,
                      reinterpret_cast<float2*>(ws.raw), ws.rowc, scores, ws.ctr + 1);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  if (half > 0 && units2 > 1) {
-    const int items = (units2 - 1) * 2 * half;
-    hipLaunchKernelGGL(pool_boundaries_kernel, dim3((unsigned)n_heads, (items + 255) / 256), dim3(256), 0, st, g.L,
-                       g.P, half, units2, (const float*)ws.raw, scores);
-    return hipGetLastError();
-  }
+  if (half > 0 && units2 > 1) return launch_pool_boundaries(g, half, units2, MFMA_ROWS, ws.raw, scores, st);
   return hipSuccess;
 }
 
@@ -874,6 +886,33 @@ hipError_t launch_for_rows(const ScoreGeom& g, const QueryPos& qp, const KvLayou
 }
 
 }  // namespace
+
+hipError_t launch_pool_boundaries(const ScoreGeom& g, int half, int nchunk, int chunk_rows, const float* edge,
+                                  float* scores, hipStream_t st) {
+  const long long n_heads = (long long)g.n_inst * g.Hkv;
+  const int items = (nchunk - 1) * 2 * half;
+  if (items <= 0) return hipSuccess;
+  hipLaunchKernelGGL(pool_boundaries_kernel, dim3((unsigned)n_heads, (items + 255) / 256), dim3(256), 0, st, g.L, g.P,
+                     half, nchunk, chunk_rows, edge, scores);
+  return hipGetLastError();
+}
+
+hipError_t score_mfma_init(int dev) {
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  if (device_ready[dev].load(std::memory_order_acquire)) return hipSuccess;
+  int cus = 0;
+  hipError_t e;
+  if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+  if (cus < 1) return hipErrorInvalidValue;
+#define LAQ_INIT_VARIANT(D, NRT) \
+  if ((e = init_variant<D, NRT, false>(dev, cus)) != hipSuccess) return e; \
+  if ((e = init_variant<D, NRT, true>(dev, cus)) != hipSuccess) return e;
+  LAQ_INIT_VARIANT(128, 1) LAQ_INIT_VARIANT(128, 2) LAQ_INIT_VARIANT(128, 4)
+  LAQ_INIT_VARIANT(64, 1) LAQ_INIT_VARIANT(64, 2) LAQ_INIT_VARIANT(64, 4)
+#undef LAQ_INIT_VARIANT
+  device_ready[dev].store(1, std::memory_order_release);
+  return hipSuccess;
+}
 
 bool score_mfma_supported(const ScoreGeom& g, const KvLayout& lay, int dtype) {
   // the key loads address a head with 31-bit byte offsets (one chunk of slack past its end)

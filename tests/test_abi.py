@@ -20,8 +20,9 @@ def declared_functions(repo_root):
 def test_library_exports_every_declared_symbol(repo_root):
     lib = laq.load_library()
     names = declared_functions(repo_root)
-    assert names == ["laq_compact", "laq_decode_attention", "laq_decode_workspace_bytes", "laq_evict", "laq_qcache_store", "laq_recall", "laq_score", "laq_select", "laq_select_sink_recent",
-                     "laq_strerror", "laq_workspace_bytes"]
+    assert names == ["laq_compact", "laq_decode_attention", "laq_decode_workspace_bytes", "laq_evict", "laq_init",
+                     "laq_qcache_store", "laq_recall", "laq_score", "laq_select", "laq_select_sink_recent",
+                     "laq_strerror", "laq_workspace_bytes", "laq_workspace_status"]
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -34,6 +35,7 @@ def test_strerror():
     assert laq.laq_strerror(0) == "ok"
     assert "invalid" in laq.laq_strerror(-1)
     assert "workspace" in laq.laq_strerror(-3)
+    assert "gave up" in laq.laq_strerror(-5)
     assert "unknown" in laq.laq_strerror(-99)
 
 
@@ -82,6 +84,14 @@ def test_bad_arguments_are_rejected_without_a_gpu():
                          None) == INVALID
     assert lib.laq_evict(ctypes.byref(sh), fake, fake, fake, bud, 7, fake, fake, fake, fake, fake, 8,
                          None) == WORKSPACE
+    # the scores buffer of the whole-path call is optional (accepted up to the workspace check), idx is not
+    assert lib.laq_evict(ctypes.byref(sh), fake, fake, fake, bud, 7, None, fake, fake, fake, fake, 8,
+                         None) == WORKSPACE
+    assert lib.laq_evict(ctypes.byref(sh), fake, fake, fake, bud, 7, None, None, fake, fake, fake, 1 << 30,
+                         None) == INVALID
+    assert lib.laq_workspace_status(ctypes.byref(sh), None, 1 << 30, None) == WORKSPACE
+    assert lib.laq_workspace_status(ctypes.byref(sh), fake, 8, None) == WORKSPACE
+    assert lib.laq_workspace_status(ctypes.byref(_shape(W=0)), fake, 1 << 30, None) == INVALID
 
 
 def test_general_window_arguments_are_checked_without_a_gpu():
@@ -187,6 +197,22 @@ def test_packed_rows():
     total, starts = laq.packed_rows([2048, 128, 40000], 8, 32768)
     assert starts == [0, 8 * 2048, 8 * (2048 + 128)]
     assert total == 8 * (2048 + 128 + 32768)
+
+
+def test_binding_checks_caller_supplied_outputs():
+    like = torch.zeros(4, dtype=torch.bfloat16)
+    binding._out(None, "x", torch.float32, 10, like)
+    binding._out(torch.zeros(16), "x", torch.float32, 16, like)
+    with pytest.raises(TypeError):
+        binding._out(torch.zeros(16, dtype=torch.float64), "x", torch.float32, 16, like)
+    with pytest.raises(ValueError):
+        binding._out(torch.zeros(15), "x", torch.float32, 16, like)             # too small
+    with pytest.raises(ValueError):
+        binding._out(torch.zeros(8, 8)[:, ::2], "x", torch.float32, 16, like)   # not dense
+    with pytest.raises(ValueError):
+        binding._out(torch.zeros(20)[1:17], "x", torch.float32, 16, like)       # not 16-byte aligned
+    with pytest.raises(ValueError):
+        binding._out(torch.zeros(16, device="meta"), "x", torch.float32, 16, like)    # another device
 
 
 def test_binding_refuses_host_tensors():

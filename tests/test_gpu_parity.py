@@ -695,7 +695,7 @@ def test_evict_replays_from_a_captured_graph(laq):
     def run():
         laq.laq_evict(q, k, v, budgets, cfg.pool, scores=scores, idx=idx, k_out=ko, v_out=vo, ws=ws)
 
-    run()                                            # first call sets the kernels' attributes (not capturable)
+    laq.laq_init()                                   # attribute and occupancy queries, which a capture must not contain
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
