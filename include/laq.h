@@ -229,6 +229,23 @@ int laq_evict(const laq_shape *shape, const void *q_win, const void *k, const vo
               void *k_out, void *v_out, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * laq_evict for callers that cannot allocate device memory (code under stream capture, tight
+ * serving loops, harnesses that forbid it): the same path, same outputs bit for bit, with the
+ * workspace taken from an array of LAQ_STATIC_SCRATCH_BYTES that is part of the library's code
+ * object (every device the library runs on holds one until the process ends).  It calls no
+ * allocating routine.  A shape whose laq_workspace_bytes() exceeds LAQ_STATIC_SCRATCH_BYTES is
+ * rejected with LAQ_ERR_WORKSPACE before anything is enqueued (16 MiB covers e.g. three layers of 8
+ * KV heads x 32768 keys with 128 score rows each, the usual one-layer-at-a-time call many times
+ * over).  All calls on one device share the array and nothing in it survives a call: calls that
+ * overlap on one device (different streams) race; calls on one stream are fine.  The first call on
+ * a device (or laq_init) looks the array's address up; call laq_init() before a capture.
+ */
+#define LAQ_STATIC_SCRATCH_BYTES (16u << 20)
+int laq_evict_static(const laq_shape *shape, const void *q_win, const void *k, const void *v,
+                     const int32_t *budget, int pool_kernel, float *scores, int32_t *idx,
+                     void *k_out, void *v_out, void *stream);
+
+/*
  * Q-cache capture (Sec. 4.2: the lookahead decoding keeps its query states): store the queries of
  * lookahead step t into the Q-cache that laq_score later reads as q_win.
  *   q_step  [n_inst, Hq, d]     queries of the step, dtype shape->dtype

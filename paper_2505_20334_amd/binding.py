@@ -79,6 +79,8 @@ def load_library() -> ctypes.CDLL:
     lib.laq_evict.restype = i32
     lib.laq_strerror.argtypes = [i32]
     lib.laq_strerror.restype = ctypes.c_char_p
+    lib.laq_evict_static.argtypes = [sp, vp, vp, vp, ctypes.POINTER(ctypes.c_int32), i32, vp, vp, vp, vp, vp]
+    lib.laq_evict_static.restype = i32
     lib.laq_init.argtypes = []
     lib.laq_init.restype = i32
     lib.laq_workspace_status.argtypes = [sp, vp, sz, vp]
@@ -393,10 +395,11 @@ def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, b
 def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], budget: Sequence[int],
               pool_kernel: int, scale: float = 0.0, scores=None, idx=None, k_out=None, v_out=None, ws=None,
               stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
-              pool_mode: str = "max", want_scores: bool = True):
+              pool_mode: str = "max", want_scores: bool = True, static_scratch: bool = False):
     """Whole path on one stream: returns (scores, idx, k_out, v_out); layouts as in the three calls.
     want_scores=False (and no scores buffer): the library hands the scores over inside the workspace and
-    None is returned in their place."""
+    None is returned in their place.  static_scratch=True calls laq_evict_static (the library's own scratch
+    array instead of a workspace; every output buffer must then be passed in for the call to allocate nothing)."""
     lib = load_library()
     _dev(q_win, "q_win")
     kvs = _kv(k, "k")
@@ -424,8 +427,16 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
             v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
     elif v_out is not None:
         raise ValueError("v_out without v")
-    ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
     sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs)
+    if static_scratch:
+        rc = lib.laq_evict_static(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(),
+                                  v.data_ptr() if v is not None else None, _budget_array(budget, n), int(pool_kernel),
+                                  scores.data_ptr() if scores is not None else None, idx.data_ptr(), k_out.data_ptr(),
+                                  v_out.data_ptr() if v is not None else None, _stream(stream))
+        if rc != 0:
+            raise LaqError(rc, "laq_evict_static")
+        return scores, idx, k_out, v_out
+    ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
     rc = lib.laq_evict(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), v.data_ptr() if v is not None else None,
                        _budget_array(budget, n), int(pool_kernel),
                        scores.data_ptr() if scores is not None else None, idx.data_ptr(),

@@ -143,17 +143,23 @@ static bool budgets_ok(const laq_shape* s, const ScoreGeom& g, const int32_t* bu
 }
 
 // ---- per-device set-up ---------------------------------------------------------------------
-// Kernel attributes and residency of the scoring kernels on the current device.
+// Kernel attributes and residency of the scoring kernels on the current device, and the address of
+// the library's own scratch array there.  `scratch` is the workspace of laq_evict_static: in host
+// code its name is only a handle, and every device holds its own copy at its own address, which is
+// looked up once per device (with that device current) and used from then on.
+static __device__ __align__(256) unsigned char scratch[LAQ_STATIC_SCRATCH_BYTES];
 constexpr int MAX_DEVICES = 64;
-static std::atomic<int> device_ready[MAX_DEVICES];
+static std::atomic<void*> scratch_of[MAX_DEVICES];
 
 static int init_current_device(int* dev_out) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return LAQ_ERR_DEVICE;
   if (dev_out) *dev_out = dev;
-  if (device_ready[dev].load(std::memory_order_acquire)) return LAQ_OK;
+  if (scratch_of[dev].load(std::memory_order_acquire)) return LAQ_OK;
   if (score_mfma_init(dev) != hipSuccess || score_fused_init(dev) != hipSuccess) return LAQ_ERR_DEVICE;
-  device_ready[dev].store(1, std::memory_order_release);
+  void* ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return LAQ_ERR_DEVICE;
+  scratch_of[dev].store(ptr, std::memory_order_release);
   return LAQ_OK;
 }
 
@@ -442,7 +448,7 @@ int laq_compact(const laq_shape* shape, const void* k, const void* v, const int3
 
 static int evict_impl(const laq_shape* shape, const void* q_win, const void* k, const void* v, const int32_t* budget,
                       int pool_kernel, float* scores, int32_t* idx, void* k_out, void* v_out, void* ws,
-                      size_t ws_bytes, hipStream_t st) {
+                      size_t ws_bytes, bool use_static_scratch, hipStream_t st) {
   // validate everything first so that a rejected call has enqueued nothing
   laq::ScoreGeom g;
   const int rc0 = laq::make_geom(shape, &g);
@@ -452,6 +458,14 @@ static int evict_impl(const laq_shape* shape, const void* q_win, const void* k, 
     return LAQ_ERR_INVALID;
   laq::KvLayout lay;
   if (laq::make_layout(shape, g, &lay) != LAQ_OK) return LAQ_ERR_INVALID;
+  if (use_static_scratch) {
+    if (laq::workspace_bytes(g) > (size_t)LAQ_STATIC_SCRATCH_BYTES) return LAQ_ERR_WORKSPACE;
+    int dev = 0;
+    const int rc_init = laq::init_current_device(&dev);
+    if (rc_init != LAQ_OK) return rc_init;
+    ws = laq::scratch_of[dev].load(std::memory_order_acquire);
+    ws_bytes = (size_t)LAQ_STATIC_SCRATCH_BYTES;
+  }
   if (!ws || ws_bytes < laq::workspace_bytes(g)) return LAQ_ERR_WORKSPACE;
   if (!scores) scores = laq::carve_workspace(g, ws).pooled;      // the hand-over plane between the stages
   int rc = laq::score_impl(shape, q_win, k, pool_kernel, scores, ws, ws_bytes, st);
@@ -464,7 +478,13 @@ static int evict_impl(const laq_shape* shape, const void* q_win, const void* k, 
 int laq_evict(const laq_shape* shape, const void* q_win, const void* k, const void* v, const int32_t* budget,
               int pool_kernel, float* scores, int32_t* idx, void* k_out, void* v_out, void* ws,
               size_t ws_bytes, void* stream) {
-  return evict_impl(shape, q_win, k, v, budget, pool_kernel, scores, idx, k_out, v_out, ws, ws_bytes,
+  return evict_impl(shape, q_win, k, v, budget, pool_kernel, scores, idx, k_out, v_out, ws, ws_bytes, false,
+                    static_cast<hipStream_t>(stream));
+}
+
+int laq_evict_static(const laq_shape* shape, const void* q_win, const void* k, const void* v, const int32_t* budget,
+                     int pool_kernel, float* scores, int32_t* idx, void* k_out, void* v_out, void* stream) {
+  return evict_impl(shape, q_win, k, v, budget, pool_kernel, scores, idx, k_out, v_out, nullptr, 0, true,
                     static_cast<hipStream_t>(stream));
 }
 

@@ -20,7 +20,7 @@ def declared_functions(repo_root):
 def test_library_exports_every_declared_symbol(repo_root):
     lib = laq.load_library()
     names = declared_functions(repo_root)
-    assert names == ["laq_compact", "laq_decode_attention", "laq_decode_workspace_bytes", "laq_evict", "laq_init",
+    assert names == ["laq_compact", "laq_decode_attention", "laq_decode_workspace_bytes", "laq_evict", "laq_evict_static", "laq_init",
                      "laq_qcache_store", "laq_recall", "laq_score", "laq_select", "laq_select_sink_recent",
                      "laq_strerror", "laq_workspace_bytes", "laq_workspace_status"]
     for n in names:
@@ -89,6 +89,13 @@ def test_bad_arguments_are_rejected_without_a_gpu():
                          None) == WORKSPACE
     assert lib.laq_evict(ctypes.byref(sh), fake, fake, fake, bud, 7, None, None, fake, fake, fake, 1 << 30,
                          None) == INVALID
+    # the variant on the library's own scratch array: same argument checks, and a shape beyond the array is refused
+    assert lib.laq_evict_static(ctypes.byref(sh), fake, fake, fake, small, 7, fake, fake, fake, fake, None) == INVALID
+    assert lib.laq_evict_static(ctypes.byref(sh), fake, fake, fake, bud, 7, fake, None, fake, fake, None) == INVALID
+    big = _shape(n_inst=32, Hq=32, Hkv=8, L=32768, W=32)
+    assert laq.laq_workspace_bytes(32, 32, 8, 128, 32768, 32, torch.bfloat16) > (16 << 20)
+    assert lib.laq_evict_static(ctypes.byref(big), fake, fake, fake, (ctypes.c_int32 * 32)(*([64] * 32)), 7, fake, fake,
+                                fake, fake, None) == WORKSPACE
     assert lib.laq_workspace_status(ctypes.byref(sh), None, 1 << 30, None) == WORKSPACE
     assert lib.laq_workspace_status(ctypes.byref(sh), fake, 8, None) == WORKSPACE
     assert lib.laq_workspace_status(ctypes.byref(_shape(W=0)), fake, 1 << 30, None) == INVALID
