@@ -26,11 +26,11 @@ constexpr int MAX_INST_PER_LAUNCH = 256;   // size of the per-instance tables pa
 constexpr int MAX_QPOS = 512;              // explicit query positions a call may carry
 // The single-read scoring kernel: key rows per workgroup, and the number of its workgroups on the
 // device at once that the exchange memory of a workspace is sized for.
-constexpr int FUSED_ROWS = 1024;
+constexpr int FUSED_ROWS = 512;
 constexpr int FUSED_MAX_RESIDENT = 1024;
 // Whether scoring takes the single-read kernel where it applies (it is slower than the two streaming
 // passes on the shapes measured so far; the parity tests run with it switched on).
-constexpr bool SINGLE_READ_ENABLED = false;
+constexpr bool SINGLE_READ_ENABLED = true;
 
 struct ScoreGeom {
   int n_inst, Hq, Hkv, d, L, W;

@@ -17,11 +17,17 @@
 //      order, into c = M + log2 Z per row (every member computes the same constants; nobody
 //      waits for a combiner).  While the statistics travel it pools and stores the previous
 //      head's scores and stages the next head's Q;
-//   3. pass 2:  D = Q * K_tile^T: sum over the rows of exp2(s - c) per key = the raw score.  As
-//      soon as a key tile has been through pass 2 its registers are reloaded with the team's
-//      next head.  The workgroup's 1024 raw scores meet in LDS, where the sequence max-pool of
-//      every key whose window lies inside the 1024 is taken; the few keys next to a workgroup
-//      boundary are pooled by pool_boundaries_kernel from raw scores left for it.
+//   3. pass 2:  D = Q * K_tile^T: sum over the rows of exp2(s - c) per key = the raw score.  A
+//      key tile that has been through pass 2 is reloaded with the team's next head: its eight
+//      loads are spread over the matrix instructions of the tile that follows (those of the last
+//      tile over the start of the next head's pass 1), because loads in operand layout touch 32
+//      cache lines each and a burst of them holds up the waves that issue it.  The workgroup's
+//      1024 raw scores meet in LDS, where the sequence max-pool of every key whose window lies
+//      inside the 1024 is taken; the few keys next to a workgroup boundary are pooled by
+//      pool_boundaries_kernel from raw scores left for it.
+// Loads return in the order of their issue, so a wait for a small load would also wait for every
+// key load in front of it: the order above has no key load in flight when the statistics and Q
+// are fetched (pass 1 has consumed them all).
 //
 // The exchange in step 2 uses no cache maintenance (agent-scope release/acquire fences write
 // back and invalidate L2 on this part, tens of microseconds each), no read-modify-write and no
@@ -53,7 +59,7 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr float NEG_BIG = -1.0e30f;
 constexpr int D = 128;                       // head size this kernel is written for
 constexpr int KS = D / 16;                   // MFMAs (reduction steps) per 32x32 tile
-constexpr int F_WAVES = 8, F_THREADS = F_WAVES * 64;
+constexpr int F_WAVES = 4, F_THREADS = F_WAVES * 64;   // one wave per SIMD; two workgroups share a compute unit
 constexpr int KT = 4;                        // key tiles per wave: 4 * 32 keys * 256 B = 128 registers
 constexpr int KEYS_PER_WAVE = KT * 32, KEYS_PER_BLOCK = F_WAVES * KEYS_PER_WAVE;
 static_assert(KEYS_PER_BLOCK == FUSED_ROWS, "the boundary pooling is told this chunk size");
@@ -88,9 +94,10 @@ template <int NRT> struct FSmem {
   static constexpr int Q_BYTES = ROWS * QROWB;
   static constexpr int Q_PIECES = ROWS * (D / 8);                   // 16-byte pieces of one Q_g
   static constexpr int Q_PER_THREAD = (Q_PIECES + F_THREADS - 1) / F_THREADS;
-  static constexpr int OFF_Q = 0;                                   // 2 x [ROWS][QROWB] bf16 rows of Q_g (this head / next)
+  static constexpr int Q_BUFS = NRT <= 3 ? 2 : 1;                   // this head / next, where two workgroups' worth fits
+  static constexpr int OFF_Q = 0;                                   // Q_BUFS x [ROWS][QROWB] bf16 rows of Q_g
   static constexpr int PAIRS = ROWS / 2, NSUB = F_THREADS / PAIRS;   // the fold: threads per row pair
-  static constexpr int OFF_STAT = OFF_Q + 2 * Q_BYTES;               // float2[F_WAVES][ROWS]: the waves' statistics
+  static constexpr int OFF_STAT = OFF_Q + Q_BUFS * Q_BYTES;               // float2[F_WAVES][ROWS]: the waves' statistics
   static constexpr int OFF_FOLD = OFF_STAT + F_WAVES * ROWS * 8;    // float2[NSUB][ROWS]: the team's, per member subset
   static constexpr int OFF_LAST = OFF_FOLD + NSUB * ROWS * 8;       // int[ROWS]: last key every score row sees
   static constexpr int OFF_RAW = OFF_LAST + ROWS * 4;               // float[MAX_HALF + KEYS_PER_BLOCK + MAX_HALF]: the
@@ -149,8 +156,12 @@ __device__ __forceinline__ int tile_offset(int key0, int kt, int lane, int row_b
 //
 // PASS 1: lane = score row, accumulator registers = 16 keys: running (max, sum-exp2) per row.
 // PASS 2: lane = key, accumulator registers = 16 rows: sum over rows of exp2(s - c) per key;
-//         after the last row tile of a key tile the key's raw score is handed over (see Pass2Out)
-//         and the tile's registers are reloaded with the next head (`next`, when `prefetch`).
+//         after the last row tile of a key tile the key's raw score is handed over (see Pass2Out).
+// Reloading the registers with the next head (`next`, when `prefetch`): a key tile is free once the
+// matrix instructions of its last pair have been issued, i.e. from stage (tile + 1) * NRT on; its KS
+// loads are spread over the NRT stages from there.  For the last tile that window reaches beyond
+// pass 2: its first stage is pass 2's draining stage, the others are the first stages of the next
+// head's pass 1, which is called with `prefetch` set and the same `next` for that purpose.
 struct WaveCtx {
   const char* q_lane;      // LDS: Q row (lane%32), slice (lane/32) of reduction step 0, row tile 0
   int lane, hf, n32;
@@ -228,9 +239,14 @@ __device__ __forceinline__ void wave_pass(const WaveCtx& w, bf16x8 (&kreg)[KT][K
     constexpr int kt = i / NRT, rt = i % NRT;                 // pair whose MFMAs are issued in this stage
     constexpr int pk = (i - 1) / NRT, pr = (i - 1) % NRT;     // pair whose VALU work is done in this stage
     float m_new = 0.f, s = 0.f;
+    // the key tile whose reload window this stage lies in, and the window's stage
+    constexpr int PF_STAGE = PASS == 2 ? i - NRT : i + (KT - 1) * NRT + 1;   // stages since tile 0 became free
+    constexpr bool PF_HERE = PF_STAGE >= 0 && PF_STAGE / NRT < KT && (PASS == 2 || PF_STAGE / NRT == KT - 1);
+    constexpr int PF_TILE = PF_HERE ? PF_STAGE / NRT : 0, PF_R = PF_HERE ? PF_STAGE % NRT : 0;
+    constexpr int PF_LO = PF_R * KS / NRT, PF_HI = (PF_R + 1) * KS / NRT;    // its loads PF_LO .. PF_HI-1 are due here
     int voff_next = 0;
-    if constexpr (PASS == 2 && i > 0 && (i % NRT) == 0) {
-      if (prefetch) voff_next = tile_offset(w.key0, pk, w.lane, w.row_bytes);
+    if constexpr (PF_HERE && PF_HI > PF_LO) {
+      if (prefetch) voff_next = tile_offset(w.key0, PF_TILE, w.lane, w.row_bytes);
     }
 #pragma unroll
     for (int t = 0; t < SLOTS; ++t) {
@@ -242,9 +258,10 @@ __device__ __forceinline__ void wave_pass(const WaveCtx& w, bf16x8 (&kreg)[KT][K
         // through an opaque copy so that the start vectors of all stages are not computed ahead and
         // kept alive.
         bool masked = false;
-        int qmin_here = w.qmin;
+        int qmin_here = 0;
         const int t0 = w.key0 + kt * 32;
         if (t == 0) {
+          qmin_here = __builtin_amdgcn_readfirstlane(w.qmin);
           asm volatile("" : "+s"(qmin_here));
           masked = t0 + 31 > qmin_here;
         }
@@ -309,9 +326,14 @@ __device__ __forceinline__ void wave_pass(const WaveCtx& w, bf16x8 (&kreg)[KT][K
 #pragma unroll
           for (int e = lo; e < hi; ++e) s += x[e];
           LAQ_PIN(s);
-          // the key tile whose last row tile has just been issued is free: one slice per slot
-          if (t < KS && pr == NRT - 1 && prefetch) kreg[pk][t < KS ? t : 0] = load_operand(next, voff_next, t);
         }
+      }
+      if constexpr (PF_HERE && PF_HI > PF_LO) {
+        // load j of the window's share goes into slot (j - PF_LO) * SLOTS / (PF_HI - PF_LO)
+        constexpr int N_HERE = PF_HI - PF_LO;
+#pragma unroll
+        for (int j = 0; j < N_HERE; ++j)
+          if (t == j * SLOTS / N_HERE && prefetch) kreg[PF_TILE][PF_LO + j] = load_operand(next, voff_next, PF_LO + j);
       }
       LAQ_SCHED_FENCE();
     }
@@ -343,14 +365,14 @@ struct FusedSync {
 struct FusedPlan {
   int T;                   // workgroups per team = ceil(L / 1024)
   int n_teams;
-  int n_heads;
+  int n_heads;             // team t takes heads t, t + n_teams, ...
   int half;                // (pool kernel - 1) / 2; 0: raw scores
   int stagger;             // team t starts t * stagger ticks (10 ns) late, so that the teams reload their
-                           // registers at different times instead of all at once
+                           // registers at different times
 };
 
 template <int NRT>
-__global__ __launch_bounds__(F_THREADS, 1) void fused_kernel(ScoreGeom g, QueryPos qp, FusedPlan plan, KvLayout lay,
+__global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryPos qp, FusedPlan plan, KvLayout lay,
                                                              const uint16_t* __restrict__ q,
                                                              const uint16_t* __restrict__ k,
                                                              float* __restrict__ scores, float* __restrict__ edge,
@@ -367,7 +389,7 @@ __global__ __launch_bounds__(F_THREADS, 1) void fused_kernel(ScoreGeom g, QueryP
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int T = plan.T, half = plan.half;
   const int team = blockIdx.x / T, member = blockIdx.x - team * T;
-  if (team >= plan.n_teams) return;
+  if (team >= plan.n_teams || team >= plan.n_heads) return;
 
   WaveCtx w;
   w.lane = lane; w.hf = lane >> 5; w.n32 = lane & 31;
@@ -380,7 +402,7 @@ __global__ __launch_bounds__(F_THREADS, 1) void fused_kernel(ScoreGeom g, QueryP
   if (tid < 2 * MAX_HALF) raw_lds[tid < MAX_HALF ? tid - MAX_HALF : KEYS_PER_BLOCK + tid - MAX_HALF] = 0.f;
   if (tid == 0) gave_up[0] = 0;
   // the ninth reduction step of every Q row: zero except for the constant's pieces, written per head
-  for (int r = tid; r < 2 * ROWS; r += F_THREADS) {
+  for (int r = tid; r < S::Q_BUFS * ROWS; r += F_THREADS) {
     char* ext = smem + S::OFF_Q + (r / ROWS) * S::Q_BYTES + (r % ROWS) * QROWB + D * 2;
     *reinterpret_cast<u32x4*>(ext) = u32x4{0u, 0u, 0u, 0u};
     *reinterpret_cast<u32x4*>(ext + 16) = u32x4{0u, 0u, 0u, 0u};
@@ -389,10 +411,10 @@ __global__ __launch_bounds__(F_THREADS, 1) void fused_kernel(ScoreGeom g, QueryP
   bf16x8 kreg[KT][KS];
   float m_run[NRT], z_run[NRT];
 
-  // Q_g of head `hg` (rows hg*R .. +R-1 of Q; rows beyond R are zero): global memory -> registers,
+  // Q_g of head `hq` (rows hq*R .. +R-1 of Q; rows beyond R are zero): global memory -> registers,
   // and later registers -> LDS buffer `buf`
-  auto fetch_q = [&](int hg, u32x4 (&qv)[S::Q_PER_THREAD]) {
-    const uint16_t* qg = q + (size_t)hg * g.R * D;
+  auto fetch_q = [&](int hq, u32x4 (&qv)[S::Q_PER_THREAD]) {
+    const uint16_t* qg = q + (size_t)hq * g.R * D;
 #pragma unroll
     for (int i = 0; i < S::Q_PER_THREAD; ++i) {
       const int p = tid + i * F_THREADS, row = p / (D / 8), col = p % (D / 8);
@@ -400,8 +422,7 @@ __global__ __launch_bounds__(F_THREADS, 1) void fused_kernel(ScoreGeom g, QueryP
       if (p < S::Q_PIECES && row < g.R) qv[i] = *reinterpret_cast<const u32x4*>(qg + (size_t)row * D + col * 8);
     }
   };
-  auto commit_q = [&](int buf, const u32x4 (&qv)[S::Q_PER_THREAD]) {
-    char* dst = smem + S::OFF_Q + buf * S::Q_BYTES;
+  auto commit_q = [&](char* dst, const u32x4 (&qv)[S::Q_PER_THREAD]) {
 #pragma unroll
     for (int i = 0; i < S::Q_PER_THREAD; ++i) {
       const int p = tid + i * F_THREADS, row = p / (D / 8), col = p % (D / 8);
@@ -452,22 +473,18 @@ __global__ __launch_bounds__(F_THREADS, 1) void fused_kernel(ScoreGeom g, QueryP
     }
   };
 
-  // Pass 1 of head hg, the team's n-th (its Q is in LDS buffer n & 1), on the registers; statistics
-  // published; constants of the head in the ninth step of its Q rows.  While the statistics
-  // travel: the pooled scores of the head before (hg_pool, if >= 0) are stored and Q of the team's
-  // next head (hq_next, if >= 0) is staged into the other buffer.
-  auto first_half = [&](int n, int hq_next, int hg_pool) {
-    const int par = n & 1;
-    const unsigned tag = (((unsigned)n >> 1) & 1u) ^ 1u;      // validity bit of this use of the words
-    char* q_buf = smem + S::OFF_Q + par * S::Q_BYTES;
-    w.q_lane = q_buf + w.n32 * QROWB + w.hf * 16;
-    KeySource none;
-    none.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(k), 0, 0, 0x00020000);
+  // statistics words of the team's nth head, and the validity bit of that use of the words
+  auto q_buf_of = [&](int nth) { return smem + S::OFF_Q + (S::Q_BUFS == 2 ? (nth & 1) : 0) * S::Q_BYTES; };
+  auto words_of = [&](int nth) { return sy.stats + ((size_t)(team * 2 + (nth & 1)) * T) * ROWS; };
+  auto tag_of = [](int nth) { return (((unsigned)nth >> 1) & 1u) ^ 1u; };
+
+  // Pass 1 of the team's nth head on the registers (its Q is in LDS buffer nth & 1); statistics
+  // published.  `arriving`: the last key tile is still being reloaded, from `src` (see wave_pass).
+  auto pass1_publish = [&](int nth, bool arriving, const KeySource& src) {
+    w.q_lane = q_buf_of(nth) + w.n32 * QROWB + w.hf * 16;
     Pass2Out no_out;
     no_out.rawbuf = nullptr;
-    wave_pass<NRT, 1>(w, kreg, m_run, z_run, no_out, false, none);
-    u32x4 qv[S::Q_PER_THREAD];              // (requested here, used after the statistics are out and the scores stored)
-    if (hq_next >= 0) fetch_q(hq_next, qv);
+    wave_pass<NRT, 1>(w, kreg, m_run, z_run, no_out, arriving, src);
     // the two lanes that share a row, then the waves
 #pragma unroll
     for (int r = 0; r < NRT; ++r) {
@@ -479,72 +496,75 @@ __global__ __launch_bounds__(F_THREADS, 1) void fused_kernel(ScoreGeom g, QueryP
       }
     }
     lds_barrier();
-    float2* team_stats = sy.stats + ((size_t)(team * 2 + par) * T) * ROWS;
     if (tid < ROWS) {
       float M = NEG_BIG, Z = 0.f;
 #pragma unroll
       for (int v = 0; v < F_WAVES; ++v) merge_stat(M, Z, stat_lds[v * ROWS + tid]);
       // (Z is a sum of non-negative terms: its sign bit is free)
-      coherent_store(team_stats + (size_t)member * ROWS + tid, make_float2(M, __uint_as_float(__float_as_uint(Z) | (tag << 31))));
+      coherent_store(words_of(nth) + (size_t)member * ROWS + tid,
+                     make_float2(M, __uint_as_float(__float_as_uint(Z) | (tag_of(nth) << 31))));
     }
-    if (hg_pool >= 0) pool_head(hg_pool);
-    if (hq_next >= 0) commit_q(par ^ 1, qv);
-    // Everybody folds the team's statistics in the same fixed order.  Thread (sub, rp) folds the
-    // row pair rp of the members sub, sub + NSUB, ...: up to B 16-byte device-coherent loads in
-    // flight at a time; a word that is not there yet is loaded again.
-    {
-      constexpr int PAIRS = S::PAIRS, NSUB = S::NSUB, B = 4;
-      const int rp = tid % PAIRS, sub = tid / PAIRS;
-      float M = NEG_BIG, Z = 0.f, M1 = NEG_BIG, Z1 = 0.f;
-      if (sub < NSUB) {
-        const __amdgpu_buffer_rsrc_t words = __builtin_amdgcn_make_buffer_rsrc(team_stats, 0, T * ROWS * 8, 0x00020000);
-        int probes = 0;
-        for (int m0 = sub; m0 < T; m0 += NSUB * B) {
-          u32x4 v[B];
+    // (the statistics buffer is next written after the next pass 1, several barriers on)
+  };
+
+  // Everybody folds the statistics of the team in the same fixed order; the row constants go into
+  // the ninth reduction step of the head's Q rows.  Thread (sub, rp) folds the row pair rp of the
+  // members sub, sub + NSUB, ...: up to B 16-byte device-coherent loads in flight at a time; a word
+  // that is not there yet is loaded again.
+  auto gather_fold = [&](int nth) {
+    constexpr int PAIRS = S::PAIRS, NSUB = S::NSUB, B = NSUB >= 16 ? 4 : 8;
+    float2* team_stats = words_of(nth);
+    const unsigned tag = tag_of(nth);
+    char* q_buf = q_buf_of(nth);
+    const int rp = tid % PAIRS, sub = tid / PAIRS;
+    float M = NEG_BIG, Z = 0.f, M1 = NEG_BIG, Z1 = 0.f;
+    if (sub < NSUB) {
+      const __amdgpu_buffer_rsrc_t words = __builtin_amdgcn_make_buffer_rsrc(team_stats, 0, T * ROWS * 8, 0x00020000);
+      int probes = 0;
+      for (int m0 = sub; m0 < T; m0 += NSUB * B) {
+        u32x4 v[B];
 #pragma unroll
-          for (int b2 = 0; b2 < B; ++b2) {
-            const int mb = m0 + b2 * NSUB;
-            v[b2] = u32x4{0u, tag << 31, 0u, tag << 31};
-            if (mb < T) v[b2] = __builtin_amdgcn_raw_buffer_load_b128(words, (mb * ROWS + 2 * rp) * 8, 0, COHERENT);
-          }
+        for (int b2 = 0; b2 < B; ++b2) {
+          const int mb = m0 + b2 * NSUB;
+          v[b2] = u32x4{0u, tag << 31, 0u, tag << 31};
+          if (mb < T) v[b2] = __builtin_amdgcn_raw_buffer_load_b128(words, (mb * ROWS + 2 * rp) * 8, 0, COHERENT);
+        }
 #pragma unroll
-          for (int b2 = 0; b2 < B; ++b2) {
-            const int mb = m0 + b2 * NSUB;
-            if (mb < T) {
-              while ((v[b2][1] >> 31) != tag || (v[b2][3] >> 31) != tag) {
-                if (gave_up[0]) break;
-                if (++probes > SPIN_LIMIT ||
-                    ((probes & 63) == 63 && __hip_atomic_load(sy.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-                  __hip_atomic_store(sy.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                  gave_up[0] = 1;
-                  break;
-                }
-                __builtin_amdgcn_s_sleep(1);
-                v[b2] = __builtin_amdgcn_raw_buffer_load_b128(words, (mb * ROWS + 2 * rp) * 8, 0, COHERENT);
+        for (int b2 = 0; b2 < B; ++b2) {
+          const int mb = m0 + b2 * NSUB;
+          if (mb < T) {
+            while ((v[b2][1] >> 31) != tag || (v[b2][3] >> 31) != tag) {
+              if (gave_up[0]) break;
+              if (++probes > SPIN_LIMIT ||
+                  ((probes & 63) == 63 && __hip_atomic_load(sy.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+                __hip_atomic_store(sy.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                gave_up[0] = 1;
+                break;
               }
-              merge_stat(M, Z, make_float2(__uint_as_float(v[b2][0]), __uint_as_float(v[b2][1] & 0x7fffffffu)));
-              merge_stat(M1, Z1, make_float2(__uint_as_float(v[b2][2]), __uint_as_float(v[b2][3] & 0x7fffffffu)));
+              __builtin_amdgcn_s_sleep(1);
+              v[b2] = __builtin_amdgcn_raw_buffer_load_b128(words, (mb * ROWS + 2 * rp) * 8, 0, COHERENT);
             }
+            merge_stat(M, Z, make_float2(__uint_as_float(v[b2][0]), __uint_as_float(v[b2][1] & 0x7fffffffu)));
+            merge_stat(M1, Z1, make_float2(__uint_as_float(v[b2][2]), __uint_as_float(v[b2][3] & 0x7fffffffu)));
           }
         }
-        fold_lds[sub * ROWS + 2 * rp] = make_float2(M, Z);
-        fold_lds[sub * ROWS + 2 * rp + 1] = make_float2(M1, Z1);
       }
-      lds_barrier();
-      if (tid < ROWS) {
-        M = NEG_BIG; Z = 0.f;
+      fold_lds[sub * ROWS + 2 * rp] = make_float2(M, Z);
+      fold_lds[sub * ROWS + 2 * rp + 1] = make_float2(M1, Z1);
+    }
+    lds_barrier();
+    if (tid < ROWS) {
+      M = NEG_BIG; Z = 0.f;
 #pragma unroll
-        for (int s2 = 0; s2 < NSUB; ++s2) merge_stat(M, Z, fold_lds[s2 * ROWS + tid]);
-        const float c = (tid < g.R) ? M + __builtin_amdgcn_logf(Z) : 1.0e30f;
-        *reinterpret_cast<uint2*>(q_buf + tid * QROWB + D * 2) = split_bf16x3(-c / g.scale2);
-      }
+      for (int s2 = 0; s2 < NSUB; ++s2) merge_stat(M, Z, fold_lds[s2 * ROWS + tid]);
+      const float c = (tid < g.R) ? M + __builtin_amdgcn_logf(Z) : 1.0e30f;
+      *reinterpret_cast<uint2*>(q_buf + tid * QROWB + D * 2) = split_bf16x3(-c / g.scale2);
     }
     lds_barrier();
   };
 
   // ---- the team's heads -----------------------------------------------------------------------
   int hg = team;
-  if (hg >= plan.n_heads) return;
   if (plan.stagger > 0) {
     const long long until = wall_clock64() + (long long)team * plan.stagger;
     while (wall_clock64() < until) __builtin_amdgcn_s_sleep(8);
@@ -559,25 +579,43 @@ __global__ __launch_bounds__(F_THREADS, 1) void fused_kernel(ScoreGeom g, QueryP
     }
     u32x4 qv[S::Q_PER_THREAD];
     fetch_q(hg, qv);
-    commit_q(0, qv);
+    commit_q(q_buf_of(0), qv);
   }
   lds_barrier();
   int hg_prev = -1;                        // the head whose raw scores wait in LDS
-  for (int n = 0;; ++n) {
+  for (int nth = 0;; ++nth) {
     const int hn = hg + plan.n_teams;
     const bool more = hn < plan.n_heads;
-    first_half(n, more ? hn : -1, hg_prev);
-    const KeySource next = keys_of(more ? hn : hg);
+    pass1_publish(nth, nth > 0, keys_of(hg));
+    // while the statistics travel (no key load is in flight any more): the next head's Q is
+    // requested, the previous head's scores are stored, Q is put into the other buffer
+    if constexpr (S::Q_BUFS == 2) {
+      u32x4 qv[S::Q_PER_THREAD];
+      if (more) fetch_q(hn, qv);
+      if (hg_prev >= 0) pool_head(hg_prev);
+      if (more) commit_q(q_buf_of(nth + 1), qv);
+    } else {
+      if (hg_prev >= 0) pool_head(hg_prev);
+    }
+    gather_fold(nth);
     Pass2Out out;
     out.rawbuf = raw_lds + wave * KEYS_PER_WAVE;
-    wave_pass<NRT, 2>(w, kreg, m_run, z_run, out, more, next);
+    wave_pass<NRT, 2>(w, kreg, m_run, z_run, out, more, keys_of(more ? hn : hg));
     lds_barrier();                         // every wave is done with this head's Q and constants; raw scores complete
     if (!more || gave_up[0]) {
       pool_head(hg);
       break;
     }
-    // (the raw scores are pooled inside the next first half; they are next overwritten by the pass 2
-    // that follows it, behind its barriers)
+    // (the raw scores are pooled inside the next round; they are next overwritten by the pass 2 of
+    // that round, behind its barriers)
+    if constexpr (S::Q_BUFS == 1) {
+      // one buffer: the next head's Q can only follow the last use of this head's (the other workgroup
+      // of the compute unit has the matrix cores meanwhile)
+      u32x4 qv[S::Q_PER_THREAD];
+      fetch_q(hn, qv);
+      commit_q(q_buf_of(nth + 1), qv);
+      lds_barrier();
+    }
     hg_prev = hg;
     hg = hn;
   }
