@@ -1,17 +1,20 @@
 // bf16 scoring on the matrix cores with K read ONCE: the keys of a head stay in registers
-// between the two softmax passes.
+// between the two softmax passes.  For KV heads with at most 64 score rows (R = G * W): there the
+// two streaming passes are bound by memory and a single read pays; with more rows both designs
+// are bound by the exponentials, which either computes twice, and the streaming kernels are as fast.
 //
 // The softmax of Eq. 4's observation window needs every score row's global (max, sum-exp) before
 // a single probability can be summed, so a head's keys are needed twice.  Here a *team* of
 // workgroups holds one whole head on chip: every wave keeps 128 key rows (32 KiB, d = 128) in
 // 128 vector registers, already in the operand layout of v_mfma_f32_32x32x16_bf16; a workgroup
-// of eight waves (one per compute unit, two waves per SIMD) covers 1024 keys, a team of
-// ceil(L / 1024) workgroups covers the head (32 workgroups = 8 MiB of registers for L = 32768),
-// and the device works on as many heads at once as it has room for teams (8).
+// of four waves (one per SIMD) covers 512 keys, a team of ceil(L / 512) workgroups covers the
+// head (64 workgroups = 8 MiB of registers for L = 32768), two workgroups share a compute unit
+// (one computes while the other waits for its team), and the device works on as many heads at
+// once as it has room for teams (8).
 //
 // Per head, every workgroup of the team
 //   1. pass 1:  D = K_tile * Q^T per (key tile, row tile): running (max, sum-exp2) per score
-//      row over its 1024 keys; the Q operands come from LDS (one copy of the head's Q_g per
+//      row over its 512 keys; the Q operands come from LDS (one copy of the head's Q_g per
 //      workgroup), the K operands from the registers;
 //   2. publishes its 2*R statistics, reads those of the whole team and folds them, in a fixed
 //      order, into c = M + log2 Z per row (every member computes the same constants; nobody
@@ -22,8 +25,8 @@
 //      loads are spread over the matrix instructions of the tile that follows (those of the last
 //      tile over the start of the next head's pass 1), because loads in operand layout touch 32
 //      cache lines each and a burst of them holds up the waves that issue it.  The workgroup's
-//      1024 raw scores meet in LDS, where the sequence max-pool of every key whose window lies
-//      inside the 1024 is taken; the few keys next to a workgroup boundary are pooled by
+//      512 raw scores meet in LDS, where the sequence max-pool of every key whose window lies
+//      inside the 512 is taken; the few keys next to a workgroup boundary are pooled by
 //      pool_boundaries_kernel from raw scores left for it.
 // Loads return in the order of their issue, so a wait for a small load would also wait for every
 // key load in front of it: the order above has no key load in flight when the statistics and Q
@@ -94,7 +97,7 @@ template <int NRT> struct FSmem {
   static constexpr int Q_BYTES = ROWS * QROWB;
   static constexpr int Q_PIECES = ROWS * (D / 8);                   // 16-byte pieces of one Q_g
   static constexpr int Q_PER_THREAD = (Q_PIECES + F_THREADS - 1) / F_THREADS;
-  static constexpr int Q_BUFS = NRT <= 3 ? 2 : 1;                   // this head / next, where two workgroups' worth fits
+  static constexpr int Q_BUFS = 2;                                  // this head / next
   static constexpr int OFF_Q = 0;                                   // Q_BUFS x [ROWS][QROWB] bf16 rows of Q_g
   static constexpr int PAIRS = ROWS / 2, NSUB = F_THREADS / PAIRS;   // the fold: threads per row pair
   static constexpr int OFF_STAT = OFF_Q + Q_BUFS * Q_BYTES;               // float2[F_WAVES][ROWS]: the waves' statistics
@@ -363,7 +366,7 @@ struct FusedSync {
   int* status;             // != 0: a wait has timed out (results are not valid)
 };
 struct FusedPlan {
-  int T;                   // workgroups per team = ceil(L / 1024)
+  int T;                   // workgroups per team = ceil(L / 512)
   int n_teams;
   int n_heads;             // team t takes heads t, t + n_teams, ...
   int half;                // (pool kernel - 1) / 2; 0: raw scores
@@ -436,7 +439,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
   };
   // Scores of head hg_ from the raw scores that its pass 2 left in LDS (zero beyond the head's last
   // key and in the margins).  Keys behind the prefix and, without pooling, all keys are stored as
-  // they are.  A prefix key whose pooling window lies inside the workgroup's 1024 keys gets the
+  // they are.  A prefix key whose pooling window lies inside the workgroup's 512 keys gets the
   // maximum over the part of the window inside the prefix; the raw scores of the first and last
   // 2*half keys go to the edge record of this workgroup, from which pool_boundaries_kernel pools the
   // keys next to a boundary.
@@ -474,7 +477,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
   };
 
   // statistics words of the team's nth head, and the validity bit of that use of the words
-  auto q_buf_of = [&](int nth) { return smem + S::OFF_Q + (S::Q_BUFS == 2 ? (nth & 1) : 0) * S::Q_BYTES; };
+  auto q_buf_of = [&](int nth) { return smem + S::OFF_Q + (nth & 1) * S::Q_BYTES; };
   auto words_of = [&](int nth) { return sy.stats + ((size_t)(team * 2 + (nth & 1)) * T) * ROWS; };
   auto tag_of = [](int nth) { return (((unsigned)nth >> 1) & 1u) ^ 1u; };
 
@@ -589,13 +592,11 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
     pass1_publish(nth, nth > 0, keys_of(hg));
     // while the statistics travel (no key load is in flight any more): the next head's Q is
     // requested, the previous head's scores are stored, Q is put into the other buffer
-    if constexpr (S::Q_BUFS == 2) {
+    {
       u32x4 qv[S::Q_PER_THREAD];
       if (more) fetch_q(hn, qv);
       if (hg_prev >= 0) pool_head(hg_prev);
       if (more) commit_q(q_buf_of(nth + 1), qv);
-    } else {
-      if (hg_prev >= 0) pool_head(hg_prev);
     }
     gather_fold(nth);
     Pass2Out out;
@@ -608,14 +609,6 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
     }
     // (the raw scores are pooled inside the next round; they are next overwritten by the pass 2 of
     // that round, behind its barriers)
-    if constexpr (S::Q_BUFS == 1) {
-      // one buffer: the next head's Q can only follow the last use of this head's (the other workgroup
-      // of the compute unit has the matrix cores meanwhile)
-      u32x4 qv[S::Q_PER_THREAD];
-      fetch_q(hn, qv);
-      commit_q(q_buf_of(nth + 1), qv);
-      lds_barrier();
-    }
     hg_prev = hg;
     hg = hn;
   }
@@ -630,7 +623,7 @@ __global__ void fused_reset_kernel(uint4* words, int n_words, int* status) {
 
 // ---- per-device set-up (see score_fused_init) -------------------------------------------------
 constexpr int MAX_DEVICES = 64;
-std::atomic<int> fused_resident[MAX_DEVICES][4];    // per row-tile count: workgroups held at once; -1: unusable
+std::atomic<int> fused_resident[MAX_DEVICES][2];    // per row-tile count: workgroups held at once; -1: unusable
 std::atomic<int> fused_ready[MAX_DEVICES];
 
 template <int NRT>
@@ -705,8 +698,6 @@ hipError_t score_fused_init(int dev) {
   if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
   if ((e = init_rows<1>(dev, cus, coop)) != hipSuccess) return e;
   if ((e = init_rows<2>(dev, cus, coop)) != hipSuccess) return e;
-  if ((e = init_rows<3>(dev, cus, coop)) != hipSuccess) return e;
-  if ((e = init_rows<4>(dev, cus, coop)) != hipSuccess) return e;
   fused_ready[dev].store(1, std::memory_order_release);
   return hipSuccess;
 }
@@ -718,7 +709,7 @@ size_t fused_sync_bytes(const ScoreGeom& g) {
 }
 
 bool score_fused_supported(const ScoreGeom& g, const KvLayout& lay, int dtype) {
-  return dtype == LAQ_BF16 && g.d == D && g.Rpad <= 128 && g.W <= MAX_QPOS &&
+  return dtype == LAQ_BF16 && g.d == D && g.Rpad <= 64 && g.W <= MAX_QPOS &&
          ((long long)g.L + KEYS_PER_BLOCK) * lay.row_bytes < 0x7fffffffLL;
 }
 
@@ -731,9 +722,7 @@ hipError_t launch_score_fused(const ScoreGeom& g, const QueryPos& qp, const KvLa
   const uint16_t* kk = static_cast<const uint16_t*>(k);
   const int ntile = g.Rpad / 32;
   if (ntile == 1) return launch_fused_rows<1>(g, qp, lay, pool, qq, kk, scores, ws, st, done);
-  if (ntile == 2) return launch_fused_rows<2>(g, qp, lay, pool, qq, kk, scores, ws, st, done);
-  if (ntile == 3) return launch_fused_rows<3>(g, qp, lay, pool, qq, kk, scores, ws, st, done);
-  return launch_fused_rows<4>(g, qp, lay, pool, qq, kk, scores, ws, st, done);
+  return launch_fused_rows<2>(g, qp, lay, pool, qq, kk, scores, ws, st, done);
 }
 
 }  // namespace laq

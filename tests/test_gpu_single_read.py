@@ -1,0 +1,141 @@
+"""The single-read scoring kernel (keys resident in registers between the softmax passes) vs the CPU
+oracle (needs an MI355X).
+
+laq_score takes that kernel for bf16 caches with d = 128 and at most 64 score rows per KV head
+(R = G * W); a team of ceil(L / 512) workgroups shares a head.  The cases walk the team sizes (one
+workgroup, a ragged last workgroup, a key count one past a boundary), the row-tile counts, heads
+fewer and more than the teams the device holds, strided caches, explicit query positions, and check
+after every call that all the kernel's waits completed (status of the workspace).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from parity_util import check_scores
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+D = 128
+
+
+@pytest.fixture(scope="module")
+def laq():
+    import paper_2505_20334_amd as m
+    m.load_library()
+    assert torch.cuda.is_available()
+    return m
+
+
+def draw(n, Hkv, G, L, W, seed, sinks=True):
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn(n, Hkv * G, W, D, generator=g)
+    k = torch.randn(n, Hkv, L, D, generator=g)
+    if sinks:
+        # a few keys that every query likes (attention sinks), and one query row with a large norm
+        k[:, :, :2] += 0.6 * q.reshape(n, Hkv, G * W, D).mean(2, keepdim=True)
+        q[:, 0, 0] *= 4.0
+    return q.bfloat16(), k.bfloat16()
+
+
+def score_and_check(laq, q, k, pool, what, heads, k_dev=None, **kw):
+    n, Hq, W, _ = q.shape
+    _, Hkv, L, _ = k.shape
+    G = Hq // Hkv
+    print("case:", what, "n=%d Hkv=%d G=%d L=%d W=%d pool=%d" % (n, Hkv, G, L, W, pool), flush=True)
+    qd = q.to(DEV)
+    kd = k.to(DEV) if k_dev is None else k_dev
+    nb = laq.laq_workspace_bytes(n, Hq, Hkv, D, L, W, torch.bfloat16)
+    ws = torch.zeros(nb, dtype=torch.uint8, device=DEV)
+    s = laq.laq_score(qd, kd, pool, ws=ws, **kw)
+    again = laq.laq_score(qd, kd, pool, ws=ws, **kw)
+    torch.cuda.synchronize()
+    assert laq.laq_workspace_status(ws, n, Hq, Hkv, D, L, W, torch.bfloat16) == 0, what + ": a wait was given up"
+    assert torch.equal(s, again), what + ": two runs differ"
+    assert torch.isfinite(s).all()
+    sc = s.cpu()
+    okw = {key: kw[key] for key in ("scale", "q_pos") if key in kw}
+    keep = kw.get("keep", W)
+    for (i, h) in heads:
+        raw = oracle.raw_scores(q[i, h * G:(h + 1) * G], k[i, h:h + 1], **okw)
+        want = oracle.maxpool(raw, keep, pool)
+        check_scores(sc[i, h], want[0], torch.bfloat16, "%s inst %d head %d" % (what, i, h))
+    return s
+
+
+SHAPES = [
+    # name, n, Hkv, G, L, W, pool
+    ("one-workgroup", 3, 2, 4, 300, 8, 7),
+    ("exactly-one-workgroup", 2, 2, 4, 512, 8, 1),
+    ("one-key-past-a-boundary", 2, 2, 4, 513, 8, 7),
+    ("window-straddles-a-boundary", 2, 2, 4, 1030, 16, 7),
+    ("ragged-team-of-ten", 2, 3, 4, 4700, 16, 7),
+    ("rows-not-a-multiple-of-32", 2, 2, 4, 2100, 5, 5),
+    ("48-rows", 2, 2, 4, 3000, 12, 3),
+    ("64-rows-no-group", 2, 4, 1, 2500, 64, 7),
+    ("group-of-eight", 2, 2, 8, 2049, 8, 7),
+    ("one-query", 2, 2, 4, 1500, 1, 1),
+    ("wide-pool", 2, 2, 4, 2600, 8, 31),
+]
+
+
+@pytest.mark.parametrize("name,n,Hkv,G,L,W,pool", SHAPES, ids=[c[0] for c in SHAPES])
+def test_shapes(laq, name, n, Hkv, G, L, W, pool):
+    q, k = draw(n, Hkv, G, L, W, seed=L + W)
+    score_and_check(laq, q, k, pool, name, [(0, 0), (n - 1, Hkv - 1)])
+
+
+def test_more_heads_than_teams_and_fewer(laq):
+    # L = 16384: 32 workgroups per team, the device holds 16 teams; 40 heads take three rounds with an
+    # unequal share, 3 heads leave most of the device idle
+    for (n, Hkv) in ((5, 8), (1, 3)):
+        q, k = draw(n, Hkv, 4, 16384, 16, seed=n * 100 + Hkv, sinks=False)
+        score_and_check(laq, q, k, 7, "heads-%d" % (n * Hkv), [(0, 0), (n - 1, Hkv - 1), (n // 2, 1)])
+
+
+def test_long_head_small_team_count(laq):
+    # L = 70000: 137 workgroups per team, 3 teams on the device
+    q, k = draw(1, 5, 4, 70000, 8, seed=7, sinks=False)
+    score_and_check(laq, q, k, 7, "long-head", [(0, 0), (0, 4)])
+
+
+def test_strided_and_token_major_caches(laq):
+    n, Hkv, G, L, W = 2, 3, 4, 2300, 16
+    q, k = draw(n, Hkv, G, L, W, seed=11)
+    dense = score_and_check(laq, q, k, 7, "dense", [(0, 0), (1, 2)])
+    # head-padded cache: every head is followed by 40 unused rows
+    padded = torch.zeros(n, Hkv, L + 40, D, dtype=torch.bfloat16, device=DEV)
+    padded[:, :, :L] = k.to(DEV)
+    s_pad = score_and_check(laq, q, k, 7, "head-padded", [(1, 1)], k_dev=padded[:, :, :L])
+    # token-major cache [n, L, Hkv, d] viewed as [n, Hkv, L, d]
+    tm = k.to(DEV).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    assert not tm.is_contiguous()
+    s_tm = score_and_check(laq, q, k, 7, "token-major", [(0, 2)], k_dev=tm)
+    assert torch.equal(dense, s_pad) and torch.equal(dense, s_tm)
+
+
+def test_explicit_query_positions_and_scale(laq):
+    n, Hkv, G, L, W = 2, 2, 4, 1800, 8
+    q, k = draw(n, Hkv, G, L, W, seed=5)
+    # queries in the middle of the sequence: keys behind a query's position are invisible to it
+    q_pos = [700, 701, 900, 1100, 1101, 1102, 1500, 1799]
+    score_and_check(laq, q, k, 1, "positions", [(0, 0), (1, 1)], q_pos=q_pos, keep=0)
+    score_and_check(laq, q, k, 7, "positions-pooled", [(0, 1)], q_pos=q_pos, keep=0)
+    # a sharper softmax (large logits): the probabilities span hundreds of binary orders of magnitude
+    score_and_check(laq, q, k, 1, "scale-1.5", [(0, 0), (1, 1)], scale=1.5)
+
+
+def test_constant_keys_give_uniform_probabilities(laq):
+    # all keys equal: every visible key gets probability 1 / (number visible), whatever the team split
+    n, Hkv, G, L, W = 1, 2, 4, 1300, 8
+    g = torch.Generator().manual_seed(3)
+    q = torch.randn(n, Hkv * G, W, D, generator=g).bfloat16()
+    k = torch.randn(1, 1, 1, D, generator=g).expand(n, Hkv, L, D).contiguous().bfloat16()
+    s = laq.laq_score(q.to(DEV), k.to(DEV), 1).cpu().double()
+    P = L - W
+    want = torch.zeros(L, dtype=torch.float64)
+    for w in range(W):
+        want[: P + w + 1] += G / (P + w + 1)
+    np.testing.assert_allclose(s[0, 0].numpy(), want.numpy(), rtol=2e-6)
+    np.testing.assert_allclose(s[0, 1].numpy(), want.numpy(), rtol=2e-6)
