@@ -36,14 +36,30 @@ def algorithmic_bytes(cfg, budgets):
 
 
 def read_traffic(workload):
-    """HBM bytes per score-stage launch from committed rocprofv3 --pmc summaries, if present."""
-    path = os.path.join(ROOT, "profiles", "traffic_%s.txt" % workload)
+    """(HBM bytes per score-stage launch, where the figure comes from).  The bytes are not measured
+    by this run: they are read from the committed rocprofv3 --pmc summary of the same command, if there
+    is one for this workload; the source says so."""
+    rel = os.path.join("profiles", "traffic_%s.txt" % workload)
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, "no committed counter summary for this workload"
+    kernels = ""
     for line in open(path):
+        if line.startswith("score_kernels="):
+            kernels = line.split("=", 1)[1].strip()
         if line.startswith("traffic_bytes_per_launch="):
-            return float(line.split("=", 1)[1])
-    return None
+            return float(line.split("=", 1)[1]), ("%s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, "
+                                                  "recorded for the kernels: %s; not re-measured in this run)" % (rel, kernels))
+    return None, "%s holds no traffic figure" % rel
+
+
+SCORE_KERNEL_TEXT = {
+    "single-read": "laq_score stage: fused_reset_kernel + fused_kernel (K read once, kept in registers between the "
+                   "softmax passes) + pool_boundaries_kernel",
+    "two-pass": "laq_score stage: stream_kernel<pass 1> + row_constants_mfma_kernel + stream_kernel<pass 2> + "
+                "pool_boundaries_kernel (K counted once in the algorithmic bytes, read twice)",
+    "vector": "laq_score stage: vector-ALU kernels (K counted once in the algorithmic bytes, read twice)",
+}
 
 
 def bench_decode(args, torch, laq, cfg, budgets, dev):
@@ -96,7 +112,8 @@ def bench_decode(args, torch, laq, cfg, budgets, dev):
                    "d": cfg.d, "L": cfg.L, "budget": cfg.budget, "packed_rows": total,
                    "cache_copies_cycled": len(copies)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(workload),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(workload)[0],
+                     "traffic_source": read_traffic(workload)[1],
                      "kernel": "decode_kernel + merge_parts_kernel (K' and V' rows read once, q read, out written)",
                      "algorithmic_bytes_per_launch": ab, "ms_per_launch": round(ms_kernel, 4)},
     }
@@ -127,8 +144,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=4, help="workload: index into BASELINE.json configs (1-based)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-instances", type=int, default=5,
-                    help="instances the CPU oracle is timed on (spread over the layers; about 2-5 s each)")
+    ap.add_argument("--cpu-instances", type=int, default=0,
+                    help="instances the CPU oracle is timed on, spread over the layers (about 2-5 s of one core "
+                         "each); 0 (default): all of them")
+    ap.add_argument("--cpu-threads", type=int, default=16, help="threads the CPU oracle's instances are spread over")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="headline workload only: skip the batched 32k workload that the default run reports next to it")
     ap.add_argument("--path", choices=["evict", "decode"], default="evict",
                     help="evict (default): the re-eviction hot path, the headline workload; decode: one new "
                          "token's attention over the compacted cache of the same config (Sec. 4.3)")
@@ -169,6 +190,24 @@ def main():
     n = cfg.n_inst
     if args.path == "decode":
         return bench_decode(args, torch, laq, cfg, budgets, dev)
+    out = measure_evict(args, torch, laq, cfg, budgets, dev, args.steps, args.warmup, primary=True)
+    # the batched 32k workload next to the headline one (default run only): the same path on 8 sequences x 32
+    # layers, 64 score rows per KV head
+    if args.config == 4 and args.window == "trailing" and args.pool_mode == "max" and args.layout == "dense" \
+            and not args.no_extra:
+        torch.cuda.empty_cache()
+        cfg5 = CONFIGS[5]
+        extra = measure_evict(args, torch, laq, cfg5, budgets_for(cfg5), dev, min(args.steps, 10), min(args.warmup, 3),
+                              primary=False)
+        out["other_workloads"] = [{key: extra[key] for key in ("config", "value", "unit", "ms_per_step", "steps", "warmup",
+                                                              "whole_path", "roofline")}]
+    print(json.dumps(out))
+
+
+def measure_evict(args, torch, laq, cfg, budgets, dev, steps, warmup, primary):
+    """Times laq_evict on one workload; returns the JSON object of that workload."""
+    from laq_inputs import make_instance
+    n = cfg.n_inst
     q_pos, keep, workload = None, None, cfg.name
     if args.window != "trailing":
         import dataclasses
@@ -205,31 +244,33 @@ def main():
     ws = torch.empty(laq.laq_workspace_bytes(n, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, cfg.W, dt, q_pos, keep),
                      dtype=torch.uint8, device=dev)
     keep_rows = cfg.W if keep is None else keep
+    strides = (0, 0, 0) if k.is_contiguous() else (k.stride(0), k.stride(1), k.stride(2))
+    score_kernel = laq.laq_score_kernel(n, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, cfg.W, dt, q_pos, keep, strides)
 
     def step():
         laq.laq_evict(q, k, v, budgets, cfg.pool, scores=scores, idx=idx, k_out=k_out, v_out=v_out, ws=ws,
                       q_pos=q_pos, keep=keep, pool_mode=args.pool_mode)
 
-    if args.calibrate_copy:
+    if args.calibrate_copy and primary:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
         dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
     value = n * cfg.L / (ms_per_step * 1e-3)
 
     # ---- per-stage durations with events on the launch stream (torch's current stream) ----
     stages = {"score": 0.0, "select": 0.0, "compact": 0.0}
-    reps = max(3, min(args.steps, 10))
+    reps = max(3, min(steps, 10))
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
     for _ in range(reps):
         ev[0].record()
@@ -243,19 +284,22 @@ def main():
         stages["score"] += ev[0].elapsed_time(ev[1]) / reps
         stages["select"] += ev[1].elapsed_time(ev[2]) / reps
         stages["compact"] += ev[2].elapsed_time(ev[3]) / reps
+    if laq.laq_workspace_status(ws, n, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, cfg.W, dt) != 0:
+        print("bench.py: the scoring kernel gave up a wait; the timings are not valid", file=sys.stderr)
+        sys.exit(1)
     ab = algorithmic_bytes(cfg, budgets)
     achieved = ab["score"] / (stages["score"] * 1e-3) / 1e9
+    traffic, traffic_source = read_traffic(workload)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(workload),
-                "kernel": "laq_score stage: stream_kernel<pass 1> + row_constants_mfma_kernel + "
-                          "stream_kernel<pass 2> (K counted once in the algorithmic bytes, read twice)",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
+                "kernel": SCORE_KERNEL_TEXT[score_kernel],
                 "algorithmic_bytes_per_launch": ab["score"],
                 "ms_per_launch": round(stages["score"], 4)}
 
     out = {
         "metric": "prefill key-tokens scored+compacted/sec per layer (all heads)",
-        "value": round(value, 1), "unit": "key-tokens/s/layer", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "value": round(value, 1), "unit": "key-tokens/s/layer", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": workload, "cfg_id": cfg.cfg_id, "instances": n, "Hq": cfg.Hq, "Hkv": cfg.Hkv,
                    "d": cfg.d, "L": cfg.L, "W": cfg.W, "pool": cfg.pool, "budget": cfg.budget},
@@ -267,7 +311,7 @@ def main():
 
     # quality probe in the spirit of Eq. 1-3 (untimed): how much of the selection made by all W window
     # queries (placed after the prompt, nothing kept) is recovered by the first quarter of them
-    if args.window == "trailing" and cfg.W >= 4 and not args.no_probe:
+    if primary and args.window == "trailing" and cfg.W >= 4 and not args.no_probe:
         see_all = [cfg.L] * cfg.W
         few = cfg.W // 4
         gold = laq.laq_evict(q, k, v, budgets, cfg.pool, q_pos=see_all, keep=0, pool_mode=args.pool_mode)[1]
@@ -280,21 +324,30 @@ def main():
             "what": "mean over (instance, KV head) of |M_pred & M_gold| / |M_gold|: M_gold selected by all %d "
                     "window queries, M_pred by the first %d, every query after the prompt, synthetic data" % (cfg.W, few)}
 
-    if not args.no_cpu_baseline:
+    if primary and not args.no_cpu_baseline:
+        # the oracle (plain C behind ctypes, which releases the interpreter lock) on every instance of the
+        # workload, one instance per thread at a time
+        from concurrent.futures import ThreadPoolExecutor
         import oracle
         oracle.build()
-        m = max(1, min(args.cpu_instances, n))
+        m = n if args.cpu_instances <= 0 else max(1, min(args.cpu_instances, n))
         ids = sorted(set(round(i * (n - 1) / max(m - 1, 1)) for i in range(m)))      # spread over the layers
-        t_cpu = 0.0
-        for i in ids:
-            qi, ki, vi = q[i].cpu(), k[i].cpu(), v[i].cpu()
-            c0 = time.perf_counter()
-            oracle.evict(qi, ki, vi, budgets[i], cfg.pool, q_pos=q_pos, keep=keep, pool_mode=args.pool_mode)
-            t_cpu += time.perf_counter() - c0
+        threads = max(1, min(args.cpu_threads, len(ids), os.cpu_count() or 1))
+        host = [(q[i].cpu(), k[i].cpu(), v[i].cpu()) for i in ids]
+
+        def one(j):
+            qi, ki, vi = host[j]
+            oracle.evict(qi, ki, vi, budgets[ids[j]], cfg.pool, q_pos=q_pos, keep=keep, pool_mode=args.pool_mode)
+
+        c0 = time.perf_counter()
+        with ThreadPoolExecutor(threads) as pool:
+            list(pool.map(one, range(len(ids))))
+        t_cpu = time.perf_counter() - c0
         out["cpu_baseline"] = {"value": round(len(ids) * cfg.L / t_cpu, 1), "unit": "key-tokens/s/layer",
-                               "cores": 1, "kind": "oracle",
-                               "sample": "instances %s of %d (all heads, full length), %.1f s" % (ids, n, t_cpu)}
-    print(json.dumps(out))
+                               "cores": threads, "kind": "oracle",
+                               "sample": "%s of the %d instances (all heads, full length), %d threads, %.1f s wall"
+                                         % ("all" if len(ids) == n else "instances %s" % ids, n, threads, t_cpu)}
+    return out
 
 
 if __name__ == "__main__":

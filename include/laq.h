@@ -139,10 +139,11 @@ int laq_workspace_status(const laq_shape *shape, const void *ws, size_t ws_bytes
  * Importance scores (Eq. 4's sum over the Q-cache, taken on attention scores).
  *   q_win  [n_inst, Hq, W, d]   observation-window queries (Q-cache, local window, or both); always
  *                               dense (no strides)
- *   k      [n_inst, Hkv, L, d]  key cache.  Read once where a team of workgroups can keep a head on
- *                               chip between the two softmax passes (bf16, d = 128, at
- *                               most 128 score rows per KV head, L up to 512 x the workgroups the
+ *   k      [n_inst, Hkv, L, d]  key cache.  Read once where a team of workgroups keeps a head on
+ *                               chip between the two softmax passes (bf16, d = 128, at most 64
+ *                               score rows G * W per KV head, L up to 512 x the workgroups the
  *                               device holds: 262144 on an MI355X), otherwise streamed twice
+ *                               (laq_score_kernel() says which)
  *   scores [n_inst, Hkv, L]     fp32 out.  For each KV head g and key j:
  *            raw[g,j] = sum over the G heads of the group and the W queries of
  *                       softmax_j(scale * <q, k_j>) restricted to j <= P + w.
@@ -188,6 +189,17 @@ int laq_select(const laq_shape *shape, const float *scores, const int32_t *budge
  */
 int laq_select_sink_recent(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t *budget,
                            int32_t n_sink, int32_t *idx, void *stream);
+
+/*
+ * Which kernels laq_score (and laq_evict) take for this shape on the current device, for callers
+ * that account for memory traffic (Sec. 4.3's scoring reads K once or twice accordingly):
+ * LAQ_KERNEL_VECTOR (vector-ALU path, K streamed twice), LAQ_KERNEL_TWO_PASS (matrix cores, K
+ * streamed twice) or LAQ_KERNEL_SINGLE_READ (matrix cores, K read once); a negative error code
+ * for an invalid shape.  The pooling mode and the strides of `shape` are taken into account
+ * like laq_score does.  Launches nothing.
+ */
+enum { LAQ_KERNEL_VECTOR = 0, LAQ_KERNEL_TWO_PASS = 1, LAQ_KERNEL_SINGLE_READ = 2 };
+int laq_score_kernel(const laq_shape *shape);
 
 /*
  * Recall of one selection against another (Sec. 3, Eq. 1-3): with M_gold the positions selected

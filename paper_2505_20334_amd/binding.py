@@ -85,6 +85,8 @@ def load_library() -> ctypes.CDLL:
     lib.laq_init.restype = i32
     lib.laq_workspace_status.argtypes = [sp, vp, sz, vp]
     lib.laq_workspace_status.restype = i32
+    lib.laq_score_kernel.argtypes = [sp]
+    lib.laq_score_kernel.restype = i32
     _lib = lib
     return lib
 
@@ -108,6 +110,22 @@ def laq_workspace_status(ws: torch.Tensor, n_inst: int, Hq: int, Hkv: int, d: in
     sh = _shape(n_inst, Hq, Hkv, d, L, W, code, 0.0)
     return int(load_library().laq_workspace_status(ctypes.byref(sh), ws.data_ptr(), ws.numel() * ws.element_size(),
                                                    _stream(stream)))
+
+
+SCORE_KERNELS = ("vector", "two-pass", "single-read")
+
+
+def laq_score_kernel(n_inst: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: torch.dtype,
+                     q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
+                     kv_strides: Tuple[int, int, int] = (0, 0, 0)) -> str:
+    """Which kernels laq_score takes for this shape on the current device: "vector", "two-pass"
+    (K streamed twice) or "single-read" (K read once)."""
+    code = LAQ_F32 if dtype == torch.float32 else LAQ_BF16
+    sh = _shape(n_inst, Hq, Hkv, d, L, W, code, 0.0, q_pos, keep, "max", kv_strides)
+    rc = int(load_library().laq_score_kernel(ctypes.byref(sh)))
+    if rc < 0:
+        raise LaqError(rc, "laq_score_kernel")
+    return SCORE_KERNELS[rc]
 
 
 def _dtype_code(t: torch.Tensor) -> int:

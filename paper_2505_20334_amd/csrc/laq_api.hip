@@ -490,6 +490,20 @@ int laq_evict_static(const laq_shape* shape, const void* q_win, const void* k, c
 
 int laq_init(void) { return laq::init_current_device(nullptr); }
 
+int laq_score_kernel(const laq_shape* shape) {
+  laq::ScoreGeom g;
+  laq::QueryPos qp;
+  memset(&qp, 0, sizeof qp);
+  const int rc = laq::make_geom(shape, &g, &qp);
+  if (rc != LAQ_OK) return rc;
+  laq::KvLayout lay;
+  if (laq::make_layout(shape, g, &lay) != LAQ_OK) return LAQ_ERR_INVALID;
+  if (!laq::score_mfma_supported(g, lay, shape->dtype)) return LAQ_KERNEL_VECTOR;
+  bool single = false;
+  if (laq::SINGLE_READ_ENABLED && laq::score_fused_applies(g, lay, shape->dtype, &single) != hipSuccess) return LAQ_ERR_DEVICE;
+  return single ? LAQ_KERNEL_SINGLE_READ : LAQ_KERNEL_TWO_PASS;
+}
+
 int laq_workspace_status(const laq_shape* shape, const void* ws, size_t ws_bytes, void* stream) {
   laq::ScoreGeom g;
   const int rc0 = laq::make_geom(shape, &g);

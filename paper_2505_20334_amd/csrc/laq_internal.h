@@ -164,6 +164,7 @@ hipError_t score_mfma_init(int dev);
 hipError_t score_fused_init(int dev);
 size_t fused_sync_bytes(const ScoreGeom& g);
 bool score_fused_supported(const ScoreGeom& g, const KvLayout& lay, int dtype);
+hipError_t score_fused_applies(const ScoreGeom& g, const KvLayout& lay, int dtype, bool* yes);
 // single-read scoring (K streamed once); *done = false: not launched, take the two-pass kernels
 hipError_t launch_score_fused(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int pool, const void* q,
                               const void* k, float* scores, const Workspace& ws, hipStream_t st, bool* done);

@@ -638,6 +638,27 @@ hipError_t init_rows(int dev, int cus, int coop) {
   return hipSuccess;
 }
 
+// The team layout of a call on this device; false: the device cannot hold a team of this length (or
+// has no cooperative launch) and the caller takes the two-pass kernels.
+bool make_plan(const ScoreGeom& g, int pool, int resident, FusedPlan* out) {
+  const int nrt = g.Rpad / 32;
+  FusedPlan plan;
+  plan.T = (g.L + KEYS_PER_BLOCK - 1) / KEYS_PER_BLOCK;
+  plan.half = (pool - 1) / 2;
+  const long long n_heads = (long long)g.n_inst * g.Hkv;
+  if (resident <= 0 || plan.T > resident || n_heads > 0x7fffffffLL) return false;
+  plan.n_heads = (int)n_heads;
+  plan.n_teams = resident / plan.T;
+  if (plan.n_teams > plan.n_heads) plan.n_teams = plan.n_heads;
+  // a head takes a team roughly 5 us per 32-row tile; with at least four heads per team the teams
+  // are spread over that time
+  plan.stagger = (plan.n_heads >= 4 * plan.n_teams && plan.n_teams > 1) ? 500 * nrt / plan.n_teams : 0;
+  // the exchange memory is sized for FUSED_MAX_RESIDENT workgroups
+  if ((size_t)plan.n_teams * plan.T > (size_t)FUSED_MAX_RESIDENT) return false;
+  *out = plan;
+  return true;
+}
+
 template <int NRT>
 hipError_t launch_fused_rows(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int pool, const uint16_t* q,
                              const uint16_t* k,
@@ -647,24 +668,11 @@ hipError_t launch_fused_rows(const ScoreGeom& g, const QueryPos& qp, const KvLay
   hipError_t e;
   if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
   if ((e = score_fused_init(dev)) != hipSuccess) return e;
-  const int resident = fused_resident[dev][NRT - 1].load(std::memory_order_acquire);
-  if (resident <= 0) return hipSuccess;
   constexpr int bytes = FSmem<NRT>::BYTES;
   constexpr int ROWS = NRT * 32;
   FusedPlan plan;
-  plan.T = (g.L + KEYS_PER_BLOCK - 1) / KEYS_PER_BLOCK;
-  plan.half = (pool - 1) / 2;
-  const long long n_heads = (long long)g.n_inst * g.Hkv;
-  if (plan.T > resident || n_heads > 0x7fffffffLL) return hipSuccess;
-  plan.n_heads = (int)n_heads;
-  plan.n_teams = resident / plan.T;
-  if (plan.n_teams > plan.n_heads) plan.n_teams = plan.n_heads;
-  // a head takes a team roughly 5 us per 32-row tile; with at least four heads per team the teams
-  // are spread over that time
-  plan.stagger = (plan.n_heads >= 4 * plan.n_teams && plan.n_teams > 1) ? 500 * NRT / plan.n_teams : 0;
-  // the exchange memory is sized for FUSED_MAX_RESIDENT workgroups
+  if (!make_plan(g, pool, fused_resident[dev][NRT - 1].load(std::memory_order_acquire), &plan)) return hipSuccess;
   const size_t slots = (size_t)plan.n_teams * 2 * plan.T;
-  if (slots > 2 * (size_t)FUSED_MAX_RESIDENT) return hipSuccess;
   FusedSync sy;
   sy.stats = reinterpret_cast<float2*>(ws.fused);
   sy.status = ws.status;
@@ -711,6 +719,19 @@ size_t fused_sync_bytes(const ScoreGeom& g) {
 bool score_fused_supported(const ScoreGeom& g, const KvLayout& lay, int dtype) {
   return dtype == LAQ_BF16 && g.d == D && g.Rpad <= 64 && g.W <= MAX_QPOS &&
          ((long long)g.L + KEYS_PER_BLOCK) * lay.row_bytes < 0x7fffffffLL;
+}
+
+// Whether launch_score_fused would launch for this call on the current device.
+hipError_t score_fused_applies(const ScoreGeom& g, const KvLayout& lay, int dtype, bool* yes) {
+  *yes = false;
+  if (!score_fused_supported(g, lay, dtype)) return hipSuccess;
+  int dev = 0;
+  hipError_t e;
+  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+  if ((e = score_fused_init(dev)) != hipSuccess) return e;
+  FusedPlan plan;
+  *yes = make_plan(g, 1, fused_resident[dev][g.Rpad / 32 - 1].load(std::memory_order_acquire), &plan);
+  return hipSuccess;
 }
 
 // Scores of every head into `scores`: raw with pool == 1, else max-pooled over the prefix.  *done

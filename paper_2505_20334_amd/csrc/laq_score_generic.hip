@@ -187,9 +187,12 @@ __global__ __launch_bounds__(256) void pool_kernel(int L, int P, int half, bool 
 
 // Combine the per-chunk (m, z) of every score row into c = M + log2(Z), so that the
 // attention probability of a logit s (base-2 units) is exp2(s - c).  Rows beyond R
-// (padding up to a multiple of 32) get a huge c, i.e. probability 0.
-__global__ void row_constants_kernel(ScoreGeom g, const float2* __restrict__ part, float* __restrict__ rowc) {
+// (padding up to a multiple of 32) get a huge c, i.e. probability 0.  Also clears the workspace's
+// status word (these kernels have no wait to give up).
+__global__ void row_constants_kernel(ScoreGeom g, const float2* __restrict__ part, float* __restrict__ rowc,
+                                     int* __restrict__ status) {
   const int head = blockIdx.x, inst = blockIdx.y;
+  if (head == 0 && inst == 0 && threadIdx.x == 0) *status = 0;
   const float2* p = part + ((size_t)inst * g.Hkv + head) * g.nchunk * g.Rpad;
   float* c = rowc + ((size_t)inst * g.Hkv + head) * g.Rpad;
   for (int r = threadIdx.x; r < g.Rpad; r += blockDim.x) {
@@ -207,7 +210,7 @@ __global__ void row_constants_kernel(ScoreGeom g, const float2* __restrict__ par
 
 hipError_t launch_row_constants(const ScoreGeom& g, const Workspace& ws, hipStream_t st) {
   dim3 grid(g.Hkv, g.n_inst);
-  hipLaunchKernelGGL(row_constants_kernel, grid, dim3(128), 0, st, g, ws.part, ws.rowc);
+  hipLaunchKernelGGL(row_constants_kernel, grid, dim3(128), 0, st, g, ws.part, ws.rowc, ws.status);
   return hipGetLastError();
 }
 

@@ -735,9 +735,11 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
   }
 }
 
-// Sets the work counters of the two streaming passes to zero.
-__global__ void reset_counters_kernel(int* ctr) {
+// Sets the work counters of the two streaming passes to zero, and the workspace's status word (these
+// kernels have no wait to give up).
+__global__ void reset_counters_kernel(int* ctr, int* status) {
   if (threadIdx.x < 2) ctr[threadIdx.x] = 0;
+  if (threadIdx.x == 2) *status = 0;
 }
 
 // Combine the (m, z) of all chunks of a head into c = M + log2 Z per score row.  One workgroup per
@@ -858,7 +860,7 @@ hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, const KvLayout&
   };
   int grid1 = 0, grid2 = 0;
   const StreamPlan p1 = make_plan(nu1, units1, &grid1), p2 = make_plan(nu2, units2, &grid2);
-  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, ws.ctr);
+  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, ws.ctr, ws.status);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((stream_kernel<D, NRT, 1, STRIDED>), dim3(grid1), dim3(THREADS), bytes, st, g, qp, 0, p1, lay, q, k,
                      ws.part,

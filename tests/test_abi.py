@@ -21,8 +21,8 @@ def test_library_exports_every_declared_symbol(repo_root):
     lib = laq.load_library()
     names = declared_functions(repo_root)
     assert names == ["laq_compact", "laq_decode_attention", "laq_decode_workspace_bytes", "laq_evict", "laq_evict_static", "laq_init",
-                     "laq_qcache_store", "laq_recall", "laq_score", "laq_select", "laq_select_sink_recent",
-                     "laq_strerror", "laq_workspace_bytes", "laq_workspace_status"]
+                     "laq_qcache_store", "laq_recall", "laq_score", "laq_score_kernel", "laq_select",
+                     "laq_select_sink_recent", "laq_strerror", "laq_workspace_bytes", "laq_workspace_status"]
     for n in names:
         assert getattr(lib, n) is not None
 

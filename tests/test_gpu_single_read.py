@@ -46,6 +46,9 @@ def score_and_check(laq, q, k, pool, what, heads, k_dev=None, **kw):
     print("case:", what, "n=%d Hkv=%d G=%d L=%d W=%d pool=%d" % (n, Hkv, G, L, W, pool), flush=True)
     qd = q.to(DEV)
     kd = k.to(DEV) if k_dev is None else k_dev
+    strides = (0, 0, 0) if kd.is_contiguous() else (kd.stride(0), kd.stride(1), kd.stride(2))
+    assert laq.laq_score_kernel(n, Hq, Hkv, D, L, W, torch.bfloat16, kw.get("q_pos"), kw.get("keep"),
+                                strides) == "single-read", what
     nb = laq.laq_workspace_bytes(n, Hq, Hkv, D, L, W, torch.bfloat16)
     ws = torch.zeros(nb, dtype=torch.uint8, device=DEV)
     s = laq.laq_score(qd, kd, pool, ws=ws, **kw)
@@ -124,6 +127,33 @@ def test_explicit_query_positions_and_scale(laq):
     score_and_check(laq, q, k, 7, "positions-pooled", [(0, 1)], q_pos=q_pos, keep=0)
     # a sharper softmax (large logits): the probabilities span hundreds of binary orders of magnitude
     score_and_check(laq, q, k, 1, "scale-1.5", [(0, 0), (1, 1)], scale=1.5)
+
+
+def test_which_kernel(laq):
+    bf, f32 = torch.bfloat16, torch.float32
+    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 8, bf) == "single-read"         # 32 rows
+    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 16, bf) == "single-read"        # 64 rows
+    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 17, bf) == "two-pass"           # 68 rows
+    assert laq.laq_score_kernel(2, 32, 8, 128, 32768, 32, bf) == "two-pass"          # 128 rows
+    assert laq.laq_score_kernel(2, 32, 8, 64, 4096, 8, bf) == "two-pass"             # d = 64
+    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 8, f32) == "vector"
+    assert laq.laq_score_kernel(1, 4, 1, 128, 400000, 8, bf) == "two-pass"           # a team longer than the device holds
+    with pytest.raises(laq.LaqError):
+        laq.laq_score_kernel(2, 32, 8, 128, 4096, 0, bf)
+
+
+def test_status_is_defined_after_every_kind_of_call(laq):
+    # a workspace full of ones: whichever kernels score, the call leaves "all waits completed" behind
+    for (W, d, dt, kind) in ((8, 128, torch.bfloat16, "single-read"), (32, 128, torch.bfloat16, "two-pass"),
+                             (8, 64, torch.float32, "vector")):
+        n, Hq, Hkv, L = 1, 8, 2, 1200
+        assert laq.laq_score_kernel(n, Hq, Hkv, d, L, W, dt) == kind
+        g = torch.Generator().manual_seed(W)
+        q = torch.randn(n, Hq, W, d, generator=g).to(dt).to(DEV)
+        k = torch.randn(n, Hkv, L, d, generator=g).to(dt).to(DEV)
+        ws = torch.full((laq.laq_workspace_bytes(n, Hq, Hkv, d, L, W, dt),), 0xFF, dtype=torch.uint8, device=DEV)
+        laq.laq_score(q, k, 7, ws=ws)
+        assert laq.laq_workspace_status(ws, n, Hq, Hkv, d, L, W, dt) == 0, kind
 
 
 def test_constant_keys_give_uniform_probabilities(laq):
