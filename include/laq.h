@@ -104,6 +104,22 @@ typedef struct laq_shape {
   int64_t kv_stride_inst;
   int64_t kv_stride_head;
   int64_t kv_stride_row;
+  /*
+   * Paged cache (optional; all zero: none).  With a block table, k and v are pools of blocks of
+   * block_rows key rows each, as serving engines keep the caches of many sequences (Sec. 4.3's
+   * re-eviction then reads the prefill cache through the table and writes a packed one):
+   *   block_table      DEVICE array int32 [n_inst, ceil(L / block_rows)], dense.  Key row j of instance i
+   *                    is row j % block_rows of block block_table[i][j / block_rows]; instances may
+   *                    share blocks.  Block numbers are not checked: each must name a block of the pool.
+   *   block_rows       rows per block: a multiple of 256, the unit of the scoring kernels
+   *   kv_stride_block  distance between blocks of the pool, in elements (a multiple of 16 bytes)
+   * kv_stride_head and kv_stride_row then describe the inside of a block (both zero: the dense block
+   * [Hkv, block_rows, d]; a token-major block [block_rows, Hkv, d] is {d, Hkv*d}); kv_stride_inst is
+   * not used.  laq_score, laq_compact and laq_evict read paged caches; scoring streams K twice then.
+   */
+  const int32_t *block_table;
+  int32_t block_rows;
+  int64_t kv_stride_block;
 } laq_shape;
 
 /*

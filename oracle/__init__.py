@@ -8,7 +8,7 @@ The functions mirror the steps of the re-eviction procedure (paper Sec. 4.3,
 Eq. 4): ``raw_scores`` (window attention summed over the Q-cache and the GQA
 group), ``maxpool``, ``select`` (ArgSort[:B] per KV head with the window
 retained) and ``compact`` (row gather).  ``evict`` chains them for one
-instance.  Tensors are CPU torch tensors (fp32 or bf16); results are fp64 /
+instance; ``gather_paged`` writes a paged cache out densely first.  Tensors are CPU torch tensors (fp32 or bf16); results are fp64 /
 int32 torch tensors.
 """
 from __future__ import annotations
@@ -210,6 +210,27 @@ def compact(src: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
                                     idx.data_ptr(), Bk, out.data_ptr())
     if rc != 0:
         raise ValueError("laq_oracle_compact rejected its arguments")
+    return out
+
+
+def gather_paged(pool: torch.Tensor, block_table: torch.Tensor, L: int) -> torch.Tensor:
+    """A paged cache written out densely (the layout a serving engine hands to the re-eviction of
+    Sec. 4.3): pool [n_blocks, Hkv, block_rows, d], block_table int [n, ceil(L / block_rows)] ->
+    [n, Hkv, L, d].  Key row j of instance i is row j % block_rows of block block_table[i][j // block_rows].
+    Plain loops over instances and blocks; the other functions then take the dense result."""
+    pool, block_table = _cpu(pool), block_table.detach().cpu()
+    n_blocks, Hkv, block_rows, d = pool.shape
+    n, per = block_table.shape
+    if per != -(-L // block_rows):
+        raise ValueError("the table needs ceil(L / block_rows) entries per instance")
+    out = torch.empty(n, Hkv, L, d, dtype=pool.dtype)
+    for i in range(n):
+        for b in range(per):
+            blk = int(block_table[i, b])
+            if not 0 <= blk < n_blocks:
+                raise ValueError("block number out of range")
+            rows = min(block_rows, L - b * block_rows)
+            out[i, :, b * block_rows:b * block_rows + rows] = pool[blk, :, :rows]
     return out
 
 

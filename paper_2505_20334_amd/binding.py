@@ -32,7 +32,9 @@ class _Shape(ctypes.Structure):
                 ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("q_pos", ctypes.POINTER(ctypes.c_int32)), ("keep", ctypes.c_int32),
                 ("pool_mode", ctypes.c_int32), ("kv_stride_inst", ctypes.c_int64),
-                ("kv_stride_head", ctypes.c_int64), ("kv_stride_row", ctypes.c_int64)]
+                ("kv_stride_head", ctypes.c_int64), ("kv_stride_row", ctypes.c_int64),
+                ("block_table", ctypes.c_void_p), ("block_rows", ctypes.c_int32),
+                ("kv_stride_block", ctypes.c_int64)]
 
 
 def lib_path() -> str:
@@ -117,11 +119,11 @@ SCORE_KERNELS = ("vector", "two-pass", "single-read")
 
 def laq_score_kernel(n_inst: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: torch.dtype,
                      q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
-                     kv_strides: Tuple[int, int, int] = (0, 0, 0)) -> str:
+                     kv_strides: Tuple[int, int, int] = (0, 0, 0), paged=None) -> str:
     """Which kernels laq_score takes for this shape on the current device: "vector", "two-pass"
     (K streamed twice) or "single-read" (K read once)."""
     code = LAQ_F32 if dtype == torch.float32 else LAQ_BF16
-    sh = _shape(n_inst, Hq, Hkv, d, L, W, code, 0.0, q_pos, keep, "max", kv_strides)
+    sh = _shape(n_inst, Hq, Hkv, d, L, W, code, 0.0, q_pos, keep, "max", kv_strides, paged)
     rc = int(load_library().laq_score_kernel(ctypes.byref(sh)))
     if rc < 0:
         raise LaqError(rc, "laq_score_kernel")
@@ -156,6 +158,30 @@ def _kv(t: torch.Tensor, name: str) -> Tuple[int, int, int]:
     return (t.stride(0), t.stride(1), t.stride(2))
 
 
+def _cache(k: torch.Tensor, name: str, block_table: Optional[torch.Tensor], L: Optional[int]):
+    """The cache a call reads: (n, Hkv, L, d, strides, paged).  Without a block table k is
+    [n, Hkv, L, d] (strided views allowed).  With one, k is a pool of blocks [n_blocks, Hkv, block_rows, d]
+    (or a strided view of that shape, e.g. of token-major blocks), block_table is int32 [n, ceil(L /
+    block_rows)] on the same device and L must be given."""
+    if block_table is None:
+        if L is not None and L != k.shape[2]:
+            raise ValueError("L is only given with a block table")
+        kvs = _kv(k, name)
+        return k.shape[0], k.shape[1], k.shape[2], k.shape[3], kvs, None
+    if L is None:
+        raise ValueError("a paged cache needs L, the number of key rows per instance")
+    if k.device.type != "cuda" or k.dim() != 4 or k.stride(3) != 1:
+        raise ValueError("%s must be a pool [n_blocks, Hkv, block_rows, d] on the GPU with contiguous rows" % name)
+    if block_table.device != k.device or block_table.dtype != torch.int32 or block_table.dim() != 2 \
+            or not block_table.is_contiguous():
+        raise ValueError("block_table must be a dense int32 [n, blocks per instance] tensor on %s" % k.device)
+    n_blocks, Hkv, block_rows, d = k.shape
+    if block_rows % 256 or block_table.shape[1] != -(-int(L) // block_rows):
+        raise ValueError("blocks hold a multiple of 256 rows and the table ceil(L / block_rows) entries per instance")
+    inner = (0, 0, 0) if (k.stride(1) == block_rows * d and k.stride(2) == d) else (0, k.stride(1), k.stride(2))
+    return block_table.shape[0], Hkv, int(L), d, inner, (block_table, block_rows, k.stride(0))
+
+
 def _out(t: Optional[torch.Tensor], name: str, dtype: torch.dtype, numel: int, like: torch.Tensor) -> None:
     """A caller-supplied output buffer must be what the kernels will write: right dtype and device, dense,
     at least `numel` elements, 16-byte aligned."""
@@ -186,15 +212,21 @@ def _stream(stream) -> int:
 
 def _shape(n: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: int, scale: float,
            q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None, pool_mode: str = "max",
-           kv_strides: Tuple[int, int, int] = (0, 0, 0)) -> _Shape:
+           kv_strides: Tuple[int, int, int] = (0, 0, 0), paged=None) -> _Shape:
     """q_pos: position of every window query in the key sequence (None: the trailing window);
-    keep: trailing keys always retained (None: W); pool_mode "max" or "avg".  The position array
-    stays alive with the struct."""
+    keep: trailing keys always retained (None: W); pool_mode "max" or "avg"; paged: None or (block
+    table tensor, rows per block, element stride between blocks).  The position array and the table
+    stay alive with the struct."""
     if pool_mode not in ("max", "avg"):
         raise ValueError("pool_mode is 'max' or 'avg'")
     sh = _Shape(n, Hq, Hkv, d, L, W, dtype, float(scale), None, -1 if keep is None else int(keep),
                 LAQ_POOL_AVG if pool_mode == "avg" else LAQ_POOL_MAX, int(kv_strides[0]), int(kv_strides[1]),
-                int(kv_strides[2]))
+                int(kv_strides[2]), None, 0, 0)
+    if paged is not None:
+        sh._table_keepalive = paged[0]
+        sh.block_table = paged[0].data_ptr()
+        sh.block_rows = int(paged[1])
+        sh.kv_stride_block = int(paged[2])
     if q_pos is not None:
         if len(q_pos) != W:
             raise ValueError("q_pos needs one entry per window query")
@@ -225,9 +257,10 @@ def laq_workspace_bytes(n_inst: int, Hq: int, Hkv: int, d: int, L: int, W: int, 
     return int(load_library().laq_workspace_bytes(ctypes.byref(sh)))
 
 
-def _workspace(q_win, k, ws, q_pos=None, keep=None):
+def _workspace(q_win, k, ws, q_pos=None, keep=None, Hkv=None, L=None):
     n, Hq, W, d = q_win.shape
-    _, Hkv, L, _ = k.shape
+    if Hkv is None:
+        _, Hkv, L, _ = k.shape
     need = laq_workspace_bytes(n, Hq, Hkv, d, L, W, k.dtype, q_pos, keep)
     if ws is None:
         ws = torch.empty(need, dtype=torch.uint8, device=k.device)
@@ -239,23 +272,23 @@ def _workspace(q_win, k, ws, q_pos=None, keep=None):
 def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale: float = 0.0,
               scores: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
               stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
-              pool_mode: str = "max") -> torch.Tensor:
+              pool_mode: str = "max", block_table: Optional[torch.Tensor] = None,
+              L: Optional[int] = None) -> torch.Tensor:
     """q_win [n, Hq, W, d], k [n, Hkv, L, d] -> scores [n, Hkv, L] fp32 (pooled if pool_kernel > 1).
     q_pos / keep: the general observation window of laq_shape (None: trailing window); pool_mode:
-    "max" or "avg" (laq_pool_mode)."""
+    "max" or "avg" (laq_pool_mode); block_table / L: k is a paged cache (see _cache)."""
     lib = load_library()
     _dev(q_win, "q_win")
-    kvs = _kv(k, "k")
     n, Hq, W, d = q_win.shape
-    n2, Hkv, L, d2 = k.shape
+    n2, Hkv, L, d2, kvs, paged = _cache(k, "k", block_table, L)
     if n != n2 or d != d2 or q_win.dtype != k.dtype:
         raise ValueError("q_win / k mismatch")
     _aligned(q_win, "q_win"), _aligned(k, "k")
     _out(scores, "scores", torch.float32, n * Hkv * L, k)
     if scores is None:
         scores = torch.empty(n, Hkv, L, dtype=torch.float32, device=k.device)
-    ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
-    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs)
+    ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep, Hkv, L)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs, paged)
     rc = lib.laq_score(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), int(pool_kernel), scores.data_ptr(),
                        ws.data_ptr(), ws_bytes, _stream(stream))
     if rc != 0:
@@ -378,13 +411,13 @@ def laq_decode_workspace_bytes(n_inst: int, Hq: int, Hkv: int, d: int, L: int, d
 
 
 def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, budget: Sequence[int], keep: int,
-                k_out: Optional[torch.Tensor] = None, v_out: Optional[torch.Tensor] = None, stream=None):
+                k_out: Optional[torch.Tensor] = None, v_out: Optional[torch.Tensor] = None, stream=None,
+                block_table: Optional[torch.Tensor] = None, L: Optional[int] = None):
     """k, v [n, Hkv, L, d] + packed idx -> packed k_out, v_out [rows, d]; keep as in laq_select
-    (only used to check the budgets)."""
+    (only used to check the budgets); block_table / L: k, v are paged caches (see _cache)."""
     lib = load_library()
     _dev(idx, "idx")
-    kvs = _kv(k, "k")
-    n, Hkv, L, d = k.shape
+    n, Hkv, L, d, kvs, paged = _cache(k, "k", block_table, L)
     total, _ = packed_rows(budget, Hkv, L)
     if idx.dtype != torch.int32 or idx.numel() < total:
         raise ValueError("idx must be int32 with at least %d entries" % total)
@@ -393,7 +426,7 @@ def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, b
     if k_out is None:
         k_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
     if v is not None:
-        if v.shape != k.shape or v.dtype != k.dtype or _kv(v, "v") != kvs:
+        if v.shape != k.shape or v.dtype != k.dtype or v.stride() != k.stride():
             raise ValueError("k / v mismatch (shape, dtype or strides)")
         _aligned(v, "v")
         _out(v_out, "v_out", k.dtype, total * d, k)
@@ -401,7 +434,7 @@ def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, b
             v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
     elif v_out is not None:
         raise ValueError("v_out without v")
-    sh = _shape(n, Hkv, Hkv, d, L, 1, _dtype_code(k), 0.0, None, keep, "max", kvs)
+    sh = _shape(n, Hkv, Hkv, d, L, 1, _dtype_code(k), 0.0, None, keep, "max", kvs, paged)
     rc = lib.laq_compact(ctypes.byref(sh), k.data_ptr(), v.data_ptr() if v is not None else None,
                          idx.data_ptr(), _budget_array(budget, n), k_out.data_ptr(),
                          v_out.data_ptr() if v is not None else None, _stream(stream))
@@ -413,16 +446,16 @@ def laq_compact(k: torch.Tensor, v: Optional[torch.Tensor], idx: torch.Tensor, b
 def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], budget: Sequence[int],
               pool_kernel: int, scale: float = 0.0, scores=None, idx=None, k_out=None, v_out=None, ws=None,
               stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
-              pool_mode: str = "max", want_scores: bool = True, static_scratch: bool = False):
+              pool_mode: str = "max", want_scores: bool = True, static_scratch: bool = False,
+              block_table: Optional[torch.Tensor] = None, L: Optional[int] = None):
     """Whole path on one stream: returns (scores, idx, k_out, v_out); layouts as in the three calls.
     want_scores=False (and no scores buffer): the library hands the scores over inside the workspace and
     None is returned in their place.  static_scratch=True calls laq_evict_static (the library's own scratch
     array instead of a workspace; every output buffer must then be passed in for the call to allocate nothing)."""
     lib = load_library()
     _dev(q_win, "q_win")
-    kvs = _kv(k, "k")
     n, Hq, W, d = q_win.shape
-    n2, Hkv, L, d2 = k.shape
+    n2, Hkv, L, d2, kvs, paged = _cache(k, "k", block_table, L)
     if n != n2 or d != d2 or q_win.dtype != k.dtype:
         raise ValueError("q_win / k mismatch")
     total, _ = packed_rows(budget, Hkv, L)
@@ -437,7 +470,7 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
     if k_out is None:
         k_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
     if v is not None:
-        if v.shape != k.shape or v.dtype != k.dtype or _kv(v, "v") != kvs:
+        if v.shape != k.shape or v.dtype != k.dtype or v.stride() != k.stride():
             raise ValueError("k / v mismatch (shape, dtype or strides)")
         _aligned(v, "v")
         _out(v_out, "v_out", k.dtype, total * d, k)
@@ -445,7 +478,7 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
             v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
     elif v_out is not None:
         raise ValueError("v_out without v")
-    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs, paged)
     if static_scratch:
         rc = lib.laq_evict_static(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(),
                                   v.data_ptr() if v is not None else None, _budget_array(budget, n), int(pool_kernel),
@@ -454,7 +487,7 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
         if rc != 0:
             raise LaqError(rc, "laq_evict_static")
         return scores, idx, k_out, v_out
-    ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep)
+    ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep, Hkv, L)
     rc = lib.laq_evict(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), v.data_ptr() if v is not None else None,
                        _budget_array(budget, n), int(pool_kernel),
                        scores.data_ptr() if scores is not None else None, idx.data_ptr(),

@@ -56,6 +56,30 @@ static int make_geom(const laq_shape* s, ScoreGeom* g, QueryPos* qp = nullptr) {
 static int make_layout(const laq_shape* s, const ScoreGeom& g, KvLayout* lay) {
   const int eb = s->dtype == LAQ_F32 ? 4 : 2;
   const int64_t si = s->kv_stride_inst, sh = s->kv_stride_head, sr = s->kv_stride_row;
+  lay->table = nullptr;
+  lay->blocks_per_inst = 0;
+  lay->block_rows = 0;
+  lay->block = 0;
+  if (s->block_table) {
+    // a pool of blocks: strides inside a block, and between blocks
+    const int64_t br = s->block_rows, sb = s->kv_stride_block;
+    if (br < 256 || br % 256 || br > (1 << 24)) return LAQ_ERR_INVALID;
+    if ((sh == 0) != (sr == 0)) return LAQ_ERR_INVALID;
+    lay->row = sr ? sr : g.d;
+    lay->head = sh ? sh : br * g.d;
+    if (lay->row < g.d || lay->head < 1 || sb < 1 || (lay->row * eb) % 16 || (lay->head * eb) % 16 || (sb * eb) % 16)
+      return LAQ_ERR_INVALID;
+    if (lay->row * eb > 0x7fffffffLL) return LAQ_ERR_INVALID;
+    lay->inst = 0;
+    lay->dense = 0;
+    lay->table = s->block_table;
+    lay->blocks_per_inst = (int32_t)((g.L + br - 1) / br);
+    lay->block_rows = (int32_t)br;
+    lay->block = sb;
+    lay->row_bytes = (int32_t)(lay->row * eb);
+    return LAQ_OK;
+  }
+  if (s->block_rows != 0 || s->kv_stride_block != 0) return LAQ_ERR_INVALID;
   if (si == 0 && sh == 0 && sr == 0) {
     lay->row = g.d;
     lay->head = (int64_t)g.L * g.d;

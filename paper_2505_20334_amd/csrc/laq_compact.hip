@@ -2,7 +2,8 @@
 // decoder continues on (Sec. 4.3, the re-eviction that follows the ranking of Eq. 4).
 // Pure data movement: each 16-byte piece of an output row is copied by one lane, so a
 // 256-byte bf16 row (d = 128) is one coalesced 16-lane read and one coalesced write.  The source
-// rows are addressed through byte strides (instance, head, row); the output is packed.
+// rows are addressed through byte strides (instance, head, row), or through the block table of a
+// paged cache; the output is packed.
 #include "laq_internal.h"
 
 namespace laq {
@@ -12,7 +13,8 @@ namespace {
 constexpr int CP_THREADS = COMPACT_THREADS;
 
 __global__ __launch_bounds__(CP_THREADS) void compact_kernel(int n_inst, int Hkv, int L, int row_bytes, size_t inst_bytes,
-                                                             size_t head_bytes, size_t src_row_bytes, CompactTable tab,
+                                                             size_t head_bytes, size_t src_row_bytes, KvLayout lay,
+                                                             CompactTable tab,
                                                              int inst0, const char* __restrict__ k,
                                                              const char* __restrict__ v,
                                                              const int32_t* __restrict__ idx,
@@ -37,8 +39,14 @@ __global__ __launch_bounds__(CP_THREADS) void compact_kernel(int n_inst, int Hkv
   if (j < 0 || j >= L) return;
   const char* src = (blockIdx.y == 0) ? k : v;
   char* dst = (blockIdx.y == 0) ? k_out : v_out;
-  const size_t so = (size_t)(inst0 + li) * inst_bytes + (size_t)head * head_bytes + (size_t)j * src_row_bytes +
-                    (size_t)col * 16;
+  size_t so = (size_t)(inst0 + li) * inst_bytes + (size_t)j * src_row_bytes;
+  if (lay.table) {                       // paged cache: the row's block, and its row in there
+    int r;
+    const size_t eb = src_row_bytes / (size_t)lay.row;
+    so = (size_t)paged_block_offset(lay, inst0 + li, j, &r) * eb;
+    so += (size_t)r * src_row_bytes;
+  }
+  so += (size_t)head * head_bytes + (size_t)col * 16;
   const size_t dof = (size_t)orow * row_bytes + (size_t)col * 16;
   *reinterpret_cast<uint4*>(dst + dof) = *reinterpret_cast<const uint4*>(src + so);
 }
@@ -52,7 +60,7 @@ hipError_t launch_compact(int n_inst, int inst0, int Hkv, int L, int row_bytes, 
   dim3 grid((unsigned)tab.blk0[n_inst], v ? 2 : 1);
   const size_t eb = (size_t)lay.row_bytes / (size_t)lay.row;        // element size of the source rows
   hipLaunchKernelGGL(compact_kernel, grid, dim3(CP_THREADS), 0, st, n_inst, Hkv, L, row_bytes, (size_t)lay.inst * eb,
-                     (size_t)lay.head * eb, (size_t)lay.row_bytes, tab, inst0,
+                     (size_t)lay.head * eb, (size_t)lay.row_bytes, lay, tab, inst0,
                      static_cast<const char*>(k), static_cast<const char*>(v), idx, static_cast<char*>(k_out),
                      static_cast<char*>(v_out));
   return hipGetLastError();

@@ -113,7 +113,24 @@ struct KvLayout {
   int64_t inst, head, row;
   int32_t row_bytes;
   int32_t dense;
+  // paged cache (table != nullptr): key row j of instance i is row j % block_rows of block
+  // table[i * blocks_per_inst + j / block_rows]; blocks lie `block` elements apart, head / row are
+  // the strides inside a block, inst is not used
+  const int32_t* table;
+  int32_t blocks_per_inst;
+  int32_t block_rows;
+  int64_t block;
 };
+
+#ifdef __HIPCC__
+// Paged caches: element offset, from the pool's start, of the block that holds key row j of an
+// instance, and the row's number inside that block.
+__device__ __forceinline__ int64_t paged_block_offset(const KvLayout& lay, int inst, int j, int* row_in_block) {
+  const int b = j / lay.block_rows;
+  *row_in_block = j - b * lay.block_rows;
+  return (int64_t)lay.table[(size_t)inst * lay.blocks_per_inst + b] * lay.block;
+}
+#endif
 
 // Two packed index lists side by side, for up to MAX_PAIR_PER_LAUNCH instances.
 constexpr int MAX_PAIR_PER_LAUNCH = 128;

@@ -717,7 +717,7 @@ size_t fused_sync_bytes(const ScoreGeom& g) {
 }
 
 bool score_fused_supported(const ScoreGeom& g, const KvLayout& lay, int dtype) {
-  return dtype == LAQ_BF16 && g.d == D && g.Rpad <= 64 && g.W <= MAX_QPOS &&
+  return dtype == LAQ_BF16 && g.d == D && g.Rpad <= 64 && g.W <= MAX_QPOS && !lay.table &&
          ((long long)g.L + KEYS_PER_BLOCK) * lay.row_bytes < 0x7fffffffLL;
 }
 

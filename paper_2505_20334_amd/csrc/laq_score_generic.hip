@@ -35,7 +35,14 @@ __global__ __launch_bounds__(CHUNK_ROWS) void stats_generic_kernel(ScoreGeom g, 
   const int tid = threadIdx.x, dc = tid % PP, ks = tid / PP;
   const bool active = dc * 8 < g.d;
   const int j0 = chunk * CHUNK_ROWS;
-  const T* kbase = k + (size_t)inst * lay.inst + (size_t)head * lay.head + dc * 8;
+  // first row of the head (of a paged cache: where row 0 would lie if this chunk's block held the whole
+  // head; a block holds whole chunks)
+  int64_t head_off = (int64_t)inst * lay.inst;
+  if (lay.table) {
+    int r0;
+    head_off = paged_block_offset(lay, inst, j0, &r0) - (int64_t)(j0 - r0) * lay.row;
+  }
+  const T* kbase = k + head_off + (int64_t)head * lay.head + dc * 8;
   const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d + dc * 8;
   float2* out = part + (((size_t)inst * g.Hkv + head) * g.nchunk + chunk) * g.Rpad;
 
@@ -102,7 +109,14 @@ __global__ __launch_bounds__(CHUNK_ROWS) void norm_generic_kernel(ScoreGeom g, Q
   const int tid = threadIdx.x, dc = tid % PP, ks = tid / PP;
   const bool active = dc * 8 < g.d;
   const int j0 = chunk * CHUNK_ROWS;
-  const T* kbase = k + (size_t)inst * lay.inst + (size_t)head * lay.head + dc * 8;
+  // first row of the head (of a paged cache: where row 0 would lie if this chunk's block held the whole
+  // head; a block holds whole chunks)
+  int64_t head_off = (int64_t)inst * lay.inst;
+  if (lay.table) {
+    int r0;
+    head_off = paged_block_offset(lay, inst, j0, &r0) - (int64_t)(j0 - r0) * lay.row;
+  }
+  const T* kbase = k + head_off + (int64_t)head * lay.head + dc * 8;
   const T* qg = q + ((size_t)inst * g.Hq + (size_t)head * g.G) * g.W * g.d + dc * 8;
   const float* c = rowc + ((size_t)inst * g.Hkv + head) * g.Rpad;
   float acc[KPG];

@@ -628,10 +628,21 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
   if (run_u >= run_end) return;           // (host: never with a dynamic part, every workgroup has a first run)
 
   // key rows of chunk c_ of head hg_ (STRIDED: `lay` gives the element strides between instances and
-  // heads and the byte distance between rows; otherwise the cache is dense and `lay` is not read)
+  // heads and the byte distance between rows, or the block table of a paged cache, whose blocks hold
+  // whole chunks; otherwise the cache is dense and `lay` is not read)
   auto rows_of = [&](int hg_, int c_) {
     if constexpr (STRIDED) {
       const int inst = hg_ / g.Hkv, head = hg_ - inst * g.Hkv;
+      if (lay.table) {
+        int r0;
+        int64_t off = paged_block_offset(lay, inst, c_ * MFMA_ROWS, &r0);
+        // (the same in every lane: the descriptor stays in scalar registers)
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)(unsigned long long)off);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((unsigned long long)off >> 32));
+        off = (int64_t)(((unsigned long long)hi << 32) | lo);
+        return key_rows_strided<D>(k + off + (size_t)head * lay.head, r0, r0 + min(MFMA_ROWS, g.L - c_ * MFMA_ROWS), tid,
+                                   lay.row_bytes);
+      }
       return key_rows_strided<D>(k + (size_t)inst * lay.inst + (size_t)head * lay.head, c_ * MFMA_ROWS, g.L, tid,
                                  lay.row_bytes);
     } else {
@@ -919,7 +930,8 @@ hipError_t score_mfma_init(int dev) {
 bool score_mfma_supported(const ScoreGeom& g, const KvLayout& lay, int dtype) {
   // the key loads address a head with 31-bit byte offsets (one chunk of slack past its end)
   return dtype == LAQ_BF16 && (g.d == 128 || g.d == 64) && g.W <= MAX_QPOS &&
-         g.n_inst * (long long)g.Hkv <= 0x7fffffff && ((long long)g.L + MFMA_ROWS) * lay.row_bytes < 0x7fffffffLL;
+         g.n_inst * (long long)g.Hkv <= 0x7fffffff &&
+         ((long long)(lay.table ? lay.block_rows : g.L) + MFMA_ROWS) * lay.row_bytes < 0x7fffffffLL;
 }
 
 hipError_t launch_score_mfma(const ScoreGeom& g, const QueryPos& qp, const KvLayout& lay, int pool, const void* q,

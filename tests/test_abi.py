@@ -50,7 +50,7 @@ def test_workspace_bytes_grows_with_shape():
 
 def _shape(**kw):
     base = dict(n_inst=1, Hq=8, Hkv=2, d=128, L=512, W=8, dtype=1, scale=0.0, q_pos=None, keep=-1, pool_mode=0,
-                kv_stride_inst=0, kv_stride_head=0, kv_stride_row=0)
+                kv_stride_inst=0, kv_stride_head=0, kv_stride_row=0, block_table=None, block_rows=0, kv_stride_block=0)
     base.update(kw)
     return binding._Shape(*[base[f] for f, _ in binding._Shape._fields_])
 
@@ -198,6 +198,29 @@ def test_key_value_strides_are_checked_without_a_gpu():
                              None) == INVALID
     with pytest.raises(ValueError):
         binding._kv(torch.zeros(1, 2, 8, 16)[..., ::2], "k")                      # host tensor is refused first
+
+
+def test_paged_cache_fields_are_checked_without_a_gpu():
+    lib = laq.load_library()
+    fake = ctypes.c_void_p(0x1000)
+    INVALID, WORKSPACE = -1, -3
+    bud = (ctypes.c_int32 * 1)(64)
+    table = 0x2000                       # never read: every call below returns before a launch
+    good = _shape(block_table=table, block_rows=256, kv_stride_block=2 * 256 * 128)
+    assert lib.laq_score(ctypes.byref(good), fake, fake, 7, fake, fake, 16, None) == WORKSPACE             # accepted
+    token_major_blocks = _shape(block_table=table, block_rows=512, kv_stride_block=2 * 512 * 128, kv_stride_head=128,
+                                kv_stride_row=2 * 128)
+    assert lib.laq_score(ctypes.byref(token_major_blocks), fake, fake, 7, fake, fake, 16, None) == WORKSPACE
+    for bad in (_shape(block_table=table, block_rows=128, kv_stride_block=2 * 128 * 128),      # not a multiple of 256 rows
+                _shape(block_table=table, block_rows=300, kv_stride_block=2 * 300 * 128),
+                _shape(block_table=table, block_rows=256, kv_stride_block=0),                  # blocks on top of each other
+                _shape(block_table=table, block_rows=256, kv_stride_block=65540 + 1),          # not a 16-byte multiple
+                _shape(block_table=table, block_rows=256, kv_stride_block=65536, kv_stride_row=256),   # half an inner layout
+                _shape(block_rows=256), _shape(kv_stride_block=65536)):                        # block fields without a table
+        assert lib.laq_score(ctypes.byref(bad), fake, fake, 7, fake, fake, 1 << 30, None) == INVALID
+        assert lib.laq_compact(ctypes.byref(bad), fake, None, fake, bud, fake, None, None) == INVALID
+        assert lib.laq_evict(ctypes.byref(bad), fake, fake, fake, bud, 7, fake, fake, fake, fake, fake, 1 << 30,
+                             None) == INVALID
 
 
 def test_packed_rows():

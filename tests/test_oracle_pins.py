@@ -737,3 +737,59 @@ def test_sink_recent_writes_exactly_its_rows():
     assert lib.laq_oracle_sink_recent(Hkv, L, n_sink, budget, buf.data_ptr()) == 0
     assert buf[:Hkv * budget].view(Hkv, budget).tolist() == [[0, 1, 2, 3]] * Hkv
     assert buf[Hkv * budget:].tolist() == [-7] * 8
+
+
+# ----------------------------------------------------------------------------
+# paged caches: the gather that precedes the dense functions
+# ----------------------------------------------------------------------------
+def _scatter_into_pool(dense, block_rows, n_blocks, gen):
+    """Writes a dense cache [n, Hkv, L, d] into a pool through a random block table, with numpy
+    fancy indexing on flattened rows (independent of the oracle's loops); unused pool rows hold NaN."""
+    n, Hkv, L, d = dense.shape
+    per = -(-L // block_rows)
+    table = torch.randperm(n_blocks, generator=gen)[: n * per].reshape(n, per).int()
+    pool = torch.full((n_blocks, Hkv, block_rows, d), float("nan"), dtype=dense.dtype)
+    j = np.arange(L)
+    for i in range(n):
+        blk = table[i].numpy()[j // block_rows]                  # block of every row
+        pool.numpy()[blk, :, j % block_rows] = dense[i].permute(1, 0, 2).numpy()
+    return pool, table
+
+
+@pytest.mark.parametrize("L,block_rows", [(512, 256), (700, 256), (1000, 512), (256, 256), (5, 256)])
+def test_gather_paged_inverts_an_independent_scatter(L, block_rows):
+    gen = torch.Generator().manual_seed(L)
+    dense = torch.randn(3, 2, L, 8, generator=gen)
+    pool, table = _scatter_into_pool(dense, block_rows, 3 * (-(-L // block_rows)) + 4, gen)
+    back = oracle.gather_paged(pool, table, L)
+    assert torch.equal(back, dense)                              # no NaN leaked in: only valid rows were read
+
+
+def test_gather_paged_shared_blocks_identity_table_and_rejections():
+    gen = torch.Generator().manual_seed(1)
+    pool = torch.randn(4, 2, 256, 8, generator=gen)
+    # the identity table of one instance is a reshape
+    one = oracle.gather_paged(pool, torch.arange(4).reshape(1, 4).int(), 1024)
+    assert torch.equal(one[0], pool.permute(1, 0, 2, 3).reshape(2, 1024, 8))
+    # two instances that share their first block (a common prompt prefix) and differ afterwards
+    two = oracle.gather_paged(pool, torch.tensor([[0, 1], [0, 2]]).int(), 300)
+    assert torch.equal(two[0, :, :256], two[1, :, :256]) and torch.equal(two[0, :, 256:], pool[1, :, :44])
+    assert torch.equal(two[1, :, 256:], pool[2, :, :44])
+    with pytest.raises(ValueError):
+        oracle.gather_paged(pool, torch.tensor([[0, 4]]).int(), 300)      # no such block
+    with pytest.raises(ValueError):
+        oracle.gather_paged(pool, torch.tensor([[0, 1, 2]]).int(), 300)   # table longer than L needs
+
+
+def test_evict_on_a_gathered_paged_cache_equals_evict_on_the_dense_cache():
+    cfg = CONFIGS[1]
+    q, k, v, _ = make_instance(cfg, 0, 0)
+    gen = torch.Generator().manual_seed(9)
+    kp, table = _scatter_into_pool(k.unsqueeze(0), 256, 7, gen)
+    vp = torch.full_like(kp, float("nan"))
+    j = np.arange(cfg.L)
+    vp.numpy()[table[0].numpy()[j // 256], :, j % 256] = v.permute(1, 0, 2).numpy()
+    a = oracle.evict(q, k, v, 64, cfg.pool)
+    b = oracle.evict(q, oracle.gather_paged(kp, table, cfg.L)[0], oracle.gather_paged(vp, table, cfg.L)[0], 64, cfg.pool)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
