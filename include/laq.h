@@ -120,6 +120,13 @@ typedef struct laq_shape {
   const int32_t *block_table;
   int32_t block_rows;
   int64_t kv_stride_block;
+  /*
+   * Which scoring kernels to take where more than one applies (laq_score_choice; 0 = LAQ_CHOOSE_AUTO:
+   * the single-read kernel from 128 MiB of keys per call on, below that the two streaming passes,
+   * whose launches cost less).  A choice that does not apply to the shape is ignored; laq_score_kernel()
+   * tells what a call will run.
+   */
+  int32_t score_choice;
 } laq_shape;
 
 /*
@@ -158,8 +165,9 @@ int laq_workspace_status(const laq_shape *shape, const void *ws, size_t ws_bytes
  *   k      [n_inst, Hkv, L, d]  key cache.  Read once where a team of workgroups keeps a head on
  *                               chip between the two softmax passes (bf16, d = 128, at most 64
  *                               score rows G * W per KV head, L up to 512 x the workgroups the
- *                               device holds: 262144 on an MI355X), otherwise streamed twice
- *                               (laq_score_kernel() says which)
+ *                               device holds: 262144 on an MI355X, not paged, and enough keys in
+ *                               the call for that kernel to pay or shape.score_choice asking for
+ *                               it), otherwise streamed twice (laq_score_kernel() says which)
  *   scores [n_inst, Hkv, L]     fp32 out.  For each KV head g and key j:
  *            raw[g,j] = sum over the G heads of the group and the W queries of
  *                       softmax_j(scale * <q, k_j>) restricted to j <= P + w.
@@ -211,10 +219,11 @@ int laq_select_sink_recent(int32_t n_inst, int32_t Hkv, int32_t L, const int32_t
  * that account for memory traffic (Sec. 4.3's scoring reads K once or twice accordingly):
  * LAQ_KERNEL_VECTOR (vector-ALU path, K streamed twice), LAQ_KERNEL_TWO_PASS (matrix cores, K
  * streamed twice) or LAQ_KERNEL_SINGLE_READ (matrix cores, K read once); a negative error code
- * for an invalid shape.  The pooling mode and the strides of `shape` are taken into account
- * like laq_score does.  Launches nothing.
+ * for an invalid shape.  The strides, the block table and the score_choice of `shape` are taken
+ * into account like laq_score does.  Launches nothing.
  */
 enum { LAQ_KERNEL_VECTOR = 0, LAQ_KERNEL_TWO_PASS = 1, LAQ_KERNEL_SINGLE_READ = 2 };
+typedef enum { LAQ_CHOOSE_AUTO = 0, LAQ_CHOOSE_TWO_PASS = 1, LAQ_CHOOSE_SINGLE_READ = 2 } laq_score_choice;
 int laq_score_kernel(const laq_shape *shape);
 
 /*

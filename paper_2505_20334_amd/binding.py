@@ -34,7 +34,7 @@ class _Shape(ctypes.Structure):
                 ("pool_mode", ctypes.c_int32), ("kv_stride_inst", ctypes.c_int64),
                 ("kv_stride_head", ctypes.c_int64), ("kv_stride_row", ctypes.c_int64),
                 ("block_table", ctypes.c_void_p), ("block_rows", ctypes.c_int32),
-                ("kv_stride_block", ctypes.c_int64)]
+                ("kv_stride_block", ctypes.c_int64), ("score_choice", ctypes.c_int32)]
 
 
 def lib_path() -> str:
@@ -119,11 +119,11 @@ SCORE_KERNELS = ("vector", "two-pass", "single-read")
 
 def laq_score_kernel(n_inst: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: torch.dtype,
                      q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
-                     kv_strides: Tuple[int, int, int] = (0, 0, 0), paged=None) -> str:
+                     kv_strides: Tuple[int, int, int] = (0, 0, 0), paged=None, choose: str = "auto") -> str:
     """Which kernels laq_score takes for this shape on the current device: "vector", "two-pass"
     (K streamed twice) or "single-read" (K read once)."""
     code = LAQ_F32 if dtype == torch.float32 else LAQ_BF16
-    sh = _shape(n_inst, Hq, Hkv, d, L, W, code, 0.0, q_pos, keep, "max", kv_strides, paged)
+    sh = _shape(n_inst, Hq, Hkv, d, L, W, code, 0.0, q_pos, keep, "max", kv_strides, paged, choose)
     rc = int(load_library().laq_score_kernel(ctypes.byref(sh)))
     if rc < 0:
         raise LaqError(rc, "laq_score_kernel")
@@ -212,7 +212,7 @@ def _stream(stream) -> int:
 
 def _shape(n: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: int, scale: float,
            q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None, pool_mode: str = "max",
-           kv_strides: Tuple[int, int, int] = (0, 0, 0), paged=None) -> _Shape:
+           kv_strides: Tuple[int, int, int] = (0, 0, 0), paged=None, choose: str = "auto") -> _Shape:
     """q_pos: position of every window query in the key sequence (None: the trailing window);
     keep: trailing keys always retained (None: W); pool_mode "max" or "avg"; paged: None or (block
     table tensor, rows per block, element stride between blocks).  The position array and the table
@@ -221,7 +221,7 @@ def _shape(n: int, Hq: int, Hkv: int, d: int, L: int, W: int, dtype: int, scale:
         raise ValueError("pool_mode is 'max' or 'avg'")
     sh = _Shape(n, Hq, Hkv, d, L, W, dtype, float(scale), None, -1 if keep is None else int(keep),
                 LAQ_POOL_AVG if pool_mode == "avg" else LAQ_POOL_MAX, int(kv_strides[0]), int(kv_strides[1]),
-                int(kv_strides[2]), None, 0, 0)
+                int(kv_strides[2]), None, 0, 0, ("auto", "two-pass", "single-read").index(choose))
     if paged is not None:
         sh._table_keepalive = paged[0]
         sh.block_table = paged[0].data_ptr()
@@ -273,10 +273,11 @@ def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale:
               scores: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
               stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
               pool_mode: str = "max", block_table: Optional[torch.Tensor] = None,
-              L: Optional[int] = None) -> torch.Tensor:
+              L: Optional[int] = None, choose: str = "auto") -> torch.Tensor:
     """q_win [n, Hq, W, d], k [n, Hkv, L, d] -> scores [n, Hkv, L] fp32 (pooled if pool_kernel > 1).
     q_pos / keep: the general observation window of laq_shape (None: trailing window); pool_mode:
-    "max" or "avg" (laq_pool_mode); block_table / L: k is a paged cache (see _cache)."""
+    "max" or "avg" (laq_pool_mode); block_table / L: k is a paged cache (see _cache); choose: "auto",
+    "two-pass" or "single-read" (laq_score_choice)."""
     lib = load_library()
     _dev(q_win, "q_win")
     n, Hq, W, d = q_win.shape
@@ -288,7 +289,7 @@ def laq_score(q_win: torch.Tensor, k: torch.Tensor, pool_kernel: int = 1, scale:
     if scores is None:
         scores = torch.empty(n, Hkv, L, dtype=torch.float32, device=k.device)
     ws, ws_bytes = _workspace(q_win, k, ws, q_pos, keep, Hkv, L)
-    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs, paged)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs, paged, choose)
     rc = lib.laq_score(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(), int(pool_kernel), scores.data_ptr(),
                        ws.data_ptr(), ws_bytes, _stream(stream))
     if rc != 0:
@@ -447,7 +448,7 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
               pool_kernel: int, scale: float = 0.0, scores=None, idx=None, k_out=None, v_out=None, ws=None,
               stream=None, q_pos: Optional[Sequence[int]] = None, keep: Optional[int] = None,
               pool_mode: str = "max", want_scores: bool = True, static_scratch: bool = False,
-              block_table: Optional[torch.Tensor] = None, L: Optional[int] = None):
+              block_table: Optional[torch.Tensor] = None, L: Optional[int] = None, choose: str = "auto"):
     """Whole path on one stream: returns (scores, idx, k_out, v_out); layouts as in the three calls.
     want_scores=False (and no scores buffer): the library hands the scores over inside the workspace and
     None is returned in their place.  static_scratch=True calls laq_evict_static (the library's own scratch
@@ -478,7 +479,7 @@ def laq_evict(q_win: torch.Tensor, k: torch.Tensor, v: Optional[torch.Tensor], b
             v_out = torch.empty(total, d, dtype=k.dtype, device=k.device)
     elif v_out is not None:
         raise ValueError("v_out without v")
-    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs, paged)
+    sh = _shape(n, Hq, Hkv, d, L, W, _dtype_code(k), scale, q_pos, keep, pool_mode, kvs, paged, choose)
     if static_scratch:
         rc = lib.laq_evict_static(ctypes.byref(sh), q_win.data_ptr(), k.data_ptr(),
                                   v.data_ptr() if v is not None else None, _budget_array(budget, n), int(pool_kernel),

@@ -187,6 +187,16 @@ static int init_current_device(int* dev_out) {
   return LAQ_OK;
 }
 
+// The single-read kernel's cooperative launch and its serial start cost about 15 us more than the
+// launches of the two streaming passes; measured on an MI355X it is the faster one from 128 MiB of
+// keys per call on (21-27 % at 1 GiB and more).
+static bool single_read_wanted(const laq_shape* shape, const ScoreGeom& g) {
+  if (shape->score_choice == LAQ_CHOOSE_SINGLE_READ) return true;
+  if (shape->score_choice == LAQ_CHOOSE_TWO_PASS) return false;
+  const long long key_bytes = (long long)g.n_inst * g.Hkv * g.L * g.d * (shape->dtype == LAQ_F32 ? 4 : 2);
+  return key_bytes >= (128LL << 20);
+}
+
 static int score_impl(const laq_shape* shape, const void* q_win, const void* k, int pool, float* scores,
                       void* ws, size_t ws_bytes, hipStream_t st) {
   ScoreGeom g;
@@ -206,7 +216,7 @@ static int score_impl(const laq_shape* shape, const void* q_win, const void* k, 
   hipError_t e;
   const bool avg = pool_avg(shape) && pool > 1;
   const bool mfma = score_mfma_supported(g, lay, shape->dtype);
-  const bool fused = SINGLE_READ_ENABLED && score_fused_supported(g, lay, shape->dtype);
+  const bool fused = SINGLE_READ_ENABLED && score_fused_supported(g, lay, shape->dtype) && single_read_wanted(shape, g);
   // matrix cores: the single-read kernel where a team of workgroups can hold a head, else the two
   // streaming passes; both fuse the max pooling, the average goes through the raw-score plane
   auto score_on_matrix_cores = [&](int p, float* dst) -> hipError_t {
@@ -524,7 +534,9 @@ int laq_score_kernel(const laq_shape* shape) {
   if (laq::make_layout(shape, g, &lay) != LAQ_OK) return LAQ_ERR_INVALID;
   if (!laq::score_mfma_supported(g, lay, shape->dtype)) return LAQ_KERNEL_VECTOR;
   bool single = false;
-  if (laq::SINGLE_READ_ENABLED && laq::score_fused_applies(g, lay, shape->dtype, &single) != hipSuccess) return LAQ_ERR_DEVICE;
+  if (laq::SINGLE_READ_ENABLED && laq::single_read_wanted(shape, g) &&
+      laq::score_fused_applies(g, lay, shape->dtype, &single) != hipSuccess)
+    return LAQ_ERR_DEVICE;
   return single ? LAQ_KERNEL_SINGLE_READ : LAQ_KERNEL_TWO_PASS;
 }
 

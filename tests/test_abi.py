@@ -50,7 +50,7 @@ def test_workspace_bytes_grows_with_shape():
 
 def _shape(**kw):
     base = dict(n_inst=1, Hq=8, Hkv=2, d=128, L=512, W=8, dtype=1, scale=0.0, q_pos=None, keep=-1, pool_mode=0,
-                kv_stride_inst=0, kv_stride_head=0, kv_stride_row=0, block_table=None, block_rows=0, kv_stride_block=0)
+                kv_stride_inst=0, kv_stride_head=0, kv_stride_row=0, block_table=None, block_rows=0, kv_stride_block=0, score_choice=0)
     base.update(kw)
     return binding._Shape(*[base[f] for f, _ in binding._Shape._fields_])
 

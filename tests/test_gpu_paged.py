@@ -128,6 +128,7 @@ def test_paged_arguments_are_checked(laq):
         laq.laq_score(q, kp, 1, block_table=table.long(), L=500)                     # int64 table
     with pytest.raises(ValueError):
         laq.laq_score(q, kp[:, :, :128], 1, block_table=table, L=200)                # blocks of 128 rows
-    assert laq.laq_score_kernel(1, 8, 2, 128, 500, 8, torch.bfloat16, paged=(table, 256, kp.stride(0))) == "two-pass"
+    assert laq.laq_score_kernel(1, 8, 2, 128, 500, 8, torch.bfloat16, paged=(table, 256, kp.stride(0)),
+                                choose="single-read") == "two-pass"
     s = laq.laq_score(q, kp, 1, block_table=table, L=500)
     np.testing.assert_allclose(s.sum(dim=2).cpu().numpy(), 4 * 8, rtol=1e-5)         # zero keys: uniform rows

@@ -2,7 +2,8 @@
 oracle (needs an MI355X).
 
 laq_score takes that kernel for bf16 caches with d = 128 and at most 64 score rows per KV head
-(R = G * W); a team of ceil(L / 512) workgroups shares a head.  The cases walk the team sizes (one
+(R = G * W), by itself from 128 MiB of keys per call on and below that when the shape asks for it, as
+the cases here do; a team of ceil(L / 512) workgroups shares a head.  The cases walk the team sizes (one
 workgroup, a ragged last workgroup, a key count one past a boundary), the row-tile counts, heads
 fewer and more than the teams the device holds, strided caches, explicit query positions, and check
 after every call that all the kernel's waits completed (status of the workspace).
@@ -48,7 +49,8 @@ def score_and_check(laq, q, k, pool, what, heads, k_dev=None, **kw):
     kd = k.to(DEV) if k_dev is None else k_dev
     strides = (0, 0, 0) if kd.is_contiguous() else (kd.stride(0), kd.stride(1), kd.stride(2))
     assert laq.laq_score_kernel(n, Hq, Hkv, D, L, W, torch.bfloat16, kw.get("q_pos"), kw.get("keep"),
-                                strides) == "single-read", what
+                                strides, choose="single-read") == "single-read", what
+    kw = dict(kw, choose="single-read")
     nb = laq.laq_workspace_bytes(n, Hq, Hkv, D, L, W, torch.bfloat16)
     ws = torch.zeros(nb, dtype=torch.uint8, device=DEV)
     s = laq.laq_score(qd, kd, pool, ws=ws, **kw)
@@ -131,13 +133,18 @@ def test_explicit_query_positions_and_scale(laq):
 
 def test_which_kernel(laq):
     bf, f32 = torch.bfloat16, torch.float32
-    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 8, bf) == "single-read"         # 32 rows
-    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 16, bf) == "single-read"        # 64 rows
-    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 17, bf) == "two-pass"           # 68 rows
-    assert laq.laq_score_kernel(2, 32, 8, 128, 32768, 32, bf) == "two-pass"          # 128 rows
-    assert laq.laq_score_kernel(2, 32, 8, 64, 4096, 8, bf) == "two-pass"             # d = 64
-    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 8, f32) == "vector"
-    assert laq.laq_score_kernel(1, 4, 1, 128, 400000, 8, bf) == "two-pass"           # a team longer than the device holds
+    want = "single-read"
+    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 8, bf) == "two-pass"            # 16 MiB of keys: not worth it
+    assert laq.laq_score_kernel(64, 32, 8, 128, 4096, 8, bf) == "single-read"        # 512 MiB
+    assert laq.laq_score_kernel(16, 32, 8, 128, 4096, 16, bf) == "single-read"       # 128 MiB, 64 rows
+    assert laq.laq_score_kernel(64, 32, 8, 128, 4096, 8, bf, choose="two-pass") == "two-pass"
+    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 8, bf, choose=want) == "single-read"     # 32 rows
+    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 16, bf, choose=want) == "single-read"    # 64 rows
+    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 17, bf, choose=want) == "two-pass"       # 68 rows
+    assert laq.laq_score_kernel(64, 32, 8, 128, 32768, 32, bf, choose=want) == "two-pass"     # 128 rows
+    assert laq.laq_score_kernel(2, 32, 8, 64, 4096, 8, bf, choose=want) == "two-pass"         # d = 64
+    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 8, f32, choose=want) == "vector"
+    assert laq.laq_score_kernel(1, 4, 1, 128, 400000, 8, bf, choose=want) == "two-pass"       # a team longer than the device holds
     with pytest.raises(laq.LaqError):
         laq.laq_score_kernel(2, 32, 8, 128, 4096, 0, bf)
 
@@ -145,15 +152,30 @@ def test_which_kernel(laq):
 def test_status_is_defined_after_every_kind_of_call(laq):
     # a workspace full of ones: whichever kernels score, the call leaves "all waits completed" behind
     for (W, d, dt, kind) in ((8, 128, torch.bfloat16, "single-read"), (32, 128, torch.bfloat16, "two-pass"),
-                             (8, 64, torch.float32, "vector")):
+                             (8, 128, torch.bfloat16, "two-pass"), (8, 64, torch.float32, "vector")):
         n, Hq, Hkv, L = 1, 8, 2, 1200
-        assert laq.laq_score_kernel(n, Hq, Hkv, d, L, W, dt) == kind
+        assert laq.laq_score_kernel(n, Hq, Hkv, d, L, W, dt, choose=kind if kind != "vector" else "auto") == kind
         g = torch.Generator().manual_seed(W)
         q = torch.randn(n, Hq, W, d, generator=g).to(dt).to(DEV)
         k = torch.randn(n, Hkv, L, d, generator=g).to(dt).to(DEV)
         ws = torch.full((laq.laq_workspace_bytes(n, Hq, Hkv, d, L, W, dt),), 0xFF, dtype=torch.uint8, device=DEV)
-        laq.laq_score(q, k, 7, ws=ws)
+        laq.laq_score(q, k, 7, ws=ws, choose=kind if kind != "vector" else "auto")
         assert laq.laq_workspace_status(ws, n, Hq, Hkv, d, L, W, dt) == 0, kind
+
+
+def test_both_kernels_on_the_same_call(laq):
+    # the two designs sum in different orders: equal to within fp32 rounding, not bit for bit
+    n, Hkv, G, L, W = 3, 4, 4, 6000, 16
+    q, k = draw(n, Hkv, G, L, W, seed=21)
+    a = laq.laq_score(q.to(DEV), k.to(DEV), 7, choose="single-read")
+    b = laq.laq_score(q.to(DEV), k.to(DEV), 7, choose="two-pass")
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(a.cpu().numpy(), b.cpu().numpy(), rtol=2e-5, atol=1e-30)
+    # and the whole path agrees wherever the ranking is not decided inside that rounding
+    budgets = [300, 301, 302]
+    ia = laq.laq_evict(q.to(DEV), k.to(DEV), None, budgets, 7, choose="single-read")[1]
+    ib = laq.laq_evict(q.to(DEV), k.to(DEV), None, budgets, 7, choose="two-pass")[1]
+    assert (ia != ib).float().mean().item() < 0.01
 
 
 def test_constant_keys_give_uniform_probabilities(laq):
@@ -162,7 +184,7 @@ def test_constant_keys_give_uniform_probabilities(laq):
     g = torch.Generator().manual_seed(3)
     q = torch.randn(n, Hkv * G, W, D, generator=g).bfloat16()
     k = torch.randn(1, 1, 1, D, generator=g).expand(n, Hkv, L, D).contiguous().bfloat16()
-    s = laq.laq_score(q.to(DEV), k.to(DEV), 1).cpu().double()
+    s = laq.laq_score(q.to(DEV), k.to(DEV), 1, choose="single-read").cpu().double()
     P = L - W
     want = torch.zeros(L, dtype=torch.float64)
     for w in range(W):
