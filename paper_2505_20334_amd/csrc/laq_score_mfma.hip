@@ -746,19 +746,20 @@ __global__ __launch_bounds__(THREADS, MFMA_BLOCKS) void stream_kernel(ScoreGeom 
   }
 }
 
-// Sets the work counters of the two streaming passes to zero, and the workspace's status word (these
-// kernels have no wait to give up).
-__global__ void reset_counters_kernel(int* ctr, int* status) {
+// Sets the work counters of the two streaming passes to zero (launched only when a pass claims units
+// through them).
+__global__ void reset_counters_kernel(int* ctr) {
   if (threadIdx.x < 2) ctr[threadIdx.x] = 0;
-  if (threadIdx.x == 2) *status = 0;
 }
 
 // Combine the (m, z) of all chunks of a head into c = M + log2 Z per score row.  One workgroup per
-// (head, 32-row tile): 8 threads share a row and split the chunks; fixed merge order.
+// (head, 32-row tile): 8 threads share a row and split the chunks; fixed merge order.  Also clears the
+// workspace's status word (these kernels have no wait to give up).
 __global__ __launch_bounds__(256) void row_constants_mfma_kernel(ScoreGeom g, const float2* __restrict__ part,
-                                                                  float* __restrict__ rowc) {
+                                                                  float* __restrict__ rowc, int* __restrict__ status) {
   __shared__ float2 stat[256];
   const int hg = blockIdx.x, rt = blockIdx.y, tid = threadIdx.x;
+  if (hg == 0 && rt == 0 && tid == 0) *status = 0;
   const int r = rt * 32 + (tid & 31), sel = tid >> 5;
   const float2* p = part + (size_t)hg * g.nchunk * g.Rpad + r;
   float M = NEG_BIG, Z = 0.f;
@@ -871,14 +872,16 @@ hipError_t launch_stream(const ScoreGeom& g, const QueryPos& qp, const KvLayout&
   };
   int grid1 = 0, grid2 = 0;
   const StreamPlan p1 = make_plan(nu1, units1, &grid1), p2 = make_plan(nu2, units2, &grid2);
-  hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, ws.ctr, ws.status);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (p1.dynamic || p2.dynamic) {
+    hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(64), 0, st, ws.ctr);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   hipLaunchKernelGGL((stream_kernel<D, NRT, 1, STRIDED>), dim3(grid1), dim3(THREADS), bytes, st, g, qp, 0, p1, lay, q, k,
                      ws.part,
                      (const float*)nullptr, (float*)nullptr, ws.ctr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(row_constants_mfma_kernel, dim3((unsigned)n_heads, g.Rpad / 32), dim3(256), 0, st, gm, ws.part,
-                     ws.rowc);
+                     ws.rowc, ws.status);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   // (the edge records, at most 124 floats per 256-key chunk and only written when a head has more
   // than one chunk, fit the workspace's raw-score area of L floats per head)
