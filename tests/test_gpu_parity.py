@@ -677,10 +677,12 @@ def test_qcache_capture_feeds_scoring(laq):
 
 
 # ---- the path under stream capture ----
-def test_evict_replays_from_a_captured_graph(laq):
+@pytest.mark.parametrize("choose", ["two-pass", "single-read"])
+def test_evict_replays_from_a_captured_graph(laq, choose):
     """laq_evict enqueues kernels only (no allocation, no synchronisation, no memset node), so a
     caller may capture it into a graph; every replay must give the eager bits, also after the
-    inputs changed in place and with eager work in between."""
+    inputs changed in place and with eager work in between.  With either scoring kernel (the
+    single-read one is a cooperative launch)."""
     cfg = dataclasses.replace(CONFIGS[2], L=3000)
     q, k, v, budgets, _ = make_batch(cfg, device=DEV)
     n = q.shape[0]
@@ -693,8 +695,9 @@ def test_evict_replays_from_a_captured_graph(laq):
                      device=DEV)
 
     def run():
-        laq.laq_evict(q, k, v, budgets, cfg.pool, scores=scores, idx=idx, k_out=ko, v_out=vo, ws=ws)
+        laq.laq_evict(q, k, v, budgets, cfg.pool, scores=scores, idx=idx, k_out=ko, v_out=vo, ws=ws, choose=choose)
 
+    assert laq.laq_score_kernel(n, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, cfg.W, k.dtype, choose=choose) == choose
     laq.laq_init()                                   # attribute and occupancy queries, which a capture must not contain
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
@@ -704,7 +707,7 @@ def test_evict_replays_from_a_captured_graph(laq):
     for rep in range(4):
         if rep:
             k.copy_(torch.randn(k.shape, generator=gen, device=DEV).to(k.dtype))      # new inputs, same buffers
-        eager = [t.clone() for t in laq.laq_evict(q, k, v, budgets, cfg.pool)]
+        eager = [t.clone() for t in laq.laq_evict(q, k, v, budgets, cfg.pool, choose=choose)]
         for t in (scores, idx, ko, vo):
             t.zero_()
         torch.cuda.synchronize()
