@@ -54,8 +54,8 @@ def read_traffic(workload):
 
 
 SCORE_KERNEL_TEXT = {
-    "single-read": "laq_score stage: fused_reset_kernel + fused_kernel (K read once, kept in registers between the "
-                   "softmax passes) + pool_boundaries_kernel",
+    "single-read": "laq_score stage: fused_reset_kernel + fused_kernel (K read once; the unnormalised probabilities "
+                   "stay in registers until the softmax denominators are known) + pool_boundaries_kernel",
     "two-pass": "laq_score stage: stream_kernel<pass 1> + row_constants_mfma_kernel + stream_kernel<pass 2> + "
                 "pool_boundaries_kernel (K counted once in the algorithmic bytes, read twice)",
     "vector": "laq_score stage: vector-ALU kernels (K counted once in the algorithmic bytes, read twice)",

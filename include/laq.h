@@ -162,12 +162,13 @@ int laq_workspace_status(const laq_shape *shape, const void *ws, size_t ws_bytes
  * Importance scores (Eq. 4's sum over the Q-cache, taken on attention scores).
  *   q_win  [n_inst, Hq, W, d]   observation-window queries (Q-cache, local window, or both); always
  *                               dense (no strides)
- *   k      [n_inst, Hkv, L, d]  key cache.  Read once where a team of workgroups keeps a head on
- *                               chip between the two softmax passes (bf16, d = 128, at most 64
- *                               score rows G * W per KV head, L up to 512 x the workgroups the
- *                               device holds: 262144 on an MI355X, not paged, and enough keys in
- *                               the call for that kernel to pay or shape.score_choice asking for
- *                               it), otherwise streamed twice (laq_score_kernel() says which)
+ *   k      [n_inst, Hkv, L, d]  key cache.  Read once where a team of workgroups keeps a head's
+ *                               unnormalised probabilities on chip until the softmax denominators
+ *                               are known (bf16, d = 128, at most 64 score rows G * W per KV
+ *                               head, L up to 512 x the workgroups the device holds: 262144
+ *                               on an MI355X, not paged, and enough keys in the call for
+ *                               that kernel to pay or shape.score_choice asking for it),
+ *                               otherwise streamed twice (laq_score_kernel() says which)
  *   scores [n_inst, Hkv, L]     fp32 out.  For each KV head g and key j:
  *            raw[g,j] = sum over the G heads of the group and the W queries of
  *                       softmax_j(scale * <q, k_j>) restricted to j <= P + w.

@@ -144,7 +144,7 @@ def test_which_kernel(laq):
     assert laq.laq_score_kernel(64, 32, 8, 128, 32768, 32, bf, choose=want) == "two-pass"     # 128 rows
     assert laq.laq_score_kernel(2, 32, 8, 64, 4096, 8, bf, choose=want) == "two-pass"         # d = 64
     assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 8, f32, choose=want) == "vector"
-    assert laq.laq_score_kernel(1, 4, 1, 128, 400000, 8, bf, choose=want) == "two-pass"       # a team longer than the device holds
+    assert laq.laq_score_kernel(1, 4, 1, 128, 600000, 8, bf, choose=want) == "two-pass"       # a team longer than the device holds
     with pytest.raises(laq.LaqError):
         laq.laq_score_kernel(2, 32, 8, 128, 4096, 0, bf)
 
