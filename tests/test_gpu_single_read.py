@@ -1,12 +1,13 @@
-"""The single-read scoring kernel (keys resident in registers between the softmax passes) vs the CPU
-oracle (needs an MI355X).
+"""The single-read scoring kernel (a head's unnormalised probabilities stay in registers until the
+softmax denominators are known) vs the CPU oracle (needs an MI355X).
 
 laq_score takes that kernel for bf16 caches with d = 128 and at most 64 score rows per KV head
 (R = G * W), by itself from 128 MiB of keys per call on and below that when the shape asks for it, as
-the cases here do; a team of ceil(L / 512) workgroups shares a head.  The cases walk the team sizes (one
-workgroup, a ragged last workgroup, a key count one past a boundary), the row-tile counts, heads
-fewer and more than the teams the device holds, strided caches, explicit query positions, and check
-after every call that all the kernel's waits completed (status of the workspace).
+the cases here do; a team of workgroups shares a head, 512 keys each with more than 32 score rows,
+1024 otherwise.  The cases walk the team sizes (one workgroup, a ragged last workgroup, a key count
+one past a boundary) for both, the row counts, heads fewer and more than the teams the device
+holds, strided caches, explicit query positions, and check after every call that all the kernel's
+waits completed (status of the workspace).
 """
 import numpy as np
 import pytest
@@ -72,9 +73,13 @@ def score_and_check(laq, q, k, pool, what, heads, k_dev=None, **kw):
 SHAPES = [
     # name, n, Hkv, G, L, W, pool
     ("one-workgroup", 3, 2, 4, 300, 8, 7),
-    ("exactly-one-workgroup", 2, 2, 4, 512, 8, 1),
-    ("one-key-past-a-boundary", 2, 2, 4, 513, 8, 7),
-    ("window-straddles-a-boundary", 2, 2, 4, 1030, 16, 7),
+    ("exactly-one-workgroup-32-rows", 2, 2, 4, 1024, 8, 1),
+    ("exactly-one-workgroup-64-rows", 2, 2, 4, 512, 16, 1),
+    ("one-key-past-a-boundary-32-rows", 2, 2, 4, 1025, 8, 7),
+    ("one-key-past-a-boundary-64-rows", 2, 2, 4, 513, 16, 7),
+    ("window-straddles-a-boundary-32-rows", 2, 2, 4, 2054, 8, 7),
+    ("window-straddles-a-boundary-64-rows", 2, 2, 4, 1030, 16, 7),
+    ("pool-window-straddles-boundaries", 2, 2, 4, 1540, 12, 15),
     ("ragged-team-of-ten", 2, 3, 4, 4700, 16, 7),
     ("rows-not-a-multiple-of-32", 2, 2, 4, 2100, 5, 5),
     ("48-rows", 2, 2, 4, 3000, 12, 3),
@@ -92,17 +97,19 @@ def test_shapes(laq, name, n, Hkv, G, L, W, pool):
 
 
 def test_more_heads_than_teams_and_fewer(laq):
-    # L = 16384: 32 workgroups per team, the device holds 16 teams; 40 heads take three rounds with an
-    # unequal share, 3 heads leave most of the device idle
+    # L = 16384, 64 score rows: 32 workgroups per team, the device holds 16 teams; 40 heads take three
+    # rounds with an unequal share, 3 heads leave most of the device idle
     for (n, Hkv) in ((5, 8), (1, 3)):
         q, k = draw(n, Hkv, 4, 16384, 16, seed=n * 100 + Hkv, sinks=False)
         score_and_check(laq, q, k, 7, "heads-%d" % (n * Hkv), [(0, 0), (n - 1, Hkv - 1), (n // 2, 1)])
 
 
 def test_long_head_small_team_count(laq):
-    # L = 70000: 137 workgroups per team, 3 teams on the device
-    q, k = draw(1, 5, 4, 70000, 8, seed=7, sinks=False)
-    score_and_check(laq, q, k, 7, "long-head", [(0, 0), (0, 4)])
+    # L = 70000: 137 workgroups per team with 64 score rows (3 teams on the device), 69 with 32 (7 teams)
+    q, k = draw(1, 5, 4, 70000, 16, seed=7, sinks=False)
+    score_and_check(laq, q, k, 7, "long-head-64-rows", [(0, 0), (0, 4)])
+    q, k = draw(1, 9, 4, 70000, 8, seed=8, sinks=False)
+    score_and_check(laq, q, k, 7, "long-head-32-rows", [(0, 0), (0, 8)])
 
 
 def test_strided_and_token_major_caches(laq):
