@@ -50,7 +50,7 @@ def read_traffic(workload):
         if line.startswith("traffic_bytes_per_launch="):
             return float(line.split("=", 1)[1]), ("%s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, "
                                                   "recorded for the kernels: %s; not re-measured in this run)" % (rel, kernels))
-    return None, "%s holds no traffic figure" % rel
+    return None, "%s holds no traffic figure for the kernels of this build (see the note at its top)" % rel
 
 
 SCORE_KERNEL_TEXT = {
