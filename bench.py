@@ -160,9 +160,9 @@ def main():
     ap.add_argument("--pool-mode", choices=["max", "avg"], default="max",
                     help="sequence pooling: max (default, the headline workload) or the average of the "
                          "stage-1 eviction variant (Sec. 5.1)")
-    ap.add_argument("--layout", choices=["dense", "token-major"], default="dense",
+    ap.add_argument("--layout", choices=["dense", "token-major", "paged"], default="dense",
                     help="dense (default): k, v stored [n, Hkv, L, d]; token-major: stored [n, L, Hkv, d] and handed "
-                         "over as strided views")
+                         "over as strided views; paged: pools of 256-row blocks behind a shuffled block table")
     ap.add_argument("--no-probe", action="store_true",
                     help="skip the untimed recall probe (keeps profiler runs to the timed kernels)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -226,7 +226,7 @@ def measure_evict(args, torch, laq, cfg, budgets, dev, steps, warmup, primary):
     # ---- inputs, generated on the device, resident before any timing ----
     dt = cfg.torch_dtype
     q = torch.empty(n, cfg.Hq, cfg.W, cfg.d, dtype=dt, device=dev)
-    if args.layout == "dense":
+    if args.layout != "token-major":
         k = torch.empty(n, cfg.Hkv, cfg.L, cfg.d, dtype=dt, device=dev)
         v = torch.empty(n, cfg.Hkv, cfg.L, cfg.d, dtype=dt, device=dev)
     else:
@@ -236,6 +236,22 @@ def measure_evict(args, torch, laq, cfg, budgets, dev, steps, warmup, primary):
         seq, layer = divmod(i, cfg.n_layer)
         qi, ki, vi, _ = make_instance(cfg, seq, layer, device=dev)
         q[i].copy_(qi); k[i].copy_(ki); v[i].copy_(vi)
+    paged = {}
+    k_in, v_in = k, v                       # what the library is handed (k, v stay dense for the CPU oracle)
+    if args.layout == "paged":
+        # the same rows in pools of 256-row blocks, the blocks of all instances shuffled
+        br = 256
+        per = -(-cfg.L // br)
+        gen = torch.Generator(device="cpu").manual_seed(7)
+        table = torch.randperm(n * per, generator=gen).reshape(n, per).int().to(dev)
+        k_in = torch.zeros(n * per, cfg.Hkv, br, cfg.d, dtype=dt, device=dev)
+        v_in = torch.zeros(n * per, cfg.Hkv, br, cfg.d, dtype=dt, device=dev)
+        for i in range(n):
+            for b in range(per):
+                rows = min(br, cfg.L - b * br)
+                k_in[table[i, b], :, :rows] = k[i, :, b * br:b * br + rows]
+                v_in[table[i, b], :, :rows] = v[i, :, b * br:b * br + rows]
+        paged = {"block_table": table, "L": cfg.L}
     total_rows, _ = laq.packed_rows(budgets, cfg.Hkv, cfg.L)
     scores = torch.empty(n, cfg.Hkv, cfg.L, dtype=torch.float32, device=dev)
     idx = torch.empty(total_rows, dtype=torch.int32, device=dev)
@@ -245,11 +261,12 @@ def measure_evict(args, torch, laq, cfg, budgets, dev, steps, warmup, primary):
                      dtype=torch.uint8, device=dev)
     keep_rows = cfg.W if keep is None else keep
     strides = (0, 0, 0) if k.is_contiguous() else (k.stride(0), k.stride(1), k.stride(2))
-    score_kernel = laq.laq_score_kernel(n, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, cfg.W, dt, q_pos, keep, strides)
+    score_kernel = laq.laq_score_kernel(n, cfg.Hq, cfg.Hkv, cfg.d, cfg.L, cfg.W, dt, q_pos, keep, strides,
+                                        paged=(paged["block_table"], 256, k_in.stride(0)) if paged else None)
 
     def step():
-        laq.laq_evict(q, k, v, budgets, cfg.pool, scores=scores, idx=idx, k_out=k_out, v_out=v_out, ws=ws,
-                      q_pos=q_pos, keep=keep, pool_mode=args.pool_mode)
+        laq.laq_evict(q, k_in, v_in, budgets, cfg.pool, scores=scores, idx=idx, k_out=k_out, v_out=v_out, ws=ws,
+                      q_pos=q_pos, keep=keep, pool_mode=args.pool_mode, **paged)
 
     if args.calibrate_copy and primary:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -274,11 +291,11 @@ def measure_evict(args, torch, laq, cfg, budgets, dev, steps, warmup, primary):
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
     for _ in range(reps):
         ev[0].record()
-        laq.laq_score(q, k, cfg.pool, scores=scores, ws=ws, q_pos=q_pos, keep=keep, pool_mode=args.pool_mode)
+        laq.laq_score(q, k_in, cfg.pool, scores=scores, ws=ws, q_pos=q_pos, keep=keep, pool_mode=args.pool_mode, **paged)
         ev[1].record()
         laq.laq_select(scores, budgets, 1, keep_rows, idx=idx)
         ev[2].record()
-        laq.laq_compact(k, v, idx, budgets, keep_rows, k_out=k_out, v_out=v_out)
+        laq.laq_compact(k_in, v_in, idx, budgets, keep_rows, k_out=k_out, v_out=v_out, **paged)
         ev[3].record()
         torch.cuda.synchronize()
         stages["score"] += ev[0].elapsed_time(ev[1]) / reps
