@@ -115,7 +115,8 @@ typedef struct laq_shape {
    *   kv_stride_block  distance between blocks of the pool, in elements (a multiple of 16 bytes)
    * kv_stride_head and kv_stride_row then describe the inside of a block (both zero: the dense block
    * [Hkv, block_rows, d]; a token-major block [block_rows, Hkv, d] is {d, Hkv*d}); kv_stride_inst is
-   * not used.  laq_score, laq_compact and laq_evict read paged caches; scoring streams K twice then.
+   * not used.  laq_score, laq_compact and laq_evict read paged caches, with the same choice of
+   * scoring kernels as for dense ones.
    */
   const int32_t *block_table;
   int32_t block_rows;
@@ -166,7 +167,7 @@ int laq_workspace_status(const laq_shape *shape, const void *ws, size_t ws_bytes
  *                               unnormalised probabilities on chip until the softmax denominators
  *                               are known (bf16, d = 128, at most 64 score rows G * W per KV
  *                               head, L up to 512 x the workgroups the device holds: 262144
- *                               on an MI355X, not paged, and enough keys in the call for
+ *                               on an MI355X, and enough keys in the call for
  *                               that kernel to pay or shape.score_choice asking for it),
  *                               otherwise streamed twice (laq_score_kernel() says which)
  *   scores [n_inst, Hkv, L]     fp32 out.  For each KV head g and key j:

@@ -41,6 +41,7 @@
 // which it does after reading head n).  All waits are bounded, and end at once after one of
 // them has timed out (status word of the workspace).  The kernel is started with a cooperative
 // launch, which guarantees that the workgroups of a team are on the device together.
+#include <algorithm>
 #include <atomic>
 #include <type_traits>
 
@@ -125,11 +126,13 @@ __device__ __forceinline__ bf16x8 lds_operand(const char* p) { return *reinterpr
 
 // ---- key rows: global memory -> operand registers -------------------------------------------
 // Lane l of a wave supplies key row l%32 of a tile and the 16-byte slice 2t + l/32 of that row
-// for reduction step t.  Buffer loads against a descriptor that ends with the head's last row: rows
-// beyond L-1 read as zeros (they are causally masked).  Consecutive rows lie row_bytes apart (256
-// in a dense cache, more in a token-major or padded one).
+// for reduction step t.  Buffer loads against a descriptor that ends with the head's last row (of a
+// paged cache: the block's last valid row): rows beyond it read as zeros (they are causally
+// masked).  Consecutive rows lie row_bytes apart (256 in a dense cache, more in a token-major or
+// padded one).
 struct KeySource {
   __amdgpu_buffer_rsrc_t rsrc;
+  int row0;                // the tile's first row, counted from the descriptor's first
 };
 __device__ __forceinline__ KeySource key_source(const uint16_t* khead, int L, int row_bytes) {
   // (the address is the same in every lane; saying so keeps the descriptor in scalar registers)
@@ -137,20 +140,22 @@ __device__ __forceinline__ KeySource key_source(const uint16_t* khead, int L, in
   const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
   KeySource s;
   s.rsrc = __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((unsigned long long)hi << 32) | lo), 0,
-                                             __builtin_amdgcn_readfirstlane((L - 1) * row_bytes + D * 2), 0x00020000);
+                                             __builtin_amdgcn_readfirstlane(L > 0 ? (L - 1) * row_bytes + D * 2 : 0),
+                                             0x00020000);
+  s.row0 = 0;
   return s;
 }
 __device__ __forceinline__ bf16x8 load_operand(const KeySource& s, int voff_tile, int t) {
   return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(s.rsrc, voff_tile + t * 32, 0, 0));
 }
-// Byte offset within the head of (key tile kt of the wave, row l%32, slice l/32).  Recomputed
-// where it is needed (it is the same for every head, and a register held across the whole kernel
-// costs more than three instructions per tile), and opaque to the optimiser so that the step
-// offsets fold into the instructions' immediate fields.
-__device__ __forceinline__ int tile_offset(int key0, int kt, int lane, int row_bytes) {
+// Byte offset from the descriptor's first row of (row l%32 of the tile, slice l/32).  Recomputed
+// where it is needed (a register held across the whole kernel costs more than three instructions
+// per tile), and opaque to the optimiser so that the step offsets fold into the instructions'
+// immediate fields.
+__device__ __forceinline__ int tile_offset(const KeySource& s, int lane, int row_bytes) {
   int l = lane;
   asm volatile("" : "+v"(l));
-  return (key0 + kt * 32 + (l & 31)) * row_bytes + (l >> 5) * 16;
+  return (s.row0 + (l & 31)) * row_bytes + (l >> 5) * 16;
 }
 
 struct WaveCtx {
@@ -172,9 +177,10 @@ struct WaveCtx {
 // slot is reloaded as soon as its tile has been through its last pair: with the tile four further
 // on, or (slot 0, when `more`) with tile 0 of the next head.
 constexpr int RING = 4;
-template <int NRT>
+// cur(kt) / next(kt): where key tile kt of this head / of the next head lies.
+template <int NRT, typename CUR, typename NEXT>
 __device__ __forceinline__ void wave_main(const WaveCtx& w, f32x16 (&E)[Cfg<NRT>::PAIRS], bf16x8 (&kring)[RING][KS],
-                                          const KeySource& cur, const KeySource& next, bool more) {
+                                          CUR cur, NEXT next, bool more) {
   constexpr int NP = Cfg<NRT>::PAIRS, KT = Cfg<NRT>::KT;
   constexpr int AHEAD = 2;                 // Q operands requested from LDS this many MFMAs ahead
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -187,9 +193,10 @@ __device__ __forceinline__ void wave_main(const WaveCtx& w, f32x16 (&E)[Cfg<NRT>
   for (int n = 0; n < AHEAD; ++n) ring[n] = lds_operand(q_addr(n));
 #pragma unroll
   for (int kt = 1; kt < RING && kt < KT; ++kt) {
-    const int v = tile_offset(w.key0, kt, w.lane, w.row_bytes);
+    const KeySource src = cur(kt);
+    const int v = tile_offset(src, w.lane, w.row_bytes);
 #pragma unroll
-    for (int t = 0; t < KS; ++t) kring[kt][t] = load_operand(cur, v, t);
+    for (int t = 0; t < KS; ++t) kring[kt][t] = load_operand(src, v, t);
   }
 
   static_for<0, NP>([&](auto I) {
@@ -234,14 +241,16 @@ __device__ __forceinline__ void wave_main(const WaveCtx& w, f32x16 (&E)[Cfg<NRT>
       // first tile of the next head (slot 0, once no tile of this head needs it any more)
       constexpr int after = kt + RING;
       if constexpr (after < KT) {
-        const int v = tile_offset(w.key0, after, w.lane, w.row_bytes);
+        const KeySource src = cur(after);
+        const int v = tile_offset(src, w.lane, w.row_bytes);
 #pragma unroll
-        for (int t = 0; t < KS; ++t) kring[kt % RING][t] = load_operand(cur, v, t);
+        for (int t = 0; t < KS; ++t) kring[kt % RING][t] = load_operand(src, v, t);
       } else if constexpr (kt % RING == 0) {
         if (more) {
-          const int v = tile_offset(w.key0, 0, w.lane, w.row_bytes);
+          const KeySource src = next(0);
+          const int v = tile_offset(src, w.lane, w.row_bytes);
 #pragma unroll
-          for (int t = 0; t < KS; ++t) kring[0][t] = load_operand(next, v, t);
+          for (int t = 0; t < KS; ++t) kring[0][t] = load_operand(src, v, t);
         }
       }
     }
@@ -263,7 +272,7 @@ struct FusedPlan {
   int stagger;             // team t starts t * stagger ticks (10 ns) late
 };
 
-template <int NRT>
+template <int NRT, bool PAGED>
 __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryPos qp, FusedPlan plan, KvLayout lay,
                                                              const uint16_t* __restrict__ q,
                                                              const uint16_t* __restrict__ k,
@@ -328,10 +337,23 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
       if (p < S::Q_PIECES) *reinterpret_cast<u32x4*>(q_lds + row * QROWB + col * 16) = qv[i];
     }
   };
-  // key rows of head hg_ (instance hg_ / Hkv, KV head hg_ % Hkv)
-  auto keys_of = [&](int hg_) {
+  // key tile kt of this wave in head hg_ (instance hg_ / Hkv, KV head hg_ % Hkv).  Paged cache: the
+  // tile lies inside one block (blocks hold a multiple of 256 rows); a tile beyond the head's end
+  // gets an empty descriptor, every row of it reads as zeros
+  auto tile_of = [&](int hg_, int kt) {
     const int inst = hg_ / g.Hkv, head = hg_ - inst * g.Hkv;
-    return key_source(k + (size_t)inst * lay.inst + (size_t)head * lay.head, g.L, lay.row_bytes);
+    const int j0 = w.key0 + kt * 32;
+    if constexpr (PAGED) {
+      if (j0 >= g.L) return key_source(k, 0, lay.row_bytes);
+      int r0;
+      const int64_t off = paged_block_offset(lay, inst, j0, &r0);
+      KeySource s = key_source(k + off + (size_t)head * lay.head, min(lay.block_rows, g.L - (j0 - r0)), lay.row_bytes);
+      s.row0 = r0;
+      return s;
+    }
+    KeySource s = key_source(k + (size_t)inst * lay.inst + (size_t)head * lay.head, g.L, lay.row_bytes);
+    s.row0 = j0;
+    return s;
   };
   // Scores of head hg_ from the raw scores that step F left in LDS (zero beyond the head's last key
   // and in the margins).  Keys behind the prefix and, without pooling, all keys are stored as they
@@ -455,8 +477,8 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
     while (wall_clock64() < until) __builtin_amdgcn_s_sleep(8);
   }
   {
-    const KeySource src = keys_of(hg);
-    const int v = tile_offset(w.key0, 0, lane, lay.row_bytes);
+    const KeySource src = tile_of(hg, 0);
+    const int v = tile_offset(src, lane, lay.row_bytes);
 #pragma unroll
     for (int t = 0; t < KS; ++t) kring[0][t] = load_operand(src, v, t);
     u32x4 qv[S::Q_PER_THREAD];
@@ -470,7 +492,8 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
     const int hn = hg + plan.n_teams;
     const bool more = hn < plan.n_heads;
     // B
-    wave_main<NRT>(w, E, kring, keys_of(hg), keys_of(more ? hn : hg), more);
+    const int h_next = more ? hn : hg;
+    wave_main<NRT>(w, E, kring, [&](int kt) { return tile_of(hg, kt); }, [&](int kt) { return tile_of(h_next, kt); }, more);
     // C: the rows' maxima over this workgroup's keys ...
     const int n32c = opaque(w.n32), hfc = opaque(w.hf);
     static_for<0, NRT>([&](auto RT) {
@@ -584,12 +607,16 @@ std::atomic<int> fused_ready[MAX_DEVICES];
 template <int NRT>
 hipError_t init_rows(int dev, int cus, int coop) {
   constexpr int bytes = Cfg<NRT>::BYTES;
-  const void* fn = reinterpret_cast<const void*>(&fused_kernel<NRT>);
   hipError_t e;
-  int per_cu = 0;
-  if ((e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
-  if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, F_THREADS, bytes)) != hipSuccess) return e;
-  fused_resident[dev][NRT - 1].store((coop && per_cu > 0) ? cus * per_cu : -1, std::memory_order_release);
+  int resident = 0x7fffffff;
+  for (const void* fn : {reinterpret_cast<const void*>(&fused_kernel<NRT, false>),
+                         reinterpret_cast<const void*>(&fused_kernel<NRT, true>)}) {
+    int per_cu = 0;
+    if ((e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)) != hipSuccess) return e;
+    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, F_THREADS, bytes)) != hipSuccess) return e;
+    resident = std::min(resident, cus * per_cu);
+  }
+  fused_resident[dev][NRT - 1].store((coop && resident > 0) ? resident : -1, std::memory_order_release);
   return hipSuccess;
 }
 
@@ -641,7 +668,8 @@ hipError_t launch_fused_rows(const ScoreGeom& g, const QueryPos& qp, const KvLay
   QueryPos qq = qp;
   KvLayout ll = lay;
   float* edge = ws.raw;
-  const void* fn = reinterpret_cast<const void*>(&fused_kernel<NRT>);
+  const void* fn = lay.table ? reinterpret_cast<const void*>(&fused_kernel<NRT, true>)
+                             : reinterpret_cast<const void*>(&fused_kernel<NRT, false>);
   void* args[] = {&gg, &qq, &plan, &ll, &q, &k, &scores, &edge, &sy};
   e = hipLaunchCooperativeKernel(fn, dim3(plan.n_teams * plan.T), dim3(F_THREADS), args, bytes, st);
   if (e != hipSuccess) return e;
@@ -674,8 +702,8 @@ size_t fused_sync_bytes(const ScoreGeom& g) {
 }
 
 bool score_fused_supported(const ScoreGeom& g, const KvLayout& lay, int dtype) {
-  return dtype == LAQ_BF16 && g.d == D && g.Rpad <= 64 && g.W <= MAX_QPOS && !lay.table &&
-         ((long long)g.L + keys_per_block(g.Rpad / 32)) * lay.row_bytes < 0x7fffffffLL;
+  return dtype == LAQ_BF16 && g.d == D && g.Rpad <= 64 && g.W <= MAX_QPOS &&
+         ((long long)(lay.table ? lay.block_rows : g.L) + keys_per_block(g.Rpad / 32)) * lay.row_bytes < 0x7fffffffLL;
 }
 
 // Whether launch_score_fused would launch for this call on the current device.
