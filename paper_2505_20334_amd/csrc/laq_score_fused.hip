@@ -60,6 +60,7 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr float NEG_BIG = -1.0e30f;
 constexpr int D = 128;                       // head size this kernel is written for
 constexpr int KS = D / 16;                   // MFMAs (reduction steps) per 32x32 tile
+constexpr int TILE_BYTES = 32 * D * 2;       // a key tile: 32 rows
 constexpr int F_WAVES = 4, F_THREADS = F_WAVES * 64;   // one wave per SIMD; two workgroups share a compute unit
 // LDS row of Q: the d elements and 16 bytes that make 128-bit operand reads of 16 consecutive
 // rows conflict-free
@@ -104,7 +105,9 @@ template <int NRT> struct Cfg {
   static constexpr int OFF_RAW = OFF_LAST + ROWS * 4;               // float[MAX_HALF + KEYS_PER_BLOCK + MAX_HALF]: the
                                                                     // workgroup's raw scores between zero margins
   static constexpr int OFF_FLAG = OFF_RAW + (KEYS_PER_BLOCK + 2 * MAX_HALF) * 4;   // int: "a wait has timed out"
-  static constexpr int BYTES = OFF_FLAG + 16;
+  static constexpr int OFF_STAGE = (OFF_FLAG + 16 + 15) & ~15;      // char[F_WAVES][TILE_BYTES]: one key tile per wave, in flight
+                                                                    // from memory across the steps that have no registers for it
+  static constexpr int BYTES = OFF_STAGE + F_WAVES * TILE_BYTES;
 };
 
 // ---- words that workgroups hand to each other ------------------------------------------------
@@ -130,19 +133,25 @@ __device__ __forceinline__ bf16x8 lds_operand(const char* p) { return *reinterpr
 // paged cache: the block's last valid row): rows beyond it read as zeros (they are causally
 // masked).  Consecutive rows lie row_bytes apart (256 in a dense cache, more in a token-major or
 // padded one).
+// Where a key tile lies: its first row is row `row0` of the `rows` rows that start at `base`.
+struct TileRef {
+  const uint16_t* base;
+  int rows;
+  int row0;
+};
 struct KeySource {
   __amdgpu_buffer_rsrc_t rsrc;
-  int row0;                // the tile's first row, counted from the descriptor's first
+  int row0;
 };
-__device__ __forceinline__ KeySource key_source(const uint16_t* khead, int L, int row_bytes) {
+__device__ __forceinline__ KeySource key_source(const TileRef& r, int row_bytes) {
   // (the address is the same in every lane; saying so keeps the descriptor in scalar registers)
-  const unsigned long long a = reinterpret_cast<unsigned long long>(khead);
+  const unsigned long long a = reinterpret_cast<unsigned long long>(r.base);
   const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a), hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
   KeySource s;
   s.rsrc = __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((unsigned long long)hi << 32) | lo), 0,
-                                             __builtin_amdgcn_readfirstlane(L > 0 ? (L - 1) * row_bytes + D * 2 : 0),
+                                             __builtin_amdgcn_readfirstlane(r.rows > 0 ? (r.rows - 1) * row_bytes + D * 2 : 0),
                                              0x00020000);
-  s.row0 = 0;
+  s.row0 = r.row0;
   return s;
 }
 __device__ __forceinline__ bf16x8 load_operand(const KeySource& s, int voff_tile, int t) {
@@ -152,10 +161,39 @@ __device__ __forceinline__ bf16x8 load_operand(const KeySource& s, int voff_tile
 // where it is needed (a register held across the whole kernel costs more than three instructions
 // per tile), and opaque to the optimiser so that the step offsets fold into the instructions'
 // immediate fields.
-__device__ __forceinline__ int tile_offset(const KeySource& s, int lane, int row_bytes) {
+__device__ __forceinline__ int tile_offset(int row0, int lane, int row_bytes) {
   int l = lane;
   asm volatile("" : "+v"(l));
-  return (s.row0 + (l & 31)) * row_bytes + (l >> 5) * 16;
+  return (row0 + (l & 31)) * row_bytes + (l >> 5) * 16;
+}
+
+// The same tile, memory -> LDS without passing through registers: eight 16-byte loads per lane
+// whose data the memory pipeline writes to LDS itself, lane l's piece of reduction step t at
+// stage + t * 1024 + l * 16 (rows beyond the descriptor's end arrive as zeros, as in registers).
+// The loads count as vector memory loads of the wave (wait with stage_wait()); the compiler does
+// not see them: its own waits for loads issued earlier can only become longer by that, never
+// shorter, because loads complete in the order of their issue.  M0, which carries the LDS address, is put back.
+__device__ __forceinline__ void stage_tile(const TileRef& r, int row_bytes, int lane, unsigned stage) {
+  const unsigned long long a = reinterpret_cast<unsigned long long>(r.base);
+  u32x4 words;
+  words[0] = __builtin_amdgcn_readfirstlane((unsigned)a);
+  words[1] = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32)) & 0xffffu;
+  words[2] = __builtin_amdgcn_readfirstlane(r.rows > 0 ? (r.rows - 1) * row_bytes + D * 2 : 0);
+  words[3] = 0x00020000u;
+  const int voff = tile_offset(r.row0, lane, row_bytes);
+  const unsigned lds = __builtin_amdgcn_readfirstlane(stage);
+#pragma unroll
+  for (int t = 0; t < KS; ++t) {
+    unsigned keep;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, %4 offen lds\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep)
+                 : "s"(lds + t * 1024), "v"(voff), "s"(words), "s"(t * 32)
+                 : "memory");
+  }
+}
+__device__ __forceinline__ void stage_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+  return (unsigned)(unsigned long long)(__attribute__((address_space(3))) const char*)p;
 }
 
 struct WaveCtx {
@@ -166,21 +204,24 @@ struct WaveCtx {
   int row_bytes;           // distance between consecutive key rows
   int qmin;                // keys up to here are seen by every row: tiles below need no mask
   const int* last;         // LDS: last key every score row sees, for the causal mask
+  const char* stage;       // LDS: this wave's staged key tile
 };
 
 // ---- step B: the wave's (key tile, row tile) pairs --------------------------------------------
 // E[pair] = Q_rt * K_tile^T over the head size: lane = key, accumulator registers = 16 rows; -inf
 // where a row does not see a key.  Key tile kt is in kring[kt % 4].  Tile 0 is there when the pass
-// begins (loaded during the previous head's pass); the loads of the next three tiles are issued at
-// once at its start -- the registers that will hold the later pairs' results are still free then,
-// so three tiles can be in flight where the other steps of a head leave room for one -- and every
-// slot is reloaded as soon as its tile has been through its last pair: with the tile four further
-// on, or (slot 0, when `more`) with tile 0 of the next head.
+// begins (loaded into registers during the previous head's pass) and tile 1 waits in the wave's LDS
+// stage (requested at the end of the previous head's pass: it travels while the other steps run,
+// which have no registers to receive it); the loads of the next two tiles are issued at once at
+// the start -- the registers that will hold the later pairs' results are still free then -- and
+// every slot is reloaded as soon as its tile has been through its last pair: with the tile four
+// further on, or (slot 0, when `more`) with tile 0 of the next head.  Tile 1 of the next head is
+// requested at the end.
 constexpr int RING = 4;
 // cur(kt) / next(kt): where key tile kt of this head / of the next head lies.
-template <int NRT, typename CUR, typename NEXT>
+template <int NRT, typename CUR, typename NEXT, typename STAGE>
 __device__ __forceinline__ void wave_main(const WaveCtx& w, f32x16 (&E)[Cfg<NRT>::PAIRS], bf16x8 (&kring)[RING][KS],
-                                          CUR cur, NEXT next, bool more) {
+                                          CUR cur, NEXT next, STAGE stage_next, bool more) {
   constexpr int NP = Cfg<NRT>::PAIRS, KT = Cfg<NRT>::KT;
   constexpr int AHEAD = 2;                 // Q operands requested from LDS this many MFMAs ahead
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -191,10 +232,18 @@ __device__ __forceinline__ void wave_main(const WaveCtx& w, f32x16 (&E)[Cfg<NRT>
   bf16x8 ring[AHEAD];
 #pragma unroll
   for (int n = 0; n < AHEAD; ++n) ring[n] = lds_operand(q_addr(n));
+  {
+    static_assert(KT >= 2, "the staged tile is tile 1");
+    stage_wait();
+    int l = w.lane;
+    asm volatile("" : "+v"(l));
 #pragma unroll
-  for (int kt = 1; kt < RING && kt < KT; ++kt) {
+    for (int t = 0; t < KS; ++t) kring[1][t] = lds_operand(w.stage + t * 1024 + l * 16);
+  }
+#pragma unroll
+  for (int kt = 2; kt < RING && kt < KT; ++kt) {
     const KeySource src = cur(kt);
-    const int v = tile_offset(src, w.lane, w.row_bytes);
+    const int v = tile_offset(src.row0, w.lane, w.row_bytes);
 #pragma unroll
     for (int t = 0; t < KS; ++t) kring[kt][t] = load_operand(src, v, t);
   }
@@ -242,19 +291,20 @@ __device__ __forceinline__ void wave_main(const WaveCtx& w, f32x16 (&E)[Cfg<NRT>
       constexpr int after = kt + RING;
       if constexpr (after < KT) {
         const KeySource src = cur(after);
-        const int v = tile_offset(src, w.lane, w.row_bytes);
+        const int v = tile_offset(src.row0, w.lane, w.row_bytes);
 #pragma unroll
         for (int t = 0; t < KS; ++t) kring[kt % RING][t] = load_operand(src, v, t);
       } else if constexpr (kt % RING == 0) {
         if (more) {
           const KeySource src = next(0);
-          const int v = tile_offset(src, w.lane, w.row_bytes);
+          const int v = tile_offset(src.row0, w.lane, w.row_bytes);
 #pragma unroll
           for (int t = 0; t < KS; ++t) kring[0][t] = load_operand(src, v, t);
         }
       }
     }
   });
+  if (more) stage_next();
 }
 
 // ---- exchange buffers --------------------------------------------------------------------------
@@ -303,6 +353,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
   w.key0 = member * KEYS_PER_BLOCK + wave * KEYS_PER_WAVE;
   w.L = g.L; w.qmin = g.qmin; w.row_bytes = lay.row_bytes;
   w.last = last_lds;
+  w.stage = smem + S::OFF_STAGE + wave * TILE_BYTES;
   // rows beyond R (zero queries) see every key; their weight is zero
   for (int r = tid; r < ROWS; r += F_THREADS) last_lds[r] = r < g.R ? qp.last[r % g.W] : g.L - 1;
   if (tid < 2 * MAX_HALF) raw_lds[tid < MAX_HALF ? tid - MAX_HALF : KEYS_PER_BLOCK + tid - MAX_HALF] = 0.f;
@@ -337,23 +388,32 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
       if (p < S::Q_PIECES) *reinterpret_cast<u32x4*>(q_lds + row * QROWB + col * 16) = qv[i];
     }
   };
-  // key tile kt of this wave in head hg_ (instance hg_ / Hkv, KV head hg_ % Hkv).  Paged cache: the
-  // tile lies inside one block (blocks hold a multiple of 256 rows); a tile beyond the head's end
-  // gets an empty descriptor, every row of it reads as zeros
-  auto tile_of = [&](int hg_, int kt) {
+  // The memory that holds this wave's keys of head hg_ (instance hg_ / Hkv, KV head hg_ % Hkv): the
+  // head's first row, or in a paged cache the first row of the block with the wave's keys -- blocks
+  // hold a multiple of 256 rows and a wave's keys are 128 or 256 aligned ones, so they share a block.
+  // One look-up per head, made a step ahead of its first use.  (The table is not written while the
+  // kernel runs: read as constant memory, an entry comes through the scalar cache; a vector load
+  // would return behind every key load issued before it.)
+  auto wave_base = [&](int hg_) -> const uint16_t* {
     const int inst = hg_ / g.Hkv, head = hg_ - inst * g.Hkv;
+    if constexpr (PAGED) {
+      if (w.key0 >= g.L) return k;
+      typedef __attribute__((address_space(4))) const int32_t* ConstTable;
+      const int32_t blk = ((ConstTable)(unsigned long long)lay.table)[(size_t)inst * lay.blocks_per_inst + w.key0 / lay.block_rows];
+      return k + (int64_t)blk * lay.block + (size_t)head * lay.head;
+    }
+    return k + (size_t)inst * lay.inst + (size_t)head * lay.head;
+  };
+  // key tile kt of this wave; a tile beyond the head's end of a paged cache gets an empty range,
+  // every row of it reads as zeros
+  auto tile_at = [&](const uint16_t* base, int kt) {
     const int j0 = w.key0 + kt * 32;
     if constexpr (PAGED) {
-      if (j0 >= g.L) return key_source(k, 0, lay.row_bytes);
-      int r0;
-      const int64_t off = paged_block_offset(lay, inst, j0, &r0);
-      KeySource s = key_source(k + off + (size_t)head * lay.head, min(lay.block_rows, g.L - (j0 - r0)), lay.row_bytes);
-      s.row0 = r0;
-      return s;
+      if (j0 >= g.L) return TileRef{k, 0, 0};
+      const int first = w.key0 / lay.block_rows * lay.block_rows;      // the block's first key
+      return TileRef{base, min(lay.block_rows, g.L - first), j0 - first};
     }
-    KeySource s = key_source(k + (size_t)inst * lay.inst + (size_t)head * lay.head, g.L, lay.row_bytes);
-    s.row0 = j0;
-    return s;
+    return TileRef{base, g.L, j0};
   };
   // Scores of head hg_ from the raw scores that step F left in LDS (zero beyond the head's last key
   // and in the margins).  Keys behind the prefix and, without pooling, all keys are stored as they
@@ -472,15 +532,17 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
 
   // ---- the team's heads -----------------------------------------------------------------------
   int hg = team;
+  const uint16_t* base = wave_base(hg);
   if (plan.stagger > 0) {
     const long long until = wall_clock64() + (long long)team * plan.stagger;
     while (wall_clock64() < until) __builtin_amdgcn_s_sleep(8);
   }
   {
-    const KeySource src = tile_of(hg, 0);
-    const int v = tile_offset(src, lane, lay.row_bytes);
+    const KeySource src = key_source(tile_at(base, 0), lay.row_bytes);
+    const int v = tile_offset(src.row0, lane, lay.row_bytes);
 #pragma unroll
     for (int t = 0; t < KS; ++t) kring[0][t] = load_operand(src, v, t);
+    stage_tile(tile_at(base, 1), lay.row_bytes, lane, lds_address(w.stage));
     u32x4 qv[S::Q_PER_THREAD];
     fetch_q(hg, qv);
     commit_q(qv);
@@ -492,8 +554,11 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
     const int hn = hg + plan.n_teams;
     const bool more = hn < plan.n_heads;
     // B
-    const int h_next = more ? hn : hg;
-    wave_main<NRT>(w, E, kring, [&](int kt) { return tile_of(hg, kt); }, [&](int kt) { return tile_of(h_next, kt); }, more);
+    const uint16_t* base_next = wave_base(more ? hn : hg);
+    wave_main<NRT>(
+        w, E, kring, [&](int kt) { return key_source(tile_at(base, kt), lay.row_bytes); },
+        [&](int kt) { return key_source(tile_at(base_next, kt), lay.row_bytes); },
+        [&]() { stage_tile(tile_at(base_next, 1), lay.row_bytes, opaque(threadIdx.x) & 63, lds_address(w.stage)); }, more);
     // C: the rows' maxima over this workgroup's keys ...
     const int n32c = opaque(w.n32), hfc = opaque(w.hf);
     static_for<0, NRT>([&](auto RT) {
@@ -589,7 +654,9 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
     // that round, behind its barriers)
     hg_prev = hg;
     hg = hn;
+    base = base_next;
   }
+  stage_wait();                            // (a tile requested before a wait timed out: nothing writes LDS after the end)
 }
 
 // zero in the statistics words (validity bit of "nothing yet") and the status word
