@@ -72,6 +72,14 @@ constexpr int COHERENT = 16;                 // cache policy bit "sc1": coherent
 
 #define LAQ_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// Issue priority of this wave against the waves of the other workgroup on the compute unit.  The
+// steps between two heads are a chain of short, latency-bound pieces (reductions, the publication
+// of the statistics, the reads of the team's) around two long pieces of bulk work (the matrix
+// products with their loads, the sweep of exponentials).  Without priorities the older wave of a
+// SIMD wins every arbitration, whatever it is doing; with them a wave in a short piece goes first
+// and a wave in the sweep of exponentials yields (config 5: 4.15 -> 3.75 ms for the stage).
+constexpr int PRIO_BULK = 0, PRIO_MATRIX = 1, PRIO_CHAIN = 3;
+
 // Workgroup barrier for data that travels through LDS only: waits for this wave's LDS operations,
 // not for its outstanding global loads (key rows are in flight most of the time, and the barrier of
 // __syncthreads() would wait for all of them).
@@ -554,12 +562,14 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
     const int hn = hg + plan.n_teams;
     const bool more = hn < plan.n_heads;
     // B
+    __builtin_amdgcn_s_setprio(PRIO_MATRIX);
     const uint16_t* base_next = wave_base(more ? hn : hg);
     wave_main<NRT>(
         w, E, kring, [&](int kt) { return key_source(tile_at(base, kt), lay.row_bytes); },
         [&](int kt) { return key_source(tile_at(base_next, kt), lay.row_bytes); },
         [&]() { stage_tile(tile_at(base_next, 1), lay.row_bytes, opaque(threadIdx.x) & 63, lds_address(w.stage)); }, more);
     // C: the rows' maxima over this workgroup's keys ...
+    __builtin_amdgcn_s_setprio(PRIO_CHAIN);
     const int n32c = opaque(w.n32), hfc = opaque(w.hf);
     static_for<0, NRT>([&](auto RT) {
       constexpr int rt = decltype(RT)::value;
@@ -581,6 +591,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
     }
     lds_barrier();
     // ... e = exp2(s - m) in place, and the rows' sums
+    __builtin_amdgcn_s_setprio(PRIO_BULK);
     static_for<0, NRT>([&](auto RT) {
       constexpr int rt = decltype(RT)::value;
       f32x4 mv[4];
@@ -604,6 +615,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
       const float z = over_keys(zs, [](float a, float b) { return a + b; }, n32c, hfc);
       if (hfc == 0) stat_lds[wave * ROWS + rt * 32 + n32c] = z;
     });
+    __builtin_amdgcn_s_setprio(PRIO_CHAIN);                  // (until step B of the next head)
     lds_barrier();
     if (tid < ROWS) {
       float Z = stat_lds[tid];
