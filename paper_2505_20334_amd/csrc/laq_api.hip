@@ -193,8 +193,11 @@ static int init_current_device(int* dev_out) {
 static bool single_read_wanted(const laq_shape* shape, const ScoreGeom& g) {
   if (shape->score_choice == LAQ_CHOOSE_SINGLE_READ) return true;
   if (shape->score_choice == LAQ_CHOOSE_TWO_PASS) return false;
+  // by itself: where it is the faster one -- at most 64 score rows per KV head (with more, a
+  // workgroup holds 256 keys and reads as many bytes of its team's statistics as of keys) and
+  // enough keys to pay for the cooperative launch
   const long long key_bytes = (long long)g.n_inst * g.Hkv * g.L * g.d * (shape->dtype == LAQ_F32 ? 4 : 2);
-  return key_bytes >= (128LL << 20);
+  return g.Rpad <= 64 && key_bytes >= (128LL << 20);
 }
 
 static int score_impl(const laq_shape* shape, const void* q_win, const void* k, int pool, float* scores,

@@ -102,12 +102,17 @@ template <int NRT> struct Cfg {
   static constexpr int Q_BYTES = ROWS * QROWB;
   static constexpr int Q_PIECES = ROWS * (D / 8);                   // 16-byte pieces of one Q_g
   static constexpr int Q_PER_THREAD = (Q_PIECES + F_THREADS - 1) / F_THREADS;
-  static constexpr int RPAIRS = ROWS / 2, NSUB = F_THREADS / RPAIRS;   // the fold: threads per pair of rows
   static constexpr int OFF_Q = 0;                                   // [ROWS][QROWB] bf16 rows of Q_g
-  static constexpr int OFF_ZT = OFF_Q + Q_BYTES;                    // float[F_WAVES][32][ZT_STRIDE]: transposition tiles
-  static constexpr int OFF_STAT = OFF_ZT + F_WAVES * 32 * ZT_STRIDE * 4;   // float[F_WAVES][ROWS]: the waves' maxima / sums
+  // float[F_WAVES][32][ZT_STRIDE]: transposition tiles.  They are used between the last read of a
+  // head's Q and the arrival of the next head's, so where Q is large enough (128 score rows) they
+  // lie inside it; a barrier then separates them from the last matrix product.
+  static constexpr int ZT_BYTES = F_WAVES * 32 * ZT_STRIDE * 4;
+  static constexpr bool ZT_IN_Q = Q_BYTES >= ZT_BYTES;
+  static constexpr int OFF_ZT = ZT_IN_Q ? OFF_Q : OFF_Q + Q_BYTES;
+  static constexpr int OFF_STAT = OFF_Q + Q_BYTES + (ZT_IN_Q ? 0 : ZT_BYTES);   // float[F_WAVES][ROWS]: the waves' maxima / sums
   static constexpr int OFF_REF = OFF_STAT + F_WAVES * ROWS * 4;     // float[ROWS]: the rows' maxima over the workgroup (log2 units)
   static constexpr int OFF_WTS = OFF_REF + ROWS * 4;                // float[ROWS]: the rows' weights exp2(m - c)
+  static constexpr int RPAIRS = ROWS / 2, NSUB = F_THREADS / RPAIRS;   // the fold: threads per pair of rows
   static constexpr int OFF_FOLD = OFF_WTS + ROWS * 4;               // float2[NSUB][ROWS]: the team's statistics, per member subset
   static constexpr int OFF_LAST = OFF_FOLD + NSUB * ROWS * 8;       // int[ROWS]: last key every score row sees
   static constexpr int OFF_RAW = OFF_LAST + ROWS * 4;               // float[MAX_HALF + KEYS_PER_BLOCK + MAX_HALF]: the
@@ -568,6 +573,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
         w, E, kring, [&](int kt) { return key_source(tile_at(base, kt), lay.row_bytes); },
         [&](int kt) { return key_source(tile_at(base_next, kt), lay.row_bytes); },
         [&]() { stage_tile(tile_at(base_next, 1), lay.row_bytes, opaque(threadIdx.x) & 63, lds_address(w.stage)); }, more);
+    if constexpr (S::ZT_IN_Q) lds_barrier();                  // the transposition tiles lie inside Q: every wave is done with it
     // C: the rows' maxima over this workgroup's keys ...
     __builtin_amdgcn_s_setprio(PRIO_CHAIN);
     const int n32c = opaque(w.n32), hfc = opaque(w.hf);
@@ -680,7 +686,10 @@ __global__ void fused_reset_kernel(uint4* words, int n_words, int* status) {
 
 // ---- per-device set-up (see score_fused_init) -------------------------------------------------
 constexpr int MAX_DEVICES = 64;
-std::atomic<int> fused_resident[MAX_DEVICES][2];    // per row-tile count: workgroups held at once; -1: unusable
+std::atomic<int> fused_resident[MAX_DEVICES][3];    // per kernel (32, 64, 128 score rows): workgroups held at once; -1: unusable
+constexpr int slot_of(int nrt) { return nrt == 4 ? 2 : nrt - 1; }
+// row tiles of the kernel that takes Rpad score rows
+int tiles_for(int Rpad) { return Rpad > 64 ? 4 : Rpad / 32; }
 std::atomic<int> fused_ready[MAX_DEVICES];
 
 template <int NRT>
@@ -695,16 +704,18 @@ hipError_t init_rows(int dev, int cus, int coop) {
     if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, F_THREADS, bytes)) != hipSuccess) return e;
     resident = std::min(resident, cus * per_cu);
   }
-  fused_resident[dev][NRT - 1].store((coop && resident > 0) ? resident : -1, std::memory_order_release);
+  fused_resident[dev][slot_of(NRT)].store((coop && resident > 0) ? resident : -1, std::memory_order_release);
   return hipSuccess;
 }
 
-int keys_per_block(int nrt) { return nrt == 1 ? Cfg<1>::KEYS_PER_BLOCK : Cfg<2>::KEYS_PER_BLOCK; }
+int keys_per_block(int nrt) {
+  return nrt == 1 ? Cfg<1>::KEYS_PER_BLOCK : nrt == 2 ? Cfg<2>::KEYS_PER_BLOCK : Cfg<4>::KEYS_PER_BLOCK;
+}
 
 // The team layout of a call on this device; false: the device cannot hold a team of this length (or
 // has no cooperative launch) and the caller takes the two-pass kernels.
 bool make_plan(const ScoreGeom& g, int pool, int resident, FusedPlan* out) {
-  const int nrt = g.Rpad / 32;
+  const int nrt = tiles_for(g.Rpad);
   FusedPlan plan;
   plan.T = (g.L + keys_per_block(nrt) - 1) / keys_per_block(nrt);
   plan.half = (pool - 1) / 2;
@@ -734,7 +745,7 @@ hipError_t launch_fused_rows(const ScoreGeom& g, const QueryPos& qp, const KvLay
   constexpr int bytes = Cfg<NRT>::BYTES;
   constexpr int ROWS = NRT * 32;
   FusedPlan plan;
-  if (!make_plan(g, pool, fused_resident[dev][NRT - 1].load(std::memory_order_acquire), &plan)) return hipSuccess;
+  if (!make_plan(g, pool, fused_resident[dev][slot_of(NRT)].load(std::memory_order_acquire), &plan)) return hipSuccess;
   const size_t slots = (size_t)plan.n_teams * 2 * plan.T;
   FusedSync sy;
   sy.stats = reinterpret_cast<float2*>(ws.fused);
@@ -770,6 +781,7 @@ hipError_t score_fused_init(int dev) {
   if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
   if ((e = init_rows<1>(dev, cus, coop)) != hipSuccess) return e;
   if ((e = init_rows<2>(dev, cus, coop)) != hipSuccess) return e;
+  if ((e = init_rows<4>(dev, cus, coop)) != hipSuccess) return e;
   fused_ready[dev].store(1, std::memory_order_release);
   return hipSuccess;
 }
@@ -777,12 +789,12 @@ hipError_t score_fused_init(int dev) {
 // Bytes of exchange memory of the single-read kernel: two sets of statistics words for
 // FUSED_MAX_RESIDENT workgroups.
 size_t fused_sync_bytes(const ScoreGeom& g) {
-  return 2 * (size_t)FUSED_MAX_RESIDENT * (size_t)g.Rpad * sizeof(float2);
+  return 2 * (size_t)FUSED_MAX_RESIDENT * (size_t)(tiles_for(g.Rpad) * 32) * sizeof(float2);
 }
 
 bool score_fused_supported(const ScoreGeom& g, const KvLayout& lay, int dtype) {
-  return dtype == LAQ_BF16 && g.d == D && g.Rpad <= 64 && g.W <= MAX_QPOS &&
-         ((long long)(lay.table ? lay.block_rows : g.L) + keys_per_block(g.Rpad / 32)) * lay.row_bytes < 0x7fffffffLL;
+  return dtype == LAQ_BF16 && g.d == D && g.Rpad <= 128 && g.W <= MAX_QPOS &&
+         ((long long)(lay.table ? lay.block_rows : g.L) + keys_per_block(tiles_for(g.Rpad))) * lay.row_bytes < 0x7fffffffLL;
 }
 
 // Whether launch_score_fused would launch for this call on the current device.
@@ -794,7 +806,7 @@ hipError_t score_fused_applies(const ScoreGeom& g, const KvLayout& lay, int dtyp
   if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
   if ((e = score_fused_init(dev)) != hipSuccess) return e;
   FusedPlan plan;
-  *yes = make_plan(g, 1, fused_resident[dev][g.Rpad / 32 - 1].load(std::memory_order_acquire), &plan);
+  *yes = make_plan(g, 1, fused_resident[dev][slot_of(tiles_for(g.Rpad))].load(std::memory_order_acquire), &plan);
   return hipSuccess;
 }
 
@@ -805,9 +817,10 @@ hipError_t launch_score_fused(const ScoreGeom& g, const QueryPos& qp, const KvLa
                               const void* k, float* scores, const Workspace& ws, hipStream_t st, bool* done) {
   const uint16_t* qq = static_cast<const uint16_t*>(q);
   const uint16_t* kk = static_cast<const uint16_t*>(k);
-  const int ntile = g.Rpad / 32;
+  const int ntile = tiles_for(g.Rpad);
   if (ntile == 1) return launch_fused_rows<1>(g, qp, lay, pool, qq, kk, scores, ws, st, done);
-  return launch_fused_rows<2>(g, qp, lay, pool, qq, kk, scores, ws, st, done);
+  if (ntile == 2) return launch_fused_rows<2>(g, qp, lay, pool, qq, kk, scores, ws, st, done);
+  return launch_fused_rows<4>(g, qp, lay, pool, qq, kk, scores, ws, st, done);
 }
 
 }  // namespace laq

@@ -87,6 +87,15 @@ SHAPES = [
     ("group-of-eight", 2, 2, 8, 2049, 8, 7),
     ("one-query", 2, 2, 4, 1500, 1, 1),
     ("wide-pool", 2, 2, 4, 2600, 8, 31),
+    # 65 ... 128 score rows: 256 keys per workgroup
+    ("exactly-one-workgroup-128-rows", 2, 2, 4, 256, 32, 1),
+    ("one-key-past-a-boundary-128-rows", 2, 2, 4, 257, 32, 7),
+    ("window-straddles-a-boundary-128-rows", 2, 2, 4, 530, 32, 7),
+    ("128-rows-team-of-eleven", 2, 3, 4, 2700, 32, 7),
+    ("96-rows", 2, 2, 4, 1900, 24, 5),
+    ("68-rows", 2, 2, 4, 1300, 17, 7),
+    ("128-rows-group-of-eight", 2, 2, 8, 1111, 16, 3),
+    ("128-rows-one-head-per-query", 1, 2, 1, 900, 128, 7),
 ]
 
 
@@ -147,8 +156,10 @@ def test_which_kernel(laq):
     assert laq.laq_score_kernel(64, 32, 8, 128, 4096, 8, bf, choose="two-pass") == "two-pass"
     assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 8, bf, choose=want) == "single-read"     # 32 rows
     assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 16, bf, choose=want) == "single-read"    # 64 rows
-    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 17, bf, choose=want) == "two-pass"       # 68 rows
-    assert laq.laq_score_kernel(64, 32, 8, 128, 32768, 32, bf, choose=want) == "two-pass"     # 128 rows
+    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 17, bf, choose=want) == "single-read"    # 68 rows
+    assert laq.laq_score_kernel(64, 32, 8, 128, 32768, 32, bf, choose=want) == "single-read"  # 128 rows
+    assert laq.laq_score_kernel(64, 32, 8, 128, 32768, 32, bf) == "two-pass"                  # ... but not by itself
+    assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 33, bf, choose=want) == "two-pass"       # 132 rows
     assert laq.laq_score_kernel(2, 32, 8, 64, 4096, 8, bf, choose=want) == "two-pass"         # d = 64
     assert laq.laq_score_kernel(2, 32, 8, 128, 4096, 8, f32, choose=want) == "vector"
     assert laq.laq_score_kernel(1, 4, 1, 128, 600000, 8, bf, choose=want) == "two-pass"       # a team longer than the device holds
