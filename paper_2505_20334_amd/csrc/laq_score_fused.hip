@@ -332,7 +332,6 @@ struct FusedPlan {
   int n_teams;
   int n_heads;             // team t takes heads t, t + n_teams, ...
   int half;                // (pool kernel - 1) / 2; 0: raw scores
-  int stagger;             // team t starts t * stagger ticks (10 ns) late
 };
 
 template <int NRT, bool PAGED>
@@ -546,10 +545,6 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
   // ---- the team's heads -----------------------------------------------------------------------
   int hg = team;
   const uint16_t* base = wave_base(hg);
-  if (plan.stagger > 0) {
-    const long long until = wall_clock64() + (long long)team * plan.stagger;
-    while (wall_clock64() < until) __builtin_amdgcn_s_sleep(8);
-  }
   {
     const KeySource src = key_source(tile_at(base, 0), lay.row_bytes);
     const int v = tile_offset(src.row0, lane, lay.row_bytes);
@@ -724,9 +719,6 @@ bool make_plan(const ScoreGeom& g, int pool, int resident, FusedPlan* out) {
   plan.n_heads = (int)n_heads;
   plan.n_teams = resident / plan.T;
   if (plan.n_teams > plan.n_heads) plan.n_teams = plan.n_heads;
-  // a head takes a team roughly 5 us per 32-row tile; with at least four heads per team the teams
-  // are spread over that time
-  plan.stagger = (plan.n_heads >= 4 * plan.n_teams && plan.n_teams > 1) ? 500 * nrt / plan.n_teams : 0;
   // the exchange memory is sized for FUSED_MAX_RESIDENT workgroups
   if ((size_t)plan.n_teams * plan.T > (size_t)FUSED_MAX_RESIDENT) return false;
   *out = plan;
