@@ -123,8 +123,9 @@ typedef struct laq_shape {
   int64_t kv_stride_block;
   /*
    * Which scoring kernels to take where more than one applies (laq_score_choice; 0 = LAQ_CHOOSE_AUTO:
-   * the single-read kernel from 128 MiB of keys per call on, below that the two streaming passes,
-   * whose launches cost less).  A choice that does not apply to the shape is ignored; laq_score_kernel()
+   * the single-read kernel for at most 64 score rows per KV head from 128 MiB of keys per call on,
+   * otherwise the two streaming passes, whose launches cost less and which are the faster ones with
+   * more rows).  A choice that does not apply to the shape is ignored; laq_score_kernel()
    * tells what a call will run.
    */
   int32_t score_choice;
@@ -165,11 +166,13 @@ int laq_workspace_status(const laq_shape *shape, const void *ws, size_t ws_bytes
  *                               dense (no strides)
  *   k      [n_inst, Hkv, L, d]  key cache.  Read once where a team of workgroups keeps a head's
  *                               unnormalised probabilities on chip until the softmax denominators
- *                               are known (bf16, d = 128, at most 64 score rows G * W per KV
- *                               head, L up to 512 x the workgroups the device holds: 262144
- *                               on an MI355X, and enough keys in the call for
- *                               that kernel to pay or shape.score_choice asking for it),
- *                               otherwise streamed twice (laq_score_kernel() says which)
+ *                               are known: bf16, d = 128, at most 128 score rows G * W per KV
+ *                               head, L up to 1024 / 512 / 256 keys (for at most 32 / 64 / 128
+ *                               score rows) x the workgroups the device holds, 512 on an MI355X.
+ *                               The library takes that kernel by itself with at most 64 score
+ *                               rows and at least 128 MiB of keys in the call, where it is the
+ *                               faster one; shape.score_choice asks for it or against it.
+ *                               Otherwise K is streamed twice (laq_score_kernel() says which).
  *   scores [n_inst, Hkv, L]     fp32 out.  For each KV head g and key j:
  *            raw[g,j] = sum over the G heads of the group and the W queries of
  *                       softmax_j(scale * <q, k_j>) restricted to j <= P + w.

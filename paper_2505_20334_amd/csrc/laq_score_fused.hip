@@ -9,15 +9,17 @@
 // until the team of workgroups that shares the head has folded the rows' (m, Z = sum_keys e) into
 // c = M + log2 Z.  The key's score is then sum_rows e * exp2(m - c): one multiply-add per stored
 // number.  Key rows pass through registers once and are never needed again, so their loads do
-// not depend on the exchange.  For KV heads with at most 64 score rows.
+// not depend on the exchange.  For KV heads with at most 128 score rows (32, 64 or 128: one
+// instantiation each).
 //
 // A workgroup has four waves (one per SIMD; two workgroups share a compute unit, so that one of
 // them computes while the other waits for its team); a wave holds 8 / (R / 32) key tiles, a
 // workgroup four times that many keys, a team of ceil(L / keys per workgroup) workgroups one head.
 // Per head, every workgroup of the team
 //   B. D = Q * K_tile^T per (key tile, row tile): lane = key, accumulator registers = 16 rows; the
-//      next key tile is loaded while this one is worked on (the first one of the next head during
-//      the last);
+//      next key tiles are loaded while this one is worked on; the first two of the next head are
+//      requested during the pass, one into registers, one into LDS (loads that write LDS directly),
+//      and travel while the other steps run;
 //   C. row maxima over its keys (registers, a transposition through LDS per wave, LDS across
 //      waves), e = exp2(D * scale2 - m) in place, row sums the same way; publishes (m, Z) per row;
 //   D. pools and stores the previous head's scores, stages the next head's Q;
