@@ -173,6 +173,12 @@ int laq_workspace_status(const laq_shape *shape, const void *ws, size_t ws_bytes
  *                               rows and at least 128 MiB of keys in the call, where it is the
  *                               faster one; shape.score_choice asks for it or against it.
  *                               Otherwise K is streamed twice (laq_score_kernel() says which).
+ *                               The single-read kernel is started with a cooperative launch,
+ *                               which keeps a team of workgroups on the device together; with
+ *                               LAQ_COOPERATIVE_LAUNCH=0 in the environment (read at the first
+ *                               such call) it is an ordinary launch of the same grid, for
+ *                               profilers that cannot follow cooperative launches -- then
+ *                               other work on the device can make the call end in LAQ_ERR_TIMEOUT.
  *   scores [n_inst, Hkv, L]     fp32 out.  For each KV head g and key j:
  *            raw[g,j] = sum over the G heads of the group and the W queries of
  *                       softmax_j(scale * <q, k_j>) restricted to j <= P + w.

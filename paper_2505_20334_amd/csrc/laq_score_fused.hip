@@ -45,6 +45,7 @@
 // launch, which guarantees that the workgroups of a team are on the device together.
 #include <algorithm>
 #include <atomic>
+#include <cstdlib>
 #include <type_traits>
 
 #include "laq_internal.h"
@@ -755,7 +756,17 @@ hipError_t launch_fused_rows(const ScoreGeom& g, const QueryPos& qp, const KvLay
   const void* fn = lay.table ? reinterpret_cast<const void*>(&fused_kernel<NRT, true>)
                              : reinterpret_cast<const void*>(&fused_kernel<NRT, false>);
   void* args[] = {&gg, &qq, &plan, &ll, &q, &k, &scores, &edge, &sy};
-  e = hipLaunchCooperativeKernel(fn, dim3(plan.n_teams * plan.T), dim3(F_THREADS), args, bytes, st);
+  // LAQ_COOPERATIVE_LAUNCH=0 in the environment: an ordinary launch of the same grid, for tools that
+  // cannot follow cooperative launches (a process profiled by rocprofv3 ends in a segmentation fault
+  // after any cooperative launch, also of an empty kernel).  The grid still fits the device, but
+  // nothing then keeps other work from taking its place; the kernel's bounded waits turn a team
+  // that is not on the device together into LAQ_ERR_TIMEOUT.
+  static const bool plain_launch = [] {
+    const char* v = getenv("LAQ_COOPERATIVE_LAUNCH");
+    return v != nullptr && v[0] == '0';
+  }();
+  if (plain_launch) e = hipLaunchKernel(fn, dim3(plan.n_teams * plan.T), dim3(F_THREADS), args, bytes, st);
+  else e = hipLaunchCooperativeKernel(fn, dim3(plan.n_teams * plan.T), dim3(F_THREADS), args, bytes, st);
   if (e != hipSuccess) return e;
   if (plan.half > 0 && plan.T > 1) {
     if ((e = launch_pool_boundaries(g, plan.half, plan.T, Cfg<NRT>::KEYS_PER_BLOCK, edge, scores, st)) != hipSuccess) return e;
