@@ -209,3 +209,29 @@ def test_constant_keys_give_uniform_probabilities(laq):
         want[: P + w + 1] += G / (P + w + 1)
     np.testing.assert_allclose(s[0, 0].numpy(), want.numpy(), rtol=2e-6)
     np.testing.assert_allclose(s[0, 1].numpy(), want.numpy(), rtol=2e-6)
+
+
+def test_ordinary_launch_gives_the_same_bits(laq, tmp_path):
+    # LAQ_COOPERATIVE_LAUNCH=0 (read once per process, so a child process): the same kernel on the same
+    # grid, started without the cooperative guarantee, for profilers that cannot follow cooperative launches
+    import os
+    import subprocess
+    import sys
+    n, Hkv, G, L, W = 2, 3, 4, 5000, 16
+    q, k = draw(n, Hkv, G, L, W, seed=77)
+    want = laq.laq_score(q.to(DEV), k.to(DEV), 7, choose="single-read").cpu()
+    torch.save({"q": q, "k": k}, tmp_path / "in.pt")
+    code = (
+        "import sys, torch\n"
+        "sys.path.insert(0, %r)\n"
+        "import paper_2505_20334_amd as laq\n"
+        "d = torch.load(%r, weights_only=True)\n"
+        "s = laq.laq_score(d['q'].to('cuda:0'), d['k'].to('cuda:0'), 7, choose='single-read')\n"
+        "torch.cuda.synchronize()\n"
+        "torch.save(s.cpu(), %r)\n"
+    ) % (os.path.dirname(os.path.dirname(os.path.abspath(__file__))), str(tmp_path / "in.pt"), str(tmp_path / "out.pt"))
+    env = dict(os.environ, LAQ_COOPERATIVE_LAUNCH="0")
+    res = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=110)
+    assert res.returncode == 0, res.stderr[-2000:]
+    got = torch.load(tmp_path / "out.pt", weights_only=True)
+    assert torch.equal(got, want)
