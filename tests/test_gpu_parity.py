@@ -111,13 +111,18 @@ def test_config3_two_layers_full_length(laq):
     run_and_check(laq, q, k, v, budgets, cfg.pool, "cfg3", heads=[0, 5])
 
 
-def test_config4_sampled_full_size(laq):
-    # full 32-layer launch shape; the oracle checks sampled (instance, head) pairs
+@pytest.mark.parametrize("choose", ["auto", "single-read"])
+def test_config4_sampled_full_size(laq, choose):
+    # full 32-layer launch shape; the oracle checks sampled (instance, head) pairs.  By itself the
+    # library streams K twice here (128 score rows); on request the single-read kernel takes it with
+    # teams of 128 workgroups
     cfg = CONFIGS[4]
     q, k, v, budgets, _ = make_batch(cfg, device=DEV)
     n, Hkv, L, W, G = cfg.n_inst, cfg.Hkv, cfg.L, cfg.W, cfg.G
-    scores, idx, ko, vo = laq.laq_evict(q, k, v, budgets, cfg.pool)
-    raw = laq.laq_score(q, k, 1)
+    want = "two-pass" if choose == "auto" else "single-read"
+    assert laq.laq_score_kernel(n, cfg.Hq, Hkv, cfg.d, L, W, k.dtype, choose=choose) == want
+    scores, idx, ko, vo = laq.laq_evict(q, k, v, budgets, cfg.pool, choose=choose)
+    raw = laq.laq_score(q, k, 1, choose=choose)
     torch.cuda.synchronize()
     idx_l = split_packed(idx.cpu(), budgets, Hkv, L)
     ko_l = split_packed(ko.cpu(), budgets, Hkv, L)
