@@ -216,6 +216,7 @@ struct WaveCtx {
   const char* q_lane;      // LDS: Q row (lane%32), slice (lane/32) of reduction step 0, row tile 0
   int lane, hf, n32;
   int key0;                // first key of this wave within the head
+  int rot;                 // the wave's tile kt holds keys (kt + rot) % KT * 32 .. + 31 of its range
   int L;
   int row_bytes;           // distance between consecutive key rows
   int qmin;                // keys up to here are seen by every row: tiles below need no mask
@@ -276,7 +277,7 @@ __device__ __forceinline__ void wave_main(const WaveCtx& w, f32x16 (&E)[Cfg<NRT>
         // instructions so that the common one needs no copy of its start value; the bound goes
         // through an opaque copy so that the start vectors of all pairs are not computed ahead and
         // kept alive.
-        const int t0 = w.key0 + kt * 32;
+        const int t0 = w.key0 + ((kt + w.rot) % KT) * 32;
         int qmin_here = __builtin_amdgcn_readfirstlane(w.qmin);
         asm volatile("" : "+s"(qmin_here));
         if (t0 + 31 > qmin_here) {
@@ -366,6 +367,10 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
   w.lane = lane; w.hf = lane >> 5; w.n32 = lane & 31;
   w.q_lane = q_lds + w.n32 * QROWB + w.hf * 16;
   w.key0 = member * KEYS_PER_BLOCK + wave * KEYS_PER_WAVE;
+  // (the members of a team start at different tiles of their ranges, so that the addresses the
+  // device is asked for at the same time do not all lie the same distance into a 32 KiB piece: about
+  // 2 % on the stage time of config 5, averaged over its modes)
+  w.rot = __builtin_amdgcn_readfirstlane(member % KT);
   w.L = g.L; w.qmin = g.qmin; w.row_bytes = lay.row_bytes;
   w.last = last_lds;
   w.stage = smem + S::OFF_STAGE + wave * TILE_BYTES;
@@ -422,7 +427,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
   // key tile kt of this wave; a tile beyond the head's end of a paged cache gets an empty range,
   // every row of it reads as zeros
   auto tile_at = [&](const uint16_t* base, int kt) {
-    const int j0 = w.key0 + kt * 32;
+    const int j0 = w.key0 + ((kt + w.rot) % KT) * 32;
     if constexpr (PAGED) {
       if (j0 >= g.L) return TileRef{k, 0, 0};
       const int first = w.key0 / lay.block_rows * lay.block_rows;      // the block's first key
@@ -657,8 +662,9 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
 #pragma unroll
       for (int kt = 0; kt < KT; ++kt) {
         const float tot = part[kt] + __shfl_xor(part[kt], 32);
-        const int j = w.key0 + kt * 32 + n32f;
-        if (hff == 0) raw_lds[wave * KEYS_PER_WAVE + kt * 32 + n32f] = j < g.L ? tot : 0.f;
+        const int kp = (kt + w.rot) % KT;
+        const int j = w.key0 + kp * 32 + n32f;
+        if (hff == 0) raw_lds[wave * KEYS_PER_WAVE + kp * 32 + n32f] = j < g.L ? tot : 0.f;
       }
     }
     lds_barrier();                         // raw scores complete; weights and maxima free
