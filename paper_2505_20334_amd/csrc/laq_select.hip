@@ -6,8 +6,10 @@
 // T still fit (ties go to the lower position).  A last sweep emits, in ascending
 // position order, every key above T plus the first `want` keys equal to T, then the `keep`
 // window positions.  Keys live in registers (each wave owns a contiguous segment of the
-// prefix, 64 consecutive positions per register row) for prefixes up to 32768; longer
-// prefixes re-read the scores from memory in every pass.
+// prefix, 64 consecutive positions per register row -- or, where the scores need no pooling
+// here and lie 16-byte aligned, 256 consecutive positions per four registers, a lane holding
+// four neighbours that it fetched with one load) for prefixes up to 32768; longer prefixes
+// re-read the scores from memory in every pass.
 #include "laq_internal.h"
 
 namespace laq {
@@ -32,7 +34,8 @@ __device__ __forceinline__ int lanes_below(uint64_t m) {
 // WAVES_PER_SIMD = 4: one workgroup per compute unit, up to 128 registers per lane; 8: two workgroups
 // per compute unit on 64 registers (the 32-key variant then spills a few of them, which costs
 // 12 % when there is one workgroup per compute unit anyway and gains 30 % when there are many).
-template <int ITEMS, int WAVES_PER_SIMD>
+// QUADS: register 4q + c of a lane holds position seg0 + 256 q + 4 lane + c (one 16-byte load per q).
+template <int ITEMS, int WAVES_PER_SIMD, bool QUADS>
 __global__ __launch_bounds__(SEL_THREADS, WAVES_PER_SIMD) void select_kernel(int Hkv, int L, int keep, int pool, bool avg,
                                                              const float* __restrict__ scores, InstTable tab,
                                                              int inst0, int32_t* __restrict__ idx) {
@@ -59,8 +62,22 @@ __global__ __launch_bounds__(SEL_THREADS, WAVES_PER_SIMD) void select_kernel(int
   const int items = (ITEMS > 0) ? ITEMS : (P + SEL_THREADS - 1) / SEL_THREADS;
   const int seg0 = wave * items * 64;          // first position of this wave's segment
 
+  static_assert(!QUADS || (ITEMS > 0 && ITEMS % 4 == 0), "four registers per load");
   uint32_t key[ITEMS > 0 ? ITEMS : 1];
-  if (ITEMS > 0) {
+  if constexpr (QUADS) {
+#pragma unroll
+    for (int q4 = 0; q4 < ITEMS / 4; ++q4) {
+      const int pos = seg0 + q4 * 256 + lane * 4;
+      if (pos + 3 < P) {
+        const float4 v = *reinterpret_cast<const float4*>(s + pos);
+        key[4 * q4] = order_key(v.x); key[4 * q4 + 1] = order_key(v.y);
+        key[4 * q4 + 2] = order_key(v.z); key[4 * q4 + 3] = order_key(v.w);
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) key[4 * q4 + c] = (pos + c < P) ? order_key(s[pos + c]) : 0u;
+      }
+    }
+  } else if (ITEMS > 0) {
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
       const int pos = seg0 + i * 64 + lane;
@@ -137,6 +154,32 @@ __global__ __launch_bounds__(SEL_THREADS, WAVES_PER_SIMD) void select_kernel(int
   __syncthreads();
   int run_gt = 0, run_eq = 0;
   for (int v = 0; v < wave; ++v) { run_gt += wtot_gt[v]; run_eq += wtot_eq[v]; }
+  if constexpr (QUADS) {
+    // ascending positions = (q, lane, c): before a lane's four come those of the lower lanes
+#pragma unroll
+    for (int q4 = 0; q4 < ITEMS / 4; ++q4) {
+      uint64_t mg[4], me[4];
+      int g_before = run_gt, e_before = run_eq;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        mg[c] = __ballot(key[4 * q4 + c] > T);
+        me[c] = __ballot(key[4 * q4 + c] == T);
+        g_before += lanes_below(mg[c]);
+        e_before += lanes_below(me[c]);
+        run_gt += __popcll(mg[c]);
+        run_eq += __popcll(me[c]);
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint32_t kv = key[4 * q4 + c];
+        const bool gt = kv > T, eq = kv == T;
+        if (gt || (eq && e_before < want)) out[g_before + min(e_before, want)] = seg0 + q4 * 256 + lane * 4 + c;
+        g_before += gt;
+        e_before += eq;
+      }
+    }
+    return;
+  }
 #pragma unroll UNROLL
   for (int i = 0; i < items; ++i) {
     const uint32_t kv = key_of(i);
@@ -153,12 +196,20 @@ __global__ __launch_bounds__(SEL_THREADS, WAVES_PER_SIMD) void select_kernel(int
 template <int ITEMS>
 hipError_t launch_one(int n_inst, int inst0, int Hkv, int L, int keep, int pool, bool avg, const float* scores,
                       const InstTable& tab, int32_t* idx, hipStream_t st) {
-  if ((long long)Hkv * n_inst >= SEL_MANY_WORKGROUPS)
-    hipLaunchKernelGGL((select_kernel<ITEMS, 8>), dim3(Hkv, n_inst), dim3(SEL_THREADS), 0, st, Hkv, L, keep, pool, avg,
-                       scores, tab, inst0, idx);
-  else
-    hipLaunchKernelGGL((select_kernel<ITEMS, 4>), dim3(Hkv, n_inst), dim3(SEL_THREADS), 0, st, Hkv, L, keep, pool, avg,
-                       scores, tab, inst0, idx);
+  // scores that are final (no pooling here) and whose rows start 16-byte aligned: four per load
+  constexpr bool CAN_QUAD = ITEMS > 0 && ITEMS % 4 == 0;
+  const bool quads = CAN_QUAD && pool == 1 && L % 4 == 0 && reinterpret_cast<uintptr_t>(scores) % 16 == 0;
+  const bool many = (long long)Hkv * n_inst >= SEL_MANY_WORKGROUPS;
+  const dim3 grid(Hkv, n_inst), block(SEL_THREADS);
+  if constexpr (CAN_QUAD) {
+    if (quads) {
+      if (many) hipLaunchKernelGGL((select_kernel<ITEMS, 8, true>), grid, block, 0, st, Hkv, L, keep, pool, avg, scores, tab, inst0, idx);
+      else hipLaunchKernelGGL((select_kernel<ITEMS, 4, true>), grid, block, 0, st, Hkv, L, keep, pool, avg, scores, tab, inst0, idx);
+      return hipGetLastError();
+    }
+  }
+  if (many) hipLaunchKernelGGL((select_kernel<ITEMS, 8, false>), grid, block, 0, st, Hkv, L, keep, pool, avg, scores, tab, inst0, idx);
+  else hipLaunchKernelGGL((select_kernel<ITEMS, 4, false>), grid, block, 0, st, Hkv, L, keep, pool, avg, scores, tab, inst0, idx);
   return hipGetLastError();
 }
 
