@@ -314,6 +314,33 @@ def test_select_alone_with_ties_and_memory_path(laq):
             assert torch.equal(parts[i], oracle.select(pooled, W, b))
 
 
+def test_select_four_scores_per_load_and_its_fallbacks(laq):
+    # final scores (pool 1) whose rows start 16-byte aligned are fetched four per load; row lengths
+    # that are not a multiple of four and a misaligned score plane take the single loads.  Few
+    # distinct values: ties across the boundary in every register class (8 and 32 keys per lane) and
+    # in the many-heads instantiation
+    g = torch.Generator().manual_seed(14)
+    cases = [(2, 32768, 16, 1500, False), (3, 20000, 8, 999, False), (2, 8192 + 8, 8, 4000, False),
+             (2, 30001, 8, 700, False), (2, 6002, 4, 300, False), (2, 32768, 16, 1500, True), (2, 6000, 8, 64, True),
+             (400, 9000, 8, 240, False)]
+    for (Hkv, L, W, budget, misaligned) in cases:
+        n = 2
+        vals = torch.randint(0, 40, (n, Hkv, L), generator=g).float() / 7
+        if misaligned:
+            flat = torch.empty(n * Hkv * L + 1, device=DEV)
+            s = flat[1:].view(n, Hkv, L)
+            s.copy_(vals)
+            assert s.data_ptr() % 16 == 4 and s.is_contiguous()
+        else:
+            s = vals.to(DEV)
+        print("select case", Hkv, L, W, budget, misaligned, flush=True)
+        idx = laq.laq_select(s, [budget, budget + 3], 1, W)
+        torch.cuda.synchronize()
+        parts = split_packed(idx.cpu(), [budget, budget + 3], Hkv, L)
+        for i, bud in enumerate([budget, budget + 3]):
+            assert torch.equal(parts[i], oracle.select(vals[i], W, bud))
+
+
 def test_deterministic_bits(laq):
     cfg = dataclasses.replace(CONFIGS[3], L=4096, n_layer=3)
     q, k, v, budgets, _ = make_batch(cfg, device=DEV)
