@@ -6,8 +6,8 @@
 A step is one pass of the whole path (laq_evict) over every (sequence, layer) instance of the
 workload, inputs resident in HBM.  Prints ONE JSON line: whole-job throughput in prefill
 key-tokens scored+compacted per second per layer, the roofline of the dominant kernel
-(algorithmic bytes / live HIP-event duration against 8 TB/s) and the CPU oracle timed on a
-bounded sample of the same workload.
+(algorithmic bytes / live HIP-event duration against 8 TB/s; its HBM traffic from two short
+profiled child runs of the same command) and the CPU oracle timed on the same workload.
 """
 import argparse
 import json
@@ -51,6 +51,60 @@ def read_traffic(workload):
             return float(line.split("=", 1)[1]), ("%s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, "
                                                   "recorded for the kernels: %s; not re-measured in this run)" % (rel, kernels))
     return None, "%s holds no traffic figure for the kernels of this build (see the note at its top)" % rel
+
+
+SCORE_STAGE_KERNELS = ("stream_kernel", "row_constants", "reset_counters", "pool_boundaries", "fused_kernel",
+                       "fused_reset", "stats_generic_kernel", "norm_generic_kernel", "pool_kernel")
+
+
+def live_traffic(args, cfg_id):
+    """(HBM bytes per score-stage launch, source) measured now, or (None, why not).  Two short runs of this
+    script as child processes under rocprofv3 (--pmc FETCH_SIZE, then WRITE_SIZE: one counter per run, 3
+    steps each, same workload flags), each counter scaled by what it reads in the same run for a 1 GiB
+    device-to-device copy; per kernel the average over its dispatches, summed over the kernels of the
+    score stage.  The child runs start the single-read kernel with an ordinary launch
+    (LAQ_COOPERATIVE_LAUNCH=0): a process profiled by rocprofv3 does not survive a cooperative one."""
+    import csv
+    import shutil
+    import subprocess
+    import tempfile
+    if shutil.which("rocprofv3") is None:
+        return None, "rocprofv3 not found"
+    flags = ["--config", str(cfg_id), "--window", args.window, "--pool-mode", args.pool_mode, "--layout", args.layout]
+    env = dict(os.environ, TMPDIR="/tmp", LAQ_COOPERATIVE_LAUNCH="0")
+    total, names = 0.0, []
+    with tempfile.TemporaryDirectory(dir="/tmp") as tmp:
+        for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+            out_dir = os.path.join(tmp, counter)
+            cmd = ["rocprofv3", "--pmc", counter, "--output-format", "csv", "-d", out_dir, "-o", "t", "--",
+                   sys.executable, os.path.abspath(__file__), "--no-cpu-baseline", "--no-probe", "--no-extra",
+                   "--calibrate-copy", "--steps", "3", "--warmup", "1"] + flags
+            try:
+                res = subprocess.run(cmd, cwd="/tmp", env=env, capture_output=True, text=True, timeout=150)
+            except (subprocess.TimeoutExpired, OSError) as err:
+                return None, "profiled child run failed: %s" % type(err).__name__
+            if res.returncode != 0:
+                return None, "profiled child run ended with status %d" % res.returncode
+            found = [os.path.join(d, f) for d, _, fs in os.walk(out_dir) for f in fs if f.endswith("counter_collection.csv")]
+            if not found:
+                return None, "the profiled child run left no counter file"
+            per_kernel, copy = {}, 0.0
+            for row in csv.DictReader(open(found[0])):
+                if row["Counter_Name"] != counter:
+                    continue
+                name, val = row["Kernel_Name"], float(row["Counter_Value"])
+                if "copyBuffer" in name:
+                    copy = max(copy, val)
+                elif "laq::" in name and any(k in name for k in SCORE_STAGE_KERNELS):
+                    per_kernel.setdefault(name, []).append(val)
+            if copy <= 0 or not per_kernel:
+                return None, "the counter file holds no %s for the copy or for the score kernels" % counter
+            to_bytes = float(1 << 30) / copy            # the copy reads 1 GiB and writes 1 GiB
+            total += sum(sum(v) / len(v) for v in per_kernel.values()) * to_bytes
+            names = sorted(n.replace("void ", "").replace("(anonymous namespace)::", "").replace("laq::", "").split("(")[0]
+                           for n in per_kernel)
+    return float(round(total)), ("measured in this run: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE on two child runs of this command "
+                   "(3 steps each), scaled by a 1 GiB device copy in the same runs; kernels: %s" % ", ".join(names))
 
 
 SCORE_KERNEL_TEXT = {
@@ -164,7 +218,10 @@ def main():
                     help="dense (default): k, v stored [n, Hkv, L, d]; token-major: stored [n, L, Hkv, d] and handed "
                          "over as strided views; paged: pools of 256-row blocks behind a shuffled block table")
     ap.add_argument("--no-probe", action="store_true",
-                    help="skip the untimed recall probe (keeps profiler runs to the timed kernels)")
+                    help="skip the untimed extras -- the recall probe and the profiled child runs that measure "
+                         "roofline.traffic -- (keeps profiler runs to the timed kernels)")
+    ap.add_argument("--no-live-traffic", action="store_true",
+                    help="take roofline.traffic from the committed counter summary instead of measuring it now")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device tensor copy (a kernel of known traffic, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -306,7 +363,13 @@ def measure_evict(args, torch, laq, cfg, budgets, dev, steps, warmup, primary):
         sys.exit(1)
     ab = algorithmic_bytes(cfg, budgets)
     achieved = ab["score"] / (stages["score"] * 1e-3) / 1e9
-    traffic, traffic_source = read_traffic(workload)
+    traffic, traffic_source = None, None
+    if not args.no_probe and not args.no_live_traffic:
+        traffic, why = live_traffic(args, cfg.cfg_id)
+        traffic_source = why
+    if traffic is None:
+        traffic, from_file = read_traffic(workload)
+        traffic_source = from_file if traffic_source is None else "%s; %s" % (from_file, traffic_source)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
                 "kernel": SCORE_KERNEL_TEXT[score_kernel],
