@@ -57,7 +57,10 @@ SCORE_STAGE_KERNELS = ("stream_kernel", "row_constants", "reset_counters", "pool
                        "fused_reset", "stats_generic_kernel", "norm_generic_kernel", "pool_kernel")
 
 
-def live_traffic(args, cfg_id):
+DECODE_KERNELS = ("decode_kernel", "merge_parts_kernel")
+
+
+def live_traffic(args, cfg_id, kernels=SCORE_STAGE_KERNELS):
     """(HBM bytes per score-stage launch, source) measured now, or (None, why not).  Two short runs of this
     script as child processes under rocprofv3 (--pmc FETCH_SIZE, then WRITE_SIZE: one counter per run, 3
     steps each, same workload flags), each counter scaled by what it reads in the same run for a 1 GiB
@@ -70,7 +73,8 @@ def live_traffic(args, cfg_id):
     import tempfile
     if shutil.which("rocprofv3") is None:
         return None, "rocprofv3 not found"
-    flags = ["--config", str(cfg_id), "--window", args.window, "--pool-mode", args.pool_mode, "--layout", args.layout]
+    flags = ["--config", str(cfg_id), "--window", args.window, "--pool-mode", args.pool_mode, "--layout", args.layout,
+             "--path", args.path]
     env = dict(os.environ, TMPDIR="/tmp", LAQ_COOPERATIVE_LAUNCH="0")
     total, names = 0.0, []
     with tempfile.TemporaryDirectory(dir="/tmp") as tmp:
@@ -95,10 +99,10 @@ def live_traffic(args, cfg_id):
                 name, val = row["Kernel_Name"], float(row["Counter_Value"])
                 if "copyBuffer" in name:
                     copy = max(copy, val)
-                elif "laq::" in name and any(k in name for k in SCORE_STAGE_KERNELS):
+                elif "laq::" in name and any(k in name for k in kernels):
                     per_kernel.setdefault(name, []).append(val)
             if copy <= 0 or not per_kernel:
-                return None, "the counter file holds no %s for the copy or for the score kernels" % counter
+                return None, "the counter file holds no %s for the copy or for the kernels looked for" % counter
             to_bytes = float(1 << 30) / copy            # the copy reads 1 GiB and writes 1 GiB
             total += sum(sum(v) / len(v) for v in per_kernel.values()) * to_bytes
             names = sorted(n.replace("void ", "").replace("(anonymous namespace)::", "").replace("laq::", "").split("(")[0]
@@ -138,6 +142,12 @@ def bench_decode(args, torch, laq, cfg, budgets, dev):
         turn[0] += 1
         laq.laq_decode_attention(q, k_now, v_now, budgets, cfg.Hkv, cfg.L, out=out_t, ws=ws)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -157,6 +167,12 @@ def bench_decode(args, torch, laq, cfg, budgets, dev):
     ab = 2 * total * cfg.d * cfg.elem_bytes + q.numel() * cfg.elem_bytes + out_t.numel() * 4
     achieved = ab / (ms_kernel * 1e-3) / 1e9
     workload = cfg.name + "+decode"
+    traffic, traffic_source = None, None
+    if not args.no_probe and not args.no_live_traffic:
+        traffic, traffic_source = live_traffic(args, cfg.cfg_id, DECODE_KERNELS)
+    if traffic is None:
+        traffic, from_file = read_traffic(workload)
+        traffic_source = from_file if traffic_source is None else "%s; %s" % (from_file, traffic_source)
     out = {
         "metric": "retained key-tokens attended/sec per layer (all heads)",
         "value": round(total / cfg.Hkv / (ms_per_step * 1e-3), 1), "unit": "key-tokens/s/layer", "n_gpus": 1,
@@ -166,8 +182,7 @@ def bench_decode(args, torch, laq, cfg, budgets, dev):
                    "d": cfg.d, "L": cfg.L, "budget": cfg.budget, "packed_rows": total,
                    "cache_copies_cycled": len(copies)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(workload)[0],
-                     "traffic_source": read_traffic(workload)[1],
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "decode_kernel + merge_parts_kernel (K' and V' rows read once, q read, out written)",
                      "algorithmic_bytes_per_launch": ab, "ms_per_launch": round(ms_kernel, 4)},
     }
