@@ -132,10 +132,13 @@ __device__ __forceinline__ void coherent_store(float2* p, float2 v) {
   __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// (M, Z) <- (M, Z) merged with p = (m, z): the sums rescaled to the larger maximum.  One of the two
+// scale factors is exp2(0): only the other one is computed.
 __device__ __forceinline__ void merge_stat(float& M, float& Z, float2 p) {
-  const float Mn = fmaxf(M, p.x);
-  Z = Z * __builtin_amdgcn_exp2f(M - Mn) + p.y * __builtin_amdgcn_exp2f(p.x - Mn);
-  M = Mn;
+  const float d = p.x - M;
+  const float f = __builtin_amdgcn_exp2f(-fabsf(d));
+  Z = d > 0.f ? fmaf(Z, f, p.y) : fmaf(p.y, f, Z);
+  M = fmaxf(M, p.x);
 }
 
 // Row index (0..31) of accumulator register i for a lane in half hf of the 32x32 output layout.
