@@ -58,6 +58,7 @@ SCORE_STAGE_KERNELS = ("stream_kernel", "row_constants", "reset_counters", "pool
 
 
 DECODE_KERNELS = ("decode_kernel", "merge_parts_kernel")
+LIVE_TRAFFIC_FAILED = []                   # why a profiled child run of this process failed, if one did
 
 
 def live_traffic(args, cfg_id, kernels=SCORE_STAGE_KERNELS):
@@ -71,8 +72,15 @@ def live_traffic(args, cfg_id, kernels=SCORE_STAGE_KERNELS):
     import shutil
     import subprocess
     import tempfile
+    if LIVE_TRAFFIC_FAILED:
+        return None, "not measured in this run: %s" % LIVE_TRAFFIC_FAILED[0]
     if shutil.which("rocprofv3") is None:
+        LIVE_TRAFFIC_FAILED.append("rocprofv3 not found")
         return None, "rocprofv3 not found"
+
+    def failed(why):                       # one failure is enough: later workloads of the run do not try again
+        LIVE_TRAFFIC_FAILED.append(why)
+        return None, why
     flags = ["--config", str(cfg_id), "--window", args.window, "--pool-mode", args.pool_mode, "--layout", args.layout,
              "--path", args.path]
     env = dict(os.environ, TMPDIR="/tmp", LAQ_COOPERATIVE_LAUNCH="0")
@@ -84,14 +92,14 @@ def live_traffic(args, cfg_id, kernels=SCORE_STAGE_KERNELS):
                    sys.executable, os.path.abspath(__file__), "--no-cpu-baseline", "--no-probe", "--no-extra",
                    "--calibrate-copy", "--steps", "3", "--warmup", "1"] + flags
             try:
-                res = subprocess.run(cmd, cwd="/tmp", env=env, capture_output=True, text=True, timeout=150)
+                res = subprocess.run(cmd, cwd="/tmp", env=env, capture_output=True, text=True, timeout=100)
             except (subprocess.TimeoutExpired, OSError) as err:
-                return None, "profiled child run failed: %s" % type(err).__name__
+                return failed("profiled child run failed: %s" % type(err).__name__)
             if res.returncode != 0:
-                return None, "profiled child run ended with status %d" % res.returncode
+                return failed("profiled child run ended with status %d" % res.returncode)
             found = [os.path.join(d, f) for d, _, fs in os.walk(out_dir) for f in fs if f.endswith("counter_collection.csv")]
             if not found:
-                return None, "the profiled child run left no counter file"
+                return failed("the profiled child run left no counter file")
             per_kernel, copy = {}, 0.0
             for row in csv.DictReader(open(found[0])):
                 if row["Counter_Name"] != counter:
@@ -102,7 +110,7 @@ def live_traffic(args, cfg_id, kernels=SCORE_STAGE_KERNELS):
                 elif "laq::" in name and any(k in name for k in kernels):
                     per_kernel.setdefault(name, []).append(val)
             if copy <= 0 or not per_kernel:
-                return None, "the counter file holds no %s for the copy or for the kernels looked for" % counter
+                return failed("the counter file holds no %s for the copy or for the kernels looked for" % counter)
             to_bytes = float(1 << 30) / copy            # the copy reads 1 GiB and writes 1 GiB
             total += sum(sum(v) / len(v) for v in per_kernel.values()) * to_bytes
             names = sorted(n.replace("void ", "").replace("(anonymous namespace)::", "").replace("laq::", "").split("(")[0]
