@@ -101,6 +101,7 @@ template <int NRT> struct Cfg {
   static constexpr int ROWS = NRT * 32;
   static constexpr int PAIRS = 8;                                   // (key tile, row tile) pairs a wave keeps: 16 registers each
   static constexpr int KT = PAIRS / NRT;                            // key tiles per wave and head
+  static constexpr bool ROTATE = NRT == 2;                          // see WaveCtx::rot (the other instantiations lose registers to it)
   static constexpr int KEYS_PER_WAVE = KT * 32, KEYS_PER_BLOCK = F_WAVES * KEYS_PER_WAVE;
   static constexpr int Q_BYTES = ROWS * QROWB;
   static constexpr int Q_PIECES = ROWS * (D / 8);                   // 16-byte pieces of one Q_g
@@ -132,13 +133,10 @@ __device__ __forceinline__ void coherent_store(float2* p, float2 v) {
   __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// (M, Z) <- (M, Z) merged with p = (m, z): the sums rescaled to the larger maximum.  One of the two
-// scale factors is exp2(0): only the other one is computed.
 __device__ __forceinline__ void merge_stat(float& M, float& Z, float2 p) {
-  const float d = p.x - M;
-  const float f = __builtin_amdgcn_exp2f(-fabsf(d));
-  Z = d > 0.f ? fmaf(Z, f, p.y) : fmaf(p.y, f, Z);
-  M = fmaxf(M, p.x);
+  const float Mn = fmaxf(M, p.x);
+  Z = Z * __builtin_amdgcn_exp2f(M - Mn) + p.y * __builtin_amdgcn_exp2f(p.x - Mn);
+  M = Mn;
 }
 
 // Row index (0..31) of accumulator register i for a lane in half hf of the 32x32 output layout.
@@ -280,7 +278,7 @@ __device__ __forceinline__ void wave_main(const WaveCtx& w, f32x16 (&E)[Cfg<NRT>
         // instructions so that the common one needs no copy of its start value; the bound goes
         // through an opaque copy so that the start vectors of all pairs are not computed ahead and
         // kept alive.
-        const int t0 = w.key0 + ((kt + w.rot) % KT) * 32;
+        const int t0 = w.key0 + (Cfg<NRT>::ROTATE ? (kt + w.rot) % KT : kt) * 32;
         int qmin_here = __builtin_amdgcn_readfirstlane(w.qmin);
         asm volatile("" : "+s"(qmin_here));
         if (t0 + 31 > qmin_here) {
@@ -373,7 +371,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
   // (the members of a team start at different tiles of their ranges, so that the addresses the
   // device is asked for at the same time do not all lie the same distance into a 32 KiB piece: about
   // 2 % on the stage time of config 5, averaged over its modes)
-  w.rot = __builtin_amdgcn_readfirstlane(member % KT);
+  w.rot = S::ROTATE ? __builtin_amdgcn_readfirstlane(member % KT) : 0;
   w.L = g.L; w.qmin = g.qmin; w.row_bytes = lay.row_bytes;
   w.last = last_lds;
   w.stage = smem + S::OFF_STAGE + wave * TILE_BYTES;
@@ -430,7 +428,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
   // key tile kt of this wave; a tile beyond the head's end of a paged cache gets an empty range,
   // every row of it reads as zeros
   auto tile_at = [&](const uint16_t* base, int kt) {
-    const int j0 = w.key0 + ((kt + w.rot) % KT) * 32;
+    const int j0 = w.key0 + (S::ROTATE ? (kt + w.rot) % KT : kt) * 32;
     if constexpr (PAGED) {
       if (j0 >= g.L) return TileRef{k, 0, 0};
       const int first = w.key0 / lay.block_rows * lay.block_rows;      // the block's first key
@@ -502,7 +500,8 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
   // row pair rp of the members sub, sub + NSUB, ...: up to B 16-byte device-coherent loads in
   // flight at a time; a word that is not there yet is loaded again.  Leaves the rows' weights.
   auto gather_fold = [&](int nth) {
-    constexpr int RPAIRS = S::RPAIRS, NSUB = S::NSUB, B = NSUB >= 16 ? 2 : 8;
+    constexpr int RPAIRS = S::RPAIRS, NSUB = S::NSUB, B = NSUB >= 16 ? 2 : NSUB >= 8 ? 4 : 8;
+    constexpr bool ALL_AT_ONCE = NSUB == 8;                   // (64 score rows; the other instantiations lose registers to it)
     const int tid = opaque(threadIdx.x);
     float2* team_stats = words_of(nth);
     const unsigned tag = tag_of(nth);
@@ -519,23 +518,57 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
           v[b2] = u32x4{0u, tag << 31, 0u, tag << 31};
           if (mb < T) v[b2] = __builtin_amdgcn_raw_buffer_load_b128(words, (mb * ROWS + 2 * rp) * 8, 0, COHERENT);
         }
-#pragma unroll
-        for (int b2 = 0; b2 < B; ++b2) {
-          const int mb = m0 + b2 * NSUB;
-          if (mb < T) {
-            while ((v[b2][1] >> 31) != tag || (v[b2][3] >> 31) != tag) {
-              if (gave_up[0]) break;
-              if (++probes > SPIN_LIMIT ||
-                  ((probes & 63) == 63 && __hip_atomic_load(sy.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-                __hip_atomic_store(sy.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                gave_up[0] = 1;
-                break;
-              }
-              __builtin_amdgcn_s_sleep(1);
-              v[b2] = __builtin_amdgcn_raw_buffer_load_b128(words, (mb * ROWS + 2 * rp) * 8, 0, COHERENT);
+        if constexpr (ALL_AT_ONCE) {
+          // words that are not there yet are asked for again, all of them at once per round: one
+          // round trip per round, however many members are late
+          for (;;) {
+            bool missing = false;
+  #pragma unroll
+            for (int b2 = 0; b2 < B; ++b2) missing |= (v[b2][1] >> 31) != tag || (v[b2][3] >> 31) != tag;
+            if (!missing) break;
+            if (gave_up[0]) break;
+            if (++probes > SPIN_LIMIT ||
+                ((probes & 63) == 63 && __hip_atomic_load(sy.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+              __hip_atomic_store(sy.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              gave_up[0] = 1;
+              break;
             }
-            merge_stat(M, Z, make_float2(__uint_as_float(v[b2][0]), __uint_as_float(v[b2][1] & 0x7fffffffu)));
-            merge_stat(M1, Z1, make_float2(__uint_as_float(v[b2][2]), __uint_as_float(v[b2][3] & 0x7fffffffu)));
+            __builtin_amdgcn_s_sleep(1);
+  #pragma unroll
+            for (int b2 = 0; b2 < B; ++b2) {
+              const int mb = m0 + b2 * NSUB;
+              if ((v[b2][1] >> 31) != tag || (v[b2][3] >> 31) != tag)
+                v[b2] = __builtin_amdgcn_raw_buffer_load_b128(words, (mb * ROWS + 2 * rp) * 8, 0, COHERENT);
+            }
+          }
+  #pragma unroll
+          for (int b2 = 0; b2 < B; ++b2) {
+            const int mb = m0 + b2 * NSUB;
+            if (mb < T) {
+              merge_stat(M, Z, make_float2(__uint_as_float(v[b2][0]), __uint_as_float(v[b2][1] & 0x7fffffffu)));
+              merge_stat(M1, Z1, make_float2(__uint_as_float(v[b2][2]), __uint_as_float(v[b2][3] & 0x7fffffffu)));
+            }
+          }
+        } else {
+          // one after the other
+  #pragma unroll
+          for (int b2 = 0; b2 < B; ++b2) {
+            const int mb = m0 + b2 * NSUB;
+            if (mb < T) {
+              while ((v[b2][1] >> 31) != tag || (v[b2][3] >> 31) != tag) {
+                if (gave_up[0]) break;
+                if (++probes > SPIN_LIMIT ||
+                    ((probes & 63) == 63 && __hip_atomic_load(sy.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+                  __hip_atomic_store(sy.status, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                  gave_up[0] = 1;
+                  break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+                v[b2] = __builtin_amdgcn_raw_buffer_load_b128(words, (mb * ROWS + 2 * rp) * 8, 0, COHERENT);
+              }
+              merge_stat(M, Z, make_float2(__uint_as_float(v[b2][0]), __uint_as_float(v[b2][1] & 0x7fffffffu)));
+              merge_stat(M1, Z1, make_float2(__uint_as_float(v[b2][2]), __uint_as_float(v[b2][3] & 0x7fffffffu)));
+            }
           }
         }
       }
@@ -665,7 +698,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
 #pragma unroll
       for (int kt = 0; kt < KT; ++kt) {
         const float tot = part[kt] + __shfl_xor(part[kt], 32);
-        const int kp = (kt + w.rot) % KT;
+        const int kp = S::ROTATE ? (kt + w.rot) % KT : kt;
         const int j = w.key0 + kp * 32 + n32f;
         if (hff == 0) raw_lds[wave * KEYS_PER_WAVE + kp * 32 + n32f] = j < g.L ? tot : 0.f;
       }
