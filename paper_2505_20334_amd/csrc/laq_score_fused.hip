@@ -523,7 +523,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
           // round trip per round, however many members are late
           for (;;) {
             bool missing = false;
-  #pragma unroll
+#pragma unroll
             for (int b2 = 0; b2 < B; ++b2) missing |= (v[b2][1] >> 31) != tag || (v[b2][3] >> 31) != tag;
             if (!missing) break;
             if (gave_up[0]) break;
@@ -534,14 +534,14 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
               break;
             }
             __builtin_amdgcn_s_sleep(1);
-  #pragma unroll
+#pragma unroll
             for (int b2 = 0; b2 < B; ++b2) {
               const int mb = m0 + b2 * NSUB;
               if ((v[b2][1] >> 31) != tag || (v[b2][3] >> 31) != tag)
                 v[b2] = __builtin_amdgcn_raw_buffer_load_b128(words, (mb * ROWS + 2 * rp) * 8, 0, COHERENT);
             }
           }
-  #pragma unroll
+#pragma unroll
           for (int b2 = 0; b2 < B; ++b2) {
             const int mb = m0 + b2 * NSUB;
             if (mb < T) {
@@ -551,7 +551,7 @@ __global__ __launch_bounds__(F_THREADS, 2) void fused_kernel(ScoreGeom g, QueryP
           }
         } else {
           // one after the other
-  #pragma unroll
+#pragma unroll
           for (int b2 = 0; b2 < B; ++b2) {
             const int mb = m0 + b2 * NSUB;
             if (mb < T) {
